@@ -1,0 +1,182 @@
+/*
+ * cham.h -- C ABI of libcham: the data-parallel core of Adaptive Sampling
+ * (Chameleon, arXiv 2001.08743, Sec. 3.3 and Algorithm 1) for AMD MI355X (gfx950).
+ *
+ * One call of Algorithm 1 takes the candidate configurations s_Theta of a tuning
+ * task and the visited configurations v_Theta and returns the configurations to
+ * measure.  The library runs that for a batch of independent tasks on one GPU:
+ *
+ *   cham_kmeans_sweep     k-means for every k of a sweep (Algorithm 1, first loop body)
+ *   cham_select_k         threshold test on the loss curve (Algorithm 1, knee exit)
+ *   cham_snap_centroids   member configuration nearest to each centroid of the chosen k
+ *   cham_synthesize       per-knob mode replacement of redundant / invalid picks and
+ *                         dedupe against the visited set (Algorithm 1, second loop)
+ *
+ * Conventions
+ *   - A configuration is one small integer per knob (Sec. 2.2): a uint8 knob index.
+ *   - X is a structure-of-arrays matrix in DEVICE memory: knob j of row i is X[j*ld + i].
+ *     ld >= total rows, ld % 4 == 0, X 4-byte aligned.  All tasks share X; task t owns
+ *     rows [task_off[t], task_off[t+1]).
+ *   - "DEVICE" pointers are hipMalloc'd (or torch) device memory, "HOST" pointers ordinary
+ *     host memory that is read before the call returns.  The caller owns every buffer and
+ *     keeps device buffers alive until the stream has run the call.
+ *   - Work is enqueued on `stream` (a hipStream_t passed as void*, NULL = default
+ *     stream); calls do not synchronise.  Small HOST arrays are copied into the
+ *     workspace with an asynchronous copy on that stream.
+ *   - Every function returns CHAM_OK or a negative error; on an argument error nothing
+ *     is enqueued and no output is written.  Functions never throw or abort.
+ *   - ks is strictly increasing, 1 <= k <= 256.  Ksum = sum(ks), koff[i] = ks[0]+..+ks[i-1],
+ *     k_max = ks[n_k-1].
+ *   - Integer outputs are exact and reproducible run to run; floating-point outputs are
+ *     IEEE doubles computed in a fixed order (see each function).
+ */
+#ifndef CHAM_H
+#define CHAM_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define CHAM_OK              0
+#define CHAM_E_NULL         (-1)   /* a required pointer is NULL */
+#define CHAM_E_BAD_DIM      (-2)   /* d outside [1,32], ld < rows, ld % 4 != 0, misaligned X, n_iter < 0, T < 1 */
+#define CHAM_E_BAD_K        (-3)   /* ks empty, not strictly increasing, k < 1 or k > 256 */
+#define CHAM_E_BAD_OFFSETS  (-4)   /* task_off not non-decreasing from >= 0, a task larger than 2^23 rows */
+#define CHAM_E_CARD         (-5)   /* a cardinality is 0 or above 256 */
+#define CHAM_E_WORKSPACE    (-6)   /* workspace NULL or smaller than cham_*_workspace_bytes says */
+#define CHAM_E_HIP          (-7)   /* a HIP runtime call failed; see cham_last_hip_error() */
+#define CHAM_E_BAD_FLAG     (-8)   /* unknown bits in flags / unknown init_mode */
+
+/* values of out_flag (cham_synthesize) */
+#define CHAM_OUT_EMPTY   0   /* cluster has no member (or index >= chosen k) */
+#define CHAM_OUT_KEPT    1   /* the cluster's pick is valid and not visited: kept as is */
+#define CHAM_OUT_SYNTH   2   /* pick replaced by the per-knob mode of the cluster */
+#define CHAM_OUT_DROPPED 3   /* pick flagged and no usable replacement exists */
+
+/* flags of cham_kmeans_sweep / cham_snap_centroids */
+#define CHAM_F_FORCE_EXACT   1   /* evaluate every distance in double (slow; verification aid) */
+#define CHAM_F_STREAMING     2   /* force the multi-workgroup-per-task path */
+#define CHAM_F_RESIDENT      4   /* force the one-workgroup-per-(task,k) path */
+#define CHAM_F_NO_MFMA       8   /* never use the matrix-core distance path */
+
+int32_t     cham_version(void);
+const char *cham_strerror(int32_t code);
+/* Last HIP error code seen by this thread's library calls (0 = none). */
+int32_t     cham_last_hip_error(void);
+
+/* Bytes of DEVICE workspace cham_kmeans_sweep needs for these arguments (all HOST),
+ * or a negative error code. */
+int64_t cham_sweep_workspace_bytes(int64_t ld, int32_t d, const int64_t *task_off, int32_t T,
+                                   const int32_t *ks, int32_t n_k, int32_t n_iter, int32_t flags);
+
+/*
+ * K-means sweep (Algorithm 1, "K-means.run(s_Theta, k)" for every k; Sec. 3.3: centroids and
+ * the L2 loss per number of clusters).  The whole list ks is run (no early exit; the knee
+ * test is cham_select_k).
+ *
+ * For each task t and each k = ks[ki]:
+ *   start:  init_mode 0: the first k distinct rows of the task, in row order;
+ *           init_mode 1: init_centroids[(t*Ksum + koff[ki] + c)*d + j]  (DEVICE, doubles);
+ *   n_iter times: label every row with its nearest centroid (squared Euclidean distance on
+ *           the raw knob indices, lowest cluster index on ties); move every non-empty
+ *           centroid to the mean of its rows (an empty cluster keeps its centroid);
+ *   then one more labelling with the final centroids, which fixes labels, counts and loss.
+ * Distances are screened in fp32 with a proven error bound; every decision inside that
+ * bound is re-evaluated in double as sum_j ((double)x_j - mu_j)^2 (j ascending, no fused
+ * multiply-add), so labels are those of a plain double-precision implementation.
+ * Cluster sums are integers; centroids are (double)sum / (double)count.
+ *
+ * Outputs (all DEVICE):
+ *   centroids [T][Ksum][d] double  final centroids, row (t,ki,c) at t*Ksum + koff[ki] + c
+ *   counts    [T][Ksum]    int32   final cluster sizes
+ *   inertia   [T][n_k]     double  loss: sum over rows of the squared distance to the row's
+ *                                  final centroid (double terms, fixed summation tree)
+ *   status    [T][n_k]     int32   0 ok; 1 = task has fewer than k distinct rows (init_mode 0):
+ *                                  centroids, counts, loss and labels of that (t,k) are zero
+ *   labels    [n_k][ld]    uint8   final labels per k (optional, may be NULL)
+ *   inertia_trace [T][n_k][n_iter+1] double  loss seen by every labelling pass (optional)
+ * workspace: DEVICE scratch of at least cham_sweep_workspace_bytes(...) bytes, 256-byte aligned.
+ */
+int32_t cham_kmeans_sweep(const uint8_t *X, int64_t ld, int32_t d,
+                          const int64_t *task_off, int32_t T,
+                          const int32_t *ks, int32_t n_k,
+                          int32_t n_iter, int32_t init_mode, const double *init_centroids,
+                          double *centroids, int32_t *counts, double *inertia, int32_t *status,
+                          uint8_t *labels, double *inertia_trace,
+                          void *workspace, int64_t workspace_bytes, int32_t flags, void *stream);
+
+/*
+ * Knee selection (Algorithm 1: previous_loss = infinity; for each k in order: stop at the
+ * first k with threshold * loss(k) >= previous_loss, and that k is the result; if no k
+ * stops the loop the last k is the result).  Entries with status != 0 are skipped as if
+ * absent.  chosen_idx[t] (DEVICE int32 [T]) receives the index into ks, -1 if none usable.
+ * The paper's threshold is 2.5 (hyper-parameter table, threshold_meta).
+ */
+int32_t cham_select_k(const double *inertia, const int32_t *status, int32_t T, int32_t n_k,
+                      double threshold, int32_t *chosen_idx, void *stream);
+/* The same rule on HOST arrays (status may be NULL); returns the index or -1. */
+int32_t cham_select_k_host(const double *curve, const int32_t *status, int32_t n_k, double threshold);
+
+int64_t cham_snap_workspace_bytes(int64_t ld, int32_t d, const int64_t *task_off, int32_t T,
+                                  const int32_t *ks, int32_t n_k);
+/*
+ * Representatives of the chosen clustering (Sec. 3.3: centroids stand for their clusters; a
+ * centroid is real-valued, so the representative is the member configuration nearest to it).
+ * For task t with k* = ks[chosen_idx[t]] and its centroids from cham_kmeans_sweep:
+ *   labels_sel [ld] uint8          nearest-centroid label of every row (same rule as the sweep)
+ *   pick_row [T][k_max] int32      row (relative to the task's first row) of the member with the
+ *                                  smallest distance to centroid c, lowest row on ties;
+ *                                  -1 for an empty cluster and for c >= k*
+ *   pick_cfg [T][k_max][d] uint8   that row's knob values (zeros where pick_row = -1)
+ * chosen_idx = -1 leaves the task's picks at -1.  All pointers DEVICE except task_off, ks.
+ */
+int32_t cham_snap_centroids(const uint8_t *X, int64_t ld, int32_t d,
+                            const int64_t *task_off, int32_t T, const int32_t *ks, int32_t n_k,
+                            const int32_t *chosen_idx, const double *centroids,
+                            uint8_t *labels_sel, int32_t *pick_row, uint8_t *pick_cfg,
+                            void *workspace, int64_t workspace_bytes, int32_t flags, void *stream);
+
+int64_t cham_synth_workspace_bytes(int64_t ld, int32_t d, const int64_t *task_off, int32_t T,
+                                   const int32_t *ks, int32_t n_k);
+/*
+ * Sample Synthesis and dedupe (Algorithm 1, second loop; Sec. 3.3 "most frequent = mode,
+ * non-invalid choice for each knob").
+ *   cards [T][d] HOST uint16     cardinality of each knob (every value of X is < its card)
+ *   valid [ld] DEVICE uint8      1 = valid configuration, 0 = known invalid; NULL = all valid
+ *   visited DEVICE uint64        hashes (cham_hash_config) of measured configurations, sorted
+ *                                ascending; membership is by hash
+ *   task_salt [T] HOST uint64    hash salt per task; NULL = task index
+ * A pick is flagged if its row is invalid or its hash is in visited.  Unflagged picks are
+ * KEPT.  Flagged clusters, in ascending order, are replaced by the per-knob mode over the
+ * cluster's valid members (smallest value on ties); the replacement is DROPPED if the cluster
+ * has no valid member, if its hash is visited, if it equals a kept pick or a replacement
+ * accepted for a lower cluster; otherwise SYNTH.
+ *   out_cfg [T][k_max][d] uint8, out_flag [T][k_max] uint8 (CHAM_OUT_*), out_count [T] int32
+ *   (number of KEPT + SYNTH); rows of out_cfg that are not KEPT / SYNTH are zero.
+ */
+int32_t cham_synthesize(const uint8_t *X, int64_t ld, int32_t d,
+                        const int64_t *task_off, int32_t T, const uint16_t *cards,
+                        const uint8_t *valid, const int32_t *ks, int32_t n_k,
+                        const int32_t *chosen_idx, const uint8_t *labels_sel,
+                        const int32_t *pick_row, const uint8_t *pick_cfg,
+                        const uint64_t *visited, int64_t n_visited, const uint64_t *task_salt,
+                        uint8_t *out_cfg, uint8_t *out_flag, int32_t *out_count,
+                        void *workspace, int64_t workspace_bytes, void *stream);
+
+/*
+ * Configuration hash used for the visited set: 64-bit FNV-1a over the d knob bytes, the
+ * offset basis first XORed with salt * 0x9E3779B97F4A7C15 (mod 2^64).  salt 0 gives plain
+ * FNV-1a.  cfg is HOST memory.
+ */
+uint64_t cham_hash_config(const uint8_t *cfg, int32_t d, uint64_t salt);
+/* Batch version on the device: rows is DEVICE row-major [n][d]; salts DEVICE [n] or NULL
+ * (then salt_all is used for every row); out DEVICE [n]. */
+int32_t cham_hash_rows(const uint8_t *rows, int64_t n, int32_t d, const uint64_t *salts,
+                       uint64_t salt_all, uint64_t *out, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CHAM_H */

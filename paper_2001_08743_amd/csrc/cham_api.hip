@@ -1,0 +1,409 @@
+// C ABI of libcham: argument checks, workspace carving, staging of the small host arrays and
+// kernel launches for the Adaptive Sampling path (paper Sec. 3.3, Algorithm 1).
+#include "../../include/cham.h"
+
+#include <vector>
+
+#include "cham_internal.h"
+
+namespace cham {
+
+namespace {
+
+thread_local int32_t g_last_hip = 0;
+
+int32_t hip_fail(hipError_t e)
+{
+    g_last_hip = (int32_t)e;
+    return CHAM_E_HIP;
+}
+
+constexpr int64_t kAlign = 256;
+inline int64_t up(int64_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
+
+// Small host arrays travel to the device inside kernel arguments (copied at launch time), so
+// no host buffer has to outlive the call and nothing is allocated.
+constexpr int kPokeWords = 120;
+struct PokeArgs {
+    uint64_t v[kPokeWords];
+    uint64_t *dst;
+    int n;
+};
+__global__ void poke_kernel(const PokeArgs p)
+{
+    const int i = threadIdx.x;
+    if (i < p.n) p.dst[i] = p.v[i];
+}
+
+hipError_t stage_words(const std::vector<uint64_t> &blob, uint64_t *dst, hipStream_t s)
+{
+    for (size_t o = 0; o < blob.size(); o += kPokeWords) {
+        PokeArgs p;
+        p.n = (int)((blob.size() - o) < (size_t)kPokeWords ? (blob.size() - o) : (size_t)kPokeWords);
+        for (int i = 0; i < p.n; ++i) p.v[i] = blob[o + i];
+        p.dst = dst + o;
+        hipLaunchKernelGGL(poke_kernel, dim3(1), dim3(128), 0, s, p);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    return hipSuccess;
+}
+
+// Host blob: [task_off (T+1) x i64][ks n_k x i32][koff (n_k+1) x i32][extra ...], 8-byte units.
+struct Plan {
+    int T = 0, n_k = 0, Ksum = 0, kmax = 0, DP = 0, nt = 0;
+    int64_t n_total = 0, n_max = 0;
+    std::vector<uint64_t> blob;
+    int64_t off_task = 0, off_ks = 0, off_koff = 0, off_extra = 0;   // byte offsets in the blob
+};
+
+int32_t check_common(const void *X, int64_t ld, int32_t d, const int64_t *task_off, int32_t T,
+                     const int32_t *ks, int32_t n_k, bool need_x, Plan &pl)
+{
+    if ((need_x && !X) || !task_off || !ks) return CHAM_E_NULL;
+    if (d < 1 || d > 32 || T < 1 || ld < 0 || (ld % 4) != 0) return CHAM_E_BAD_DIM;
+    if (need_x && (reinterpret_cast<uintptr_t>(X) % 4) != 0) return CHAM_E_BAD_DIM;
+    if (n_k < 1 || n_k > 256) return CHAM_E_BAD_K;
+    int64_t ksum = 0;
+    for (int i = 0; i < n_k; ++i) {
+        if (ks[i] < 1 || ks[i] > 256) return CHAM_E_BAD_K;
+        if (i > 0 && ks[i] <= ks[i - 1]) return CHAM_E_BAD_K;
+        ksum += ks[i];
+    }
+    if (task_off[0] < 0) return CHAM_E_BAD_OFFSETS;
+    int64_t nmax = 0;
+    for (int t = 0; t < T; ++t) {
+        const int64_t n = task_off[t + 1] - task_off[t];
+        if (n < 0 || n > ((int64_t)1 << 23)) return CHAM_E_BAD_OFFSETS;
+        if (n > nmax) nmax = n;
+    }
+    if (task_off[T] > ld) return CHAM_E_BAD_DIM;
+    pl.T = T;
+    pl.n_k = n_k;
+    pl.Ksum = (int)ksum;
+    pl.kmax = ks[n_k - 1];
+    pl.DP = (d + 3) / 4 * 4;
+    pl.n_total = task_off[T];
+    pl.n_max = nmax;
+    const int maxnt = pl.DP <= 24 ? 1024 : 512;
+    int64_t nt = ((nmax + 3 + 3) / 4 + 63) / 64 * 64;
+    if (nt < 64) nt = 64;
+    if (nt > maxnt) nt = maxnt;
+    pl.nt = (int)nt;
+
+    // blob
+    const size_t w_task = (size_t)T + 1;
+    const size_t w_ks = ((size_t)n_k + 1) / 2;
+    const size_t w_koff = ((size_t)n_k + 2) / 2;
+    pl.blob.assign(w_task + w_ks + w_koff, 0);
+    for (int t = 0; t <= T; ++t) pl.blob[t] = (uint64_t)task_off[t];
+    int32_t *pk = reinterpret_cast<int32_t *>(pl.blob.data() + w_task);
+    for (int i = 0; i < n_k; ++i) pk[i] = ks[i];
+    int32_t *po = reinterpret_cast<int32_t *>(pl.blob.data() + w_task + w_ks);
+    int acc = 0;
+    for (int i = 0; i < n_k; ++i) {
+        po[i] = acc;
+        acc += ks[i];
+    }
+    po[n_k] = acc;
+    pl.off_task = 0;
+    pl.off_ks = (int64_t)w_task * 8;
+    pl.off_koff = (int64_t)(w_task + w_ks) * 8;
+    pl.off_extra = (int64_t)(w_task + w_ks + w_koff) * 8;
+    return CHAM_OK;
+}
+
+struct SweepWs {
+    int64_t blob = 0, init_rows = 0, ndist = 0, labbuf = 0, total = 0;
+};
+
+SweepWs sweep_ws(const Plan &pl, int64_t ld, bool own_labels)
+{
+    SweepWs w;
+    int64_t o = 0;
+    w.blob = o;
+    o += up((int64_t)pl.blob.size() * 8);
+    w.init_rows = o;
+    o += up((int64_t)pl.T * pl.kmax * 4);
+    w.ndist = o;
+    o += up((int64_t)pl.T * 4);
+    w.labbuf = o;
+    if (own_labels) o += up((int64_t)pl.n_k * ld);
+    w.total = o;
+    return w;
+}
+
+}  // namespace
+
+}  // namespace cham
+
+using namespace cham;
+
+extern "C" {
+
+int32_t cham_version(void) { return 100; }
+
+int32_t cham_last_hip_error(void) { return g_last_hip; }
+
+const char *cham_strerror(int32_t code)
+{
+    switch (code) {
+    case CHAM_OK: return "ok";
+    case CHAM_E_NULL: return "a required pointer is NULL";
+    case CHAM_E_BAD_DIM: return "bad dimension (d outside [1,32], ld < rows or not a multiple of 4, misaligned X, n_iter < 0, T < 1)";
+    case CHAM_E_BAD_K: return "bad k list (empty, not strictly increasing, or outside [1,256])";
+    case CHAM_E_BAD_OFFSETS: return "bad task offsets (negative, decreasing, or a task above 2^23 rows)";
+    case CHAM_E_CARD: return "bad cardinality (0 or above 256)";
+    case CHAM_E_WORKSPACE: return "workspace missing or too small";
+    case CHAM_E_HIP: return "HIP runtime error (see cham_last_hip_error)";
+    case CHAM_E_BAD_FLAG: return "unknown flag bits or init mode";
+    default: return "unknown error code";
+    }
+}
+
+int64_t cham_sweep_workspace_bytes(int64_t ld, int32_t d, const int64_t *task_off, int32_t T,
+                                   const int32_t *ks, int32_t n_k, int32_t n_iter, int32_t flags)
+{
+    (void)n_iter;
+    (void)flags;
+    Plan pl;
+    const int32_t rc = check_common(nullptr, ld, d, task_off, T, ks, n_k, false, pl);
+    if (rc != CHAM_OK) return rc;
+    return sweep_ws(pl, ld, true).total;
+}
+
+int32_t cham_kmeans_sweep(const uint8_t *X, int64_t ld, int32_t d, const int64_t *task_off, int32_t T,
+                          const int32_t *ks, int32_t n_k, int32_t n_iter, int32_t init_mode,
+                          const double *init_centroids, double *centroids, int32_t *counts,
+                          double *inertia, int32_t *status, uint8_t *labels, double *inertia_trace,
+                          void *workspace, int64_t workspace_bytes, int32_t flags, void *stream)
+{
+    Plan pl;
+    int32_t rc = check_common(X, ld, d, task_off, T, ks, n_k, true, pl);
+    if (rc != CHAM_OK) return rc;
+    if (!centroids || !counts || !inertia || !status) return CHAM_E_NULL;
+    if (n_iter < 0) return CHAM_E_BAD_DIM;
+    if (init_mode != 0 && init_mode != 1) return CHAM_E_BAD_FLAG;
+    if (init_mode == 1 && !init_centroids) return CHAM_E_NULL;
+    if (flags & ~(CHAM_F_FORCE_EXACT | CHAM_F_STREAMING | CHAM_F_RESIDENT | CHAM_F_NO_MFMA)) return CHAM_E_BAD_FLAG;
+    const SweepWs w = sweep_ws(pl, ld, labels == nullptr);
+    if (!workspace || workspace_bytes < w.total) return CHAM_E_WORKSPACE;
+    if (reinterpret_cast<uintptr_t>(workspace) % kAlign) return CHAM_E_WORKSPACE;
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    unsigned char *ws = static_cast<unsigned char *>(workspace);
+
+    hipError_t e = stage_words(pl.blob, reinterpret_cast<uint64_t *>(ws + w.blob), s);
+    if (e != hipSuccess) return hip_fail(e);
+
+    SweepArgs a;
+    a.X = X;
+    a.ld = ld;
+    a.d = d;
+    a.T = T;
+    a.n_k = n_k;
+    a.Ksum = pl.Ksum;
+    a.kmax = pl.kmax;
+    a.n_iter = n_iter;
+    a.init_mode = init_mode;
+    a.flags = flags;
+    a.task_off = reinterpret_cast<const int64_t *>(ws + w.blob + pl.off_task);
+    a.ks = reinterpret_cast<const int *>(ws + w.blob + pl.off_ks);
+    a.koff = reinterpret_cast<const int *>(ws + w.blob + pl.off_koff);
+    a.init_centroids = init_centroids;
+    a.init_rows = reinterpret_cast<const int *>(ws + w.init_rows);
+    a.ndist = reinterpret_cast<const int *>(ws + w.ndist);
+    a.centroids = centroids;
+    a.counts = counts;
+    a.inertia = inertia;
+    a.status = status;
+    a.labbuf = labels ? labels : ws + w.labbuf;
+    a.trace = inertia_trace;
+
+    if (init_mode == 0) {
+        e = launch_first_distinct(a, reinterpret_cast<int *>(ws + w.init_rows),
+                                  reinterpret_cast<int *>(ws + w.ndist), s);
+        if (e != hipSuccess) return hip_fail(e);
+    }
+    e = launch_resident_sweep(a, pl.nt, s);
+    if (e != hipSuccess) return hip_fail(e);
+    return CHAM_OK;
+}
+
+int32_t cham_select_k_host(const double *curve, const int32_t *status, int32_t n_k, double threshold)
+{
+    if (!curve || n_k < 1) return -1;
+    bool have_prev = false;
+    double prev = 0.0;
+    int32_t last = -1;
+    for (int32_t i = 0; i < n_k; ++i) {
+        if (status && status[i] != 0) continue;
+        if (have_prev && threshold * curve[i] >= prev) return i;
+        prev = curve[i];
+        have_prev = true;
+        last = i;
+    }
+    return last;
+}
+
+int32_t cham_select_k(const double *inertia, const int32_t *status, int32_t T, int32_t n_k,
+                      double threshold, int32_t *chosen_idx, void *stream)
+{
+    if (!inertia || !status || !chosen_idx) return CHAM_E_NULL;
+    if (T < 1) return CHAM_E_BAD_DIM;
+    if (n_k < 1 || n_k > 256) return CHAM_E_BAD_K;
+    hipError_t e = launch_select_k(inertia, status, T, n_k, threshold, chosen_idx,
+                                   reinterpret_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return hip_fail(e);
+    return CHAM_OK;
+}
+
+int64_t cham_snap_workspace_bytes(int64_t ld, int32_t d, const int64_t *task_off, int32_t T,
+                                  const int32_t *ks, int32_t n_k)
+{
+    Plan pl;
+    const int32_t rc = check_common(nullptr, ld, d, task_off, T, ks, n_k, false, pl);
+    if (rc != CHAM_OK) return rc;
+    return up((int64_t)pl.blob.size() * 8) + up(ld * 8);
+}
+
+int32_t cham_snap_centroids(const uint8_t *X, int64_t ld, int32_t d, const int64_t *task_off, int32_t T,
+                            const int32_t *ks, int32_t n_k, const int32_t *chosen_idx,
+                            const double *centroids, uint8_t *labels_sel, int32_t *pick_row,
+                            uint8_t *pick_cfg, void *workspace, int64_t workspace_bytes, int32_t flags,
+                            void *stream)
+{
+    Plan pl;
+    int32_t rc = check_common(X, ld, d, task_off, T, ks, n_k, true, pl);
+    if (rc != CHAM_OK) return rc;
+    if (!chosen_idx || !centroids || !labels_sel || !pick_row || !pick_cfg) return CHAM_E_NULL;
+    if (flags & ~(CHAM_F_FORCE_EXACT | CHAM_F_STREAMING | CHAM_F_RESIDENT | CHAM_F_NO_MFMA)) return CHAM_E_BAD_FLAG;
+    const int64_t blob_bytes = up((int64_t)pl.blob.size() * 8);
+    if (!workspace || workspace_bytes < blob_bytes + up(ld * 8)) return CHAM_E_WORKSPACE;
+    if (reinterpret_cast<uintptr_t>(workspace) % kAlign) return CHAM_E_WORKSPACE;
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    unsigned char *ws = static_cast<unsigned char *>(workspace);
+    hipError_t e = stage_words(pl.blob, reinterpret_cast<uint64_t *>(ws), s);
+    if (e != hipSuccess) return hip_fail(e);
+    SnapArgs a;
+    a.X = X;
+    a.ld = ld;
+    a.d = d;
+    a.T = T;
+    a.n_k = n_k;
+    a.Ksum = pl.Ksum;
+    a.kmax = pl.kmax;
+    a.flags = flags;
+    a.task_off = reinterpret_cast<const int64_t *>(ws + pl.off_task);
+    a.ks = reinterpret_cast<const int *>(ws + pl.off_ks);
+    a.koff = reinterpret_cast<const int *>(ws + pl.off_koff);
+    a.chosen = chosen_idx;
+    a.centroids = centroids;
+    a.labels_sel = labels_sel;
+    a.pick_row = pick_row;
+    a.pick_cfg = pick_cfg;
+    a.dist_ws = reinterpret_cast<double *>(ws + blob_bytes);
+    e = launch_snap(a, pl.nt, s);
+    if (e != hipSuccess) return hip_fail(e);
+    return CHAM_OK;
+}
+
+static int64_t synth_blob_extra_words(int32_t T, int32_t d)
+{
+    return (int64_t)T + ((int64_t)T * d + 3) / 4;      // salts (u64) + cards (u16)
+}
+
+int64_t cham_synth_workspace_bytes(int64_t ld, int32_t d, const int64_t *task_off, int32_t T,
+                                   const int32_t *ks, int32_t n_k)
+{
+    Plan pl;
+    const int32_t rc = check_common(nullptr, ld, d, task_off, T, ks, n_k, false, pl);
+    if (rc != CHAM_OK) return rc;
+    return up(((int64_t)pl.blob.size() + synth_blob_extra_words(T, d)) * 8);
+}
+
+int32_t cham_synthesize(const uint8_t *X, int64_t ld, int32_t d, const int64_t *task_off, int32_t T,
+                        const uint16_t *cards, const uint8_t *valid, const int32_t *ks, int32_t n_k,
+                        const int32_t *chosen_idx, const uint8_t *labels_sel, const int32_t *pick_row,
+                        const uint8_t *pick_cfg, const uint64_t *visited, int64_t n_visited,
+                        const uint64_t *task_salt, uint8_t *out_cfg, uint8_t *out_flag,
+                        int32_t *out_count, void *workspace, int64_t workspace_bytes, void *stream)
+{
+    Plan pl;
+    int32_t rc = check_common(X, ld, d, task_off, T, ks, n_k, true, pl);
+    if (rc != CHAM_OK) return rc;
+    if (!cards || !chosen_idx || !labels_sel || !pick_row || !pick_cfg || !out_cfg || !out_flag || !out_count)
+        return CHAM_E_NULL;
+    if (n_visited < 0 || (n_visited > 0 && !visited)) return CHAM_E_NULL;
+    int cmax = 1;
+    for (int64_t i = 0; i < (int64_t)T * d; ++i) {
+        if (cards[i] < 1 || cards[i] > 256) return CHAM_E_CARD;
+        if (cards[i] > cmax) cmax = cards[i];
+    }
+    const int64_t base_words = (int64_t)pl.blob.size();
+    const int64_t need = up((base_words + synth_blob_extra_words(T, d)) * 8);
+    if (!workspace || workspace_bytes < need) return CHAM_E_WORKSPACE;
+    if (reinterpret_cast<uintptr_t>(workspace) % kAlign) return CHAM_E_WORKSPACE;
+    // extend the blob: salts then cards
+    pl.blob.resize((size_t)(base_words + synth_blob_extra_words(T, d)), 0);
+    for (int t = 0; t < T; ++t) pl.blob[(size_t)base_words + t] = task_salt ? task_salt[t] : (uint64_t)t;
+    uint16_t *pc = reinterpret_cast<uint16_t *>(pl.blob.data() + base_words + T);
+    for (int64_t i = 0; i < (int64_t)T * d; ++i) pc[i] = cards[i];
+
+    hipStream_t s = reinterpret_cast<hipStream_t>(stream);
+    unsigned char *ws = static_cast<unsigned char *>(workspace);
+    hipError_t e = stage_words(pl.blob, reinterpret_cast<uint64_t *>(ws), s);
+    if (e != hipSuccess) return hip_fail(e);
+
+    SynthArgs a;
+    a.X = X;
+    a.ld = ld;
+    a.d = d;
+    a.T = T;
+    a.n_k = n_k;
+    a.kmax = pl.kmax;
+    // LDS histogram: room for every cluster if that fits in 96 KiB, never less than one cluster
+    int64_t words = (int64_t)pl.kmax * d * cmax;
+    if (words > 24576) words = 24576;
+    if (words < (int64_t)d * cmax) words = (int64_t)d * cmax;
+    a.hist_words = (int)words;
+    a.task_off = reinterpret_cast<const int64_t *>(ws + pl.off_task);
+    a.ks = reinterpret_cast<const int *>(ws + pl.off_ks);
+    a.salts = reinterpret_cast<const uint64_t *>(ws + base_words * 8);
+    a.cards = reinterpret_cast<const uint16_t *>(ws + (base_words + T) * 8);
+    a.valid = valid;
+    a.chosen = chosen_idx;
+    a.labels_sel = labels_sel;
+    a.pick_row = pick_row;
+    a.pick_cfg = pick_cfg;
+    a.visited = visited;
+    a.n_visited = n_visited;
+    a.out_cfg = out_cfg;
+    a.out_flag = out_flag;
+    a.out_count = out_count;
+    int nt = pl.nt < 256 ? 256 : pl.nt;
+    if (nt > 1024) nt = 1024;
+    e = launch_synth(a, nt, s);
+    if (e != hipSuccess) return hip_fail(e);
+    return CHAM_OK;
+}
+
+uint64_t cham_hash_config(const uint8_t *cfg, int32_t d, uint64_t salt)
+{
+    uint64_t h = 0xCBF29CE484222325ULL ^ (salt * 0x9E3779B97F4A7C15ULL);
+    if (!cfg) return h;
+    for (int32_t j = 0; j < d; ++j) h = (h ^ (uint64_t)cfg[j]) * 0x100000001B3ULL;
+    return h;
+}
+
+int32_t cham_hash_rows(const uint8_t *rows, int64_t n, int32_t d, const uint64_t *salts,
+                       uint64_t salt_all, uint64_t *out, void *stream)
+{
+    if (n < 0 || d < 0) return CHAM_E_BAD_DIM;
+    if (n == 0) return CHAM_OK;
+    if (!rows || !out) return CHAM_E_NULL;
+    hipError_t e = launch_hash_rows(rows, n, d, salts, salt_all, out, reinterpret_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return hip_fail(e);
+    return CHAM_OK;
+}
+
+}  // extern "C"

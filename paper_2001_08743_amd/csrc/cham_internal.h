@@ -1,0 +1,104 @@
+// Host/device shared declarations internal to libcham (not part of the public ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace cham {
+
+// Arguments of the sweep kernels.  Pointers are device pointers.
+struct SweepArgs {
+    const uint8_t *X;
+    int64_t ld;
+    int d;
+    int T;
+    int n_k;
+    int Ksum;
+    int kmax;
+    int n_iter;
+    int init_mode;
+    int flags;
+    const int64_t *task_off;       // [T+1]
+    const int *ks;                 // [n_k]
+    const int *koff;               // [n_k+1]
+    const double *init_centroids;  // [T][Ksum][d] or null
+    const int *init_rows;          // [T][kmax] first distinct rows (task-relative)
+    const int *ndist;              // [T] how many distinct rows were found (<= kmax)
+    double *centroids;             // [T][Ksum][d]
+    int *counts;                   // [T][Ksum]
+    double *inertia;               // [T][n_k]
+    int *status;                   // [T][n_k]
+    uint8_t *labbuf;               // [n_k][ld] working / final labels
+    double *trace;                 // [T][n_k][n_iter+1] or null
+};
+
+// LDS bytes the resident kernel needs for padded knob count DP and largest k.
+inline size_t resident_lds_bytes(int DP, int kmax)
+{
+    size_t b = 0;
+    b += sizeof(double) * (size_t)DP * kmax;          // mu64T
+    b += sizeof(float) * (size_t)kmax * (DP + 4);     // wf
+    b += sizeof(int) * (size_t)kmax * DP;             // S
+    b += sizeof(int) * (size_t)kmax;                  // n
+    b += sizeof(float) * (size_t)DP;                  // ojf
+    b += sizeof(double) * 16;                         // per-wave partials
+    b += 64;                                          // m2 bits and padding
+    return b;
+}
+
+// Arguments of the snap kernel.
+struct SnapArgs {
+    const uint8_t *X;
+    int64_t ld;
+    int d;
+    int T;
+    int n_k;
+    int Ksum;
+    int kmax;
+    int flags;
+    const int64_t *task_off;
+    const int *ks;
+    const int *koff;
+    const int *chosen;          // [T]
+    const double *centroids;    // [T][Ksum][d]
+    uint8_t *labels_sel;        // [ld]
+    int *pick_row;              // [T][kmax]
+    uint8_t *pick_cfg;          // [T][kmax][d]
+    double *dist_ws;            // [ld] exact distance of every row to its centroid
+};
+
+// Arguments of the synthesis kernel.
+struct SynthArgs {
+    const uint8_t *X;
+    int64_t ld;
+    int d;
+    int T;
+    int n_k;
+    int kmax;
+    int hist_words;             // LDS words available for value histograms
+    const int64_t *task_off;
+    const int *ks;
+    const uint16_t *cards;      // [T][d]
+    const uint64_t *salts;      // [T]
+    const uint8_t *valid;       // [ld] or null
+    const int *chosen;          // [T]
+    const uint8_t *labels_sel;  // [ld]
+    const int *pick_row;        // [T][kmax]
+    const uint8_t *pick_cfg;    // [T][kmax][d]
+    const uint64_t *visited;    // sorted
+    int64_t n_visited;
+    uint8_t *out_cfg;           // [T][kmax][d]
+    uint8_t *out_flag;          // [T][kmax]
+    int *out_count;             // [T]
+};
+
+hipError_t launch_first_distinct(const SweepArgs &a, int *init_rows, int *ndist, hipStream_t s);
+hipError_t launch_resident_sweep(const SweepArgs &a, int nt, hipStream_t s);
+hipError_t launch_select_k(const double *inertia, const int *status, int T, int n_k, double thr,
+                           int *chosen, hipStream_t s);
+hipError_t launch_snap(const SnapArgs &a, int nt, hipStream_t s);
+size_t synth_lds_bytes(int d, int kmax, int hist_words);
+hipError_t launch_synth(const SynthArgs &a, int nt, hipStream_t s);
+hipError_t launch_hash_rows(const uint8_t *rows, int64_t n, int d, const uint64_t *salts,
+                            uint64_t salt_all, uint64_t *out, hipStream_t s);
+
+}  // namespace cham

@@ -1,0 +1,328 @@
+// One workgroup runs the whole Lloyd iteration of one (task, k) unit of the sweep
+// (paper Algorithm 1: K-means.run(s_Theta, k) for one k; Sec. 3.3).
+//
+// Centroids, integer cluster sums and counts live in LDS for the whole unit; the task's rows
+// are read from global memory (L2-resident after the first pass) four rows per lane and pass.
+// Cluster sums are kept incrementally: a row touches the sums only when its label changes,
+// which is exact because the sums are integers.
+#include "cham_device.h"
+#include "cham_internal.h"
+
+namespace cham {
+
+namespace {
+
+template <int DP>
+struct UnitLds {
+    double *mu64T;
+    float *wf;
+    int *S;
+    int *n;
+    float *ojf;
+    double *red;
+    unsigned *m2bits;
+    __device__ UnitLds(unsigned char *base, int kmax)
+    {
+        mu64T = reinterpret_cast<double *>(base);
+        base += sizeof(double) * (size_t)DP * kmax;
+        red = reinterpret_cast<double *>(base);
+        base += sizeof(double) * 16;
+        wf = reinterpret_cast<float *>(base);
+        base += sizeof(float) * (size_t)kmax * (DP + 4);
+        S = reinterpret_cast<int *>(base);
+        base += sizeof(int) * (size_t)kmax * DP;
+        n = reinterpret_cast<int *>(base);
+        base += sizeof(int) * (size_t)kmax;
+        ojf = reinterpret_cast<float *>(base);
+        base += sizeof(float) * (size_t)DP;
+        m2bits = reinterpret_cast<unsigned *>(base);
+    }
+};
+
+// From the exact centroids build the fp32 screening form: w = -2*(mu - o), b = |mu - o|^2,
+// and the bound m2 >= max_c b.  Caller synchronises before and after.
+template <int DP>
+__device__ __forceinline__ void derive_screen(const UnitLds<DP> &U, int k, int kp)
+{
+    for (int c = threadIdx.x; c < k; c += blockDim.x) {
+        double b = 0.0;
+        float *w = U.wf + (size_t)c * (DP + 4);
+#pragma unroll
+        for (int j = 0; j < DP; ++j) {
+            const double m = U.mu64T[(size_t)j * kp + c] - (double)U.ojf[j];
+            b = __builtin_fma(m, m, b);
+            w[j] = (float)(-2.0 * m);
+        }
+        w[DP] = (float)b;
+        w[DP + 1] = 0.0f;
+        w[DP + 2] = 0.0f;
+        w[DP + 3] = 0.0f;
+        const float bu = __double2float_ru(b) * 1.0000005f;
+        atomicMax(U.m2bits, __float_as_uint(bu));
+    }
+}
+
+template <int DP, int MAXNT>
+__global__ __launch_bounds__(MAXNT) void resident_sweep_kernel(const SweepArgs a)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    UnitLds<DP> U(smem, a.kmax);
+
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWave - 1);
+    const int wave = tid / kWave;
+    const int nwaves = blockDim.x / kWave;
+
+    // units in descending-k order so that the longest ones start first
+    const int u = blockIdx.x;
+    const int ki = a.n_k - 1 - u / a.T;
+    const int t = u % a.T;
+    const int k = a.ks[ki];
+    const int kp = k;
+    const int d = a.d;
+    const int64_t r0 = a.task_off[t], r1 = a.task_off[t + 1];
+    const int64_t slot = (int64_t)t * a.n_k + ki;
+    const int64_t crow = (int64_t)t * a.Ksum + a.koff[ki];
+    uint8_t *labrow = a.labbuf + (int64_t)ki * a.ld;
+    const int64_t g0 = r0 & ~(int64_t)3;
+    const int tile_rows = blockDim.x * kRowsPerThread;
+    const bool force_exact = (a.flags & 1) != 0;
+
+    if (a.init_mode == 0 && a.ndist[t] < k) {
+        // fewer than k distinct rows: the unit is reported as unusable, all outputs zero
+        for (int e = tid; e < k * d; e += blockDim.x) a.centroids[crow * d + e] = 0.0;
+        for (int c = tid; c < k; c += blockDim.x) a.counts[crow + c] = 0;
+        for (int64_t r = r0 + tid; r < r1; r += blockDim.x) labrow[r] = 0;
+        if (tid == 0) {
+            a.status[slot] = 1;
+            a.inertia[slot] = 0.0;
+        }
+        if (a.trace)
+            for (int e = tid; e <= a.n_iter; e += blockDim.x) a.trace[slot * (a.n_iter + 1) + e] = 0.0;
+        return;
+    }
+
+    // ---- set-up: zero state, stage the starting centroids, choose centring offsets
+    for (int e = tid; e < DP * kp; e += blockDim.x) U.mu64T[e] = 0.0;
+    for (int e = tid; e < k * DP; e += blockDim.x) U.S[e] = 0;
+    for (int c = tid; c < k; c += blockDim.x) U.n[c] = 0;
+    if (tid == 0) *U.m2bits = 0u;
+    __syncthreads();
+    for (int e = tid; e < k * d; e += blockDim.x) {
+        const int c = e / d, j = e % d;
+        double v;
+        if (a.init_mode == 0) {
+            const int row = a.init_rows[(int64_t)t * a.kmax + c];
+            v = (double)a.X[(int64_t)j * a.ld + r0 + row];
+        } else {
+            v = a.init_centroids[(crow + c) * d + j];
+        }
+        U.mu64T[(size_t)j * kp + c] = v;
+    }
+    __syncthreads();
+    if (tid < DP) {
+        float o = 0.0f;
+        if (tid < d) {
+            double s = 0.0;
+            for (int c = 0; c < k; ++c) s += U.mu64T[(size_t)tid * kp + c];
+            double m = rint(s / (double)k);
+            m = m < 0.0 ? 0.0 : (m > 255.0 ? 255.0 : m);
+            o = (float)m;
+        }
+        U.ojf[tid] = o;
+    }
+    __syncthreads();
+    derive_screen<DP>(U, k, kp);
+    __syncthreads();
+
+    const int64_t span = r1 - g0;
+    const int ntiles = (int)((span + tile_rows - 1) / tile_rows);
+    double loss = 0.0;
+
+    for (int it = 0; it <= a.n_iter; ++it) {
+        const bool final_pass = (it == a.n_iter);
+        const bool want_dist = final_pass || (a.trace != nullptr);
+        CentroidView L;
+        L.mu64T = U.mu64T;
+        L.wf = U.wf;
+        L.ojf = U.ojf;
+        L.m2 = __uint_as_float(*U.m2bits);
+        L.kp = kp;
+        L.k = k;
+        double part = 0.0;
+
+        for (int tile = 0; tile < ntiles; ++tile) {
+            const int64_t g = g0 + (int64_t)tile * tile_rows + (int64_t)tid * kRowsPerThread;
+            const bool in_range = g < r1;
+            uint32_t rowmask = 0;
+#pragma unroll
+            for (int p = 0; p < 4; ++p)
+                if (g + p >= r0 && g + p < r1) rowmask |= 1u << p;
+
+            float xf[4][DP];
+            float x2[4];
+            load_rows<DP>(a.X, a.ld, d, g, in_range, U.ojf, xf, x2);
+
+            int lab[4];
+            double dist[4] = {0.0, 0.0, 0.0, 0.0};
+            assign_rows<DP>(xf, x2, rowmask, L, force_exact, want_dist, lab, dist);
+
+            uint32_t prevpack = 0;
+            if (it > 0 && in_range) prevpack = *reinterpret_cast<const uint32_t *>(labrow + g);
+            uint32_t newpack = 0;
+            bool changed = false;
+#pragma unroll
+            for (int p = 0; p < 4; ++p) {
+                const int prev = (prevpack >> (8 * p)) & 0xFF;
+                const bool on = (rowmask >> p) & 1u;
+                const int cur = on ? lab[p] : prev;
+                newpack |= (uint32_t)cur << (8 * p);
+                if (on && (it == 0 || cur != prev)) {
+                    changed = true;
+                    for (int j = 0; j < d; ++j) {
+                        const int xi = (int)(xf[p][j] + U.ojf[j]);
+                        atomicAdd(&U.S[cur * DP + j], xi);
+                        if (it > 0) atomicSub(&U.S[prev * DP + j], xi);
+                    }
+                    atomicAdd(&U.n[cur], 1);
+                    if (it > 0) atomicSub(&U.n[prev], 1);
+                }
+                if (on && want_dist) part = part + dist[p];
+            }
+            if (changed) {
+                if (rowmask == 0xFu) {
+                    *reinterpret_cast<uint32_t *>(labrow + g) = newpack;
+                } else {
+#pragma unroll
+                    for (int p = 0; p < 4; ++p)
+                        if ((rowmask >> p) & 1u) labrow[g + p] = (uint8_t)lab[p];
+                }
+            }
+        }
+
+        if (want_dist) {
+            // fixed-order reduction: lanes (butterfly), then waves in order
+            const double ws = wave_sum(part);
+            if (lane == 0) U.red[wave] = ws;
+        }
+        __syncthreads();
+        if (want_dist && tid == 0) {
+            double s = 0.0;
+            for (int w = 0; w < nwaves; ++w) s = s + U.red[w];
+            loss = s;
+            if (a.trace) a.trace[slot * (a.n_iter + 1) + it] = s;
+        }
+
+        if (!final_pass) {
+            // centroid update: mean of the members, an empty cluster keeps its centroid
+            if (tid == 0) *U.m2bits = 0u;
+            for (int e = tid; e < k * d; e += blockDim.x) {
+                const int c = e / d, j = e % d;
+                const int cnt = U.n[c];
+                if (cnt > 0) U.mu64T[(size_t)j * kp + c] = (double)U.S[c * DP + j] / (double)cnt;
+            }
+            __syncthreads();
+            derive_screen<DP>(U, k, kp);
+            __syncthreads();
+        }
+    }
+
+    for (int e = tid; e < k * d; e += blockDim.x) {
+        const int c = e / d, j = e % d;
+        a.centroids[(crow + c) * d + j] = U.mu64T[(size_t)j * kp + c];
+    }
+    for (int c = tid; c < k; c += blockDim.x) a.counts[crow + c] = U.n[c];
+    if (tid == 0) {
+        a.status[slot] = 0;
+        a.inertia[slot] = loss;
+    }
+}
+
+// First kmax distinct rows of each task, in row order: one wave per task walks the rows 64 at a
+// time; a row is taken unless it equals a row taken before it.
+__global__ __launch_bounds__(64) void first_distinct_kernel(const SweepArgs a, int *init_rows, int *ndist)
+{
+    __shared__ uint64_t taken_hash[256];
+    __shared__ int taken_row[256];
+    const int t = blockIdx.x;
+    const int lane = threadIdx.x;
+    const int d = a.d;
+    const int64_t r0 = a.task_off[t], r1 = a.task_off[t + 1];
+    const int kmax = a.kmax;
+    int found = 0;
+    for (int64_t base = r0; base < r1 && found < kmax; base += kWave) {
+        const int64_t r = base + lane;
+        const bool live = r < r1;
+        uint64_t h = fnv_begin(0);
+        if (live)
+            for (int j = 0; j < d; ++j) h = fnv_step(h, a.X[(int64_t)j * a.ld + r]);
+        bool fresh = live;
+        // against rows already taken
+        for (int q = 0; q < found && fresh; ++q) {
+            if (taken_hash[q] != h) continue;
+            bool same = true;
+            const int64_t rq = r0 + taken_row[q];
+            for (int j = 0; j < d && same; ++j)
+                same = a.X[(int64_t)j * a.ld + rq] == a.X[(int64_t)j * a.ld + r];
+            if (same) fresh = false;
+        }
+        // against earlier rows of this batch of 64
+        for (int q = 0; q < kWave; ++q) {
+            const uint64_t hq = __shfl(h, q, kWave);
+            if (q < lane && fresh && hq == h && base + q < r1) {
+                bool same = true;
+                for (int j = 0; j < d && same; ++j)
+                    same = a.X[(int64_t)j * a.ld + base + q] == a.X[(int64_t)j * a.ld + r];
+                if (same) fresh = false;
+            }
+        }
+        const uint64_t m = __ballot(fresh);
+        const int pos = found + __popcll(m & ((1ull << lane) - 1ull));
+        if (fresh && pos < kmax) {
+            taken_hash[pos] = h;
+            taken_row[pos] = (int)(r - r0);
+            init_rows[(int64_t)t * kmax + pos] = (int)(r - r0);
+        }
+        found += __popcll(m);
+        if (found > kmax) found = kmax;
+        __syncthreads();
+    }
+    if (lane == 0) ndist[t] = found;
+}
+
+template <int DP, int MAXNT>
+hipError_t launch_dp(const SweepArgs &a, int nt, hipStream_t s)
+{
+    const size_t lds = resident_lds_bytes(DP, a.kmax);
+    auto kern = resident_sweep_kernel<DP, MAXNT>;
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    if (nt > MAXNT) nt = MAXNT;
+    const unsigned units = (unsigned)a.T * (unsigned)a.n_k;
+    hipLaunchKernelGGL(kern, dim3(units), dim3(nt), lds, s, a);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_first_distinct(const SweepArgs &a, int *init_rows, int *ndist, hipStream_t s)
+{
+    hipLaunchKernelGGL(first_distinct_kernel, dim3(a.T), dim3(64), 0, s, a, init_rows, ndist);
+    return hipGetLastError();
+}
+
+hipError_t launch_resident_sweep(const SweepArgs &a, int nt, hipStream_t s)
+{
+    const int d = a.d;
+    if (d <= 4) return launch_dp<4, 1024>(a, nt, s);
+    if (d <= 8) return launch_dp<8, 1024>(a, nt, s);
+    if (d <= 12) return launch_dp<12, 1024>(a, nt, s);
+    if (d <= 16) return launch_dp<16, 1024>(a, nt, s);
+    if (d <= 20) return launch_dp<20, 1024>(a, nt, s);
+    if (d <= 24) return launch_dp<24, 1024>(a, nt, s);
+    if (d <= 28) return launch_dp<28, 512>(a, nt, s);
+    return launch_dp<32, 512>(a, nt, s);
+}
+
+}  // namespace cham

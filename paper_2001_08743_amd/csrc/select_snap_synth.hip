@@ -1,0 +1,407 @@
+// Knee selection, centroid snap, Sample Synthesis and dedupe kernels
+// (paper Algorithm 1: threshold exit of the sweep, and the replacement loop; Sec. 3.3).
+#include "cham_device.h"
+#include "cham_internal.h"
+
+namespace cham {
+
+namespace {
+
+// ---------------------------------------------------------------------------------------------
+// Knee: one thread per task walks its loss curve (Algorithm 1: previous_loss starts at
+// infinity; the first k with threshold * loss >= previous_loss is returned, else the last k).
+__global__ void select_k_kernel(const double *inertia, const int *status, int T, int n_k,
+                                double threshold, int *chosen)
+{
+    const int t = blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= T) return;
+    const double *L = inertia + (int64_t)t * n_k;
+    const int *st = status + (int64_t)t * n_k;
+    bool have_prev = false;
+    double prev = 0.0;
+    int last = -1, pick = -1;
+    for (int i = 0; i < n_k; ++i) {
+        if (st[i] != 0) continue;
+        if (have_prev && threshold * L[i] >= prev) {
+            pick = i;
+            break;
+        }
+        prev = L[i];
+        have_prev = true;
+        last = i;
+    }
+    chosen[t] = pick >= 0 ? pick : last;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Snap: one workgroup per task.  Labels under the chosen centroids (same two-stage exact
+// assignment as the sweep), then per cluster the member with the smallest exact distance,
+// lowest row on ties: a 64-bit minimum on the distance bits followed by a minimum on the row
+// among the members that attain it.
+template <int DP>
+struct SnapLds {
+    double *mu64T;
+    double *red;
+    float *wf;
+    unsigned long long *best;   // [k] distance bits
+    int *brow;                  // [k]
+    float *ojf;
+    unsigned *m2bits;
+    __device__ SnapLds(unsigned char *base, int kmax)
+    {
+        mu64T = reinterpret_cast<double *>(base);
+        base += sizeof(double) * (size_t)DP * kmax;
+        red = reinterpret_cast<double *>(base);
+        base += sizeof(double) * 16;
+        wf = reinterpret_cast<float *>(base);
+        base += sizeof(float) * (size_t)kmax * (DP + 4);
+        best = reinterpret_cast<unsigned long long *>(base);
+        brow = reinterpret_cast<int *>(base + sizeof(unsigned long long) * (size_t)kmax);
+        base += sizeof(int) * (size_t)kmax * DP;     // same footprint as the sweep's sums (DP >= 4)
+        base += sizeof(int) * (size_t)kmax;
+        ojf = reinterpret_cast<float *>(base);
+        base += sizeof(float) * (size_t)DP;
+        m2bits = reinterpret_cast<unsigned *>(base);
+    }
+};
+
+template <int DP, int MAXNT>
+__global__ __launch_bounds__(MAXNT) void snap_kernel(const SnapArgs a)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    SnapLds<DP> U(smem, a.kmax);
+    const int tid = threadIdx.x;
+    const int t = blockIdx.x;
+    const int d = a.d;
+    const int64_t r0 = a.task_off[t], r1 = a.task_off[t + 1];
+    const int ci = a.chosen[t];
+    const int tile_rows = blockDim.x * kRowsPerThread;
+
+    for (int c = tid; c < a.kmax; c += blockDim.x) a.pick_row[(int64_t)t * a.kmax + c] = -1;
+    for (int e = tid; e < a.kmax * d; e += blockDim.x) a.pick_cfg[(int64_t)t * a.kmax * d + e] = 0;
+    if (ci < 0 || ci >= a.n_k) return;
+    const int k = a.ks[ci];
+    const int kp = k;
+    const int64_t crow = (int64_t)t * a.Ksum + a.koff[ci];
+
+    for (int e = tid; e < DP * kp; e += blockDim.x) U.mu64T[e] = 0.0;
+    for (int c = tid; c < k; c += blockDim.x) {
+        U.best[c] = ~0ull;
+        U.brow[c] = 0x7fffffff;
+    }
+    if (tid == 0) *U.m2bits = 0u;
+    __syncthreads();
+    for (int e = tid; e < k * d; e += blockDim.x) {
+        const int c = e / d, j = e % d;
+        U.mu64T[(size_t)j * kp + c] = a.centroids[(crow + c) * d + j];
+    }
+    __syncthreads();
+    if (tid < DP) {
+        float o = 0.0f;
+        if (tid < d) {
+            double s = 0.0;
+            for (int c = 0; c < k; ++c) s += U.mu64T[(size_t)tid * kp + c];
+            double m = rint(s / (double)k);
+            m = m < 0.0 ? 0.0 : (m > 255.0 ? 255.0 : m);
+            o = (float)m;
+        }
+        U.ojf[tid] = o;
+    }
+    __syncthreads();
+    for (int c = tid; c < k; c += blockDim.x) {
+        double b = 0.0;
+        float *w = U.wf + (size_t)c * (DP + 4);
+#pragma unroll
+        for (int j = 0; j < DP; ++j) {
+            const double m = U.mu64T[(size_t)j * kp + c] - (double)U.ojf[j];
+            b = __builtin_fma(m, m, b);
+            w[j] = (float)(-2.0 * m);
+        }
+        w[DP] = (float)b;
+        w[DP + 1] = w[DP + 2] = w[DP + 3] = 0.0f;
+        atomicMax(U.m2bits, __float_as_uint(__double2float_ru(b) * 1.0000005f));
+    }
+    __syncthreads();
+
+    CentroidView L;
+    L.mu64T = U.mu64T;
+    L.wf = U.wf;
+    L.ojf = U.ojf;
+    L.m2 = __uint_as_float(*U.m2bits);
+    L.kp = kp;
+    L.k = k;
+    const bool force_exact = (a.flags & 1) != 0;
+    const int64_t g0 = r0 & ~(int64_t)3;
+    const int ntiles = (int)((r1 - g0 + tile_rows - 1) / tile_rows);
+
+    for (int tile = 0; tile < ntiles; ++tile) {
+        const int64_t g = g0 + (int64_t)tile * tile_rows + (int64_t)tid * kRowsPerThread;
+        const bool in_range = g < r1;
+        uint32_t rowmask = 0;
+#pragma unroll
+        for (int p = 0; p < 4; ++p)
+            if (g + p >= r0 && g + p < r1) rowmask |= 1u << p;
+        float xf[4][DP];
+        float x2[4];
+        load_rows<DP>(a.X, a.ld, d, g, in_range, U.ojf, xf, x2);
+        int lab[4];
+        double dist[4] = {0.0, 0.0, 0.0, 0.0};
+        assign_rows<DP>(xf, x2, rowmask, L, force_exact, true, lab, dist);
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+            if (!((rowmask >> p) & 1u)) continue;
+            a.labels_sel[g + p] = (uint8_t)lab[p];
+            a.dist_ws[g + p] = dist[p];
+            atomicMin(&U.best[lab[p]], (unsigned long long)__double_as_longlong(dist[p]));
+        }
+    }
+    __syncthreads();
+    for (int64_t r = r0 + tid; r < r1; r += blockDim.x) {
+        const int c = a.labels_sel[r];
+        if ((unsigned long long)__double_as_longlong(a.dist_ws[r]) == U.best[c])
+            atomicMin(&U.brow[c], (int)(r - r0));
+    }
+    __syncthreads();
+    for (int c = tid; c < k; c += blockDim.x) {
+        const int row = U.brow[c];
+        if (row != 0x7fffffff) a.pick_row[(int64_t)t * a.kmax + c] = row;
+    }
+    for (int e = tid; e < k * d; e += blockDim.x) {
+        const int c = e / d, j = e % d;
+        const int row = U.brow[c];
+        if (row != 0x7fffffff)
+            a.pick_cfg[((int64_t)t * a.kmax + c) * d + j] = a.X[(int64_t)j * a.ld + r0 + row];
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ bool visited_has(const uint64_t *v, int64_t n, uint64_t key)
+{
+    int64_t lo = 0, hi = n;
+    while (lo < hi) {
+        const int64_t mid = lo + ((hi - lo) >> 1);
+        if (v[mid] < key) lo = mid + 1; else hi = mid;
+    }
+    return lo < n && v[lo] == key;
+}
+
+// Synthesis: one workgroup per task.
+//  A. flag picks (invalid row, or hash in the visited set); unflagged picks are KEPT.
+//  B. histograms value counts per (flagged cluster, knob) over the cluster's valid members, a
+//     chunk of clusters at a time (as many as fit the LDS histogram), and takes the mode.
+//  C. one wave walks the flagged clusters in ascending order and accepts or drops each mode.
+__global__ __launch_bounds__(1024) void synth_kernel(const SynthArgs a)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int tid = threadIdx.x;
+    const int t = blockIdx.x;
+    const int d = a.d;
+    const int kmax = a.kmax;
+    const int64_t r0 = a.task_off[t], r1 = a.task_off[t + 1];
+    const int ci = a.chosen[t];
+    uint8_t *ocfg = a.out_cfg + (int64_t)t * kmax * d;
+    uint8_t *oflag = a.out_flag + (int64_t)t * kmax;
+
+    // LDS carve
+    unsigned *hist = reinterpret_cast<unsigned *>(smem);                       // [hist_words]
+    unsigned char *p8 = smem + sizeof(unsigned) * (size_t)a.hist_words;
+    int *slot_of = reinterpret_cast<int *>(p8);           p8 += sizeof(int) * (size_t)kmax;      // [kmax]
+    int *flagged = reinterpret_cast<int *>(p8);           p8 += sizeof(int) * (size_t)kmax;      // compact list
+    int *misc = reinterpret_cast<int *>(p8);              p8 += sizeof(int) * 8;
+    uint8_t *cfg = p8;                                    p8 += (size_t)kmax * d;                // [kmax][d] kept / accepted
+    uint8_t *mode = p8;                                   p8 += (size_t)kmax * d;                // [kmax][d] candidate modes
+    uint8_t *fl = p8;                                     p8 += (size_t)kmax;                    // [kmax] flags
+    uint8_t *hasv = p8;                                                                           // [kmax] cluster has a valid member
+
+    for (int c = tid; c < kmax; c += blockDim.x) {
+        fl[c] = 0;          // CHAM_OUT_EMPTY
+        hasv[c] = 0;
+        slot_of[c] = -1;
+    }
+    for (int e = tid; e < kmax * d; e += blockDim.x) cfg[e] = 0;
+    __syncthreads();
+    const int k = (ci >= 0 && ci < a.n_k) ? a.ks[ci] : 0;
+    const uint64_t salt = a.salts[t];
+    const uint16_t *card = a.cards + (int64_t)t * d;
+
+    // A. flag picks
+    for (int c = tid; c < k; c += blockDim.x) {
+        const int row = a.pick_row[(int64_t)t * kmax + c];
+        if (row < 0) continue;
+        const uint8_t *pc = a.pick_cfg + ((int64_t)t * kmax + c) * d;
+        uint64_t h = fnv_begin(salt);
+        for (int j = 0; j < d; ++j) h = fnv_step(h, pc[j]);
+        const bool invalid = a.valid && a.valid[r0 + row] == 0;
+        const bool bad = invalid || visited_has(a.visited, a.n_visited, h);
+        if (bad) {
+            fl[c] = 3;      // CHAM_OUT_DROPPED until a replacement is accepted
+        } else {
+            fl[c] = 1;      // CHAM_OUT_KEPT
+            for (int j = 0; j < d; ++j) cfg[c * d + j] = pc[j];
+        }
+    }
+    __syncthreads();
+    if (tid == 0) {
+        int nf = 0;
+        for (int c = 0; c < k; ++c)
+            if (fl[c] == 3) flagged[nf++] = c;
+        misc[0] = nf;
+    }
+    __syncthreads();
+    const int nf = misc[0];
+
+    // B. modes, a chunk of flagged clusters at a time
+    int cmax = 1;
+    for (int j = 0; j < d; ++j) cmax = card[j] > cmax ? card[j] : cmax;
+    const int per_cluster = d * cmax;
+    const int chunk = a.hist_words / per_cluster;       // >= 1 by construction on the host
+    for (int f0 = 0; f0 < nf; f0 += chunk) {
+        const int fn = (nf - f0) < chunk ? (nf - f0) : chunk;
+        for (int e = tid; e < fn * per_cluster; e += blockDim.x) hist[e] = 0u;
+        for (int q = tid; q < fn; q += blockDim.x) slot_of[flagged[f0 + q]] = q;
+        __syncthreads();
+        for (int64_t r = r0 + tid; r < r1; r += blockDim.x) {
+            const int s = slot_of[a.labels_sel[r]];
+            if (s < 0) continue;
+            if (a.valid && a.valid[r] == 0) continue;
+            unsigned *hrow = hist + (size_t)s * per_cluster;
+            for (int j = 0; j < d; ++j) {
+                const unsigned v = a.X[(int64_t)j * a.ld + r];
+                if (v < (unsigned)cmax) atomicAdd(&hrow[j * cmax + v], 1u);
+            }
+        }
+        __syncthreads();
+        for (int e = tid; e < fn * d; e += blockDim.x) {
+            const int q = e / d, j = e % d;
+            const unsigned *hv = hist + (size_t)q * per_cluster + (size_t)j * cmax;
+            int bv = 0;
+            unsigned bc = hv[0];
+            unsigned total = hv[0];
+            for (int v = 1; v < cmax; ++v) {
+                total += hv[v];
+                if (v < card[j] && hv[v] > bc) {
+                    bc = hv[v];
+                    bv = v;
+                }
+            }
+            const int c = flagged[f0 + q];
+            mode[c * d + j] = (uint8_t)bv;
+            if (j == 0) hasv[c] = total > 0 ? 1 : 0;
+        }
+        __syncthreads();
+        for (int q = tid; q < fn; q += blockDim.x) slot_of[flagged[f0 + q]] = -1;
+        __syncthreads();
+    }
+
+    // C. accept or drop, in ascending cluster order, by the first wave
+    if (tid < kWave) {
+        const int lane = tid;
+        for (int f = 0; f < nf; ++f) {
+            const int c = flagged[f];
+            if (!hasv[c]) continue;
+            const uint8_t *m = mode + c * d;
+            bool dup = false;
+            for (int q = lane; q < k; q += kWave) {
+                const int fq = fl[q];
+                if (fq == 1 || (fq == 2 && q < c)) {
+                    bool same = true;
+                    for (int j = 0; j < d && same; ++j) same = cfg[q * d + j] == m[j];
+                    dup = dup || same;
+                }
+            }
+            uint64_t h = fnv_begin(salt);
+            for (int j = 0; j < d; ++j) h = fnv_step(h, m[j]);
+            const bool vis = visited_has(a.visited, a.n_visited, h);
+            const bool any_dup = __ballot(dup) != 0ull;
+            if (!vis && !any_dup) {
+                if (lane == 0) fl[c] = 2;       // CHAM_OUT_SYNTH
+                for (int j = lane; j < d; j += kWave) cfg[c * d + j] = m[j];
+            }
+            __builtin_amdgcn_wave_barrier();
+            __threadfence_block();
+        }
+    }
+    __syncthreads();
+    for (int e = tid; e < kmax * d; e += blockDim.x) ocfg[e] = cfg[e];
+    for (int c = tid; c < kmax; c += blockDim.x) oflag[c] = fl[c];
+    if (tid == 0) {
+        int cnt = 0;
+        for (int c = 0; c < k; ++c) cnt += (fl[c] == 1 || fl[c] == 2) ? 1 : 0;
+        a.out_count[t] = cnt;
+    }
+}
+
+__global__ void hash_rows_kernel(const uint8_t *rows, int64_t n, int d, const uint64_t *salts,
+                                 uint64_t salt_all, uint64_t *out)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    uint64_t h = fnv_begin(salts ? salts[i] : salt_all);
+    for (int j = 0; j < d; ++j) h = fnv_step(h, rows[i * d + j]);
+    out[i] = h;
+}
+
+template <int DP, int MAXNT>
+hipError_t launch_snap_dp(const SnapArgs &a, int nt, hipStream_t s)
+{
+    const size_t lds = resident_lds_bytes(DP, a.kmax);
+    auto kern = snap_kernel<DP, MAXNT>;
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    if (nt > MAXNT) nt = MAXNT;
+    hipLaunchKernelGGL(kern, dim3(a.T), dim3(nt), lds, s, a);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_select_k(const double *inertia, const int *status, int T, int n_k, double thr,
+                           int *chosen, hipStream_t s)
+{
+    hipLaunchKernelGGL(select_k_kernel, dim3((T + 127) / 128), dim3(128), 0, s, inertia, status, T, n_k,
+                       thr, chosen);
+    return hipGetLastError();
+}
+
+hipError_t launch_snap(const SnapArgs &a, int nt, hipStream_t s)
+{
+    const int d = a.d;
+    if (d <= 4) return launch_snap_dp<4, 1024>(a, nt, s);
+    if (d <= 8) return launch_snap_dp<8, 1024>(a, nt, s);
+    if (d <= 12) return launch_snap_dp<12, 1024>(a, nt, s);
+    if (d <= 16) return launch_snap_dp<16, 1024>(a, nt, s);
+    if (d <= 20) return launch_snap_dp<20, 1024>(a, nt, s);
+    if (d <= 24) return launch_snap_dp<24, 1024>(a, nt, s);
+    if (d <= 28) return launch_snap_dp<28, 512>(a, nt, s);
+    return launch_snap_dp<32, 512>(a, nt, s);
+}
+
+size_t synth_lds_bytes(int d, int kmax, int hist_words)
+{
+    size_t b = sizeof(unsigned) * (size_t)hist_words;
+    b += sizeof(int) * (size_t)kmax * 2 + sizeof(int) * 8;
+    b += (size_t)kmax * d * 2 + (size_t)kmax * 2;
+    return (b + 15) & ~(size_t)15;
+}
+
+hipError_t launch_synth(const SynthArgs &a, int nt, hipStream_t s)
+{
+    const size_t lds = synth_lds_bytes(a.d, a.kmax, a.hist_words);
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(synth_kernel),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(synth_kernel, dim3(a.T), dim3(nt), lds, s, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_hash_rows(const uint8_t *rows, int64_t n, int d, const uint64_t *salts,
+                            uint64_t salt_all, uint64_t *out, hipStream_t s)
+{
+    if (n <= 0) return hipSuccess;
+    hipLaunchKernelGGL(hash_rows_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, rows, n, d,
+                       salts, salt_all, out);
+    return hipGetLastError();
+}
+
+}  // namespace cham

@@ -1,0 +1,69 @@
+"""Element-by-element comparison of the GPU path with the CPU oracle on the same workload."""
+import numpy as np
+
+import oracle
+from paper_2001_08743_amd import binding, workloads
+
+# The benchmark's bar for the loss is 1e-5 relative (fp32 device arithmetic against a double
+# oracle).  This build sums double terms, so only the summation order differs from the oracle's
+# sequential sum: N terms, each pairwise step rounding to 2^-53, gives far below 1e-11.
+INERTIA_RTOL = 1e-11
+
+
+def oracle_visited(wl):
+    return workloads.finalize_visited(oracle.visited_hashes(wl), wl.visited_raw, wl.n_visited)
+
+
+def check_sweep(wl, sw_gpu, sw_cpu, ld, check_labels=True):
+    cent = sw_gpu["centroids"].cpu().numpy()
+    counts = sw_gpu["counts"].cpu().numpy()
+    inertia = sw_gpu["inertia"].cpu().numpy()
+    status = sw_gpu["status"].cpu().numpy()
+    np.testing.assert_array_equal(status, sw_cpu["status"])
+    np.testing.assert_array_equal(counts, sw_cpu["counts"])
+    # centroids are (double)sum / (double)count of identical integers: bit-exact
+    np.testing.assert_array_equal(cent, sw_cpu["centroids"])
+    np.testing.assert_allclose(inertia, sw_cpu["inertia"], rtol=INERTIA_RTOL, atol=0)
+    if check_labels and sw_gpu.get("labels") is not None and sw_cpu.get("labels") is not None:
+        lab = sw_gpu["labels"].cpu().numpy()[:, :wl.n_total]
+        np.testing.assert_array_equal(lab.astype(np.int32), sw_cpu["labels"])
+    if sw_gpu.get("trace") is not None and sw_cpu.get("trace") is not None:
+        np.testing.assert_allclose(sw_gpu["trace"].cpu().numpy(), sw_cpu["trace"], rtol=INERTIA_RTOL, atol=0)
+
+
+def check_pipeline(wl, res_gpu, res_cpu):
+    chosen = res_gpu["chosen"].cpu().numpy()
+    np.testing.assert_array_equal(chosen, res_cpu["chosen_idx"])
+    sn, sy = res_gpu["snap"], res_gpu["synth"]
+    np.testing.assert_array_equal(sn["labels_sel"].cpu().numpy()[:wl.n_total].astype(np.int32), res_cpu["labels_sel"])
+    np.testing.assert_array_equal(sn["pick_row"].cpu().numpy().astype(np.int64), res_cpu["pick_row"])
+    np.testing.assert_array_equal(sn["pick_cfg"].cpu().numpy(), res_cpu["pick_cfg"])
+    np.testing.assert_array_equal(sy["out_flag"].cpu().numpy(), res_cpu["out_flag"])
+    np.testing.assert_array_equal(sy["out_cfg"].cpu().numpy(), res_cpu["out_cfg"])
+    np.testing.assert_array_equal(sy["out_count"].cpu().numpy(), res_cpu["out_count"])
+
+
+def knee_margin(inertia_row, status_row, thr):
+    """Smallest relative distance of any threshold test on the curve from equality."""
+    prev, m = None, np.inf
+    for L, st in zip(inertia_row, status_row):
+        if st != 0:
+            continue
+        if prev is not None and prev > 0:
+            m = min(m, abs(thr * L - prev) / prev)
+        prev = L
+    return m
+
+
+def run_both(wl, threshold=None, flags=0, want_labels=True, want_trace=False):
+    dw = binding.DeviceWorkload(wl)
+    vis_gpu = dw.build_visited()
+    vis_cpu = oracle_visited(wl)
+    # the two hashes are independent implementations: the visited arrays must agree word for word
+    np.testing.assert_array_equal(dw.visited_host, vis_cpu)
+    res_gpu = dw.run(threshold=threshold, flags=flags, want_labels=want_labels, want_trace=want_trace)
+    import torch
+    torch.cuda.synchronize()
+    sw_cpu = oracle.sweep(wl.rows, wl.task_off, wl.ks, wl.n_iter, want_labels=want_labels, want_trace=want_trace)
+    res_cpu = oracle.pipeline(wl, vis_cpu, threshold=threshold, sweep_out=sw_cpu)
+    return dw, res_gpu, res_cpu

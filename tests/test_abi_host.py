@@ -1,0 +1,104 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every symbol the
+public header declares, rejects bad arguments before touching the device, and its host-side
+helpers follow the paper's rules."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2001_08743_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2001_08743_amd import build
+        build.build_lib()
+    return binding.load()
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "cham.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(cham_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = declared_symbols()
+    assert "cham_kmeans_sweep" in names and "cham_synthesize" in names
+    for n in names:
+        assert hasattr(lib, n), n
+    assert sorted(binding.EXPORTS) == names
+
+
+def test_version_and_strerror(lib):
+    assert lib.cham_version() >= 100
+    assert lib.cham_strerror(0) == b"ok"
+    for code in range(-8, 0):
+        assert len(lib.cham_strerror(code)) > 3
+
+
+def test_knee_rule_on_host(lib):
+    # Algorithm 1: previous_loss starts at infinity; stop at the first k with thr*loss >= previous
+    assert binding.cham_select_k_host([100, 30, 20, 19], None, 2.5) == 2
+    assert binding.cham_select_k_host([100, 50], None, 2.0) == 1
+    assert binding.cham_select_k_host([81, 27, 9, 3], None, 2.5) == 3
+    assert binding.cham_select_k_host([5.0], None, 2.5) == 0
+    assert binding.cham_select_k_host([100, 0, 30, 20], [0, 1, 0, 0], 2.5) == 3
+    assert binding.cham_select_k_host([0, 0], [1, 1], 2.5) == -1
+
+
+def test_host_hash_matches_published_fnv1a_vectors(lib, golden_dir):
+    for line in open(os.path.join(golden_dir, "fnv1a64_vectors.txt")):
+        line = line.strip()
+        if not line or line.startswith("#"):
+            continue
+        s, digest = line.split()
+        data = b"" if s == "EMPTY" else s.encode()
+        cfg = np.frombuffer(data, dtype=np.uint8) if data else np.zeros(0, np.uint8)
+        assert binding.cham_hash_config(cfg, 0) == int(digest, 16)
+
+
+def _sweep_rc(lib, X=1024, ld=64, d=4, task_off=(0, 10), ks=(1, 2), n_iter=1, init_mode=0, ws=4096, ws_bytes=1 << 20,
+              flags=0, outs=4096):
+    to = np.asarray(task_off, dtype=np.int64)
+    k = np.asarray(ks, dtype=np.int32)
+    vp = C.c_void_p
+    return lib.cham_kmeans_sweep(vp(X), C.c_int64(ld), C.c_int32(d), to.ctypes.data_as(vp), C.c_int32(len(to) - 1),
+                                 k.ctypes.data_as(vp), C.c_int32(len(k)), C.c_int32(n_iter), C.c_int32(init_mode),
+                                 None, vp(outs), vp(outs), vp(outs), vp(outs), None, None, vp(ws),
+                                 C.c_int64(ws_bytes), C.c_int32(flags), None)
+
+
+def test_argument_errors_are_reported_before_any_device_work(lib):
+    # pointers below are fake non-null addresses: every case must be rejected before they are used
+    assert _sweep_rc(lib, X=0) == -1                       # null X
+    assert _sweep_rc(lib, d=0) == -2
+    assert _sweep_rc(lib, d=33) == -2
+    assert _sweep_rc(lib, ld=62) == -2                     # ld not a multiple of 4
+    assert _sweep_rc(lib, X=1026) == -2                    # misaligned X
+    assert _sweep_rc(lib, ld=8, task_off=(0, 10)) == -2    # rows beyond ld
+    assert _sweep_rc(lib, ks=(2, 2)) == -3                 # not strictly increasing
+    assert _sweep_rc(lib, ks=(0, 2)) == -3
+    assert _sweep_rc(lib, ks=(1, 257)) == -3
+    assert _sweep_rc(lib, task_off=(0, 10, 5)) == -4       # decreasing offsets
+    assert _sweep_rc(lib, task_off=(-4, 10)) == -4
+    assert _sweep_rc(lib, n_iter=-1) == -2
+    assert _sweep_rc(lib, init_mode=1) == -1               # init centroids missing
+    assert _sweep_rc(lib, init_mode=7) == -8
+    assert _sweep_rc(lib, flags=1 << 20) == -8
+    assert _sweep_rc(lib, outs=0) == -1                    # null outputs
+    assert _sweep_rc(lib, ws=0) == -6
+    assert _sweep_rc(lib, ws_bytes=16) == -6
+    assert _sweep_rc(lib, ws=4100) == -6                   # workspace not 256-byte aligned
+
+
+def test_workspace_queries(lib):
+    n = binding.cham_sweep_workspace_bytes(4096, 12, [0, 4096], list(range(2, 65)), 50)
+    assert n >= 63 * 4096 and n % 256 == 0
+    with pytest.raises(binding.ChamError):
+        binding.cham_sweep_workspace_bytes(4095, 12, [0, 4095], [2, 3], 5)
