@@ -1,0 +1,127 @@
+#!/usr/bin/env python3
+"""Benchmark of the Adaptive Sampling hot path on one MI355X.
+
+One step = one pass of the whole path (k-means sweep over every k, knee selection, centroid
+snap, Sample Synthesis + dedupe) over one batch of synthetic tuning tasks that is already
+resident in HBM.  Prints ONE JSON line (see the design doc for how each figure is derived).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+# published MI355X peaks used for the roofline fractions
+PEAK_FP32_VECTOR_TFLOPS = 157.3
+PEAK_HBM_GBS = 8000.0
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--cfg", type=int, default=5, help="workload number 1..5 (default: the full-model sweep)")
+    ap.add_argument("--scale", type=float, default=1.0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-tasks", type=int, default=8, help="tasks of the workload the oracle is timed on")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (--gpus 1); nothing here uses a second GPU.",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2001_08743_amd import binding, workloads
+
+    torch.cuda.set_device(0)
+    wl = workloads.make_config(args.cfg, 0, scale=args.scale)
+    dw = binding.DeviceWorkload(wl, "cuda:0")
+    dw.build_visited()
+
+    # all outputs and workspaces are allocated once, outside the timed region
+    first = dw.run()
+    bufs = dict(sweep={k: first["sweep"][k] for k in ("centroids", "counts", "inertia", "status")},
+                sweep_ws=first["sweep"]["workspace"], chosen=first["chosen"],
+                snap={k: first["snap"][k] for k in ("labels_sel", "pick_row", "pick_cfg")},
+                snap_ws=first["snap"]["workspace"],
+                synth={k: first["synth"][k] for k in ("out_cfg", "out_flag", "out_count")},
+                synth_ws=first["synth"]["workspace"])
+    bufs["sweep"]["labels"] = None
+    bufs["sweep"]["trace"] = None
+    torch.cuda.synchronize()
+
+    def step(ev=None):
+        b = bufs
+        if ev is not None:
+            ev[0].record()
+        sw = binding.cham_kmeans_sweep(dw.X, dw.ld, dw.d, wl.task_off, wl.ks, wl.n_iter,
+                                       out=b["sweep"], workspace=b["sweep_ws"])
+        if ev is not None:
+            ev[1].record()
+        chosen = binding.cham_select_k(sw["inertia"], sw["status"], wl.threshold, chosen=b["chosen"])
+        sn = binding.cham_snap_centroids(dw.X, dw.ld, dw.d, wl.task_off, wl.ks, chosen, sw["centroids"],
+                                         out=b["snap"], workspace=b["snap_ws"])
+        binding.cham_synthesize(dw.X, dw.ld, dw.d, wl.task_off, wl.cards, dw.valid, wl.ks, chosen,
+                                sn["labels_sel"], sn["pick_row"], sn["pick_cfg"], dw.visited,
+                                task_salt=wl.salts, out=b["synth"], workspace=b["synth_ws"])
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    events = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+              for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(events[i])
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    evals = wl.nominal_evals()
+    value = evals / (ms_per_step * 1e-3)
+    sweep_ms = float(np.mean([a.elapsed_time(b) for a, b in events]))
+    # dominant kernel = the sweep kernel; algorithmic work per distance evaluation: d multiply-adds
+    # in the expanded form plus the bias add and the compare = 2d + 2 flops
+    flops_per_eval = 2 * wl.d + 2
+    achieved_tflops = evals * flops_per_eval / (sweep_ms * 1e-3) / 1e12
+    roofline = dict(bound="alu", achieved=round(achieved_tflops, 3), peak=PEAK_FP32_VECTOR_TFLOPS,
+                    unit="TFLOP/s", frac=round(achieved_tflops / PEAK_FP32_VECTOR_TFLOPS, 4),
+                    traffic=None, kernel="resident_sweep_kernel", kernel_ms=round(sweep_ms, 3),
+                    flops_per_eval=flops_per_eval)
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        n_tasks = min(args.cpu_tasks, wl.T)
+        sub = wl.subset(range(n_tasks))
+        vis = workloads.finalize_visited(oracle.visited_hashes(wl), wl.visited_raw, wl.n_visited)
+        c0 = time.perf_counter()
+        oracle.pipeline(sub, vis)
+        c1 = time.perf_counter()
+        cpu = dict(value=round(sub.nominal_evals() / (c1 - c0), 1), unit="evals/s", cores=oracle.num_threads(),
+                   kind="oracle", seconds=round(c1 - c0, 2),
+                   sample=f"tasks 0..{n_tasks - 1} of {wl.T} ({sub.nominal_evals():.3e} of {evals:.3e} evals), "
+                          f"whole path, fp64, OpenMP over (task,k) units")
+
+    line = {
+        "metric": "point-centroid distance evals/sec for full k-sweep",
+        "value": round(value, 1), "unit": "evals/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 3), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{wl.name}: T={wl.T} tasks x N={wl.n_total // wl.T} rows x d={wl.d}, "
+                               f"k={wl.ks[0]}..{wl.ks[-1]} ({len(wl.ks)} values), {wl.n_iter} Lloyd steps + final pass, "
+                               f"visited={wl.n_visited}, threshold={wl.threshold}",
+                   "evals_per_step": evals, "sweep_ms": round(sweep_ms, 3)},
+        "roofline": roofline, "cpu_baseline": cpu,
+    }
+    print(json.dumps(line), flush=True)
+
+
+if __name__ == "__main__":
+    main()
