@@ -135,3 +135,54 @@ def test_hash_rows_matches_host_hash():
     ref = oracle.hash_rows(rows, salts.astype(np.uint64))
     np.testing.assert_array_equal(h, ref)
     assert binding.cham_hash_config(rows[0], int(salts[0])) == int(ref[0])
+
+
+# ------------------------------------------------------------------ full benchmark sizes
+
+def test_cfg3_full_size():
+    _full(workloads.make_config(3, 0))
+
+
+def test_cfg4_full_size():
+    """One clustering of 1,048,576 rows: the oracle runs the whole sweep (OpenMP over rows)."""
+    wl = workloads.make_config(4, 0)
+    _full(wl)
+
+
+def test_cfg5_full_size_sampled_tasks():
+    """The launch the bench times (256 tasks x 64 k values in one call); the oracle recomputes a
+    sample of whole tasks, which are independent of each other."""
+    import torch
+    wl = workloads.make_config(5, 0)
+    dw = binding.DeviceWorkload(wl)
+    dw.build_visited()
+    res = dw.run(want_labels=True)
+    torch.cuda.synchronize()
+    from parity_util import oracle_visited
+    vis = oracle_visited(wl)
+    np.testing.assert_array_equal(dw.visited_host, vis)
+    sample = [0, 101, 255]
+    sub = wl.subset(sample)
+    sw_cpu = oracle.sweep(sub.rows, sub.task_off, sub.ks, sub.n_iter, want_labels=True)
+    ref = oracle.pipeline(sub, vis, sweep_out=sw_cpu)
+    sw = res["sweep"]
+    for i, t in enumerate(sample):
+        r0, r1 = wl.task_off[t], wl.task_off[t + 1]
+        s0, s1 = sub.task_off[i], sub.task_off[i + 1]
+        np.testing.assert_array_equal(sw["counts"][t].cpu().numpy(), ref["counts"][i])
+        np.testing.assert_array_equal(sw["centroids"][t].cpu().numpy(), ref["centroids"][i])
+        np.testing.assert_allclose(sw["inertia"][t].cpu().numpy(), ref["inertia"][i], rtol=1e-11, atol=0)
+        np.testing.assert_array_equal(sw["labels"][:, r0:r1].cpu().numpy().astype(np.int32), ref["labels"][:, s0:s1])
+        assert int(res["chosen"][t]) == int(ref["chosen_idx"][i])
+        np.testing.assert_array_equal(res["snap"]["labels_sel"][r0:r1].cpu().numpy().astype(np.int32), ref["labels_sel"][s0:s1])
+        np.testing.assert_array_equal(res["snap"]["pick_row"][t].cpu().numpy().astype(np.int64), ref["pick_row"][i])
+        np.testing.assert_array_equal(res["synth"]["out_cfg"][t].cpu().numpy(), ref["out_cfg"][i])
+        np.testing.assert_array_equal(res["synth"]["out_flag"][t].cpu().numpy(), ref["out_flag"][i])
+        assert int(res["synth"]["out_count"][t]) == int(ref["out_count"][i])
+    # properties that hold for every task at any size
+    counts = sw["counts"].cpu().numpy()
+    koff = sw["koff"]
+    for ki, k in enumerate(wl.ks):
+        assert (counts[:, koff[ki]:koff[ki] + k].sum(axis=1) == 4096).all()
+    inertia = sw["inertia"].cpu().numpy()
+    assert (inertia >= 0).all()
