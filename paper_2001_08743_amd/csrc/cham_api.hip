@@ -114,7 +114,7 @@ int32_t check_common(const void *X, int64_t ld, int32_t d, const int64_t *task_o
 }
 
 struct SweepWs {
-    int64_t blob = 0, init_rows = 0, ndist = 0, labbuf = 0, total = 0;
+    int64_t blob = 0, init_rows = 0, ndist = 0, xh = 0, labbuf = 0, total = 0;
 };
 
 SweepWs sweep_ws(const Plan &pl, int64_t ld, bool own_labels)
@@ -127,6 +127,8 @@ SweepWs sweep_ws(const Plan &pl, int64_t ld, bool own_labels)
     o += up((int64_t)pl.T * pl.kmax * 4);
     w.ndist = o;
     o += up((int64_t)pl.T * 4);
+    w.xh = o;
+    o += up(ld * 32 * 2);
     w.labbuf = o;
     if (own_labels) o += up((int64_t)pl.n_k * ld);
     w.total = o;
@@ -218,13 +220,16 @@ int32_t cham_kmeans_sweep(const uint8_t *X, int64_t ld, int32_t d, const int64_t
     a.status = status;
     a.labbuf = labels ? labels : ws + w.labbuf;
     a.trace = inertia_trace;
+    a.xh = reinterpret_cast<uint16_t *>(ws + w.xh);
 
     if (init_mode == 0) {
         e = launch_first_distinct(a, reinterpret_cast<int *>(ws + w.init_rows),
                                   reinterpret_cast<int *>(ws + w.ndist), s);
         if (e != hipSuccess) return hip_fail(e);
     }
-    e = launch_resident_sweep(a, pl.nt, s);
+    const bool use_mfma = !(flags & (CHAM_F_NO_MFMA | CHAM_F_FORCE_EXACT)) &&
+                          mfma_path_fits(d, pl.kmax, pl.n_max);
+    e = use_mfma ? launch_mfma_sweep(a, pl.n_max, pl.n_total, s) : launch_resident_sweep(a, pl.nt, s);
     if (e != hipSuccess) return hip_fail(e);
     return CHAM_OK;
 }

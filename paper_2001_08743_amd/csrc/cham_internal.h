@@ -29,6 +29,7 @@ struct SweepArgs {
     int *status;                   // [T][n_k]
     uint8_t *labbuf;               // [n_k][ld] working / final labels
     double *trace;                 // [T][n_k][n_iter+1] or null
+    uint16_t *xh;                  // [ld][16 or 32] f16 row-major copy of X (matrix-core path)
 };
 
 // LDS bytes the resident kernel needs for padded knob count DP and largest k.
@@ -93,6 +94,9 @@ struct SynthArgs {
 
 hipError_t launch_first_distinct(const SweepArgs &a, int *init_rows, int *ndist, hipStream_t s);
 hipError_t launch_resident_sweep(const SweepArgs &a, int nt, hipStream_t s);
+// Matrix-core resident kernel: usable when every task has at most 4096 rows and k <= 64.
+bool mfma_path_fits(int d, int kmax, int64_t n_max);
+hipError_t launch_mfma_sweep(const SweepArgs &a, int64_t n_max, int64_t n_total, hipStream_t s);
 hipError_t launch_select_k(const double *inertia, const int *status, int T, int n_k, double thr,
                            int *chosen, hipStream_t s);
 hipError_t launch_snap(const SnapArgs &a, int nt, hipStream_t s);
