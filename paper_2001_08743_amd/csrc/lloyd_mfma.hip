@@ -1,18 +1,20 @@
 // Matrix-core variant of the resident Lloyd kernel: one workgroup runs the whole iteration of
-// one (task, k) unit (paper Algorithm 1, K-means.run(s_Theta, k); Sec. 3.3), with the
-// -2 x.mu term of the squared distance evaluated by v_mfma_f32_32x32x16_f16.
+// one (task, k) unit (paper Algorithm 1, K-means.run(s_Theta, k); Sec. 3.3), with the squared
+// distance screened by v_mfma_f32_32x32x16_f16.
 //
 // Screen:  score(c, i) = |mu'_c|^2 - 2 x'_i . mu'_c   (x', mu' centred by an integer offset)
 //   A (32 centroids x K) = [ hi(w) | lo(w) ],  w = fl32(-2 mu'),  hi = f16(w), lo = f16(w - hi)
 //   B (K x 32 rows)      = [ x' ; x' ]        (x' is a small integer: exact in f16)
-//   C                    = |mu'_c|^2 broadcast along the rows of a centroid
-// so every product is exact and only the fp32 accumulation and the 22-bit split of w round.
+//   the last knob slot (always unused: d < DK) carries the bias: B = 256, A = hi/lo of |mu'_c|^2 / 256
+// so every product is exact and only the fp32 accumulation and the 22-bit splits round.
 // Each lane then holds the scores of 16 centroids for one row; the epilogue takes the minimum
-// (v_min3), and marks every centroid within the error bound of it (one subtract and one
+// (v_min3) and marks every centroid within the error bound of it (one subtract and one
 // v_alignbit per score).  A row with a single mark is decided; the others are queued per wave
 // and their marked centroids are re-evaluated in double in the oracle's operation order.
-// Rows (as f16 B fragments), previous labels and the row norms stay in registers for all
-// passes; centroids, integer sums and counts stay in LDS.
+// The matrix instructions of the next 32-row tile are issued between the epilogue pieces of the
+// current one.  Rows (as f16 B fragments) and previous labels stay in registers for all passes;
+// centroids, integer sums and counts stay in LDS; a row touches the sums only when its label
+// changes (exact: the sums are integers), through a dense per-wave queue.
 #include "cham_device.h"
 #include "cham_internal.h"
 
@@ -23,107 +25,90 @@ namespace {
 typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef float float16v __attribute__((ext_vector_type(16)));
 
-constexpr int kRecCap = 64;          // flagged rows a wave can queue before it resolves them
-constexpr float kPadBias = 1.0e30f;  // score of a padding centroid row: never the minimum
+#ifdef CHAM_KERNEL_TIMING
+// Development aid (not built into the library): per-section cycle counts summed over waves.
+__device__ unsigned long long g_timing[16];
+#define CHAM_T(var) const unsigned long long var = __builtin_readcyclecounter()
+#define CHAM_TADD(slot, t0, t1) tacc[slot] += (t1) - (t0)
+#define CHAM_TCOUNT(slot, v) tacc[slot] += (unsigned long long)(v)
+#else
+#define CHAM_T(var)
+#define CHAM_TADD(slot, t0, t1)
+#define CHAM_TCOUNT(slot, v)
+#endif
 
-// Error bound of the matrix-core screen relative to (|x'|^2 + 2 max|mu'|^2), in units of 2^-24.
-// Inputs: w = fl32(-2mu') and the bias are rounded once (1 each), hi + lo keeps 22 bits of w (4).
-// Accumulation: each instruction adds 16 exact products to the running value; the hardware aligns
-// the 17 addends to the largest and rounds once, which is modelled very generously as 18 units
-// per instruction.  NS2 = number of chained instructions.
+constexpr int kRecCap = 64;            // queued rows whose knob values are kept in LDS
+constexpr float kBiasScale = 256.0f;   // value of the bias slot in B (exact in f16)
+constexpr float kPadBiasHi = 65504.0f; // A value of the bias slot for padding centroid rows:
+                                       // 256 * 65504 exceeds every real score (<= 4 * 31 * 255^2)
+
+// Error bound of the matrix-core screen, relative to (|x'|^2 + 2 max|mu'|^2), in units of 2^-24:
+// w = fl32(-2mu') and the bias are rounded once (1 each) and hi + lo keeps 22 bits (4);
+// each instruction adds 16 exact products to the running value: the hardware aligns the 17 addends
+// to the largest and rounds once, modelled generously as 18 units per instruction (NS2 chained
+// instructions).  The factor 2.5 = 2 (two scores are compared) x 1.25 headroom.  The absolute
+// term covers f16 underflow of the low parts.
 template <int NS2>
 __device__ __forceinline__ float mfma_bound(float x2, float m2)
 {
     constexpr float kE = 2.5f * (float)(18 * NS2 + 6) * 5.9604644775390625e-8f;
-    return kE * (x2 + 2.0f * m2);
+    return kE * (x2 + 2.0f * m2) + 4.0e-5f;
 }
 
 // LDS carve-up.  DK = padded knob count (16 or 32), KP = padded centroid count (32 or 64).
 template <int DK>
 struct MfmaLds {
-    double *mu64T;      // [DK][KP]
-    double *red;        // [16]
-    half8 *afrag;       // [KP/32][2*DK/16][64]
-    float *bias;        // [KP]
-    int *S;             // [KP][DK]
-    int *n;             // [KP]
-    float *ojf;         // [DK]
-    unsigned *m2bits;   // [1] (+pad)
+    double *mu64T;      // [DK][KP]   exact centroids, transposed
+    double *red;        // [16]       per-wave partial sums of the loss
+    double *bpart;      // [KP][4]    partial sums of |mu - o|^2 per group of 8 knobs
+    half8 *afrag;       // [KP/32][2*DK/16][64]  A fragments: hi parts then lo parts
+    int *S;             // [KP][DK]   integer cluster sums
+    int *n;             // [KP]       cluster sizes
+    int *dirty;         // [KP]       pass in which the cluster last changed
+    float *ojf;         // [DK]       centring offsets
     unsigned char *wave_base;   // per-wave regions follow
-    static constexpr size_t kWaveBytes = ((size_t)kRecCap * DK * 2 + 512 * 8 + 512 * 2 + 512 + 512 * 4 + 15) / 16 * 16;
+    static constexpr size_t kWaveBytes =
+        ((size_t)kRecCap * DK * 2 + 512 * 8 + 512 * 2 + 512 + 512 * 4 + 15) / 16 * 16;
     __host__ __device__ static size_t bytes(int KP, int nwaves)
     {
-        size_t b = sizeof(double) * DK * KP + sizeof(double) * 16;
+        size_t b = sizeof(double) * DK * KP + sizeof(double) * 16 + sizeof(double) * KP * 4;
         b += 16 * (size_t)(KP / 32) * (2 * DK / 16) * 64;
-        b += sizeof(float) * KP + sizeof(int) * (size_t)KP * DK + sizeof(int) * KP + sizeof(float) * DK + 64;
+        b += sizeof(int) * (size_t)KP * DK + sizeof(int) * KP * 2 + sizeof(float) * DK;
         b = (b + 15) & ~(size_t)15;
         return b + kWaveBytes * nwaves;
     }
-    __device__ MfmaLds(unsigned char *p, int KP)
+    __device__ MfmaLds(unsigned char *base, int KP)
     {
-        mu64T = reinterpret_cast<double *>(p);  p += sizeof(double) * DK * KP;
-        red = reinterpret_cast<double *>(p);    p += sizeof(double) * 16;
-        afrag = reinterpret_cast<half8 *>(p);   p += 16 * (size_t)(KP / 32) * (2 * DK / 16) * 64;
-        bias = reinterpret_cast<float *>(p);    p += sizeof(float) * KP;
-        S = reinterpret_cast<int *>(p);         p += sizeof(int) * (size_t)KP * DK;
-        n = reinterpret_cast<int *>(p);         p += sizeof(int) * KP;
-        ojf = reinterpret_cast<float *>(p);     p += sizeof(float) * DK;
-        m2bits = reinterpret_cast<unsigned *>(p);  p += 64;
-        wave_base = reinterpret_cast<unsigned char *>((reinterpret_cast<uintptr_t>(p) + 15) & ~(uintptr_t)15);
+        // plain offset arithmetic from the LDS base keeps every pointer provably in LDS
+        size_t o = 0;
+        mu64T = reinterpret_cast<double *>(base + o);  o += sizeof(double) * DK * KP;
+        red = reinterpret_cast<double *>(base + o);    o += sizeof(double) * 16;
+        bpart = reinterpret_cast<double *>(base + o);  o += sizeof(double) * KP * 4;
+        afrag = reinterpret_cast<half8 *>(base + o);   o += 16 * (size_t)(KP / 32) * (2 * DK / 16) * 64;
+        S = reinterpret_cast<int *>(base + o);         o += sizeof(int) * (size_t)KP * DK;
+        n = reinterpret_cast<int *>(base + o);         o += sizeof(int) * KP;
+        dirty = reinterpret_cast<int *>(base + o);     o += sizeof(int) * KP;
+        ojf = reinterpret_cast<float *>(base + o);     o += sizeof(float) * DK;
+        o = (o + 15) & ~(size_t)15;
+        wave_base = base + o;
     }
 };
-
-// Fragment position of (centroid c, part p in {hi, lo}, knob j): [mt][step][lane] half8, element i.
-template <int DK>
-__device__ __forceinline__ int afrag_index(int c, int part, int j, int &elem)
-{
-    constexpr int NS = DK / 16;
-    const int mt = c >> 5, m = c & 31;
-    const int step = part * NS + (j >> 4);
-    const int h = (j & 15) >> 3;
-    elem = j & 7;
-    return (mt * (2 * NS) + step) * 64 + 32 * h + m;
-}
-
-// From the exact centroids build the A fragments, the bias column and the bound m2.
-template <int DK>
-__device__ __forceinline__ void derive_fragments(const MfmaLds<DK> &U, int k, int KP)
-{
-    for (int c = threadIdx.x; c < k; c += blockDim.x) {
-        double b = 0.0;
-#pragma unroll 4
-        for (int j = 0; j < DK; ++j) {
-            const double m = U.mu64T[(size_t)j * KP + c] - (double)U.ojf[j];
-            b = __builtin_fma(m, m, b);
-            const float w = (float)(-2.0 * m);
-            const _Float16 hi = (_Float16)w;
-            const _Float16 lo = (_Float16)(w - (float)hi);
-            int e;
-            int idx = afrag_index<DK>(c, 0, j, e);
-            reinterpret_cast<_Float16 *>(U.afrag + idx)[e] = hi;
-            idx = afrag_index<DK>(c, 1, j, e);
-            reinterpret_cast<_Float16 *>(U.afrag + idx)[e] = lo;
-        }
-        U.bias[c] = (float)b;
-        atomicMax(U.m2bits, __float_as_uint(__double2float_ru(b) * 1.0000005f));
-    }
-}
 
 __device__ __forceinline__ float min3f(float a, float b, float c)
 {
     return __builtin_fminf(__builtin_fminf(a, b), c);
 }
 
-// centroid index of score q (processing order: m-tile, then accumulator register) in half hh
+// centroid index of score q (processing order: m-tile, then accumulator register) in lane half hh
 __device__ __forceinline__ int centroid_of(int q, int hh)
 {
     return 32 * (q >> 4) + 8 * ((q & 15) >> 2) + 4 * hh + (q & 3);
 }
 
-
-// Per-wave queue of flagged rows.  Every row of the wave can be queued (index + candidate masks
-// of both lane halves); the first kRecCap queued rows also carry their knob values (f16,
-// centred) in LDS, later ones are re-read from the packed row copy in global memory.
+// Per-wave LDS region.  Every row of the wave can be queued (index + candidate masks of both lane
+// halves); the first kRecCap queued rows also carry their knob values (f16, centred), later ones
+// are re-read from the packed row copy in global memory.  The same storage then queues the label
+// changes of the pass.
 template <int DK>
 struct WaveQueue {
     static constexpr int kRows = 512;                       // rows a wave owns at most
@@ -131,7 +116,6 @@ struct WaveQueue {
     static constexpr size_t kOffPid = kOffMask + (size_t)kRows * 8;
     static constexpr size_t kOffLab = kOffPid + (size_t)kRows * 2;
     static constexpr size_t kOffX2 = kOffLab + (size_t)kRows;
-    static constexpr size_t kBytes = (kOffX2 + (size_t)kRows * 4 + 15) / 16 * 16;
     unsigned char *base;
     __device__ explicit WaveQueue(unsigned char *wb) : base(wb) {}
     __device__ _Float16 *rec_x() const { return reinterpret_cast<_Float16 *>(base); }                    // [kRecCap][DK]
@@ -173,16 +157,36 @@ __device__ __forceinline__ void resolve_queue(const WaveQueue<DK> &Q, int nrec, 
                     cc[q] = centroid_of(b, 1);
                 }
             }
-            for (int j = 0; j < d; ++j) {
-                float xf;
-                if (r < kRecCap) xf = (float)Q.rec_x()[(size_t)r * DK + j] + ojf[j];
-                else xf = (float)xh_wave[(size_t)pid * DK + j];
-                const double xv = (double)xf;
-                const double *row = mu64T + (size_t)j * KP;
+            int ci[4];
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const double tq = xv - row[cc[q] < 0 ? 0 : cc[q]];
-                    ss[q] = ss[q] + tq * tq;
+            for (int q = 0; q < 4; ++q) ci[q] = cc[q] < 0 ? 0 : cc[q];
+            // knobs in groups of 8 (padded knobs are zero in x and in the centroids, so they add an
+            // exact zero); the loads of a group are independent and overlap
+            for (int j0 = 0; j0 < d; j0 += 8) {
+                half8 xq;
+                if (r < kRecCap) {
+                    xq = *reinterpret_cast<const half8 *>(Q.rec_x() + (size_t)r * DK + j0);
+                } else {
+                    xq = *reinterpret_cast<const half8 *>(xh_wave + (size_t)pid * DK + j0);
+                }
+                const float4 oa = *reinterpret_cast<const float4 *>(ojf + j0);
+                const float4 ob = *reinterpret_cast<const float4 *>(ojf + j0 + 4);
+                const float of[8] = {oa.x, oa.y, oa.z, oa.w, ob.x, ob.y, ob.z, ob.w};
+                double mu[8][4];
+#pragma unroll
+                for (int i = 0; i < 8; ++i)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) mu[i][q] = mu64T[(size_t)(j0 + i) * KP + ci[q]];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    float xf = r < kRecCap ? (float)xq[i] + of[i] : (float)xq[i];
+                    if (j0 + i >= d) xf = 0.0f;          // padded knobs (one of them carries the bias)
+                    const double xv = (double)xf;
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const double tq = xv - mu[i][q];
+                        ss[q] = ss[q] + tq * tq;
+                    }
                 }
             }
 #pragma unroll
@@ -218,12 +222,101 @@ __global__ void pack_rows_kernel(const uint8_t *__restrict__ X, int64_t ld, int 
     }
 }
 
-template <int DK, int NTW>
-__global__ __launch_bounds__(512) void resident_mfma_kernel(const SweepArgs a)
+// Apply queued label changes of this wave to the integer sums and counts: 128 / DK queued rows
+// per step, one lane per (row, pair of knobs).  Entry word: cur | prev << 8 | first << 16.
+template <int DK>
+__device__ __forceinline__ void apply_changes(const WaveQueue<DK> &Q, int cnt, int *S, int *n, int *dirty,
+                                              const float *ojf, int d, int stamp)
 {
+    constexpr int LPR = DK / 2;              // lanes per row
+    constexpr int EPI = 64 / LPR;            // rows per step
+    const int lane = threadIdx.x & 63;
+    const int j0 = 2 * (lane % LPR);
+    const float o0 = ojf[j0], o1 = ojf[j0 + 1];
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll 2
+    for (int e0 = 0; e0 < cnt; e0 += EPI) {
+        const int e = e0 + lane / LPR;
+        if (e < cnt && j0 < d) {
+            const unsigned w = Q.rec_mask()[e];
+            const uint32_t xw = *reinterpret_cast<const uint32_t *>(Q.rec_x() + (size_t)e * DK + j0);
+            const int cur = w & 0xFF, prev = (w >> 8) & 0xFF;
+            const bool first = (w >> 16) & 1u;
+            _Float16 xa, xb;
+            const unsigned short ua = (unsigned short)(xw & 0xFFFFu), ub = (unsigned short)(xw >> 16);
+            __builtin_memcpy(&xa, &ua, 2);
+            __builtin_memcpy(&xb, &ub, 2);
+            const int x0 = (int)((float)xa + o0);
+            const int x1 = (int)((float)xb + o1);
+            int *sc = S + cur * DK + j0;
+            atomicAdd(sc, x0);
+            if (j0 + 1 < d) atomicAdd(sc + 1, x1);
+            if (!first) {
+                int *sp = S + prev * DK + j0;
+                atomicSub(sp, x0);
+                if (j0 + 1 < d) atomicSub(sp + 1, x1);
+            }
+            if (j0 == 0) {
+                atomicAdd(&n[cur], 1);
+                dirty[cur] = stamp;
+                if (!first) {
+                    atomicSub(&n[prev], 1);
+                    dirty[prev] = stamp;
+                }
+            }
+        }
+    }
+    __builtin_amdgcn_wave_barrier();
+}
+
+// Centroid update for the clusters touched in this pass, all threads: item (c, g) owns knobs
+// 8g..8g+7 of centroid c: mean = (double)S / (double)n, then the f16 hi/lo fragments of
+// w = -2 (mu - o) (one 16-byte store each) and the partial sum of (mu - o)^2.  The last knob
+// slot (the bias slot) is left zero here; each wave fills it in its register copy.
+template <int DK>
+__device__ __forceinline__ void update_centroids(const MfmaLds<DK> &U, int k, int KP, int d, int stamp, bool all)
+{
+    constexpr int NS = DK / 16, NS2 = 2 * NS, G = DK / 8;
+    for (int item = threadIdx.x; item < k * G; item += blockDim.x) {
+        const int c = item / G, g = item % G;
+        if (8 * g >= d) continue;
+        if (!all && U.dirty[c] != stamp) continue;
+        const int cnt = U.n[c];
+        if (!all && cnt == 0) continue;          // an empty cluster keeps its centroid
+        half8 hi8, lo8;
+        double b = 0.0;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int j = 8 * g + i;
+            double mu = U.mu64T[(size_t)j * KP + c];
+            if (!all && j < d) {
+                mu = (double)U.S[c * DK + j] / (double)cnt;
+                U.mu64T[(size_t)j * KP + c] = mu;
+            }
+            const double m = j < d ? mu - (double)U.ojf[j] : 0.0;
+            b = __builtin_fma(m, m, b);
+            const float w = (float)(-2.0 * m);
+            const _Float16 hi = (_Float16)w;
+            hi8[i] = hi;
+            lo8[i] = (_Float16)(w - (float)hi);
+        }
+        const int mt = c >> 5, m32 = c & 31;
+        const int hh = g & 1, fstep = g >> 1;
+        U.afrag[(mt * NS2 + fstep) * 64 + 32 * hh + m32] = hi8;
+        U.afrag[(mt * NS2 + NS + fstep) * 64 + 32 * hh + m32] = lo8;
+        U.bpart[c * 4 + g] = b;
+    }
+}
+
+// Everything one workgroup does for its unit.  Units with more than 32 centroids use two 32-row
+// m-tiles per row tile; otherwise the two accumulators alternate between row tiles.
+template <int DK, int NTW>
+__device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem, int ki, int t, int k)
+{
+    const bool two = k > 32;
     constexpr int NS = DK / 16;          // distinct B fragments per row
     constexpr int NS2 = 2 * NS;          // chained instructions per 32x32 tile
-    extern __shared__ __align__(16) unsigned char smem[];
+    constexpr int CH = 16 / NS2;         // scores handled between two matrix instructions
     const int KP = a.kmax > 32 ? 64 : 32;
     MfmaLds<DK> U(smem, KP);
 
@@ -234,48 +327,34 @@ __global__ __launch_bounds__(512) void resident_mfma_kernel(const SweepArgs a)
     const int n32 = lane & 31;           // row within a 32-row tile
     const int h = lane >> 5;             // which half of the knob slots / centroid rows this lane holds
 
-    const int u = blockIdx.x;
-    const int ki = a.n_k - 1 - u / a.T;
-    const int t = u % a.T;
-    const int k = a.ks[ki];
     const int d = a.d;
     const int64_t r0 = a.task_off[t], r1 = a.task_off[t + 1];
     const int nrows = (int)(r1 - r0);
     const int64_t slot = (int64_t)t * a.n_k + ki;
     const int64_t crow = (int64_t)t * a.Ksum + a.koff[ki];
     uint8_t *labrow = a.labbuf + (int64_t)ki * a.ld;
-    const bool two = k > 32;
 
-    if (a.init_mode == 0 && a.ndist[t] < k) {
-        for (int e = tid; e < k * d; e += blockDim.x) a.centroids[crow * d + e] = 0.0;
-        for (int c = tid; c < k; c += blockDim.x) a.counts[crow + c] = 0;
-        for (int64_t r = r0 + tid; r < r1; r += blockDim.x) labrow[r] = 0;
-        if (tid == 0) {
-            a.status[slot] = 1;
-            a.inertia[slot] = 0.0;
-        }
-        if (a.trace)
-            for (int e = tid; e <= a.n_iter; e += blockDim.x) a.trace[slot * (a.n_iter + 1) + e] = 0.0;
-        return;
-    }
-
-    // per-wave queue of flagged rows
     WaveQueue<DK> Q(U.wave_base + MfmaLds<DK>::kWaveBytes * wave);
+    const int wave_row0 = wave * NTW * 32;                 // first row (task-relative) of this wave
+    const bool wave_live = wave_row0 < nrows;              // the wave owns at least one row
+
+    // the bias slot is the last knob slot of the fragments (knob index DK - 1 >= d)
+    constexpr int bstep = NS - 1, bhalf = 1, belem = 7;
 
     // ---- set-up
     for (int e = tid; e < DK * KP; e += blockDim.x) U.mu64T[e] = 0.0;
     for (int e = tid; e < KP * DK; e += blockDim.x) U.S[e] = 0;
     for (int c = tid; c < KP; c += blockDim.x) {
         U.n[c] = 0;
-        U.bias[c] = kPadBias;
+        U.dirty[c] = -1;
     }
+    for (int e = tid; e < KP * 4; e += blockDim.x) U.bpart[e] = 0.0;
     {
         half8 z;
 #pragma unroll
         for (int i = 0; i < 8; ++i) z[i] = (_Float16)0.0f;
         for (int e = tid; e < (KP / 32) * NS2 * 64; e += blockDim.x) U.afrag[e] = z;
     }
-    if (tid == 0) *U.m2bits = 0u;
     __syncthreads();
     for (int e = tid; e < k * d; e += blockDim.x) {
         const int c = e / d, j = e % d;
@@ -301,64 +380,68 @@ __global__ __launch_bounds__(512) void resident_mfma_kernel(const SweepArgs a)
         U.ojf[tid] = o;
     }
     __syncthreads();
-    derive_fragments<DK>(U, k, KP);
+    update_centroids<DK>(U, k, KP, d, 0, true);
 
     // ---- this lane's rows as B fragments (kept in registers for every pass)
-    const _Float16 *xh_wave = reinterpret_cast<const _Float16 *>(a.xh) + (r0 + (int64_t)wave * NTW * 32) * DK;
+    const _Float16 *xh_wave = reinterpret_cast<const _Float16 *>(a.xh) + (r0 + (wave_live ? wave_row0 : 0)) * DK;
     half8 B[NTW][NS];
     uint32_t prevpack[(NTW + 3) / 4];
 #pragma unroll
     for (int q = 0; q < (NTW + 3) / 4; ++q) prevpack[q] = 0;
-    half8 off8[NS];
-#pragma unroll
-    for (int f = 0; f < NS; ++f)
-#pragma unroll
-        for (int i = 0; i < 8; ++i) off8[f][i] = (_Float16)U.ojf[16 * f + 8 * h + i];
-#pragma unroll
-    for (int nt = 0; nt < NTW; ++nt) {
-        const int pid = (wave * NTW + nt) * 32 + n32;
-        const bool live = pid < nrows;
-        const int64_t prow = live ? (int64_t)(nt * 32 + n32) : 0;       // a valid row of the wave or row 0
-#pragma unroll
-        for (int f = 0; f < NS; ++f) {
-            half8 v = *reinterpret_cast<const half8 *>(xh_wave + prow * DK + 16 * f + 8 * h);
-            if ((wave * NTW) * 32 >= nrows) v = off8[f];                // wave owns no row at all
-            v = v - off8[f];
-#pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                if (!live || 16 * f + 8 * h + i >= d) v[i] = (_Float16)0.0f;
-            }
-            B[nt][f] = v;
-        }
-    }
-#pragma unroll
-    for (int nt = 0; nt < NTW; ++nt) {
-        float part = 0.0f;
+    {
+        half8 off8[NS];
 #pragma unroll
         for (int f = 0; f < NS; ++f)
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                const float v = (float)B[nt][f][i];
-                part = __builtin_fmaf(v, v, part);
+            for (int i = 0; i < 8; ++i) off8[f][i] = (_Float16)U.ojf[16 * f + 8 * h + i];
+#pragma unroll
+        for (int nt = 0; nt < NTW; ++nt) {
+            const bool live = wave_live && (wave_row0 + nt * 32 + n32) < nrows;
+            const int64_t prow = live ? (int64_t)(nt * 32 + n32) : 0;     // always a row of this task
+#pragma unroll
+            for (int f = 0; f < NS; ++f) {
+                half8 v = off8[f];
+                if (nrows > 0) v = *reinterpret_cast<const half8 *>(xh_wave + prow * DK + 16 * f + 8 * h);
+                v = v - off8[f];
+#pragma unroll
+                for (int i = 0; i < 8; ++i)
+                    if (!live || 16 * f + 8 * h + i >= d) v[i] = (_Float16)0.0f;
+                B[nt][f] = v;
             }
-        part = part + __shfl_xor(part, 32, 64);
-        if (h == 0) Q.x2()[nt * 32 + n32] = part;
+        }
+#pragma unroll
+        for (int nt = 0; nt < NTW; ++nt) {
+            float part = 0.0f;
+#pragma unroll
+            for (int f = 0; f < NS; ++f)
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    const float v = (float)B[nt][f][i];
+                    part = __builtin_fmaf(v, v, part);
+                }
+            part = part + __shfl_xor(part, 32, 64);
+            if (h == 0) Q.x2()[nt * 32 + n32] = part;
+            // the bias slot: a constant for every live row (after the norm, which excludes it)
+            const bool live = wave_live && (wave_row0 + nt * 32 + n32) < nrows;
+            if (live && h == bhalf) {
+#pragma unroll
+                for (int f = 0; f < NS; ++f)
+#pragma unroll
+                    for (int i = 0; i < 8; ++i)
+                        if (f == bstep && i == belem) B[nt][f][i] = (_Float16)kBiasScale;
+            }
+        }
     }
     __syncthreads();
 
     double loss = 0.0;
+#ifdef CHAM_KERNEL_TIMING
+    unsigned long long tacc[10] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+#endif
     for (int it = 0; it <= a.n_iter; ++it) {
         const bool final_pass = (it == a.n_iter);
         const bool want_dist = final_pass || (a.trace != nullptr);
-        const float m2 = __uint_as_float(*U.m2bits);
-
-        // A fragments of this pass
-        half8 A0[NS2], A1[NS2];
-#pragma unroll
-        for (int s = 0; s < NS2; ++s) {
-            A0[s] = U.afrag[s * 64 + lane];
-            A1[s] = two ? U.afrag[(NS2 + s) * 64 + lane] : A0[s];
-        }
+        CHAM_T(t_a);
 
         uint32_t newpack[(NTW + 3) / 4];
 #pragma unroll
@@ -366,113 +449,207 @@ __global__ __launch_bounds__(512) void resident_mfma_kernel(const SweepArgs a)
         uint32_t flagged_tiles = 0;
         int nrec = 0;
 
+        if (wave_live) {
+            // A fragments of this pass, the bias slot filled in from the partial sums, and the
+            // bound m2 (every wave for itself)
+            half8 A0[NS2], A1[NS2];
 #pragma unroll
-        for (int nt = 0; nt < NTW; ++nt) {
-            const int tile_first = (wave * NTW + nt) * 32;
-            if (tile_first >= nrows) continue;            // wave-uniform
-            float16v acc0, acc1;
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const float4 b0 = *reinterpret_cast<const float4 *>(U.bias + 8 * g + 4 * h);
-                acc0[4 * g + 0] = b0.x; acc0[4 * g + 1] = b0.y; acc0[4 * g + 2] = b0.z; acc0[4 * g + 3] = b0.w;
+            for (int s = 0; s < NS2; ++s) {
+                A0[s] = U.afrag[s * 64 + lane];
+                A1[s] = two ? U.afrag[(NS2 + s) * 64 + lane] : A0[s];
             }
+            float m2 = 0.0f;
 #pragma unroll
-            for (int s = 0; s < NS2; ++s)
-                acc0 = __builtin_amdgcn_mfma_f32_32x32x16_f16(A0[s], B[nt][s % NS], acc0, 0, 0, 0);
-            float best = min3f(acc0[0], acc0[1], acc0[2]);
-#pragma unroll
-            for (int i = 3; i < 15; i += 2) best = min3f(best, acc0[i], acc0[i + 1]);
-            best = __builtin_fminf(best, acc0[15]);
-            if (two) {
-#pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    const float4 b1 = *reinterpret_cast<const float4 *>(U.bias + 32 + 8 * g + 4 * h);
-                    acc1[4 * g + 0] = b1.x; acc1[4 * g + 1] = b1.y; acc1[4 * g + 2] = b1.z; acc1[4 * g + 3] = b1.w;
+            for (int mt = 0; mt < 2; ++mt) {
+                if (mt == 1 && !two) break;
+                const int c = 32 * mt + n32;
+                _Float16 bhi = (_Float16)kPadBiasHi, blo = (_Float16)0.0f;
+                if (c < k) {
+                    const double b = ((U.bpart[c * 4 + 0] + U.bpart[c * 4 + 1]) + U.bpart[c * 4 + 2]) + U.bpart[c * 4 + 3];
+                    const float bs = (float)b * (1.0f / kBiasScale);
+                    bhi = (_Float16)bs;
+                    blo = (_Float16)(bs - (float)bhi);
+                    m2 = __builtin_fmaxf(m2, __double2float_ru(b) * 1.0000005f);
                 }
+                if (h == bhalf) {
 #pragma unroll
-                for (int s = 0; s < NS2; ++s)
-                    acc1 = __builtin_amdgcn_mfma_f32_32x32x16_f16(A1[s], B[nt][s % NS], acc1, 0, 0, 0);
+                    for (int s = 0; s < NS; ++s)
 #pragma unroll
-                for (int i = 0; i < 16; i += 2) best = min3f(best, acc1[i], acc1[i + 1]);
-            }
-            best = __builtin_fminf(best, __shfl_xor(best, 32, 64));
-            const float thr = best + mfma_bound<NS2>(Q.x2()[nt * 32 + n32], m2);
-
-            // bit (31 - q) of `far` is set when score q is above the threshold
-            uint32_t far = 0;
-#pragma unroll
-            for (int i = 0; i < 16; ++i)
-                far = __builtin_amdgcn_alignbit(far, __float_as_uint(thr - acc0[i]), 31);
-            if (two) {
-#pragma unroll
-                for (int i = 0; i < 16; ++i)
-                    far = __builtin_amdgcn_alignbit(far, __float_as_uint(thr - acc1[i]), 31);
-            } else {
-                far = (far << 16) | 0xFFFFu;
-            }
-            const uint32_t cand = ~far;
-            const uint32_t cand_o = (uint32_t)__shfl_xor((int)cand, 32, 64);
-            const int total = __popc(cand) + __popc(cand_o);
-            const bool live = (tile_first + n32) < nrows;
-            const bool flagged = live && total != 1;
-            const int hh = cand ? h : 1 - h;
-            const int q = __clz((int)(cand ? cand : cand_o));
-            const int lab = centroid_of(q & 31, hh);
-            newpack[nt >> 2] |= (uint32_t)(flagged ? 0 : lab) << (8 * (nt & 3));
-
-            const uint64_t fm = __ballot(flagged) & 0xFFFFFFFFull;
-            if (fm) {
-                flagged_tiles |= flagged ? (1u << nt) : 0u;
-                if (flagged) {
-                    const int rs = nrec + __popcll(fm & ((1ull << n32) - 1ull));
-                    if (rs < kRecCap) {
-#pragma unroll
-                        for (int f = 0; f < NS; ++f)
-                            *reinterpret_cast<half8 *>(Q.rec_x() + (size_t)rs * DK + 16 * f + 8 * h) = B[nt][f];
-                    }
-                    Q.rec_mask()[rs * 2 + h] = cand;
-                    if (h == 0) Q.rec_pid()[rs] = (unsigned short)(nt * 32 + n32);
+                        for (int i = 0; i < 8; ++i)
+                            if (s == bstep && i == belem) {
+                                if (mt == 0) {
+                                    A0[s][i] = bhi;
+                                    A0[NS + s][i] = blo;
+                                } else {
+                                    A1[s][i] = bhi;
+                                    A1[NS + s][i] = blo;
+                                }
+                            }
                 }
-                nrec += __popcll(fm);
             }
-            __builtin_amdgcn_sched_barrier(0);   // keep one tile's accumulators live at a time
-        }
-        if (nrec) resolve_queue<DK>(Q, nrec, U.mu64T, U.ojf, KP, k, d, xh_wave);
+#pragma unroll
+            for (int off = 32; off >= 1; off >>= 1) m2 = __builtin_fmaxf(m2, __shfl_xor(m2, off, 64));
 
-        // label changes -> integer sums and counts (only rows whose label changed touch LDS)
-        double part = 0.0;
+            float16v accA, accB;
+            const float16v zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+
+            // one matrix instruction of the chain of a 32x32 tile
+            auto mma = [&](float16v &acc, const half8 (&Af)[NS2], const half8 (&Bt)[NS], int s) {
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(Af[s], Bt[s % NS], s == 0 ? zero16 : acc, 0, 0, 0);
+            };
+            // mark scores [i0, i0 + CH) of an accumulator: bit set = above the threshold
+            auto mark = [&](uint32_t &far, const float16v &acc, float thr, int i0) {
 #pragma unroll
-        for (int nt = 0; nt < NTW; ++nt) {
-            const int pid = (wave * NTW + nt) * 32 + n32;
-            if (pid >= nrows) continue;
-            int cur = (newpack[nt >> 2] >> (8 * (nt & 3))) & 0xFF;
-            if ((flagged_tiles >> nt) & 1u) cur = Q.lab_res()[nt * 32 + n32];
-            const int prev = (prevpack[nt >> 2] >> (8 * (nt & 3))) & 0xFF;
-            if (it == 0 || cur != prev) {
+                for (int i = 0; i < CH; ++i)
+                    far = __builtin_amdgcn_alignbit(far, __float_as_uint(thr - acc[i0 + i]), 31);
+            };
+            auto min16 = [&](const float16v &acc) {
+                float b = min3f(acc[0], acc[1], acc[2]);
 #pragma unroll
-                for (int f = 0; f < NS; ++f) {
+                for (int i = 3; i < 15; i += 2) b = min3f(b, acc[i], acc[i + 1]);
+                return __builtin_fminf(b, acc[15]);
+            };
+            // decide or queue the rows of tile nt from the candidate mask of this lane half
+            auto decide = [&](uint32_t far, int nt) {
+                const uint32_t cand = ~far;
+                const uint32_t cand_o = (uint32_t)__shfl_xor((int)cand, 32, 64);
+                const int total = __popc(cand) + __popc(cand_o);
+                const bool live = (wave_row0 + nt * 32 + n32) < nrows;
+                const bool flagged = live && total != 1;
+                const int hh = cand ? h : 1 - h;
+                const int q = __clz((int)(cand ? cand : cand_o));
+                const int lab = centroid_of(q & 31, hh);
+                newpack[nt >> 2] |= (uint32_t)(flagged ? 0 : lab) << (8 * (nt & 3));
+                const uint64_t fm = __ballot(flagged) & 0xFFFFFFFFull;
+                if (fm) {
+                    flagged_tiles |= flagged ? (1u << nt) : 0u;
+                    if (flagged) {
+                        const int rs = nrec + __popcll(fm & ((1ull << n32) - 1ull));
+                        if (rs < kRecCap) {
 #pragma unroll
-                    for (int i = 0; i < 8; ++i) {
-                        const int j = 16 * f + 8 * h + i;
-                        if (j < d) {
-                            const int xi = (int)((float)B[nt][f][i] + U.ojf[j]);
-                            atomicAdd(&U.S[cur * DK + j], xi);
-                            if (it > 0) atomicSub(&U.S[prev * DK + j], xi);
+                            for (int f = 0; f < NS; ++f) {
+                                *reinterpret_cast<half8 *>(Q.rec_x() + (size_t)rs * DK + 16 * f + 8 * h) = B[nt][f];
+                            }
                         }
+                        Q.rec_mask()[rs * 2 + h] = cand;
+                        if (h == 0) Q.rec_pid()[rs] = (unsigned short)(nt * 32 + n32);
                     }
+                    nrec += __popcll(fm);
                 }
-                if (h == 0) {
-                    atomicAdd(&U.n[cur], 1);
-                    if (it > 0) atomicSub(&U.n[prev], 1);
+            };
+
+            if (two) {
+                // accA = centroids 0..31, accB = centroids 32..63 of the current tile
+#pragma unroll
+                for (int s = 0; s < NS2; ++s) mma(accA, A0, B[0], s);
+#pragma unroll
+                for (int s = 0; s < NS2; ++s) mma(accB, A1, B[0], s);
+#pragma unroll
+                for (int nt = 0; nt < NTW; ++nt) {
+                    constexpr int kLast = NTW - 1;
+                    const int nx = nt < kLast ? nt + 1 : nt;
+                    float best = __builtin_fminf(min16(accA), min16(accB));
+                    best = __builtin_fminf(best, __shfl_xor(best, 32, 64));
+                    const float thr = best + mfma_bound<NS2>(Q.x2()[nt * 32 + n32], m2);
+                    uint32_t far = 0;
+#pragma unroll
+                    for (int s = 0; s < NS2; ++s) mark(far, accA, thr, s * CH);
+                    // accA is consumed: its next chain runs under the marking of accB
+#pragma unroll
+                    for (int s = 0; s < NS2; ++s) {
+                        __builtin_amdgcn_sched_barrier(0);
+                        if (nt < kLast) mma(accA, A0, B[nx], s);
+                        __builtin_amdgcn_sched_barrier(0);
+                        mark(far, accB, thr, s * CH);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                    if (nt < kLast) {
+#pragma unroll
+                        for (int s = 0; s < NS2; ++s) mma(accB, A1, B[nx], s);
+                    }
+                    decide(far, nt);
+                    __builtin_amdgcn_sched_barrier(0);   // labels of this tile are packed before the next tile
                 }
-                prevpack[nt >> 2] = (prevpack[nt >> 2] & ~(0xFFu << (8 * (nt & 3)))) | ((uint32_t)cur << (8 * (nt & 3)));
+            } else {
+                // one m-tile: the accumulators alternate, the next tile's chain runs under this epilogue
+#pragma unroll
+                for (int s = 0; s < NS2; ++s) mma(accA, A0, B[0], s);
+#pragma unroll
+                for (int nt = 0; nt < NTW; ++nt) {
+                    constexpr int kLast = NTW - 1;
+                    const int nx = nt < kLast ? nt + 1 : nt;
+                    float16v &cur = (nt & 1) ? accB : accA;
+                    float16v &nxt = (nt & 1) ? accA : accB;
+                    float best = min16(cur);
+                    best = __builtin_fminf(best, __shfl_xor(best, 32, 64));
+                    const float thr = best + mfma_bound<NS2>(Q.x2()[nt * 32 + n32], m2);
+                    uint32_t far = 0;
+#pragma unroll
+                    for (int s = 0; s < NS2; ++s) {
+                        __builtin_amdgcn_sched_barrier(0);
+                        if (nt < kLast) mma(nxt, A0, B[nx], s);
+                        __builtin_amdgcn_sched_barrier(0);
+                        mark(far, cur, thr, s * CH);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                    far = (far << 16) | 0xFFFFu;
+                    decide(far, nt);
+                    __builtin_amdgcn_sched_barrier(0);   // labels of this tile are packed before the next tile
+                }
             }
-            if (want_dist && h == 0) labrow[r0 + pid] = (uint8_t)cur;
         }
+        CHAM_T(t_b);
+        CHAM_TCOUNT(8, nrec);
+        if (nrec) resolve_queue<DK>(Q, nrec, U.mu64T, U.ojf, KP, k, d, xh_wave);
+        CHAM_T(t_c);
+
+        // label changes -> queue of (row, previous, new) -> integer sums.  The queue holds kRecCap
+        // rows; if a pass changes more (the first passes do), the tiles are walked again from the
+        // first tile that did not fit.
+        if (wave_live) {
+            int start = 0;
+            while (start < NTW) {
+                int cnt = 0;
+                int next_start = NTW;
+#pragma unroll
+                for (int nt = 0; nt < NTW; ++nt) {
+                    if (nt < start || next_start != NTW) continue;
+                    const int pid = wave_row0 + nt * 32 + n32;
+                    const bool live = pid < nrows;
+                    int cur = (newpack[nt >> 2] >> (8 * (nt & 3))) & 0xFF;
+                    if ((flagged_tiles >> nt) & 1u) cur = Q.lab_res()[nt * 32 + n32];
+                    const int prev = (prevpack[nt >> 2] >> (8 * (nt & 3))) & 0xFF;
+                    const bool changed = live && (it == 0 || cur != prev);
+                    const uint64_t cm = __ballot(changed) & 0xFFFFFFFFull;
+                    if (cm) {
+                        if (cnt + 32 > kRecCap) {
+                            next_start = nt;
+                            continue;
+                        }
+                        if (changed) {
+                            const int rs = cnt + __popcll(cm & ((1ull << n32) - 1ull));
+#pragma unroll
+                            for (int f = 0; f < NS; ++f)
+                                *reinterpret_cast<half8 *>(Q.rec_x() + (size_t)rs * DK + 16 * f + 8 * h) = B[nt][f];
+                            if (h == 0) Q.rec_mask()[rs] = (unsigned)cur | ((unsigned)prev << 8) | (it == 0 ? 0x10000u : 0u);
+                            prevpack[nt >> 2] = (prevpack[nt >> 2] & ~(0xFFu << (8 * (nt & 3)))) | ((uint32_t)cur << (8 * (nt & 3)));
+                        }
+                        cnt += __popcll(cm);
+                    }
+                    if (want_dist && live && h == 0) labrow[r0 + pid] = (uint8_t)cur;
+                }
+                CHAM_TCOUNT(7, cnt);
+                if (cnt) apply_changes<DK>(Q, cnt, U.S, U.n, U.dirty, U.ojf, d, it);
+                start = next_start;
+            }
+        }
+        CHAM_T(t_d);
         __syncthreads();
+        CHAM_T(t_e);
 
         if (want_dist) {
             // exact loss of this pass: every row against its centroid, double, knobs ascending
+            double part = 0.0;
             const int64_t g0 = r0 & ~(int64_t)3;
             for (int64_t g = g0 + (int64_t)tid * 4; g < r1; g += (int64_t)blockDim.x * 4) {
                 const uint32_t lw = *reinterpret_cast<const uint32_t *>(labrow + g);
@@ -503,18 +680,22 @@ __global__ __launch_bounds__(512) void resident_mfma_kernel(const SweepArgs a)
         }
 
         if (!final_pass) {
-            if (tid == 0) *U.m2bits = 0u;
-            for (int e = tid; e < k * d; e += blockDim.x) {
-                const int c = e / d, j = e % d;
-                const int cnt = U.n[c];
-                if (cnt > 0) U.mu64T[(size_t)j * KP + c] = (double)U.S[c * DK + j] / (double)cnt;
-            }
-            __syncthreads();
-            derive_fragments<DK>(U, k, KP);
+            update_centroids<DK>(U, k, KP, d, it, false);
             __syncthreads();
         }
+        CHAM_T(t_f);
+        CHAM_TADD(0, t_a, t_b);   // tiles
+        CHAM_TADD(1, t_b, t_c);   // resolve
+        CHAM_TADD(2, t_c, t_d);   // sums
+        CHAM_TADD(3, t_d, t_e);   // barrier wait
+        CHAM_TADD(4, t_e, t_f);   // loss / update
+        CHAM_TCOUNT(9, 1);
     }
 
+#ifdef CHAM_KERNEL_TIMING
+    if (lane == 0)
+        for (int q = 0; q < 10; ++q) atomicAdd(&g_timing[q], tacc[q]);
+#endif
     for (int e = tid; e < k * d; e += blockDim.x) {
         const int c = e / d, j = e % d;
         a.centroids[(crow + c) * d + j] = U.mu64T[(size_t)j * KP + c];
@@ -524,6 +705,39 @@ __global__ __launch_bounds__(512) void resident_mfma_kernel(const SweepArgs a)
         a.status[slot] = 0;
         a.inertia[slot] = loss;
     }
+}
+
+template <int DK, int NTW>
+__global__ __launch_bounds__(512) void resident_mfma_kernel(const SweepArgs a)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int tid = threadIdx.x;
+
+    // units in descending-k order so that the longest ones start first
+    const int u = blockIdx.x;
+    const int ki = a.n_k - 1 - u / a.T;
+    const int t = u % a.T;
+    const int k = a.ks[ki];
+
+    if (a.init_mode == 0 && a.ndist[t] < k) {
+        // fewer than k distinct rows: the unit is reported as unusable, all outputs zero
+        const int d = a.d;
+        const int64_t r0 = a.task_off[t], r1 = a.task_off[t + 1];
+        const int64_t slot = (int64_t)t * a.n_k + ki;
+        const int64_t crow = (int64_t)t * a.Ksum + a.koff[ki];
+        uint8_t *labrow = a.labbuf + (int64_t)ki * a.ld;
+        for (int e = tid; e < k * d; e += blockDim.x) a.centroids[crow * d + e] = 0.0;
+        for (int c = tid; c < k; c += blockDim.x) a.counts[crow + c] = 0;
+        for (int64_t r = r0 + tid; r < r1; r += blockDim.x) labrow[r] = 0;
+        if (tid == 0) {
+            a.status[slot] = 1;
+            a.inertia[slot] = 0.0;
+        }
+        if (a.trace)
+            for (int e = tid; e <= a.n_iter; e += blockDim.x) a.trace[slot * (a.n_iter + 1) + e] = 0.0;
+        return;
+    }
+    run_unit<DK, NTW>(a, smem, ki, t, k);
 }
 
 template <int DK, int NTW>
@@ -542,9 +756,19 @@ hipError_t launch_mfma_t(const SweepArgs &a, int nwaves, hipStream_t s)
 
 }  // namespace
 
+#ifdef CHAM_KERNEL_TIMING
+extern "C" int cham_dev_timing(unsigned long long *host16, int reset)
+{
+    unsigned long long z[16] = {0};
+    if (reset) return (int)hipMemcpyToSymbol(HIP_SYMBOL(g_timing), z, sizeof(z));
+    return (int)hipMemcpyFromSymbol(host16, HIP_SYMBOL(g_timing), sizeof(z));
+}
+#endif
+
+// One knob slot must stay free for the bias, so d <= 31.
 bool mfma_path_fits(int d, int kmax, int64_t n_max)
 {
-    return d >= 1 && d <= 32 && kmax <= 64 && n_max <= 4096;
+    return d >= 1 && d <= 31 && kmax <= 64 && n_max <= 4096;
 }
 
 hipError_t launch_mfma_sweep(const SweepArgs &a, int64_t n_max, int64_t n_total, hipStream_t s)
@@ -554,7 +778,7 @@ hipError_t launch_mfma_sweep(const SweepArgs &a, int64_t n_max, int64_t n_total,
     if (nwaves < 1) nwaves = 1;
     if (nwaves > 8) nwaves = 8;
     const unsigned pb = (unsigned)((n_total + 255) / 256);
-    if (a.d <= 16) {
+    if (a.d <= 15) {
         if (pb) hipLaunchKernelGGL(pack_rows_kernel<16>, dim3(pb), dim3(256), 0, s, a.X, a.ld, a.d, n_total,
                                    reinterpret_cast<_Float16 *>(a.xh));
         return ntw == 4 ? launch_mfma_t<16, 4>(a, nwaves, s) : launch_mfma_t<16, 16>(a, nwaves, s);
