@@ -99,6 +99,21 @@ __device__ __forceinline__ float min3f(float a, float b, float c)
     return __builtin_fminf(__builtin_fminf(a, b), c);
 }
 
+// Both 32-lane halves of a value: lo = the value held by lanes 0..31, hi = by lanes 32..63
+// (v_permlane32_swap: a VALU exchange, no LDS round trip).
+__device__ __forceinline__ void both_halves(unsigned v, unsigned &lo, unsigned &hi)
+{
+    const auto r = __builtin_amdgcn_permlane32_swap(v, v, false, false);
+    lo = r[0];
+    hi = r[1];
+}
+__device__ __forceinline__ float min_halves(float v)
+{
+    unsigned lo, hi;
+    both_halves(__float_as_uint(v), lo, hi);
+    return __builtin_fminf(__uint_as_float(lo), __uint_as_float(hi));
+}
+
 // centroid index of score q (processing order: m-tile, then accumulator register) in lane half hh
 __device__ __forceinline__ int centroid_of(int q, int hh)
 {
@@ -222,39 +237,38 @@ __global__ void pack_rows_kernel(const uint8_t *__restrict__ X, int64_t ld, int 
     }
 }
 
-// Apply queued label changes of this wave to the integer sums and counts: 128 / DK queued rows
-// per step, one lane per (row, pair of knobs).  Entry word: cur | prev << 8 | first << 16.
+// Apply queued label changes of this wave to the integer sums and counts: 256 / DK queued rows
+// per step, one lane per (row, group of 4 knobs).  Entry word: cur | prev << 8, prev = 0xFF for a
+// row that had no label yet.
 template <int DK>
 __device__ __forceinline__ void apply_changes(const WaveQueue<DK> &Q, int cnt, int *S, int *n, int *dirty,
                                               const float *ojf, int d, int stamp)
 {
-    constexpr int LPR = DK / 2;              // lanes per row
+    constexpr int LPR = DK / 4;              // lanes per row
     constexpr int EPI = 64 / LPR;            // rows per step
     const int lane = threadIdx.x & 63;
-    const int j0 = 2 * (lane % LPR);
-    const float o0 = ojf[j0], o1 = ojf[j0 + 1];
+    const int j0 = 4 * (lane % LPR);
+    const float4 o4 = *reinterpret_cast<const float4 *>(ojf + j0);
+    const float of[4] = {o4.x, o4.y, o4.z, o4.w};
     __builtin_amdgcn_wave_barrier();
 #pragma unroll 2
     for (int e0 = 0; e0 < cnt; e0 += EPI) {
         const int e = e0 + lane / LPR;
         if (e < cnt && j0 < d) {
             const unsigned w = Q.rec_mask()[e];
-            const uint32_t xw = *reinterpret_cast<const uint32_t *>(Q.rec_x() + (size_t)e * DK + j0);
+            typedef _Float16 half4 __attribute__((ext_vector_type(4)));
+            const half4 xq = *reinterpret_cast<const half4 *>(Q.rec_x() + (size_t)e * DK + j0);
             const int cur = w & 0xFF, prev = (w >> 8) & 0xFF;
-            const bool first = (w >> 16) & 1u;
-            _Float16 xa, xb;
-            const unsigned short ua = (unsigned short)(xw & 0xFFFFu), ub = (unsigned short)(xw >> 16);
-            __builtin_memcpy(&xa, &ua, 2);
-            __builtin_memcpy(&xb, &ub, 2);
-            const int x0 = (int)((float)xa + o0);
-            const int x1 = (int)((float)xb + o1);
+            const bool first = prev == 0xFF;
             int *sc = S + cur * DK + j0;
-            atomicAdd(sc, x0);
-            if (j0 + 1 < d) atomicAdd(sc + 1, x1);
-            if (!first) {
-                int *sp = S + prev * DK + j0;
-                atomicSub(sp, x0);
-                if (j0 + 1 < d) atomicSub(sp + 1, x1);
+            int *sp = S + (first ? cur : prev) * DK + j0;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                if (j0 + i < d) {
+                    const int xi = (int)((float)xq[i] + of[i]);
+                    atomicAdd(sc + i, xi);
+                    if (!first) atomicSub(sp + i, xi);
+                }
             }
             if (j0 == 0) {
                 atomicAdd(&n[cur], 1);
@@ -387,7 +401,7 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
     half8 B[NTW][NS];
     uint32_t prevpack[(NTW + 3) / 4];
 #pragma unroll
-    for (int q = 0; q < (NTW + 3) / 4; ++q) prevpack[q] = 0;
+    for (int q = 0; q < (NTW + 3) / 4; ++q) prevpack[q] = 0xFFFFFFFFu;   // 0xFF = row has no label yet
     {
         half8 off8[NS];
 #pragma unroll
@@ -497,29 +511,41 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
             auto mma = [&](float16v &acc, const half8 (&Af)[NS2], const half8 (&Bt)[NS], int s) {
                 acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(Af[s], Bt[s % NS], s == 0 ? zero16 : acc, 0, 0, 0);
             };
-            // mark scores [i0, i0 + CH) of an accumulator: bit set = above the threshold
-            auto mark = [&](uint32_t &far, const float16v &acc, float thr, int i0) {
+            // Scores come in groups of 4 registers = 8 centroid rows (4 per lane half).  Groups that
+            // hold only padding rows (beyond k) are skipped: ng = number of groups in use.
+            // mark scores of groups [g0, g0 + CH/4): bit set = above the threshold (or padding)
+            auto mark = [&](uint32_t &far, const float16v &acc, float thr, int i0, int ng) {
 #pragma unroll
-                for (int i = 0; i < CH; ++i)
-                    far = __builtin_amdgcn_alignbit(far, __float_as_uint(thr - acc[i0 + i]), 31);
+                for (int g = 0; g < CH / 4; ++g) {
+                    const int gi = i0 / 4 + g;
+                    if (gi < ng) {
+#pragma unroll
+                        for (int i = 0; i < 4; ++i)
+                            far = __builtin_amdgcn_alignbit(far, __float_as_uint(thr - acc[4 * gi + i]), 31);
+                    } else {
+                        far = (far << 4) | 0xFu;
+                    }
+                }
             };
-            auto min16 = [&](const float16v &acc) {
-                float b = min3f(acc[0], acc[1], acc[2]);
-#pragma unroll
-                for (int i = 3; i < 15; i += 2) b = min3f(b, acc[i], acc[i + 1]);
-                return __builtin_fminf(b, acc[15]);
+            auto min16 = [&](const float16v &acc, int ng) {
+                float b = __builtin_fminf(min3f(acc[0], acc[1], acc[2]), acc[3]);
+                if (ng > 1) b = min3f(min3f(b, acc[4], acc[5]), acc[6], acc[7]);
+                if (ng > 2) b = min3f(min3f(b, acc[8], acc[9]), acc[10], acc[11]);
+                if (ng > 3) b = min3f(min3f(b, acc[12], acc[13]), acc[14], acc[15]);
+                return b;
             };
             // decide or queue the rows of tile nt from the candidate mask of this lane half
             auto decide = [&](uint32_t far, int nt) {
                 const uint32_t cand = ~far;
-                const uint32_t cand_o = (uint32_t)__shfl_xor((int)cand, 32, 64);
-                const int total = __popc(cand) + __popc(cand_o);
+                uint32_t cand_lo, cand_hi;
+                both_halves(cand, cand_lo, cand_hi);
+                const int total = __popc(cand_lo) + __popc(cand_hi);
                 const bool live = (wave_row0 + nt * 32 + n32) < nrows;
                 const bool flagged = live && total != 1;
-                const int hh = cand ? h : 1 - h;
-                const int q = __clz((int)(cand ? cand : cand_o));
+                const int hh = cand_lo ? 0 : 1;
+                const int q = __clz((int)(cand_lo ? cand_lo : cand_hi));
                 const int lab = centroid_of(q & 31, hh);
-                newpack[nt >> 2] |= (uint32_t)(flagged ? 0 : lab) << (8 * (nt & 3));
+                newpack[nt >> 2] |= (uint32_t)(!live ? 0xFF : (flagged ? 0xFE : lab)) << (8 * (nt & 3));
                 const uint64_t fm = __ballot(flagged) & 0xFFFFFFFFull;
                 if (fm) {
                     flagged_tiles |= flagged ? (1u << nt) : 0u;
@@ -538,6 +564,9 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
                 }
             };
 
+            constexpr int ng0 = 4;                                // score groups evaluated per m-tile (all)
+            constexpr int ng1 = 4;
+            float x2cur = Q.x2()[n32];
             if (two) {
                 // accA = centroids 0..31, accB = centroids 32..63 of the current tile
 #pragma unroll
@@ -548,19 +577,19 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
                 for (int nt = 0; nt < NTW; ++nt) {
                     constexpr int kLast = NTW - 1;
                     const int nx = nt < kLast ? nt + 1 : nt;
-                    float best = __builtin_fminf(min16(accA), min16(accB));
-                    best = __builtin_fminf(best, __shfl_xor(best, 32, 64));
-                    const float thr = best + mfma_bound<NS2>(Q.x2()[nt * 32 + n32], m2);
+                    float best = min_halves(__builtin_fminf(min16(accA, 4), min16(accB, ng1)));
+                    const float thr = best + mfma_bound<NS2>(x2cur, m2);
+                    if (nt < kLast) x2cur = Q.x2()[nx * 32 + n32];
                     uint32_t far = 0;
 #pragma unroll
-                    for (int s = 0; s < NS2; ++s) mark(far, accA, thr, s * CH);
+                    for (int s = 0; s < NS2; ++s) mark(far, accA, thr, s * CH, 4);
                     // accA is consumed: its next chain runs under the marking of accB
 #pragma unroll
                     for (int s = 0; s < NS2; ++s) {
                         __builtin_amdgcn_sched_barrier(0);
                         if (nt < kLast) mma(accA, A0, B[nx], s);
                         __builtin_amdgcn_sched_barrier(0);
-                        mark(far, accB, thr, s * CH);
+                        mark(far, accB, thr, s * CH, ng1);
                     }
                     __builtin_amdgcn_sched_barrier(0);
                     if (nt < kLast) {
@@ -580,16 +609,16 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
                     const int nx = nt < kLast ? nt + 1 : nt;
                     float16v &cur = (nt & 1) ? accB : accA;
                     float16v &nxt = (nt & 1) ? accA : accB;
-                    float best = min16(cur);
-                    best = __builtin_fminf(best, __shfl_xor(best, 32, 64));
-                    const float thr = best + mfma_bound<NS2>(Q.x2()[nt * 32 + n32], m2);
+                    float best = min_halves(min16(cur, ng0));
+                    const float thr = best + mfma_bound<NS2>(x2cur, m2);
+                    if (nt < kLast) x2cur = Q.x2()[nx * 32 + n32];
                     uint32_t far = 0;
 #pragma unroll
                     for (int s = 0; s < NS2; ++s) {
                         __builtin_amdgcn_sched_barrier(0);
                         if (nt < kLast) mma(nxt, A0, B[nx], s);
                         __builtin_amdgcn_sched_barrier(0);
-                        mark(far, cur, thr, s * CH);
+                        mark(far, cur, thr, s * CH, ng0);
                     }
                     __builtin_amdgcn_sched_barrier(0);
                     far = (far << 16) | 0xFFFFu;
@@ -603,23 +632,43 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
         if (nrec) resolve_queue<DK>(Q, nrec, U.mu64T, U.ojf, KP, k, d, xh_wave);
         CHAM_T(t_c);
 
-        // label changes -> queue of (row, previous, new) -> integer sums.  The queue holds kRecCap
-        // rows; if a pass changes more (the first passes do), the tiles are walked again from the
-        // first tile that did not fit.
+        // Labels of the rows that went through the queue replace their placeholders.
+        if (wave_live && __ballot(flagged_tiles != 0u)) {
+#pragma unroll
+            for (int nt = 0; nt < NTW; ++nt) {
+                if ((flagged_tiles >> nt) & 1u) {
+                    const uint32_t lab = Q.lab_res()[nt * 32 + n32];
+                    newpack[nt >> 2] = (newpack[nt >> 2] & ~(0xFFu << (8 * (nt & 3)))) | (lab << (8 * (nt & 3)));
+                }
+            }
+        }
+        if (wave_live && want_dist) {
+#pragma unroll
+            for (int nt = 0; nt < NTW; ++nt) {
+                const int pid = wave_row0 + nt * 32 + n32;
+                if (pid < nrows && h == 0) labrow[r0 + pid] = (uint8_t)((newpack[nt >> 2] >> (8 * (nt & 3))) & 0xFF);
+            }
+        }
+        // Label changes -> queue of (previous, new, knob values) -> integer sums.  A row without a
+        // label yet has previous = 0xFF; rows outside the task keep 0xFF and never change.  The
+        // queue holds kRecCap rows; if a pass changes more (the first passes do), the tiles are
+        // walked again from the first tile that did not fit.
         if (wave_live) {
-            int start = 0;
+            uint32_t diff[(NTW + 3) / 4];
+            uint32_t any = 0;
+#pragma unroll
+            for (int q = 0; q < (NTW + 3) / 4; ++q) {
+                diff[q] = newpack[q] ^ prevpack[q];
+                any |= diff[q];
+            }
+            int start = __ballot(any != 0u) ? 0 : NTW;
             while (start < NTW) {
                 int cnt = 0;
                 int next_start = NTW;
 #pragma unroll
                 for (int nt = 0; nt < NTW; ++nt) {
                     if (nt < start || next_start != NTW) continue;
-                    const int pid = wave_row0 + nt * 32 + n32;
-                    const bool live = pid < nrows;
-                    int cur = (newpack[nt >> 2] >> (8 * (nt & 3))) & 0xFF;
-                    if ((flagged_tiles >> nt) & 1u) cur = Q.lab_res()[nt * 32 + n32];
-                    const int prev = (prevpack[nt >> 2] >> (8 * (nt & 3))) & 0xFF;
-                    const bool changed = live && (it == 0 || cur != prev);
+                    const bool changed = ((diff[nt >> 2] >> (8 * (nt & 3))) & 0xFFu) != 0u;
                     const uint64_t cm = __ballot(changed) & 0xFFFFFFFFull;
                     if (cm) {
                         if (cnt + 32 > kRecCap) {
@@ -631,17 +680,19 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
 #pragma unroll
                             for (int f = 0; f < NS; ++f)
                                 *reinterpret_cast<half8 *>(Q.rec_x() + (size_t)rs * DK + 16 * f + 8 * h) = B[nt][f];
-                            if (h == 0) Q.rec_mask()[rs] = (unsigned)cur | ((unsigned)prev << 8) | (it == 0 ? 0x10000u : 0u);
-                            prevpack[nt >> 2] = (prevpack[nt >> 2] & ~(0xFFu << (8 * (nt & 3)))) | ((uint32_t)cur << (8 * (nt & 3)));
+                            const uint32_t cur = (newpack[nt >> 2] >> (8 * (nt & 3))) & 0xFFu;
+                            const uint32_t prev = (prevpack[nt >> 2] >> (8 * (nt & 3))) & 0xFFu;
+                            if (h == 0) Q.rec_mask()[rs] = cur | (prev << 8);
                         }
                         cnt += __popcll(cm);
                     }
-                    if (want_dist && live && h == 0) labrow[r0 + pid] = (uint8_t)cur;
                 }
                 CHAM_TCOUNT(7, cnt);
                 if (cnt) apply_changes<DK>(Q, cnt, U.S, U.n, U.dirty, U.ojf, d, it);
                 start = next_start;
             }
+#pragma unroll
+            for (int q = 0; q < (NTW + 3) / 4; ++q) prevpack[q] = newpack[q];
         }
         CHAM_T(t_d);
         __syncthreads();
