@@ -17,6 +17,7 @@ if ROOT not in sys.path:
 
 # published MI355X peaks used for the roofline fractions
 PEAK_FP32_VECTOR_TFLOPS = 157.3
+PEAK_F16_MFMA_TFLOPS = 2500.0
 PEAK_HBM_GBS = 8000.0
 
 
@@ -86,14 +87,19 @@ def main():
     evals = wl.nominal_evals()
     value = evals / (ms_per_step * 1e-3)
     sweep_ms = float(np.mean([a.elapsed_time(b) for a, b in events]))
-    # dominant kernel = the sweep kernel; algorithmic work per distance evaluation: d multiply-adds
-    # in the expanded form plus the bias add and the compare = 2d + 2 flops
+    # Dominant kernel = the sweep kernel (resident_mfma_kernel when every task has <= 4096 rows, k <= 64,
+    # d <= 31; resident_sweep_kernel otherwise).  Algorithmic work per distance evaluation: d
+    # multiply-adds of the expanded form plus the bias add and the compare = 2d + 2 flops.  The
+    # contraction runs on the f16 matrix cores, so it is priced against the dense f16 MFMA peak.
     flops_per_eval = 2 * wl.d + 2
     achieved_tflops = evals * flops_per_eval / (sweep_ms * 1e-3) / 1e12
-    roofline = dict(bound="alu", achieved=round(achieved_tflops, 3), peak=PEAK_FP32_VECTOR_TFLOPS,
-                    unit="TFLOP/s", frac=round(achieved_tflops / PEAK_FP32_VECTOR_TFLOPS, 4),
-                    traffic=None, kernel="resident_sweep_kernel", kernel_ms=round(sweep_ms, 3),
-                    flops_per_eval=flops_per_eval)
+    uses_mfma = wl.d <= 31 and max(wl.ks) <= 64 and int(np.diff(wl.task_off).max()) <= 4096
+    peak = PEAK_F16_MFMA_TFLOPS if uses_mfma else PEAK_FP32_VECTOR_TFLOPS
+    roofline = dict(bound="mfma" if uses_mfma else "alu", achieved=round(achieved_tflops, 3), peak=peak,
+                    unit="TFLOP/s", frac=round(achieved_tflops / peak, 4), traffic=None,
+                    kernel="resident_mfma_kernel" if uses_mfma else "resident_sweep_kernel",
+                    kernel_ms=round(sweep_ms, 3), flops_per_eval=flops_per_eval,
+                    frac_of_fp32_vector_peak=round(achieved_tflops / PEAK_FP32_VECTOR_TFLOPS, 4))
 
     cpu = None
     if not args.no_cpu_baseline:

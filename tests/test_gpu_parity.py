@@ -186,3 +186,62 @@ def test_cfg5_full_size_sampled_tasks():
         assert (counts[:, koff[ki]:koff[ki] + k].sum(axis=1) == 4096).all()
     inertia = sw["inertia"].cpu().numpy()
     assert (inertia >= 0).all()
+
+
+# ------------------------------------------------------------------ matrix-core path specifics
+
+@pytest.mark.parametrize("d,k", [(15, 32), (16, 33), (31, 64), (24, 1), (2, 64)])
+def test_matrix_core_path_boundaries(d, k):
+    """Knob counts around the 16/32 fragment widths (one slot is kept for the bias) and centroid
+    counts around the 32-row tile."""
+    wl = workloads.random_task(700 + d + k, n=1500, d=d, n_blobs=max(2, k // 2), ks=(k,), n_iter=7,
+                               n_visited=32, card_hi=24, sigma=1.3)
+    _full(wl, threshold=1.01)
+
+
+@pytest.mark.parametrize("n", [4095, 4096, 4097])
+def test_row_counts_around_the_resident_limit(n):
+    wl = workloads.random_task(40 + n, n=n, d=9, n_blobs=7, ks=(3, 40), n_iter=5, n_visited=16)
+    _full(wl, threshold=1.01)
+
+
+def test_every_row_on_an_exact_tie_overflows_the_queue():
+    """All rows are equidistant from two caller-supplied centroids: every row is inside the error
+    bound, far more than a wave's queue keeps in LDS, and must get the lowest index."""
+    import torch
+    n, d = 4096, 6
+    rows = np.full((n, d), 4, dtype=np.uint8)
+    rows[::7, 0] = 5                      # a few rows off the tie so that later passes differ
+    wl = workloads.random_task(3, n=8, d=d)
+    wl.rows, wl.task_off = rows, np.array([0, n])
+    wl.valid = np.ones(n, np.uint8)
+    wl.cards = np.full((1, d), 16, np.uint16)
+    wl.ks, wl.n_iter = [2, 3], 3
+    init = np.zeros((1, 5, d))
+    init[0, 0] = 2.0
+    init[0, 1] = 6.0                      # k = 2: all rows with value 4 tie exactly
+    init[0, 2] = 2.0
+    init[0, 3] = 6.0
+    init[0, 4] = 6.0                      # k = 3: centroids 1 and 2 coincide as well
+    ref = oracle.sweep(wl.rows, wl.task_off, wl.ks, wl.n_iter, init=init, want_labels=True, want_trace=True)
+    dw = binding.DeviceWorkload(wl)
+    out = binding.cham_kmeans_sweep(dw.X, dw.ld, dw.d, wl.task_off, wl.ks, wl.n_iter,
+                                    init_centroids=torch.from_numpy(init).to(dw.device), want_labels=True,
+                                    want_trace=True)
+    torch.cuda.synchronize()
+    check_sweep(wl, out, ref, dw.ld)
+
+
+def test_matrix_core_and_vector_paths_agree_on_every_task():
+    """The two screens must lead to identical results (both are exact); this covers all tasks of a
+    slice of the full-model workload, beyond what the oracle samples."""
+    import torch
+    wl = workloads.make_config(5, 0, scale=16 / 256)
+    dw = binding.DeviceWorkload(wl)
+    a = binding.cham_kmeans_sweep(dw.X, dw.ld, dw.d, wl.task_off, wl.ks, wl.n_iter, want_labels=True)
+    b = binding.cham_kmeans_sweep(dw.X, dw.ld, dw.d, wl.task_off, wl.ks, wl.n_iter, want_labels=True,
+                                  flags=binding.F_NO_MFMA)
+    torch.cuda.synchronize()
+    for key in ("centroids", "counts", "status", "labels"):
+        assert torch.equal(a[key], b[key]), key
+    np.testing.assert_allclose(a["inertia"].cpu().numpy(), b["inertia"].cpu().numpy(), rtol=1e-12, atol=0)
