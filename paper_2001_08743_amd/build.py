@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libcham.so")
-SOURCES = ["cham_api.hip", "lloyd_resident.hip", "lloyd_mfma.hip", "select_snap_synth.hip"]
+SOURCES = ["cham_api.hip", "lloyd_resident.hip", "lloyd_mfma.hip", "lloyd_stream.hip", "select_snap_synth.hip"]
 
 # -ffp-contract=off: the exact re-evaluation must not fuse multiply and add; fused operations
 # in the screening code are written explicitly.  Packed fp32 instructions are switched off.

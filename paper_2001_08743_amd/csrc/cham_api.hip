@@ -113,11 +113,30 @@ int32_t check_common(const void *X, int64_t ld, int32_t d, const int64_t *task_o
     return CHAM_OK;
 }
 
+constexpr int kStreamRowsPerWg = 4096;
+
+// Which kernel family runs the sweep.
+enum class SweepPath { kMfmaResident, kVectorResident, kStream };
+
+SweepPath choose_path(const Plan &pl, int d, int flags)
+{
+    const bool exact = (flags & CHAM_F_FORCE_EXACT) != 0;
+    const bool no_mfma = (flags & CHAM_F_NO_MFMA) != 0;
+    if (exact || no_mfma || d > 31) return SweepPath::kVectorResident;
+    if (flags & CHAM_F_STREAMING) return SweepPath::kStream;
+    if (mfma_path_fits(d, pl.kmax, pl.n_max)) return SweepPath::kMfmaResident;
+    if (flags & CHAM_F_RESIDENT) return SweepPath::kVectorResident;
+    return SweepPath::kStream;
+}
+
 struct SweepWs {
     int64_t blob = 0, init_rows = 0, ndist = 0, xh = 0, labbuf = 0, total = 0;
+    // streaming path
+    int64_t x2 = 0, ojf = 0, Sg = 0, ng = 0, mu = 0, afrag = 0, m2 = 0, wg_off = 0, loss = 0;
+    int kpm = 0, n_units = 0, total_wgs = 0;
 };
 
-SweepWs sweep_ws(const Plan &pl, int64_t ld, bool own_labels)
+SweepWs sweep_ws(const Plan &pl, int64_t ld, bool own_labels, bool stream, const int64_t *task_off)
 {
     SweepWs w;
     int64_t o = 0;
@@ -131,6 +150,24 @@ SweepWs sweep_ws(const Plan &pl, int64_t ld, bool own_labels)
     o += up(ld * 32 * 2);
     w.labbuf = o;
     if (own_labels) o += up((int64_t)pl.n_k * ld);
+    if (stream) {
+        w.kpm = (pl.kmax + 31) / 32 * 32;
+        w.n_units = pl.T * pl.n_k;
+        int64_t wgs_per_sweep_of_tasks = 0;
+        for (int t = 0; t < pl.T; ++t)
+            wgs_per_sweep_of_tasks += (task_off[t + 1] - task_off[t] + kStreamRowsPerWg - 1) / kStreamRowsPerWg;
+        w.total_wgs = (int)(wgs_per_sweep_of_tasks * pl.n_k);
+        const int64_t u = w.n_units, kpm = w.kpm;
+        w.x2 = o;      o += up(ld * 4);
+        w.ojf = o;     o += up((int64_t)pl.T * 32 * 4);
+        w.Sg = o;      o += up(u * kpm * 32 * 4);
+        w.ng = o;      o += up(u * kpm * 4);
+        w.mu = o;      o += up(u * 32 * kpm * 8);
+        w.afrag = o;   o += up(u * (kpm / 32) * 4 * 64 * 16);
+        w.m2 = o;      o += up(u * 4);
+        w.wg_off = o;  o += up((u + 2) * 4);
+        w.loss = o;    o += up(((int64_t)w.total_wgs + 1) * 8);
+    }
     w.total = o;
     return w;
 }
@@ -167,11 +204,10 @@ int64_t cham_sweep_workspace_bytes(int64_t ld, int32_t d, const int64_t *task_of
                                    const int32_t *ks, int32_t n_k, int32_t n_iter, int32_t flags)
 {
     (void)n_iter;
-    (void)flags;
     Plan pl;
     const int32_t rc = check_common(nullptr, ld, d, task_off, T, ks, n_k, false, pl);
     if (rc != CHAM_OK) return rc;
-    return sweep_ws(pl, ld, true).total;
+    return sweep_ws(pl, ld, true, choose_path(pl, d, flags) == SweepPath::kStream, task_off).total;
 }
 
 int32_t cham_kmeans_sweep(const uint8_t *X, int64_t ld, int32_t d, const int64_t *task_off, int32_t T,
@@ -188,7 +224,8 @@ int32_t cham_kmeans_sweep(const uint8_t *X, int64_t ld, int32_t d, const int64_t
     if (init_mode != 0 && init_mode != 1) return CHAM_E_BAD_FLAG;
     if (init_mode == 1 && !init_centroids) return CHAM_E_NULL;
     if (flags & ~(CHAM_F_FORCE_EXACT | CHAM_F_STREAMING | CHAM_F_RESIDENT | CHAM_F_NO_MFMA)) return CHAM_E_BAD_FLAG;
-    const SweepWs w = sweep_ws(pl, ld, labels == nullptr);
+    const SweepPath path = choose_path(pl, d, flags);
+    const SweepWs w = sweep_ws(pl, ld, labels == nullptr, path == SweepPath::kStream, task_off);
     if (!workspace || workspace_bytes < w.total) return CHAM_E_WORKSPACE;
     if (reinterpret_cast<uintptr_t>(workspace) % kAlign) return CHAM_E_WORKSPACE;
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
@@ -227,9 +264,64 @@ int32_t cham_kmeans_sweep(const uint8_t *X, int64_t ld, int32_t d, const int64_t
                                   reinterpret_cast<int *>(ws + w.ndist), s);
         if (e != hipSuccess) return hip_fail(e);
     }
-    const bool use_mfma = !(flags & (CHAM_F_NO_MFMA | CHAM_F_FORCE_EXACT)) &&
-                          mfma_path_fits(d, pl.kmax, pl.n_max);
-    e = use_mfma ? launch_mfma_sweep(a, pl.n_max, pl.n_total, s) : launch_resident_sweep(a, pl.nt, s);
+    if (path == SweepPath::kStream) {
+        // first workgroup of every unit, in launch order (largest k first)
+        std::vector<uint64_t> wo(((size_t)w.n_units + 2) / 2, 0);
+        int32_t *po = reinterpret_cast<int32_t *>(wo.data());
+        int acc = 0;
+        for (int u = 0; u < w.n_units; ++u) {
+            const int t = u % T;
+            po[u] = acc;
+            acc += (int)((task_off[t + 1] - task_off[t] + kStreamRowsPerWg - 1) / kStreamRowsPerWg);
+        }
+        po[w.n_units] = acc;
+        e = stage_words(wo, reinterpret_cast<uint64_t *>(ws + w.wg_off), s);
+        if (e != hipSuccess) return hip_fail(e);
+        StreamArgs sa;
+        sa.X = X;
+        sa.ld = ld;
+        sa.d = d;
+        sa.T = T;
+        sa.n_k = n_k;
+        sa.Ksum = pl.Ksum;
+        sa.kmax = pl.kmax;
+        sa.kpm = w.kpm;
+        sa.n_iter = n_iter;
+        sa.init_mode = init_mode;
+        sa.n_units = w.n_units;
+        sa.rows_per_wg = kStreamRowsPerWg;
+        sa.it = 0;
+        sa.final_pass = 0;
+        sa.task_off = a.task_off;
+        sa.ks = a.ks;
+        sa.koff = a.koff;
+        sa.init_centroids = init_centroids;
+        sa.init_rows = a.init_rows;
+        sa.ndist = a.ndist;
+        sa.wg_off = reinterpret_cast<const int *>(ws + w.wg_off);
+        sa.centroids = centroids;
+        sa.counts = counts;
+        sa.inertia = inertia;
+        sa.status = status;
+        sa.labbuf = a.labbuf;
+        sa.trace = inertia_trace;
+        sa.xh = a.xh;
+        sa.x2 = reinterpret_cast<float *>(ws + w.x2);
+        sa.ojf = reinterpret_cast<float *>(ws + w.ojf);
+        sa.Sg = reinterpret_cast<int *>(ws + w.Sg);
+        sa.ng = reinterpret_cast<int *>(ws + w.ng);
+        sa.mu = reinterpret_cast<double *>(ws + w.mu);
+        sa.afrag = ws + w.afrag;
+        sa.m2 = reinterpret_cast<float *>(ws + w.m2);
+        sa.loss_part = reinterpret_cast<double *>(ws + w.loss);
+        if (stream_lds_bytes(d, w.kpm) > 160 * 1024) return CHAM_E_BAD_K;
+        e = w.total_wgs > 0 ? launch_stream_sweep(sa, pl.n_total, w.total_wgs, s) : hipSuccess;
+        if (w.total_wgs == 0) e = launch_resident_sweep(a, pl.nt, s);   // all tasks empty: trivial path
+    } else if (path == SweepPath::kMfmaResident) {
+        e = launch_mfma_sweep(a, pl.n_max, pl.n_total, s);
+    } else {
+        e = launch_resident_sweep(a, pl.nt, s);
+    }
     if (e != hipSuccess) return hip_fail(e);
     return CHAM_OK;
 }

@@ -46,6 +46,46 @@ inline size_t resident_lds_bytes(int DP, int kmax)
     return b;
 }
 
+// Arguments of the streaming sweep kernels (tasks too large for one workgroup).
+struct StreamArgs {
+    const uint8_t *X;
+    int64_t ld;
+    int d;
+    int T;
+    int n_k;
+    int Ksum;
+    int kmax;
+    int kpm;                       // kmax rounded up to a multiple of 32
+    int n_iter;
+    int init_mode;
+    int n_units;                   // T * n_k, unit u = (ki = n_k - 1 - u / T, t = u % T)
+    int rows_per_wg;
+    int it;                        // pass being run
+    int final_pass;
+    const int64_t *task_off;
+    const int *ks;
+    const int *koff;
+    const double *init_centroids;
+    const int *init_rows;
+    const int *ndist;
+    const int *wg_off;             // [n_units + 1] first workgroup of every unit
+    double *centroids;
+    int *counts;
+    double *inertia;
+    int *status;
+    uint8_t *labbuf;
+    double *trace;
+    uint16_t *xh;                  // [ld][16 or 32] centred f16 rows, last slot = bias constant
+    float *x2;                     // [ld] squared norm of the centred rows
+    float *ojf;                    // [T][32] centring offsets
+    int *Sg;                       // [n_units][kpm][32] integer sums
+    int *ng;                       // [n_units][kpm] counts
+    double *mu;                    // [n_units][32][kpm] exact centroids, transposed
+    void *afrag;                   // [n_units][kpm/32][4][64] 16-byte A fragments
+    float *m2;                     // [n_units] bound on max |mu'|^2; negative = unit unusable
+    double *loss_part;             // [total workgroups] loss partials of the last pass
+};
+
 // Arguments of the snap kernel.
 struct SnapArgs {
     const uint8_t *X;
@@ -97,6 +137,8 @@ hipError_t launch_resident_sweep(const SweepArgs &a, int nt, hipStream_t s);
 // Matrix-core resident kernel: usable when every task has at most 4096 rows and k <= 64.
 bool mfma_path_fits(int d, int kmax, int64_t n_max);
 hipError_t launch_mfma_sweep(const SweepArgs &a, int64_t n_max, int64_t n_total, hipStream_t s);
+int64_t stream_lds_bytes(int d, int kpm);
+hipError_t launch_stream_sweep(const StreamArgs &a, int64_t n_total, int total_wgs, hipStream_t s);
 hipError_t launch_select_k(const double *inertia, const int *status, int T, int n_k, double thr,
                            int *chosen, hipStream_t s);
 hipError_t launch_snap(const SnapArgs &a, int nt, hipStream_t s);

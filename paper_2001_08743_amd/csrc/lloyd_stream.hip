@@ -1,0 +1,604 @@
+// Streaming variant of the sweep for tasks too large to stay on one compute unit
+// (paper Algorithm 1, K-means.run(s_Theta, k); Sec. 3.3): every Lloyd pass is one launch of
+// stream_assign_kernel over (unit, row chunk) workgroups followed by one launch of
+// stream_update_kernel over units.  Labels, integer sums and counts live in global memory and are
+// updated incrementally (a row touches the sums only when its label changes: exact, integers).
+//
+// The screen is the same f16 hi/lo matrix-core screen as in the resident kernel, for up to 256
+// centroids: centroids are taken in chunks of 64 (two 32-row m-tiles); a first sweep over the
+// chunks finds the minimum score of every row, a second one counts the scores within the error
+// bound of it.  A row with exactly one such score is decided; any other row is re-evaluated by
+// the whole wave in double against all k centroids (one centroid per lane, knobs ascending, no
+// fused multiply-add, lowest index on ties).
+#include "cham_device.h"
+#include "cham_internal.h"
+#include "mfma_common.h"
+
+namespace cham {
+
+namespace {
+
+constexpr int kTiles = 4;            // 32-row tiles a wave handles per step
+constexpr int kStreamRec = 32;       // queued rows whose knob values are kept in LDS
+constexpr int kWavesPerWg = 8;
+
+// Per-unit state in global memory.  KPM = kmax rounded up to 32.
+struct UnitState {
+    int *S;            // [KPM][32]      integer sums
+    int *n;            // [KPM]          counts
+    double *mu;        // [32][KPM]      exact centroids, transposed
+    half8 *afrag;      // [KPM/32][4][64] A fragments (hi steps then lo steps; NS2 <= 4)
+};
+
+__device__ __forceinline__ UnitState unit_state(const StreamArgs &a, int u)
+{
+    UnitState s;
+    const size_t kpm = (size_t)a.kpm;
+    s.S = a.Sg + (size_t)u * kpm * 32;
+    s.n = a.ng + (size_t)u * kpm;
+    s.mu = a.mu + (size_t)u * 32 * kpm;
+    s.afrag = reinterpret_cast<half8 *>(a.afrag) + (size_t)u * (kpm / 32) * 4 * 64;
+    return s;
+}
+
+// Centring offsets per task: rounded mean of the starting centroids of the largest k.
+__global__ void stream_offsets_kernel(const StreamArgs a)
+{
+    const int t = blockIdx.x;
+    const int j = threadIdx.x;
+    if (j >= 32) return;
+    float o = 0.0f;
+    if (j < a.d) {
+        double s = 0.0;
+        int cnt = 0;
+        if (a.init_mode == 0) {
+            cnt = a.ndist[t] < a.kmax ? a.ndist[t] : a.kmax;
+            const int64_t r0 = a.task_off[t];
+            for (int c = 0; c < cnt; ++c) s += (double)a.X[(int64_t)j * a.ld + r0 + a.init_rows[(int64_t)t * a.kmax + c]];
+        } else {
+            cnt = a.kmax;
+            const int64_t crow = (int64_t)t * a.Ksum + a.koff[a.n_k - 1];
+            for (int c = 0; c < cnt; ++c) s += a.init_centroids[(crow + c) * a.d + j];
+        }
+        double m = cnt > 0 ? rint(s / (double)cnt) : 0.0;
+        m = m < 0.0 ? 0.0 : (m > 255.0 ? 255.0 : m);
+        o = (float)m;
+    }
+    a.ojf[t * 32 + j] = o;
+}
+
+// Centred f16 copy of the rows (row-major, DK halfs per row, last slot = the bias constant) and
+// the squared norm of every centred row.
+template <int DK>
+__global__ void stream_pack_kernel(const StreamArgs a, int64_t n_rows)
+{
+    const int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (r >= n_rows) return;
+    int lo = 0, hi = a.T;                      // task of row r: last t with task_off[t] <= r
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (a.task_off[mid] <= r) lo = mid; else hi = mid;
+    }
+    const float *o = a.ojf + lo * 32;
+    float x2 = 0.0f;
+    _Float16 *dst = reinterpret_cast<_Float16 *>(a.xh) + r * DK;
+#pragma unroll
+    for (int g = 0; g < DK / 8; ++g) {
+        half8 v;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int j = 8 * g + i;
+            float f = 0.0f;
+            if (j < a.d) f = (float)a.X[(int64_t)j * a.ld + r] - o[j];
+            x2 = __builtin_fmaf(f, f, x2);
+            v[i] = (_Float16)f;
+        }
+        if (g == DK / 8 - 1) v[7] = (_Float16)kBiasScale;
+        *reinterpret_cast<half8 *>(dst + 8 * g) = v;
+    }
+    a.x2[r] = x2;
+}
+
+// mode 0: start of the sweep (centroids from the first distinct rows or from the caller);
+// mode 1: centroid update after pass a.it; mode 2: outputs after the final pass.
+template <int DK>
+__global__ __launch_bounds__(256) void stream_update_kernel(const StreamArgs a, int mode)
+{
+    constexpr int NS = DK / 16, G = DK / 8;
+    __shared__ float red[256];
+    const int u = blockIdx.x;
+    const int ki = a.n_k - 1 - u / a.T;
+    const int t = u % a.T;
+    const int k = a.ks[ki];
+    const int d = a.d;
+    const int tid = threadIdx.x;
+    const int64_t slot = (int64_t)t * a.n_k + ki;
+    const int64_t crow = (int64_t)t * a.Ksum + a.koff[ki];
+    const int64_t r0 = a.task_off[t], r1 = a.task_off[t + 1];
+    const UnitState st = unit_state(a, u);
+    const int kpm = a.kpm;
+    const bool unusable = a.init_mode == 0 && a.ndist[t] < k;
+
+    if (unusable) {
+        if (mode == 0 && tid == 0) a.m2[u] = -1.0f;
+        if (mode == 2) {
+            for (int e = tid; e < k * d; e += blockDim.x) a.centroids[crow * d + e] = 0.0;
+            for (int c = tid; c < k; c += blockDim.x) a.counts[crow + c] = 0;
+            uint8_t *labrow = a.labbuf + (int64_t)ki * a.ld;
+            for (int64_t r = r0 + tid; r < r1; r += blockDim.x) labrow[r] = 0;
+            if (tid == 0) {
+                a.status[slot] = 1;
+                a.inertia[slot] = 0.0;
+            }
+            if (a.trace)
+                for (int e = tid; e <= a.n_iter; e += blockDim.x) a.trace[slot * (a.n_iter + 1) + e] = 0.0;
+        }
+        return;
+    }
+
+    // loss of the pass that just ran: workgroup partials in workgroup order
+    if (mode != 0 && tid == 0 && (mode == 2 || a.trace)) {
+        const int nwg = a.wg_off[u + 1] - a.wg_off[u];
+        double s = 0.0;
+        for (int w = 0; w < nwg; ++w) s = s + a.loss_part[(size_t)a.wg_off[u] + w];
+        if (a.trace) a.trace[slot * (a.n_iter + 1) + a.it] = s;
+        if (mode == 2) {
+            a.inertia[slot] = s;
+            a.status[slot] = 0;
+        }
+    }
+    if (mode == 2) {
+        for (int e = tid; e < k * d; e += blockDim.x) {
+            const int c = e / d, j = e % d;
+            a.centroids[(crow + c) * d + j] = st.mu[(size_t)j * kpm + c];
+        }
+        for (int c = tid; c < k; c += blockDim.x) a.counts[crow + c] = st.n[c];
+        return;
+    }
+
+    const float *o = a.ojf + t * 32;
+    float bmax = 0.0f;
+    const int kpu = (k + 31) & ~31;
+    for (int c = tid; c < kpu; c += blockDim.x) {
+        const int mt = c >> 5, m32 = c & 31;
+        if (mode == 0) {
+            st.n[c] = 0;
+            for (int j = 0; j < 32; ++j) st.S[c * 32 + j] = 0;
+        }
+        const int cnt = (mode == 1 && c < k) ? st.n[c] : 0;
+        double b = 0.0;
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            half8 hi8, lo8;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int j = 8 * g + i;
+                double m = 0.0;
+                if (c < k && j < d) {
+                    double mu;
+                    if (mode == 0) {
+                        if (a.init_mode == 0) mu = (double)a.X[(int64_t)j * a.ld + r0 + a.init_rows[(int64_t)t * a.kmax + c]];
+                        else mu = a.init_centroids[(crow + c) * d + j];
+                        st.mu[(size_t)j * kpm + c] = mu;
+                    } else if (cnt > 0) {
+                        mu = (double)st.S[c * 32 + j] / (double)cnt;      // an empty cluster keeps its centroid
+                        st.mu[(size_t)j * kpm + c] = mu;
+                    } else {
+                        mu = st.mu[(size_t)j * kpm + c];
+                    }
+                    m = mu - (double)o[j];
+                } else if (mode == 0 && c < k) {
+                    st.mu[(size_t)j * kpm + c] = 0.0;
+                }
+                b = __builtin_fma(m, m, b);
+                const float w = (float)(-2.0 * m);
+                const _Float16 hi = (_Float16)w;
+                hi8[i] = hi;
+                lo8[i] = (_Float16)(w - (float)hi);
+            }
+            if (g == G - 1) {
+                // bias slot: |mu'|^2 / 256 as hi + lo; padding centroid rows get a score above all others
+                if (c < k) {
+                    const float bs = (float)b * (1.0f / kBiasScale);
+                    const _Float16 bh = (_Float16)bs;
+                    hi8[7] = bh;
+                    lo8[7] = (_Float16)(bs - (float)bh);
+                } else {
+                    hi8[7] = (_Float16)kPadBiasHi;
+                    lo8[7] = (_Float16)0.0f;
+                }
+            }
+            const int hh = g & 1, fstep = g >> 1;
+            st.afrag[(mt * 4 + fstep) * 64 + 32 * hh + m32] = hi8;
+            st.afrag[(mt * 4 + NS + fstep) * 64 + 32 * hh + m32] = lo8;
+        }
+        if (c < k) bmax = __builtin_fmaxf(bmax, __double2float_ru(b) * 1.0000005f);
+    }
+    red[tid] = bmax;
+    __syncthreads();
+    if (tid == 0) {
+        float m = 0.0f;
+        for (int i = 0; i < (int)blockDim.x; ++i) m = __builtin_fmaxf(m, red[i]);
+        a.m2[u] = m;
+    }
+}
+
+template <int DK>
+struct StreamLds {
+    half8 *afrag;        // [KPM/32][4][64]
+    int *S;              // [KPM][DK] changes of the sums made by this workgroup
+    int *n;              // [KPM]
+    float *ojf;          // [DK]
+    double *red;         // [8]
+    unsigned char *wave_base;
+    // per wave: knob values of queued rows, their row slots, resolved labels, labels of the step
+    static constexpr size_t kWaveBytes = (size_t)kStreamRec * DK * 2 + 128 * 2 + 128 + 128 + 128 * 4;
+    __host__ __device__ static size_t bytes(int kpm)
+    {
+        size_t b = 16 * (size_t)(kpm / 32) * 4 * 64 + sizeof(int) * (size_t)kpm * DK + sizeof(int) * kpm +
+                   sizeof(float) * DK + sizeof(double) * 8;
+        b = (b + 15) & ~(size_t)15;
+        return b + ((kWaveBytes + 15) & ~(size_t)15) * kWavesPerWg;
+    }
+    __device__ StreamLds(unsigned char *base, int kpm)
+    {
+        size_t o = 0;
+        afrag = reinterpret_cast<half8 *>(base + o);  o += 16 * (size_t)(kpm / 32) * 4 * 64;
+        red = reinterpret_cast<double *>(base + o);   o += sizeof(double) * 8;
+        S = reinterpret_cast<int *>(base + o);        o += sizeof(int) * (size_t)kpm * DK;
+        n = reinterpret_cast<int *>(base + o);        o += sizeof(int) * kpm;
+        ojf = reinterpret_cast<float *>(base + o);    o += sizeof(float) * DK;
+        o = (o + 15) & ~(size_t)15;
+        wave_base = base + o;
+    }
+};
+
+template <int DK>
+__global__ __launch_bounds__(512) void stream_assign_kernel(const StreamArgs a)
+{
+    constexpr int NS = DK / 16, NS2 = 2 * NS;
+    extern __shared__ __align__(16) unsigned char smem[];
+    __shared__ int unit_sh;
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int n32 = lane & 31;
+    const int h = lane >> 5;
+
+    if (tid == 0) {
+        int lo = 0, hi = a.n_units;            // last unit with wg_off[unit] <= blockIdx.x
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if (a.wg_off[mid] <= (int)blockIdx.x) lo = mid; else hi = mid;
+        }
+        unit_sh = lo;
+    }
+    __syncthreads();
+    const int u = unit_sh;
+    const int wgi = blockIdx.x - a.wg_off[u];
+    const int ki = a.n_k - 1 - u / a.T;
+    const int t = u % a.T;
+    const int k = a.ks[ki];
+    const int d = a.d;
+    const float m2 = a.m2[u];
+    if (m2 < 0.0f) return;                     // unusable unit (fewer than k distinct rows)
+    const int kpm = a.kpm;
+    const int kpu = (k + 31) & ~31;
+    const UnitState st = unit_state(a, u);
+    StreamLds<DK> L(smem, kpm);
+
+    const int64_t t0 = a.task_off[t], t1 = a.task_off[t + 1];
+    const int64_t r0 = t0 + (int64_t)wgi * a.rows_per_wg;
+    const int64_t r1 = (r0 + a.rows_per_wg < t1) ? r0 + a.rows_per_wg : t1;
+    uint8_t *labrow = a.labbuf + (int64_t)ki * a.ld;
+    const bool first = a.it == 0;
+    const bool want_dist = a.final_pass || (a.trace != nullptr);
+
+    for (int e = tid; e < (kpu / 32) * 4 * 64; e += blockDim.x) L.afrag[e] = st.afrag[e];
+    for (int e = tid; e < k * DK; e += blockDim.x) L.S[e] = 0;
+    for (int c = tid; c < k; c += blockDim.x) L.n[c] = 0;
+    if (tid < DK) L.ojf[tid] = tid < 32 ? a.ojf[t * 32 + tid] : 0.0f;
+    __syncthreads();
+
+    unsigned char *wb = L.wave_base + ((StreamLds<DK>::kWaveBytes + 15) & ~(size_t)15) * wave;
+    _Float16 *rec_x = reinterpret_cast<_Float16 *>(wb);                                          // [kStreamRec][DK]
+    unsigned short *rec_slot = reinterpret_cast<unsigned short *>(wb + (size_t)kStreamRec * DK * 2);   // [128]
+    unsigned char *lab_res = wb + (size_t)kStreamRec * DK * 2 + 256;                              // [128]
+    unsigned char *lab_new = lab_res + 128;                                                        // [128]
+    unsigned *chg = reinterpret_cast<unsigned *>(lab_new + 128);                                   // [128] cur | prev << 8 | first << 16
+
+    const _Float16 *xh = reinterpret_cast<const _Float16 *>(a.xh);
+    const int nch = (k + 63) >> 6;
+    const float16v zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    double part = 0.0;
+
+    const int64_t step_rows = (int64_t)kWavesPerWg * kTiles * 32;
+    for (int64_t base = r0; base < r1; base += step_rows) {
+        const int64_t wrow0 = base + (int64_t)wave * kTiles * 32;      // first row of this wave's step
+        if (wrow0 >= r1) continue;                                      // wave-uniform
+
+        // rows of this step as B fragments
+        half8 B[kTiles][NS];
+        float x2[kTiles];
+        bool live[kTiles];
+#pragma unroll
+        for (int tt = 0; tt < kTiles; ++tt) {
+            const int64_t row = wrow0 + tt * 32 + n32;
+            live[tt] = row < r1;
+            const int64_t rr = live[tt] ? row : wrow0;                  // a valid row either way
+#pragma unroll
+            for (int f = 0; f < NS; ++f) {
+                half8 v = *reinterpret_cast<const half8 *>(xh + rr * DK + 16 * f + 8 * h);
+                if (!live[tt]) {
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) v[i] = (_Float16)0.0f;
+                }
+                B[tt][f] = v;
+            }
+            x2[tt] = a.x2[rr];
+        }
+
+        // sweep 1: minimum score of every row over all chunks of 64 centroids
+        float best[kTiles];
+#pragma unroll
+        for (int tt = 0; tt < kTiles; ++tt) best[tt] = __builtin_inff();
+        for (int ch = 0; ch < nch; ++ch) {
+            const bool has1 = (2 * ch + 1) * 32 < kpu;
+            half8 A0[NS2], A1[NS2];
+#pragma unroll
+            for (int s = 0; s < NS2; ++s) {
+                A0[s] = L.afrag[((2 * ch) * 4 + s) * 64 + lane];        // slots 0..NS-1 hi parts, NS..2NS-1 lo parts
+                A1[s] = has1 ? L.afrag[((2 * ch + 1) * 4 + s) * 64 + lane] : A0[s];
+            }
+#pragma unroll
+            for (int tt = 0; tt < kTiles; ++tt) {
+                float16v acc0 = zero16, acc1 = zero16;
+#pragma unroll
+                for (int s = 0; s < NS2; ++s)
+                    acc0 = __builtin_amdgcn_mfma_f32_32x32x16_f16(A0[s], B[tt][s % NS], acc0, 0, 0, 0);
+                float m = min3f(acc0[0], acc0[1], acc0[2]);
+#pragma unroll
+                for (int i = 3; i < 15; i += 2) m = min3f(m, acc0[i], acc0[i + 1]);
+                m = __builtin_fminf(m, acc0[15]);
+                if (has1) {
+#pragma unroll
+                    for (int s = 0; s < NS2; ++s)
+                        acc1 = __builtin_amdgcn_mfma_f32_32x32x16_f16(A1[s], B[tt][s % NS], acc1, 0, 0, 0);
+#pragma unroll
+                    for (int i = 0; i < 16; i += 2) m = min3f(m, acc1[i], acc1[i + 1]);
+                }
+                best[tt] = __builtin_fminf(best[tt], m);
+            }
+        }
+        float thr[kTiles];
+        int cnt[kTiles], candq[kTiles];
+#pragma unroll
+        for (int tt = 0; tt < kTiles; ++tt) {
+            thr[tt] = min_halves(best[tt]) + mfma_bound<NS2>(x2[tt], m2);
+            cnt[tt] = 0;
+            candq[tt] = 0;
+        }
+        // sweep 2: count the scores within the bound and remember where one is
+        for (int ch = 0; ch < nch; ++ch) {
+            const bool has1 = (2 * ch + 1) * 32 < kpu;
+            half8 A0[NS2], A1[NS2];
+#pragma unroll
+            for (int s = 0; s < NS2; ++s) {
+                A0[s] = L.afrag[((2 * ch) * 4 + s) * 64 + lane];
+                A1[s] = has1 ? L.afrag[((2 * ch + 1) * 4 + s) * 64 + lane] : A0[s];
+            }
+#pragma unroll
+            for (int tt = 0; tt < kTiles; ++tt) {
+                float16v acc0 = zero16, acc1 = zero16;
+#pragma unroll
+                for (int s = 0; s < NS2; ++s)
+                    acc0 = __builtin_amdgcn_mfma_f32_32x32x16_f16(A0[s], B[tt][s % NS], acc0, 0, 0, 0);
+                uint32_t far = 0;
+#pragma unroll
+                for (int i = 0; i < 16; ++i)
+                    far = __builtin_amdgcn_alignbit(far, __float_as_uint(thr[tt] - acc0[i]), 31);
+                if (has1) {
+#pragma unroll
+                    for (int s = 0; s < NS2; ++s)
+                        acc1 = __builtin_amdgcn_mfma_f32_32x32x16_f16(A1[s], B[tt][s % NS], acc1, 0, 0, 0);
+#pragma unroll
+                    for (int i = 0; i < 16; ++i)
+                        far = __builtin_amdgcn_alignbit(far, __float_as_uint(thr[tt] - acc1[i]), 31);
+                } else {
+                    far = (far << 16) | 0xFFFFu;
+                }
+                const uint32_t cand = ~far;
+                cnt[tt] += __popc(cand);
+                candq[tt] = cand ? (ch * 32 + __clz((int)cand)) : candq[tt];
+            }
+        }
+
+        // decide, or queue for the exact evaluation
+        int lab[kTiles];
+        uint32_t flagged_mask = 0;
+        int nrec = 0;
+#pragma unroll
+        for (int tt = 0; tt < kTiles; ++tt) {
+            unsigned c_lo, c_hi, q_lo, q_hi;
+            both_halves((unsigned)cnt[tt], c_lo, c_hi);
+            both_halves((unsigned)candq[tt], q_lo, q_hi);
+            const int total = (int)(c_lo + c_hi);
+            const int hh = c_lo ? 0 : 1;
+            const int qg = (int)(c_lo ? q_lo : q_hi);
+            lab[tt] = 64 * (qg >> 5) + centroid_of(qg & 31, hh);
+            const bool flagged = live[tt] && total != 1;
+            const uint64_t fm = __ballot(flagged) & 0xFFFFFFFFull;
+            if (fm) {
+                if (flagged) {
+                    flagged_mask |= 1u << tt;
+                    const int rs = nrec + __popcll(fm & ((1ull << n32) - 1ull));
+                    if (rs < kStreamRec) {
+#pragma unroll
+                        for (int f = 0; f < NS; ++f)
+                            *reinterpret_cast<half8 *>(rec_x + (size_t)rs * DK + 16 * f + 8 * h) = B[tt][f];
+                    }
+                    if (h == 0) rec_slot[rs] = (unsigned short)(tt * 32 + n32);
+                }
+                nrec += __popcll(fm);
+            }
+        }
+        if (nrec) {
+            __builtin_amdgcn_wave_barrier();
+            for (int r = 0; r < nrec; ++r) {
+                const int sl = rec_slot[r];
+                double bs = __builtin_inf();
+                int bc = 0x7fffffff;
+                for (int c0 = 0; c0 < k; c0 += 64) {
+                    int c = c0 + lane;
+                    const int cc = c < k ? c : k - 1;
+                    double s = 0.0;
+                    for (int j = 0; j < d; ++j) {
+                        float xf;
+                        if (r < kStreamRec) xf = (float)rec_x[(size_t)r * DK + j];
+                        else xf = (float)xh[(wrow0 + sl) * DK + j];
+                        const double tq = (double)(xf + L.ojf[j]) - st.mu[(size_t)j * kpm + cc];
+                        s = s + tq * tq;
+                    }
+                    if (c >= k) {
+                        s = __builtin_inf();
+                        c = 0x7fffffff;
+                    }
+                    wave_argmin(s, c);
+                    if (s < bs) {
+                        bs = s;
+                        bc = c;
+                    }
+                }
+                if (lane == 0) lab_res[sl] = (unsigned char)(bc < k ? bc : 0);
+            }
+            __builtin_amdgcn_wave_barrier();
+        }
+
+        // label changes -> sums of this workgroup (LDS), tile by tile
+#pragma unroll
+        for (int tt = 0; tt < kTiles; ++tt) {
+            const int64_t row = wrow0 + tt * 32 + n32;
+            int cur = lab[tt];
+            if ((flagged_mask >> tt) & 1u) cur = lab_res[tt * 32 + n32];
+            int prev = 0;
+            if (!first && live[tt]) prev = labrow[row];
+            const bool changed = live[tt] && (first || cur != prev);
+            if (want_dist && h == 0) lab_new[tt * 32 + n32] = (unsigned char)(live[tt] ? cur : 0);
+            const uint64_t cm = __ballot(changed) & 0xFFFFFFFFull;
+            if (cm) {
+                int ccount = 0;
+                if (changed) {
+                    const int rs = __popcll(cm & ((1ull << n32) - 1ull));
+#pragma unroll
+                    for (int f = 0; f < NS; ++f)
+                        *reinterpret_cast<half8 *>(rec_x + (size_t)rs * DK + 16 * f + 8 * h) = B[tt][f];
+                    if (h == 0) {
+                        chg[rs] = (unsigned)cur | ((unsigned)prev << 8) | (first ? 0x10000u : 0u);
+                        labrow[row] = (uint8_t)cur;
+                    }
+                }
+                ccount = __popcll(cm);
+                __builtin_amdgcn_wave_barrier();
+                // one lane per (row, group of 4 knobs)
+                constexpr int LPR = DK / 4, EPI = 64 / LPR;
+                const int j0 = 4 * (lane % LPR);
+                for (int e0 = 0; e0 < ccount; e0 += EPI) {
+                    const int e = e0 + lane / LPR;
+                    if (e < ccount && j0 < d) {
+                        const unsigned w = chg[e];
+                        const int cc = w & 0xFF, pp = (w >> 8) & 0xFF;
+                        const bool had = ((w >> 16) & 1u) == 0u;     // the row had a label before
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            if (j0 + i < d) {
+                                const int xi = (int)((float)rec_x[(size_t)e * DK + j0 + i] + L.ojf[j0 + i]);
+                                atomicAdd(&L.S[cc * DK + j0 + i], xi);
+                                if (had) atomicSub(&L.S[pp * DK + j0 + i], xi);
+                            }
+                        }
+                        if (j0 == 0) {
+                            atomicAdd(&L.n[cc], 1);
+                            if (had) atomicSub(&L.n[pp], 1);
+                        }
+                    }
+                }
+                __builtin_amdgcn_wave_barrier();
+            }
+        }
+
+        if (want_dist) {
+            // exact loss terms of the rows of this step: one row per lane, knobs ascending
+            __builtin_amdgcn_wave_barrier();
+            for (int s0 = 0; s0 < kTiles * 32; s0 += 64) {
+                const int sl = s0 + lane;
+                const int64_t row = wrow0 + sl;
+                if (row < r1) {
+                    const int c = lab_new[sl];
+                    double s = 0.0;
+                    for (int j = 0; j < d; ++j) {
+                        const double tq = (double)a.X[(int64_t)j * a.ld + row] - st.mu[(size_t)j * kpm + c];
+                        s = s + tq * tq;
+                    }
+                    part = part + s;
+                }
+            }
+        }
+    }
+
+    if (want_dist) {
+        const double ws = wave_sum(part);
+        if (lane == 0) L.red[wave] = ws;
+    }
+    __syncthreads();
+    // changes of this workgroup -> the unit's sums
+    for (int e = tid; e < k * DK; e += blockDim.x) {
+        const int v = L.S[e];
+        if (v != 0) atomicAdd(&st.S[(e / DK) * 32 + (e % DK)], v);
+    }
+    for (int c = tid; c < k; c += blockDim.x) {
+        const int v = L.n[c];
+        if (v != 0) atomicAdd(&st.n[c], v);
+    }
+    if (want_dist && tid == 0) {
+        double s = 0.0;
+        for (int w = 0; w < kWavesPerWg; ++w) s = s + (w < (int)(blockDim.x >> 6) ? L.red[w] : 0.0);
+        a.loss_part[blockIdx.x] = s;
+    }
+}
+
+template <int DK>
+hipError_t run_stream(StreamArgs a, int64_t n_total, int total_wgs, hipStream_t s)
+{
+    const size_t lds = StreamLds<DK>::bytes(a.kpm);
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(stream_assign_kernel<DK>),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(stream_offsets_kernel, dim3(a.T), dim3(64), 0, s, a);
+    const unsigned pb = (unsigned)((n_total + 255) / 256);
+    if (pb) hipLaunchKernelGGL(stream_pack_kernel<DK>, dim3(pb), dim3(256), 0, s, a, n_total);
+    a.it = 0;
+    a.final_pass = 0;
+    hipLaunchKernelGGL(stream_update_kernel<DK>, dim3(a.n_units), dim3(256), 0, s, a, 0);
+    for (int it = 0; it <= a.n_iter; ++it) {
+        a.it = it;
+        a.final_pass = it == a.n_iter ? 1 : 0;
+        hipLaunchKernelGGL(stream_assign_kernel<DK>, dim3(total_wgs), dim3(kWavesPerWg * 64), lds, s, a);
+        hipLaunchKernelGGL(stream_update_kernel<DK>, dim3(a.n_units), dim3(256), 0, s, a, a.final_pass ? 2 : 1);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace
+
+int64_t stream_lds_bytes(int d, int kpm)
+{
+    return d <= 15 ? (int64_t)StreamLds<16>::bytes(kpm) : (int64_t)StreamLds<32>::bytes(kpm);
+}
+
+hipError_t launch_stream_sweep(const StreamArgs &a, int64_t n_total, int total_wgs, hipStream_t s)
+{
+    if (a.d <= 15) return run_stream<16>(a, n_total, total_wgs, s);
+    return run_stream<32>(a, n_total, total_wgs, s);
+}
+
+}  // namespace cham

@@ -245,3 +245,72 @@ def test_matrix_core_and_vector_paths_agree_on_every_task():
     for key in ("centroids", "counts", "status", "labels"):
         assert torch.equal(a[key], b[key]), key
     np.testing.assert_allclose(a["inertia"].cpu().numpy(), b["inertia"].cpu().numpy(), rtol=1e-12, atol=0)
+
+
+# ------------------------------------------------------------------ streaming path (large tasks)
+
+def _sweep_only(wl, flags, want_trace=False, init=None):
+    import torch
+    dw = binding.DeviceWorkload(wl)
+    out = binding.cham_kmeans_sweep(dw.X, dw.ld, dw.d, wl.task_off, wl.ks, wl.n_iter, want_labels=True,
+                                    want_trace=want_trace, flags=flags,
+                                    init_centroids=None if init is None else torch.from_numpy(init).to(dw.device))
+    torch.cuda.synchronize()
+    ref = oracle.sweep(wl.rows, wl.task_off, wl.ks, wl.n_iter, init=init, want_labels=True, want_trace=want_trace)
+    check_sweep(wl, out, ref, dw.ld)
+    return out, ref
+
+
+@pytest.mark.parametrize("cfg", [1, 2])
+def test_streaming_path_on_small_configs(cfg):
+    wl = workloads.make_config(cfg, 0)
+    wl.n_iter = 12
+    _sweep_only(wl, binding.F_STREAMING, want_trace=True)
+
+
+@pytest.mark.parametrize("d,ks", [(15, (1, 7, 33)), (16, (2, 64, 65)), (31, (5, 100)), (7, (128, 255, 256))])
+def test_streaming_path_knob_and_centroid_counts(d, ks):
+    wl = workloads.random_task(1200 + d, n=6000, d=d, n_blobs=30, ks=ks, n_iter=5, card_hi=28, sigma=1.4,
+                               n_tasks=2, ragged=True)
+    _sweep_only(wl, binding.F_STREAMING)
+
+
+def test_streaming_path_is_the_default_for_large_tasks():
+    wl = workloads.random_task(77, n=20000, d=10, n_blobs=20, ks=(4, 40, 90), n_iter=6, card_hi=20)
+    out, ref = _sweep_only(wl, 0, want_trace=True)
+    # and the vector path (one workgroup per unit) gives the same
+    import torch
+    dw = binding.DeviceWorkload(wl)
+    alt = binding.cham_kmeans_sweep(dw.X, dw.ld, dw.d, wl.task_off, wl.ks, wl.n_iter, want_labels=True,
+                                    flags=binding.F_NO_MFMA)
+    torch.cuda.synchronize()
+    for key in ("centroids", "counts", "labels"):
+        assert torch.equal(out[key], alt[key]), key
+
+
+def test_streaming_path_caller_start_and_exact_ties():
+    n, d = 9000, 5
+    rows = np.full((n, d), 4, dtype=np.uint8)
+    rows[::5, 1] = 7
+    wl = workloads.random_task(3, n=8, d=d)
+    wl.rows, wl.task_off = rows, np.array([0, n])
+    wl.valid = np.ones(n, np.uint8)
+    wl.cards = np.full((1, d), 16, np.uint16)
+    wl.ks, wl.n_iter = [2], 3
+    init = np.zeros((1, 2, d))
+    init[0, 0] = 2.0
+    init[0, 1] = 6.0
+    _sweep_only(wl, binding.F_STREAMING, want_trace=True, init=init)
+
+
+def test_streaming_path_with_too_few_distinct_rows():
+    rng = np.random.default_rng(2)
+    base = rng.integers(0, 5, size=(6, 4)).astype(np.uint8)
+    rows = base[rng.integers(0, 6, size=5000)]
+    wl = workloads.random_task(1, n=8, d=4)
+    wl.rows, wl.task_off = np.ascontiguousarray(rows), np.array([0, 5000])
+    wl.valid = np.ones(5000, np.uint8)
+    wl.cards = np.full((1, 4), 5, np.uint16)
+    wl.ks, wl.n_iter = [2, 6, 9], 4
+    out, ref = _sweep_only(wl, binding.F_STREAMING)
+    assert ref["status"][0, 2] == 1
