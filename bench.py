@@ -30,6 +30,8 @@ def main():
     ap.add_argument("--scale", type=float, default=1.0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-tasks", type=int, default=8, help="tasks of the workload the oracle is timed on")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="run only a plain 1 GiB device copy (reference for the FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (--gpus 1); nothing here uses a second GPU.",
@@ -41,6 +43,15 @@ def main():
     from paper_2001_08743_amd import binding, workloads
 
     torch.cuda.set_device(0)
+    if args.calibrate_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda:0").fill_(1)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_copy_bytes": 1 << 30, "copies": 3}), flush=True)
+        return
     wl = workloads.make_config(args.cfg, 0, scale=args.scale)
     dw = binding.DeviceWorkload(wl, "cuda:0")
     dw.build_visited()
@@ -93,11 +104,14 @@ def main():
     # contraction runs on the f16 matrix cores, so it is priced against the dense f16 MFMA peak.
     flops_per_eval = 2 * wl.d + 2
     achieved_tflops = evals * flops_per_eval / (sweep_ms * 1e-3) / 1e12
-    uses_mfma = wl.d <= 31 and max(wl.ks) <= 64 and int(np.diff(wl.task_off).max()) <= 4096
+    n_max = int(np.diff(wl.task_off).max())
+    resident = max(wl.ks) <= 64 and n_max <= 4096
+    uses_mfma = wl.d <= 31
+    kernel = ("resident_mfma_kernel" if resident else "stream_assign_kernel") if uses_mfma else "resident_sweep_kernel"
     peak = PEAK_F16_MFMA_TFLOPS if uses_mfma else PEAK_FP32_VECTOR_TFLOPS
     roofline = dict(bound="mfma" if uses_mfma else "alu", achieved=round(achieved_tflops, 3), peak=peak,
                     unit="TFLOP/s", frac=round(achieved_tflops / peak, 4), traffic=None,
-                    kernel="resident_mfma_kernel" if uses_mfma else "resident_sweep_kernel",
+                    kernel=kernel,
                     kernel_ms=round(sweep_ms, 3), flops_per_eval=flops_per_eval,
                     frac_of_fp32_vector_peak=round(achieved_tflops / PEAK_FP32_VECTOR_TFLOPS, 4))
 

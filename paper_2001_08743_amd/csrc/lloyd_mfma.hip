@@ -40,7 +40,7 @@ template <int DK>
 struct MfmaLds {
     double *mu64T;      // [DK][KP]   exact centroids, transposed
     double *red;        // [16]       per-wave partial sums of the loss
-    double *bpart;      // [KP][4]    partial sums of |mu - o|^2 per group of 8 knobs
+    double *bpart;      // [KP][8]    partial sums of |mu - o|^2 per group of 4 knobs
     half8 *afrag;       // [KP/32][2*DK/16][64]  A fragments: hi parts then lo parts
     int *S;             // [KP][DK]   integer cluster sums
     int *n;             // [KP]       cluster sizes
@@ -51,7 +51,7 @@ struct MfmaLds {
         ((size_t)kRecCap * DK * 2 + 512 * 8 + 512 * 2 + 512 + 512 * 4 + 15) / 16 * 16;
     __host__ __device__ static size_t bytes(int KP, int nwaves)
     {
-        size_t b = sizeof(double) * DK * KP + sizeof(double) * 16 + sizeof(double) * KP * 4;
+        size_t b = sizeof(double) * DK * KP + sizeof(double) * 16 + sizeof(double) * KP * 8;
         b += 16 * (size_t)(KP / 32) * (2 * DK / 16) * 64;
         b += sizeof(int) * (size_t)KP * DK + sizeof(int) * KP * 2 + sizeof(float) * DK;
         b = (b + 15) & ~(size_t)15;
@@ -63,7 +63,7 @@ struct MfmaLds {
         size_t o = 0;
         mu64T = reinterpret_cast<double *>(base + o);  o += sizeof(double) * DK * KP;
         red = reinterpret_cast<double *>(base + o);    o += sizeof(double) * 16;
-        bpart = reinterpret_cast<double *>(base + o);  o += sizeof(double) * KP * 4;
+        bpart = reinterpret_cast<double *>(base + o);  o += sizeof(double) * KP * 8;
         afrag = reinterpret_cast<half8 *>(base + o);   o += 16 * (size_t)(KP / 32) * (2 * DK / 16) * 64;
         S = reinterpret_cast<int *>(base + o);         o += sizeof(int) * (size_t)KP * DK;
         n = reinterpret_cast<int *>(base + o);         o += sizeof(int) * KP;
@@ -237,25 +237,26 @@ __device__ __forceinline__ void apply_changes(const WaveQueue<DK> &Q, int cnt, i
     __builtin_amdgcn_wave_barrier();
 }
 
-// Centroid update for the clusters touched in this pass, all threads: item (c, g) owns knobs
-// 8g..8g+7 of centroid c: mean = (double)S / (double)n, then the f16 hi/lo fragments of
-// w = -2 (mu - o) (one 16-byte store each) and the partial sum of (mu - o)^2.  The last knob
+// Centroid update for the clusters touched in this pass, all threads: item (c, q) owns knobs
+// 4q..4q+3 of centroid c: mean = (double)S / (double)n, then the f16 hi/lo fragments of
+// w = -2 (mu - o) (one 8-byte store each) and the partial sum of (mu - o)^2.  The last knob
 // slot (the bias slot) is left zero here; each wave fills it in its register copy.
 template <int DK>
 __device__ __forceinline__ void update_centroids(const MfmaLds<DK> &U, int k, int KP, int d, int stamp, bool all)
 {
-    constexpr int NS = DK / 16, NS2 = 2 * NS, G = DK / 8;
-    for (int item = threadIdx.x; item < k * G; item += blockDim.x) {
-        const int c = item / G, g = item % G;
-        if (8 * g >= d) continue;
+    constexpr int NS = DK / 16, NS2 = 2 * NS, QN = DK / 4;
+    typedef _Float16 half4 __attribute__((ext_vector_type(4)));
+    for (int item = threadIdx.x; item < k * QN; item += blockDim.x) {
+        const int c = item / QN, q = item % QN;
+        if (4 * q >= d) continue;
         if (!all && U.dirty[c] != stamp) continue;
         const int cnt = U.n[c];
         if (!all && cnt == 0) continue;          // an empty cluster keeps its centroid
-        half8 hi8, lo8;
+        half4 hi4, lo4;
         double b = 0.0;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const int j = 8 * g + i;
+        for (int i = 0; i < 4; ++i) {
+            const int j = 4 * q + i;
             double mu = U.mu64T[(size_t)j * KP + c];
             if (!all && j < d) {
                 mu = (double)U.S[c * DK + j] / (double)cnt;
@@ -265,14 +266,16 @@ __device__ __forceinline__ void update_centroids(const MfmaLds<DK> &U, int k, in
             b = __builtin_fma(m, m, b);
             const float w = (float)(-2.0 * m);
             const _Float16 hi = (_Float16)w;
-            hi8[i] = hi;
-            lo8[i] = (_Float16)(w - (float)hi);
+            hi4[i] = hi;
+            lo4[i] = (_Float16)(w - (float)hi);
         }
         const int mt = c >> 5, m32 = c & 31;
-        const int hh = g & 1, fstep = g >> 1;
-        U.afrag[(mt * NS2 + fstep) * 64 + 32 * hh + m32] = hi8;
-        U.afrag[(mt * NS2 + NS + fstep) * 64 + 32 * hh + m32] = lo8;
-        U.bpart[c * 4 + g] = b;
+        const int g = q >> 1, hh = g & 1, fstep = g >> 1, sub = q & 1;
+        half4 *fh = reinterpret_cast<half4 *>(U.afrag + (mt * NS2 + fstep) * 64 + 32 * hh + m32) + sub;
+        half4 *fl = reinterpret_cast<half4 *>(U.afrag + (mt * NS2 + NS + fstep) * 64 + 32 * hh + m32) + sub;
+        *fh = hi4;
+        *fl = lo4;
+        U.bpart[c * 8 + q] = b;
     }
 }
 
@@ -316,7 +319,7 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
         U.n[c] = 0;
         U.dirty[c] = -1;
     }
-    for (int e = tid; e < KP * 4; e += blockDim.x) U.bpart[e] = 0.0;
+    for (int e = tid; e < KP * 8; e += blockDim.x) U.bpart[e] = 0.0;
     {
         half8 z;
 #pragma unroll
@@ -433,7 +436,9 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
                 const int c = 32 * mt + n32;
                 _Float16 bhi = (_Float16)kPadBiasHi, blo = (_Float16)0.0f;
                 if (c < k) {
-                    const double b = ((U.bpart[c * 4 + 0] + U.bpart[c * 4 + 1]) + U.bpart[c * 4 + 2]) + U.bpart[c * 4 + 3];
+                    double b = U.bpart[c * 8];
+#pragma unroll
+                    for (int q = 1; q < 8; ++q) b = b + U.bpart[c * 8 + q];
                     const float bs = (float)b * (1.0f / kBiasScale);
                     bhi = (_Float16)bs;
                     blo = (_Float16)(bs - (float)bhi);
