@@ -313,103 +313,132 @@ __global__ __launch_bounds__(512) void stream_assign_kernel(const StreamArgs a)
     double part = 0.0;
 
     const int64_t step_rows = (int64_t)kWavesPerWg * kTiles * 32;
-    for (int64_t base = r0; base < r1; base += step_rows) {
-        const int64_t wrow0 = base + (int64_t)wave * kTiles * 32;      // first row of this wave's step
-        if (wrow0 >= r1) continue;                                      // wave-uniform
 
-        // rows of this step as B fragments
+    // rows of one step of this wave: B fragments, squared norms, previous labels
+    struct StepRows {
         half8 B[kTiles][NS];
         float x2[kTiles];
-        bool live[kTiles];
+        int prev[kTiles];
+    };
+    auto load_step = [&](int64_t wrow0, StepRows &R) {
 #pragma unroll
         for (int tt = 0; tt < kTiles; ++tt) {
             const int64_t row = wrow0 + tt * 32 + n32;
-            live[tt] = row < r1;
-            const int64_t rr = live[tt] ? row : wrow0;                  // a valid row either way
+            const bool lv = row < r1;
+            const int64_t rr = lv ? row : (wrow0 < r1 ? wrow0 : r0);     // a valid row either way
 #pragma unroll
             for (int f = 0; f < NS; ++f) {
                 half8 v = *reinterpret_cast<const half8 *>(xh + rr * DK + 16 * f + 8 * h);
-                if (!live[tt]) {
+                if (!lv) {
 #pragma unroll
                     for (int i = 0; i < 8; ++i) v[i] = (_Float16)0.0f;
                 }
-                B[tt][f] = v;
+                R.B[tt][f] = v;
             }
-            x2[tt] = a.x2[rr];
+            R.x2[tt] = a.x2[rr];
+            R.prev[tt] = first ? 0 : (int)labrow[rr];
         }
+    };
 
-        // sweep 1: minimum score of every row over all chunks of 64 centroids
-        float best[kTiles];
+    StepRows nxt;
+    if (r0 < r1) load_step(r0 + (int64_t)wave * kTiles * 32, nxt);
+    for (int64_t base = r0; base < r1; base += step_rows) {
+        const int64_t wrow0 = base + (int64_t)wave * kTiles * 32;      // first row of this wave's step
+        const StepRows cur = nxt;
+        if (base + step_rows < r1) load_step(wrow0 + step_rows, nxt);  // next step's rows load under this step
+        if (wrow0 >= r1) continue;                                      // wave-uniform
+        bool live[kTiles];
 #pragma unroll
-        for (int tt = 0; tt < kTiles; ++tt) best[tt] = __builtin_inff();
-        for (int ch = 0; ch < nch; ++ch) {
-            const bool has1 = (2 * ch + 1) * 32 < kpu;
-            half8 A0[NS2], A1[NS2];
+        for (int tt = 0; tt < kTiles; ++tt) live[tt] = (wrow0 + tt * 32 + n32) < r1;
+
+        int cnt[kTiles], candq[kTiles];
+#pragma unroll
+        for (int tt = 0; tt < kTiles; ++tt) {
+            cnt[tt] = 0;
+            candq[tt] = 0;
+        }
+        auto load_a = [&](int ch, bool has1, half8 (&A0)[NS2], half8 (&A1)[NS2]) {
 #pragma unroll
             for (int s = 0; s < NS2; ++s) {
                 A0[s] = L.afrag[((2 * ch) * 4 + s) * 64 + lane];        // slots 0..NS-1 hi parts, NS..2NS-1 lo parts
                 A1[s] = has1 ? L.afrag[((2 * ch + 1) * 4 + s) * 64 + lane] : A0[s];
             }
+        };
+        auto chain = [&](const half8 (&Af)[NS2], const half8 (&Bt)[NS]) {
+            float16v acc = zero16;
 #pragma unroll
-            for (int tt = 0; tt < kTiles; ++tt) {
-                float16v acc0 = zero16, acc1 = zero16;
+            for (int s = 0; s < NS2; ++s)
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(Af[s], Bt[s % NS], acc, 0, 0, 0);
+            return acc;
+        };
+        auto min16 = [&](const float16v &acc) {
+            float m = min3f(acc[0], acc[1], acc[2]);
 #pragma unroll
-                for (int s = 0; s < NS2; ++s)
-                    acc0 = __builtin_amdgcn_mfma_f32_32x32x16_f16(A0[s], B[tt][s % NS], acc0, 0, 0, 0);
-                float m = min3f(acc0[0], acc0[1], acc0[2]);
+            for (int i = 3; i < 15; i += 2) m = min3f(m, acc[i], acc[i + 1]);
+            return __builtin_fminf(m, acc[15]);
+        };
+        auto mark16 = [&](uint32_t far, const float16v &acc, float thr) {
 #pragma unroll
-                for (int i = 3; i < 15; i += 2) m = min3f(m, acc0[i], acc0[i + 1]);
-                m = __builtin_fminf(m, acc0[15]);
-                if (has1) {
-#pragma unroll
-                    for (int s = 0; s < NS2; ++s)
-                        acc1 = __builtin_amdgcn_mfma_f32_32x32x16_f16(A1[s], B[tt][s % NS], acc1, 0, 0, 0);
-#pragma unroll
-                    for (int i = 0; i < 16; i += 2) m = min3f(m, acc1[i], acc1[i + 1]);
-                }
-                best[tt] = __builtin_fminf(best[tt], m);
-            }
-        }
-        float thr[kTiles];
-        int cnt[kTiles], candq[kTiles];
-#pragma unroll
-        for (int tt = 0; tt < kTiles; ++tt) {
-            thr[tt] = min_halves(best[tt]) + mfma_bound<NS2>(x2[tt], m2);
-            cnt[tt] = 0;
-            candq[tt] = 0;
-        }
-        // sweep 2: count the scores within the bound and remember where one is
-        for (int ch = 0; ch < nch; ++ch) {
-            const bool has1 = (2 * ch + 1) * 32 < kpu;
+            for (int i = 0; i < 16; ++i)
+                far = __builtin_amdgcn_alignbit(far, __float_as_uint(thr - acc[i]), 31);
+            return far;
+        };
+
+        if (nch == 1) {
+            // at most 64 centroids: one sweep, the scores stay in registers between minimum and marking
+            const bool has1 = 32 < kpu;
             half8 A0[NS2], A1[NS2];
-#pragma unroll
-            for (int s = 0; s < NS2; ++s) {
-                A0[s] = L.afrag[((2 * ch) * 4 + s) * 64 + lane];
-                A1[s] = has1 ? L.afrag[((2 * ch + 1) * 4 + s) * 64 + lane] : A0[s];
-            }
+            load_a(0, has1, A0, A1);
 #pragma unroll
             for (int tt = 0; tt < kTiles; ++tt) {
-                float16v acc0 = zero16, acc1 = zero16;
-#pragma unroll
-                for (int s = 0; s < NS2; ++s)
-                    acc0 = __builtin_amdgcn_mfma_f32_32x32x16_f16(A0[s], B[tt][s % NS], acc0, 0, 0, 0);
-                uint32_t far = 0;
-#pragma unroll
-                for (int i = 0; i < 16; ++i)
-                    far = __builtin_amdgcn_alignbit(far, __float_as_uint(thr[tt] - acc0[i]), 31);
+                const float16v acc0 = chain(A0, cur.B[tt]);
+                float16v acc1 = zero16;
+                float m = min16(acc0);
                 if (has1) {
-#pragma unroll
-                    for (int s = 0; s < NS2; ++s)
-                        acc1 = __builtin_amdgcn_mfma_f32_32x32x16_f16(A1[s], B[tt][s % NS], acc1, 0, 0, 0);
-#pragma unroll
-                    for (int i = 0; i < 16; ++i)
-                        far = __builtin_amdgcn_alignbit(far, __float_as_uint(thr[tt] - acc1[i]), 31);
-                } else {
-                    far = (far << 16) | 0xFFFFu;
+                    acc1 = chain(A1, cur.B[tt]);
+                    m = __builtin_fminf(m, min16(acc1));
                 }
+                const float thr = min_halves(m) + mfma_bound<NS2>(cur.x2[tt], m2);
+                uint32_t far = mark16(0, acc0, thr);
+                if (has1) far = mark16(far, acc1, thr);
+                else far = (far << 16) | 0xFFFFu;
                 const uint32_t cand = ~far;
-                cnt[tt] += __popc(cand);
-                candq[tt] = cand ? (ch * 32 + __clz((int)cand)) : candq[tt];
+                cnt[tt] = __popc(cand);
+                candq[tt] = __clz((int)cand) & 31;
+            }
+        } else {
+            // sweep 1: minimum score of every row over all chunks of 64 centroids
+            float best[kTiles];
+#pragma unroll
+            for (int tt = 0; tt < kTiles; ++tt) best[tt] = __builtin_inff();
+            for (int ch = 0; ch < nch; ++ch) {
+                const bool has1 = (2 * ch + 1) * 32 < kpu;
+                half8 A0[NS2], A1[NS2];
+                load_a(ch, has1, A0, A1);
+#pragma unroll
+                for (int tt = 0; tt < kTiles; ++tt) {
+                    float m = min16(chain(A0, cur.B[tt]));
+                    if (has1) m = __builtin_fminf(m, min16(chain(A1, cur.B[tt])));
+                    best[tt] = __builtin_fminf(best[tt], m);
+                }
+            }
+            float thr[kTiles];
+#pragma unroll
+            for (int tt = 0; tt < kTiles; ++tt) thr[tt] = min_halves(best[tt]) + mfma_bound<NS2>(cur.x2[tt], m2);
+            // sweep 2: count the scores within the bound and remember where one is
+            for (int ch = 0; ch < nch; ++ch) {
+                const bool has1 = (2 * ch + 1) * 32 < kpu;
+                half8 A0[NS2], A1[NS2];
+                load_a(ch, has1, A0, A1);
+#pragma unroll
+                for (int tt = 0; tt < kTiles; ++tt) {
+                    uint32_t far = mark16(0, chain(A0, cur.B[tt]), thr[tt]);
+                    if (has1) far = mark16(far, chain(A1, cur.B[tt]), thr[tt]);
+                    else far = (far << 16) | 0xFFFFu;
+                    const uint32_t cand = ~far;
+                    cnt[tt] += __popc(cand);
+                    candq[tt] = cand ? (ch * 32 + __clz((int)cand)) : candq[tt];
+                }
             }
         }
 
@@ -435,7 +464,7 @@ __global__ __launch_bounds__(512) void stream_assign_kernel(const StreamArgs a)
                     if (rs < kStreamRec) {
 #pragma unroll
                         for (int f = 0; f < NS; ++f)
-                            *reinterpret_cast<half8 *>(rec_x + (size_t)rs * DK + 16 * f + 8 * h) = B[tt][f];
+                            *reinterpret_cast<half8 *>(rec_x + (size_t)rs * DK + 16 * f + 8 * h) = cur.B[tt][f];
                     }
                     if (h == 0) rec_slot[rs] = (unsigned short)(tt * 32 + n32);
                 }
@@ -443,6 +472,8 @@ __global__ __launch_bounds__(512) void stream_assign_kernel(const StreamArgs a)
             }
         }
         if (nrec) {
+            // exact evaluation of the queued rows against all k centroids, one centroid per lane;
+            // the centroid loads of 8 knobs are issued together
             __builtin_amdgcn_wave_barrier();
             for (int r = 0; r < nrec; ++r) {
                 const int sl = rec_slot[r];
@@ -452,12 +483,20 @@ __global__ __launch_bounds__(512) void stream_assign_kernel(const StreamArgs a)
                     int c = c0 + lane;
                     const int cc = c < k ? c : k - 1;
                     double s = 0.0;
-                    for (int j = 0; j < d; ++j) {
-                        float xf;
-                        if (r < kStreamRec) xf = (float)rec_x[(size_t)r * DK + j];
-                        else xf = (float)xh[(wrow0 + sl) * DK + j];
-                        const double tq = (double)(xf + L.ojf[j]) - st.mu[(size_t)j * kpm + cc];
-                        s = s + tq * tq;
+                    for (int j0 = 0; j0 < d; j0 += 8) {
+                        double mu[8];
+                        half8 xq;
+                        if (r < kStreamRec) xq = *reinterpret_cast<const half8 *>(rec_x + (size_t)r * DK + j0);
+                        else xq = *reinterpret_cast<const half8 *>(xh + (wrow0 + sl) * DK + j0);
+#pragma unroll
+                        for (int i = 0; i < 8; ++i) mu[i] = (j0 + i < d) ? st.mu[(size_t)(j0 + i) * kpm + cc] : 0.0;
+#pragma unroll
+                        for (int i = 0; i < 8; ++i) {
+                            if (j0 + i < d) {
+                                const double tq = (double)((float)xq[i] + L.ojf[j0 + i]) - mu[i];
+                                s = s + tq * tq;
+                            }
+                        }
                     }
                     if (c >= k) {
                         s = __builtin_inf();
@@ -478,26 +517,24 @@ __global__ __launch_bounds__(512) void stream_assign_kernel(const StreamArgs a)
 #pragma unroll
         for (int tt = 0; tt < kTiles; ++tt) {
             const int64_t row = wrow0 + tt * 32 + n32;
-            int cur = lab[tt];
-            if ((flagged_mask >> tt) & 1u) cur = lab_res[tt * 32 + n32];
-            int prev = 0;
-            if (!first && live[tt]) prev = labrow[row];
-            const bool changed = live[tt] && (first || cur != prev);
-            if (want_dist && h == 0) lab_new[tt * 32 + n32] = (unsigned char)(live[tt] ? cur : 0);
+            int cl = lab[tt];
+            if ((flagged_mask >> tt) & 1u) cl = lab_res[tt * 32 + n32];
+            const int prev = cur.prev[tt];
+            const bool changed = live[tt] && (first || cl != prev);
+            if (want_dist && h == 0) lab_new[tt * 32 + n32] = (unsigned char)(live[tt] ? cl : 0);
             const uint64_t cm = __ballot(changed) & 0xFFFFFFFFull;
             if (cm) {
-                int ccount = 0;
                 if (changed) {
                     const int rs = __popcll(cm & ((1ull << n32) - 1ull));
 #pragma unroll
                     for (int f = 0; f < NS; ++f)
-                        *reinterpret_cast<half8 *>(rec_x + (size_t)rs * DK + 16 * f + 8 * h) = B[tt][f];
+                        *reinterpret_cast<half8 *>(rec_x + (size_t)rs * DK + 16 * f + 8 * h) = cur.B[tt][f];
                     if (h == 0) {
-                        chg[rs] = (unsigned)cur | ((unsigned)prev << 8) | (first ? 0x10000u : 0u);
-                        labrow[row] = (uint8_t)cur;
+                        chg[rs] = (unsigned)cl | ((unsigned)prev << 8) | (first ? 0x10000u : 0u);
+                        labrow[row] = (uint8_t)cl;
                     }
                 }
-                ccount = __popcll(cm);
+                const int ccount = __popcll(cm);
                 __builtin_amdgcn_wave_barrier();
                 // one lane per (row, group of 4 knobs)
                 constexpr int LPR = DK / 4, EPI = 64 / LPR;
