@@ -354,13 +354,46 @@ int32_t cham_select_k(const double *inertia, const int32_t *status, int32_t T, i
     return CHAM_OK;
 }
 
+// Tasks above this many rows are split over 4096-row chunks in the snap and synthesis steps.
+constexpr int64_t kWideTaskRows = 16384;
+constexpr int64_t kWideChunkRows = 4096;
+
+static bool wide_tasks(const Plan &pl) { return pl.n_max > kWideTaskRows; }
+
+// first workgroup of every task when each task is cut into 4096-row chunks; returns the total
+static int wide_offsets(const int64_t *task_off, int T, std::vector<uint64_t> &words)
+{
+    words.assign((size_t)(T + 2) / 2 + 1, 0);
+    int *w = reinterpret_cast<int *>(words.data());
+    int acc = 0;
+    for (int t = 0; t < T; ++t) {
+        w[t] = acc;
+        acc += (int)((task_off[t + 1] - task_off[t] + kWideChunkRows - 1) / kWideChunkRows);
+    }
+    w[T] = acc;
+    return acc;
+}
+
+static int64_t wide_snap_bytes(const Plan &pl)
+{
+    if (!wide_tasks(pl)) return 0;
+    return up((int64_t)(pl.T + 4) * 4) + up((int64_t)pl.T * pl.kmax * 8) + up((int64_t)pl.T * pl.kmax * 4);
+}
+
+static int64_t wide_synth_bytes(const Plan &pl, int d)
+{
+    if (!wide_tasks(pl)) return 0;
+    return up((int64_t)(pl.T + 4) * 4) + 2 * up((int64_t)pl.T * pl.kmax * 4) + up((int64_t)pl.T * 4) +
+           up((int64_t)pl.T * pl.kmax * d * 256 * 4);
+}
+
 int64_t cham_snap_workspace_bytes(int64_t ld, int32_t d, const int64_t *task_off, int32_t T,
                                   const int32_t *ks, int32_t n_k)
 {
     Plan pl;
     const int32_t rc = check_common(nullptr, ld, d, task_off, T, ks, n_k, false, pl);
     if (rc != CHAM_OK) return rc;
-    return up((int64_t)pl.blob.size() * 8) + up(ld * 8);
+    return up((int64_t)pl.blob.size() * 8) + up(ld * 8) + wide_snap_bytes(pl);
 }
 
 int32_t cham_snap_centroids(const uint8_t *X, int64_t ld, int32_t d, const int64_t *task_off, int32_t T,
@@ -375,7 +408,7 @@ int32_t cham_snap_centroids(const uint8_t *X, int64_t ld, int32_t d, const int64
     if (!chosen_idx || !centroids || !labels_sel || !pick_row || !pick_cfg) return CHAM_E_NULL;
     if (flags & ~(CHAM_F_FORCE_EXACT | CHAM_F_STREAMING | CHAM_F_RESIDENT | CHAM_F_NO_MFMA)) return CHAM_E_BAD_FLAG;
     const int64_t blob_bytes = up((int64_t)pl.blob.size() * 8);
-    if (!workspace || workspace_bytes < blob_bytes + up(ld * 8)) return CHAM_E_WORKSPACE;
+    if (!workspace || workspace_bytes < blob_bytes + up(ld * 8) + wide_snap_bytes(pl)) return CHAM_E_WORKSPACE;
     if (reinterpret_cast<uintptr_t>(workspace) % kAlign) return CHAM_E_WORKSPACE;
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
     unsigned char *ws = static_cast<unsigned char *>(workspace);
@@ -399,7 +432,24 @@ int32_t cham_snap_centroids(const uint8_t *X, int64_t ld, int32_t d, const int64
     a.pick_row = pick_row;
     a.pick_cfg = pick_cfg;
     a.dist_ws = reinterpret_cast<double *>(ws + blob_bytes);
-    e = launch_snap(a, pl.nt, s);
+    a.wg_off = nullptr;
+    a.wide_best = nullptr;
+    a.wide_row = nullptr;
+    if (wide_tasks(pl)) {
+        unsigned char *p = ws + blob_bytes + up(ld * 8);
+        std::vector<uint64_t> wo;
+        const int total = wide_offsets(task_off, T, wo);
+        e = stage_words(wo, reinterpret_cast<uint64_t *>(p), s);
+        if (e != hipSuccess) return hip_fail(e);
+        a.wg_off = reinterpret_cast<const int *>(p);
+        p += up((int64_t)(T + 4) * 4);
+        a.wide_best = reinterpret_cast<unsigned long long *>(p);
+        p += up((int64_t)T * pl.kmax * 8);
+        a.wide_row = reinterpret_cast<int *>(p);
+        e = launch_snap_wide(a, total, s);
+    } else {
+        e = launch_snap(a, pl.nt, s);
+    }
     if (e != hipSuccess) return hip_fail(e);
     return CHAM_OK;
 }
@@ -415,7 +465,7 @@ int64_t cham_synth_workspace_bytes(int64_t ld, int32_t d, const int64_t *task_of
     Plan pl;
     const int32_t rc = check_common(nullptr, ld, d, task_off, T, ks, n_k, false, pl);
     if (rc != CHAM_OK) return rc;
-    return up(((int64_t)pl.blob.size() + synth_blob_extra_words(T, d)) * 8);
+    return up(((int64_t)pl.blob.size() + synth_blob_extra_words(T, d)) * 8) + wide_synth_bytes(pl, d);
 }
 
 int32_t cham_synthesize(const uint8_t *X, int64_t ld, int32_t d, const int64_t *task_off, int32_t T,
@@ -438,7 +488,7 @@ int32_t cham_synthesize(const uint8_t *X, int64_t ld, int32_t d, const int64_t *
     }
     const int64_t base_words = (int64_t)pl.blob.size();
     const int64_t need = up((base_words + synth_blob_extra_words(T, d)) * 8);
-    if (!workspace || workspace_bytes < need) return CHAM_E_WORKSPACE;
+    if (!workspace || workspace_bytes < need + wide_synth_bytes(pl, d)) return CHAM_E_WORKSPACE;
     if (reinterpret_cast<uintptr_t>(workspace) % kAlign) return CHAM_E_WORKSPACE;
     // extend the blob: salts then cards
     pl.blob.resize((size_t)(base_words + synth_blob_extra_words(T, d)), 0);
@@ -477,9 +527,31 @@ int32_t cham_synthesize(const uint8_t *X, int64_t ld, int32_t d, const int64_t *
     a.out_cfg = out_cfg;
     a.out_flag = out_flag;
     a.out_count = out_count;
-    int nt = pl.nt < 256 ? 256 : pl.nt;
-    if (nt > 1024) nt = 1024;
-    e = launch_synth(a, nt, s);
+    a.wg_off = nullptr;
+    a.wide_cmax = cmax;
+    a.wide_slot = a.wide_list = a.wide_nf = nullptr;
+    a.wide_hist = nullptr;
+    if (wide_tasks(pl)) {
+        unsigned char *p = ws + need;
+        std::vector<uint64_t> wo;
+        const int total = wide_offsets(task_off, T, wo);
+        e = stage_words(wo, reinterpret_cast<uint64_t *>(p), s);
+        if (e != hipSuccess) return hip_fail(e);
+        a.wg_off = reinterpret_cast<const int *>(p);
+        p += up((int64_t)(T + 4) * 4);
+        a.wide_slot = reinterpret_cast<int *>(p);
+        p += up((int64_t)T * pl.kmax * 4);
+        a.wide_list = reinterpret_cast<int *>(p);
+        p += up((int64_t)T * pl.kmax * 4);
+        a.wide_nf = reinterpret_cast<int *>(p);
+        p += up((int64_t)T * 4);
+        a.wide_hist = reinterpret_cast<unsigned *>(p);
+        e = launch_synth_wide(a, total, s);
+    } else {
+        int nt = pl.nt < 256 ? 256 : pl.nt;
+        if (nt > 1024) nt = 1024;
+        e = launch_synth(a, nt, s);
+    }
     if (e != hipSuccess) return hip_fail(e);
     return CHAM_OK;
 }

@@ -105,6 +105,10 @@ struct SnapArgs {
     int *pick_row;              // [T][kmax]
     uint8_t *pick_cfg;          // [T][kmax][d]
     double *dist_ws;            // [ld] exact distance of every row to its centroid
+    // wide variant (tasks split over row chunks)
+    const int *wg_off;                  // [T+1] first workgroup of every task
+    unsigned long long *wide_best;      // [T][kmax] smallest distance bits per cluster
+    int *wide_row;                      // [T][kmax] lowest row attaining it
 };
 
 // Arguments of the synthesis kernel.
@@ -130,6 +134,13 @@ struct SynthArgs {
     uint8_t *out_cfg;           // [T][kmax][d]
     uint8_t *out_flag;          // [T][kmax]
     int *out_count;             // [T]
+    // wide variant (tasks split over row chunks)
+    const int *wg_off;          // [T+1] first workgroup of every task
+    int wide_cmax;              // largest cardinality of the batch
+    int *wide_slot;             // [T][kmax] slot of a flagged cluster, -1 otherwise
+    int *wide_list;             // [T][kmax] flagged clusters in ascending order
+    int *wide_nf;               // [T] how many
+    unsigned *wide_hist;        // [T][kmax][d][wide_cmax] value counts of flagged clusters (by slot)
 };
 
 hipError_t launch_first_distinct(const SweepArgs &a, int *init_rows, int *ndist, hipStream_t s);
@@ -142,6 +153,8 @@ hipError_t launch_stream_sweep(const StreamArgs &a, int64_t n_total, int total_w
 hipError_t launch_select_k(const double *inertia, const int *status, int T, int n_k, double thr,
                            int *chosen, hipStream_t s);
 hipError_t launch_snap(const SnapArgs &a, int nt, hipStream_t s);
+hipError_t launch_snap_wide(const SnapArgs &a, int total_wgs, hipStream_t s);
+hipError_t launch_synth_wide(const SynthArgs &a, int total_wgs, hipStream_t s);
 size_t synth_lds_bytes(int d, int kmax, int hist_words);
 hipError_t launch_synth(const SynthArgs &a, int nt, hipStream_t s);
 hipError_t launch_hash_rows(const uint8_t *rows, int64_t n, int d, const uint64_t *salts,

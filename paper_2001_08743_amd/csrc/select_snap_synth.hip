@@ -341,6 +341,366 @@ __global__ void hash_rows_kernel(const uint8_t *rows, int64_t n, int d, const ui
     out[i] = h;
 }
 
+
+// ---------------------------------------------------------------------------------------------
+// Wide variants for tasks too large for one workgroup: the same steps, split over 4096-row chunks
+// with per-cluster minima and value histograms combined through global atomics.
+
+constexpr int kWideRows = 4096;
+
+__device__ __forceinline__ void wide_locate(const int *wg_off, int T, int &t, int &chunk)
+{
+    int lo = 0, hi = T;                        // last task with wg_off[task] <= blockIdx.x
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (wg_off[mid] <= (int)blockIdx.x) lo = mid; else hi = mid;
+    }
+    t = lo;
+    chunk = (int)blockIdx.x - wg_off[lo];
+}
+
+__global__ void snap_wide_init_kernel(const SnapArgs a)
+{
+    const int t = blockIdx.x;
+    for (int c = threadIdx.x; c < a.kmax; c += blockDim.x) {
+        a.pick_row[(int64_t)t * a.kmax + c] = -1;
+        a.wide_best[(int64_t)t * a.kmax + c] = ~0ull;
+        a.wide_row[(int64_t)t * a.kmax + c] = 0x7fffffff;
+    }
+    for (int e = threadIdx.x; e < a.kmax * a.d; e += blockDim.x) a.pick_cfg[(int64_t)t * a.kmax * a.d + e] = 0;
+}
+
+template <int DP, int MAXNT>
+__global__ __launch_bounds__(MAXNT) void snap_wide_assign_kernel(const SnapArgs a)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    SnapLds<DP> U(smem, a.kmax);
+    __shared__ int loc[2];
+    const int tid = threadIdx.x;
+    if (tid == 0) wide_locate(a.wg_off, a.T, loc[0], loc[1]);
+    __syncthreads();
+    const int t = loc[0];
+    const int d = a.d;
+    const int ci = a.chosen[t];
+    if (ci < 0 || ci >= a.n_k) return;
+    const int64_t t0 = a.task_off[t], t1 = a.task_off[t + 1];
+    const int64_t r0 = t0 + (int64_t)loc[1] * kWideRows;
+    const int64_t r1 = r0 + kWideRows < t1 ? r0 + kWideRows : t1;
+    const int k = a.ks[ci];
+    const int kp = k;
+    const int64_t crow = (int64_t)t * a.Ksum + a.koff[ci];
+    const int tile_rows = blockDim.x * kRowsPerThread;
+
+    for (int e = tid; e < DP * kp; e += blockDim.x) U.mu64T[e] = 0.0;
+    for (int c = tid; c < k; c += blockDim.x) U.best[c] = ~0ull;
+    if (tid == 0) *U.m2bits = 0u;
+    __syncthreads();
+    for (int e = tid; e < k * d; e += blockDim.x) {
+        const int c = e / d, j = e % d;
+        U.mu64T[(size_t)j * kp + c] = a.centroids[(crow + c) * d + j];
+    }
+    __syncthreads();
+    if (tid < DP) {
+        float o = 0.0f;
+        if (tid < d) {
+            double s = 0.0;
+            for (int c = 0; c < k; ++c) s += U.mu64T[(size_t)tid * kp + c];
+            double m = rint(s / (double)k);
+            m = m < 0.0 ? 0.0 : (m > 255.0 ? 255.0 : m);
+            o = (float)m;
+        }
+        U.ojf[tid] = o;
+    }
+    __syncthreads();
+    for (int c = tid; c < k; c += blockDim.x) {
+        double b = 0.0;
+        float *w = U.wf + (size_t)c * (DP + 4);
+#pragma unroll
+        for (int j = 0; j < DP; ++j) {
+            const double m = U.mu64T[(size_t)j * kp + c] - (double)U.ojf[j];
+            b = __builtin_fma(m, m, b);
+            w[j] = (float)(-2.0 * m);
+        }
+        w[DP] = (float)b;
+        w[DP + 1] = w[DP + 2] = w[DP + 3] = 0.0f;
+        atomicMax(U.m2bits, __float_as_uint(__double2float_ru(b) * 1.0000005f));
+    }
+    __syncthreads();
+
+    CentroidView L;
+    L.mu64T = U.mu64T;
+    L.wf = U.wf;
+    L.ojf = U.ojf;
+    L.m2 = __uint_as_float(*U.m2bits);
+    L.kp = kp;
+    L.k = k;
+    const bool force_exact = (a.flags & 1) != 0;
+    const int64_t g0 = r0 & ~(int64_t)3;
+    const int ntiles = (int)((r1 - g0 + tile_rows - 1) / tile_rows);
+    for (int tile = 0; tile < ntiles; ++tile) {
+        const int64_t g = g0 + (int64_t)tile * tile_rows + (int64_t)tid * kRowsPerThread;
+        const bool in_range = g < r1;
+        uint32_t rowmask = 0;
+#pragma unroll
+        for (int p = 0; p < 4; ++p)
+            if (g + p >= r0 && g + p < r1) rowmask |= 1u << p;
+        float xf[4][DP];
+        float x2[4];
+        load_rows<DP>(a.X, a.ld, d, g, in_range, U.ojf, xf, x2);
+        int lab[4];
+        double dist[4] = {0.0, 0.0, 0.0, 0.0};
+        assign_rows<DP>(xf, x2, rowmask, L, force_exact, true, lab, dist);
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+            if (!((rowmask >> p) & 1u)) continue;
+            a.labels_sel[g + p] = (uint8_t)lab[p];
+            a.dist_ws[g + p] = dist[p];
+            atomicMin(&U.best[lab[p]], (unsigned long long)__double_as_longlong(dist[p]));
+        }
+    }
+    __syncthreads();
+    for (int c = tid; c < k; c += blockDim.x)
+        if (U.best[c] != ~0ull) atomicMin(&a.wide_best[(int64_t)t * a.kmax + c], U.best[c]);
+}
+
+__global__ void snap_wide_pick_kernel(const SnapArgs a)
+{
+    __shared__ int loc[2];
+    __shared__ int brow[256];
+    const int tid = threadIdx.x;
+    if (tid == 0) wide_locate(a.wg_off, a.T, loc[0], loc[1]);
+    for (int c = tid; c < 256; c += blockDim.x) brow[c] = 0x7fffffff;
+    __syncthreads();
+    const int t = loc[0];
+    const int ci = a.chosen[t];
+    if (ci < 0 || ci >= a.n_k) return;
+    const int k = a.ks[ci];
+    const int64_t t0 = a.task_off[t], t1 = a.task_off[t + 1];
+    const int64_t r0 = t0 + (int64_t)loc[1] * kWideRows;
+    const int64_t r1 = r0 + kWideRows < t1 ? r0 + kWideRows : t1;
+    for (int64_t r = r0 + tid; r < r1; r += blockDim.x) {
+        const int c = a.labels_sel[r];
+        if ((unsigned long long)__double_as_longlong(a.dist_ws[r]) == a.wide_best[(int64_t)t * a.kmax + c])
+            atomicMin(&brow[c], (int)(r - t0));
+    }
+    __syncthreads();
+    for (int c = tid; c < k; c += blockDim.x)
+        if (brow[c] != 0x7fffffff) atomicMin(&a.wide_row[(int64_t)t * a.kmax + c], brow[c]);
+}
+
+__global__ void snap_wide_finish_kernel(const SnapArgs a)
+{
+    const int t = blockIdx.x;
+    const int ci = a.chosen[t];
+    if (ci < 0 || ci >= a.n_k) return;
+    const int k = a.ks[ci];
+    const int d = a.d;
+    const int64_t t0 = a.task_off[t];
+    for (int e = threadIdx.x; e < k * d; e += blockDim.x) {
+        const int c = e / d, j = e % d;
+        const int row = a.wide_row[(int64_t)t * a.kmax + c];
+        if (row != 0x7fffffff) {
+            a.pick_cfg[((int64_t)t * a.kmax + c) * d + j] = a.X[(int64_t)j * a.ld + t0 + row];
+            if (j == 0) a.pick_row[(int64_t)t * a.kmax + c] = row;
+        }
+    }
+}
+
+// Synthesis, wide: flag picks (one workgroup per task), value histograms of the flagged clusters
+// over row chunks, then modes and the ordered accept / drop per task.
+__global__ __launch_bounds__(256) void synth_wide_flag_kernel(const SynthArgs a)
+{
+    __shared__ int nf_sh;
+    const int tid = threadIdx.x;
+    const int t = blockIdx.x;
+    const int d = a.d, kmax = a.kmax;
+    const int64_t r0 = a.task_off[t];
+    const int ci = a.chosen[t];
+    const int k = (ci >= 0 && ci < a.n_k) ? a.ks[ci] : 0;
+    const uint64_t salt = a.salts[t];
+    uint8_t *ocfg = a.out_cfg + (int64_t)t * kmax * d;
+    uint8_t *oflag = a.out_flag + (int64_t)t * kmax;
+    int *slot_of = a.wide_slot + (int64_t)t * kmax;
+    for (int e = tid; e < kmax * d; e += blockDim.x) ocfg[e] = 0;
+    for (int c = tid; c < kmax; c += blockDim.x) {
+        int f = 0;
+        slot_of[c] = -1;
+        if (c < k) {
+            const int row = a.pick_row[(int64_t)t * kmax + c];
+            if (row >= 0) {
+                const uint8_t *pc = a.pick_cfg + ((int64_t)t * kmax + c) * d;
+                uint64_t h = fnv_begin(salt);
+                for (int j = 0; j < d; ++j) h = fnv_step(h, pc[j]);
+                const bool invalid = a.valid && a.valid[r0 + row] == 0;
+                f = (invalid || visited_has(a.visited, a.n_visited, h)) ? 3 : 1;
+            }
+        }
+        oflag[c] = (uint8_t)f;
+    }
+    __syncthreads();
+    for (int c = tid; c < k; c += blockDim.x) {
+        if (oflag[c] == 1) {
+            const uint8_t *pc = a.pick_cfg + ((int64_t)t * kmax + c) * d;
+            for (int j = 0; j < d; ++j) ocfg[c * d + j] = pc[j];
+        }
+    }
+    if (tid == 0) {
+        int nf = 0;
+        for (int c = 0; c < k; ++c)
+            if (oflag[c] == 3) {
+                a.wide_list[(int64_t)t * kmax + nf] = c;
+                slot_of[c] = nf++;
+            }
+        a.wide_nf[t] = nf;
+        nf_sh = nf;
+    }
+    __syncthreads();
+    const int64_t words = (int64_t)nf_sh * d * a.wide_cmax;
+    unsigned *hist = a.wide_hist + (int64_t)t * kmax * d * a.wide_cmax;
+    for (int64_t e = tid; e < words; e += blockDim.x) hist[e] = 0u;
+}
+
+__global__ __launch_bounds__(1024) void synth_wide_hist_kernel(const SynthArgs a)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    unsigned *lh = reinterpret_cast<unsigned *>(smem);
+    __shared__ int loc[2];
+    const int tid = threadIdx.x;
+    if (tid == 0) wide_locate(a.wg_off, a.T, loc[0], loc[1]);
+    __syncthreads();
+    const int t = loc[0];
+    const int nf = a.wide_nf[t];
+    if (nf == 0) return;
+    const int d = a.d, kmax = a.kmax, cmax = a.wide_cmax;
+    const int64_t t0 = a.task_off[t], t1 = a.task_off[t + 1];
+    const int64_t r0 = t0 + (int64_t)loc[1] * kWideRows;
+    const int64_t r1 = r0 + kWideRows < t1 ? r0 + kWideRows : t1;
+    const int *slot_of = a.wide_slot + (int64_t)t * kmax;
+    unsigned *hist = a.wide_hist + (int64_t)t * kmax * d * cmax;
+    const uint16_t *card = a.cards + (int64_t)t * d;
+    int tcmax = 1;                             // values at or above the task's largest cardinality are not counted
+    for (int j = 0; j < d; ++j) tcmax = card[j] > tcmax ? card[j] : tcmax;
+    const int per_cluster = d * cmax;
+    const int chunk = a.hist_words / per_cluster;
+    for (int f0 = 0; f0 < nf; f0 += chunk) {
+        const int fn = (nf - f0) < chunk ? (nf - f0) : chunk;
+        for (int e = tid; e < fn * per_cluster; e += blockDim.x) lh[e] = 0u;
+        __syncthreads();
+        for (int64_t r = r0 + tid; r < r1; r += blockDim.x) {
+            const int s = slot_of[a.labels_sel[r]] - f0;
+            if (s < 0 || s >= fn) continue;
+            if (a.valid && a.valid[r] == 0) continue;
+            unsigned *hrow = lh + (size_t)s * per_cluster;
+            for (int j = 0; j < d; ++j) {
+                const unsigned v = a.X[(int64_t)j * a.ld + r];
+                if (v < (unsigned)tcmax) atomicAdd(&hrow[j * cmax + v], 1u);
+            }
+        }
+        __syncthreads();
+        for (int e = tid; e < fn * per_cluster; e += blockDim.x) {
+            const unsigned v = lh[e];
+            if (v) atomicAdd(&hist[(size_t)f0 * per_cluster + e], v);
+        }
+        __syncthreads();
+    }
+}
+
+__global__ __launch_bounds__(256) void synth_wide_finish_kernel(const SynthArgs a)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int tid = threadIdx.x;
+    const int t = blockIdx.x;
+    const int d = a.d, kmax = a.kmax, cmax = a.wide_cmax;
+    const int ci = a.chosen[t];
+    const int k = (ci >= 0 && ci < a.n_k) ? a.ks[ci] : 0;
+    const int nf = a.wide_nf[t];
+    const uint64_t salt = a.salts[t];
+    const uint16_t *card = a.cards + (int64_t)t * d;
+    uint8_t *ocfg = a.out_cfg + (int64_t)t * kmax * d;
+    uint8_t *oflag = a.out_flag + (int64_t)t * kmax;
+    const int *flagged = a.wide_list + (int64_t)t * kmax;
+    const unsigned *hist = a.wide_hist + (int64_t)t * kmax * d * cmax;
+    uint8_t *cfg = smem;                       // [kmax][d]
+    uint8_t *mode = cfg + (size_t)kmax * d;    // [kmax][d]
+    uint8_t *fl = mode + (size_t)kmax * d;     // [kmax]
+    uint8_t *hasv = fl + kmax;                 // [kmax]
+    for (int e = tid; e < kmax * d; e += blockDim.x) cfg[e] = ocfg[e];
+    for (int c = tid; c < kmax; c += blockDim.x) {
+        fl[c] = oflag[c];
+        hasv[c] = 0;
+    }
+    __syncthreads();
+    int tcmax = 1;
+    for (int j = 0; j < d; ++j) tcmax = card[j] > tcmax ? card[j] : tcmax;
+    for (int e = tid; e < nf * d; e += blockDim.x) {
+        const int q = e / d, j = e % d;
+        const unsigned *hv = hist + ((size_t)q * d + j) * cmax;
+        int bv = 0;
+        unsigned bc = hv[0], total = hv[0];
+        for (int v = 1; v < tcmax; ++v) {
+            total += hv[v];
+            if (v < card[j] && hv[v] > bc) {
+                bc = hv[v];
+                bv = v;
+            }
+        }
+        const int c = flagged[q];
+        mode[c * d + j] = (uint8_t)bv;
+        if (j == 0) hasv[c] = total > 0 ? 1 : 0;
+    }
+    __syncthreads();
+    if (tid < kWave) {
+        const int lane = tid;
+        for (int f = 0; f < nf; ++f) {
+            const int c = flagged[f];
+            if (!hasv[c]) continue;
+            const uint8_t *m = mode + c * d;
+            bool dup = false;
+            for (int q = lane; q < k; q += kWave) {
+                const int fq = fl[q];
+                if (fq == 1 || (fq == 2 && q < c)) {
+                    bool same = true;
+                    for (int j = 0; j < d && same; ++j) same = cfg[q * d + j] == m[j];
+                    dup = dup || same;
+                }
+            }
+            uint64_t h = fnv_begin(salt);
+            for (int j = 0; j < d; ++j) h = fnv_step(h, m[j]);
+            const bool vis = visited_has(a.visited, a.n_visited, h);
+            const bool any_dup = __ballot(dup) != 0ull;
+            if (!vis && !any_dup) {
+                if (lane == 0) fl[c] = 2;
+                for (int j = lane; j < d; j += kWave) cfg[c * d + j] = m[j];
+            }
+            __builtin_amdgcn_wave_barrier();
+            __threadfence_block();
+        }
+    }
+    __syncthreads();
+    for (int e = tid; e < kmax * d; e += blockDim.x) ocfg[e] = cfg[e];
+    for (int c = tid; c < kmax; c += blockDim.x) oflag[c] = fl[c];
+    if (tid == 0) {
+        int cnt = 0;
+        for (int c = 0; c < k; ++c) cnt += (fl[c] == 1 || fl[c] == 2) ? 1 : 0;
+        a.out_count[t] = cnt;
+    }
+}
+
+template <int DP, int MAXNT>
+hipError_t launch_snap_wide_dp(const SnapArgs &a, int total_wgs, hipStream_t s)
+{
+    const size_t lds = resident_lds_bytes(DP, a.kmax);
+    auto kern = snap_wide_assign_kernel<DP, MAXNT>;
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(snap_wide_init_kernel, dim3(a.T), dim3(256), 0, s, a);
+    hipLaunchKernelGGL(kern, dim3(total_wgs), dim3(MAXNT), lds, s, a);
+    hipLaunchKernelGGL(snap_wide_pick_kernel, dim3(total_wgs), dim3(1024), 0, s, a);
+    hipLaunchKernelGGL(snap_wide_finish_kernel, dim3(a.T), dim3(256), 0, s, a);
+    return hipGetLastError();
+}
+
 template <int DP, int MAXNT>
 hipError_t launch_snap_dp(const SnapArgs &a, int nt, hipStream_t s)
 {
@@ -375,6 +735,32 @@ hipError_t launch_snap(const SnapArgs &a, int nt, hipStream_t s)
     if (d <= 24) return launch_snap_dp<24, 1024>(a, nt, s);
     if (d <= 28) return launch_snap_dp<28, 512>(a, nt, s);
     return launch_snap_dp<32, 512>(a, nt, s);
+}
+
+hipError_t launch_snap_wide(const SnapArgs &a, int total_wgs, hipStream_t s)
+{
+    const int d = a.d;
+    if (d <= 4) return launch_snap_wide_dp<4, 1024>(a, total_wgs, s);
+    if (d <= 8) return launch_snap_wide_dp<8, 1024>(a, total_wgs, s);
+    if (d <= 12) return launch_snap_wide_dp<12, 1024>(a, total_wgs, s);
+    if (d <= 16) return launch_snap_wide_dp<16, 1024>(a, total_wgs, s);
+    if (d <= 20) return launch_snap_wide_dp<20, 1024>(a, total_wgs, s);
+    if (d <= 24) return launch_snap_wide_dp<24, 1024>(a, total_wgs, s);
+    if (d <= 28) return launch_snap_wide_dp<28, 512>(a, total_wgs, s);
+    return launch_snap_wide_dp<32, 512>(a, total_wgs, s);
+}
+
+hipError_t launch_synth_wide(const SynthArgs &a, int total_wgs, hipStream_t s)
+{
+    const size_t lds_hist = sizeof(unsigned) * (size_t)a.hist_words;
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(synth_wide_hist_kernel),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_hist);
+    if (e != hipSuccess) return e;
+    const size_t lds_fin = (size_t)a.kmax * a.d * 2 + (size_t)a.kmax * 2 + 16;
+    hipLaunchKernelGGL(synth_wide_flag_kernel, dim3(a.T), dim3(256), 0, s, a);
+    hipLaunchKernelGGL(synth_wide_hist_kernel, dim3(total_wgs), dim3(1024), lds_hist, s, a);
+    hipLaunchKernelGGL(synth_wide_finish_kernel, dim3(a.T), dim3(256), lds_fin, s, a);
+    return hipGetLastError();
 }
 
 size_t synth_lds_bytes(int d, int kmax, int hist_words)

@@ -314,3 +314,20 @@ def test_streaming_path_with_too_few_distinct_rows():
     wl.ks, wl.n_iter = [2, 6, 9], 4
     out, ref = _sweep_only(wl, binding.F_STREAMING)
     assert ref["status"][0, 2] == 1
+
+
+# ------------------------------------------------------------------ snap / synthesis over row chunks
+
+@pytest.mark.parametrize("seed,d,card_hi,ks", [(501, 7, 6, (8, 24, 60)), (502, 16, 64, (32, 256)),
+                                               (503, 3, 3, (2, 5))])
+def test_large_tasks_snap_and_synthesis_over_chunks(seed, d, card_hi, ks):
+    """Tasks above 16384 rows take the chunked snap and synthesis kernels; invalid rows and a
+    well-filled visited set make sure picks are flagged, replaced and dropped."""
+    wl = workloads.random_task(seed, n=41001, d=d, card_hi=card_hi, n_blobs=max(ks) // 2 + 1, sigma=1.5,
+                               invalid_frac=0.45, ks=ks, n_iter=4, n_visited=30000, n_tasks=3, ragged=True)
+    assert np.diff(wl.task_off).max() > 16384
+    dw, g, c = run_both(wl)
+    check_sweep(wl, g["sweep"], c, dw.ld)
+    check_pipeline(wl, g, c)
+    flags = c["out_flag"]
+    assert (flags == oracle.DROPPED).any() or (flags == oracle.SYNTH).any()
