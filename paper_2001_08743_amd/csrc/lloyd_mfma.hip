@@ -40,7 +40,7 @@ template <int DK>
 struct MfmaLds {
     double *mu64T;      // [DK][KP]   exact centroids, transposed
     double *red;        // [16]       per-wave partial sums of the loss
-    double *bpart;      // [KP][8]    partial sums of |mu - o|^2 per group of 4 knobs
+    float *bias;        // [KP]       upper bound of |mu - o|^2 per centroid (0 for padding rows)
     half8 *afrag;       // [KP/32][2*DK/16][64]  A fragments: hi parts then lo parts
     int *S;             // [KP][DK]   integer cluster sums
     int *n;             // [KP]       cluster sizes
@@ -51,7 +51,7 @@ struct MfmaLds {
         ((size_t)kRecCap * DK * 2 + 512 * 8 + 512 * 2 + 512 + 512 * 4 + 15) / 16 * 16;
     __host__ __device__ static size_t bytes(int KP, int nwaves)
     {
-        size_t b = sizeof(double) * DK * KP + sizeof(double) * 16 + sizeof(double) * KP * 8;
+        size_t b = sizeof(double) * DK * KP + sizeof(double) * 16 + sizeof(float) * KP;
         b += 16 * (size_t)(KP / 32) * (2 * DK / 16) * 64;
         b += sizeof(int) * (size_t)KP * DK + sizeof(int) * KP * 2 + sizeof(float) * DK;
         b = (b + 15) & ~(size_t)15;
@@ -63,7 +63,7 @@ struct MfmaLds {
         size_t o = 0;
         mu64T = reinterpret_cast<double *>(base + o);  o += sizeof(double) * DK * KP;
         red = reinterpret_cast<double *>(base + o);    o += sizeof(double) * 16;
-        bpart = reinterpret_cast<double *>(base + o);  o += sizeof(double) * KP * 8;
+        bias = reinterpret_cast<float *>(base + o);    o += sizeof(float) * KP;
         afrag = reinterpret_cast<half8 *>(base + o);   o += 16 * (size_t)(KP / 32) * (2 * DK / 16) * 64;
         S = reinterpret_cast<int *>(base + o);         o += sizeof(int) * (size_t)KP * DK;
         n = reinterpret_cast<int *>(base + o);         o += sizeof(int) * KP;
@@ -94,8 +94,9 @@ struct WaveQueue {
     __device__ float *x2() const { return reinterpret_cast<float *>(base + kOffX2); }                     // [kRows]
 };
 
-// Resolve the queued rows of this wave: one row per lane, exact double distances to its marked
-// centroids (four at a time, knobs ascending, no fused multiply-add), lowest index on ties.
+// Resolve the queued rows of this wave: four lanes per row, each lane takes every fourth marked
+// centroid of its row and evaluates the exact double distance (knobs ascending, no fused
+// multiply-add); the four lanes then agree on the smallest distance, lowest index on ties.
 // xh_wave points at the packed f16 copy of the wave's first row (uncentred values).
 template <int DK>
 __device__ __forceinline__ void resolve_queue(const WaveQueue<DK> &Q, int nrec, const double *mu64T,
@@ -103,70 +104,80 @@ __device__ __forceinline__ void resolve_queue(const WaveQueue<DK> &Q, int nrec, 
                                               const _Float16 *xh_wave)
 {
     const int lane = threadIdx.x & 63;
+    const int q = lane & 3;
     __builtin_amdgcn_wave_barrier();
-    for (int r = lane; r < nrec; r += 64) {
-        unsigned rem0 = Q.rec_mask()[r * 2 + 0], rem1 = Q.rec_mask()[r * 2 + 1];
-        const int pid = Q.rec_pid()[r];
+    for (int r0 = 0; r0 < nrec; r0 += 16) {
+        const int r = r0 + (lane >> 2);
+        const bool have = r < nrec;
+        const int rr = have ? r : 0;
+        unsigned rem0 = 0, rem1 = 0;
+        if (have) {
+            rem0 = Q.rec_mask()[r * 2 + 0];
+            rem1 = Q.rec_mask()[r * 2 + 1];
+        }
+        const int pid = Q.rec_pid()[rr];
+        // next marked centroid of the row, -1 when none is left
+        auto pop = [&]() -> int {
+            int c = -1;
+            if (rem0) {
+                const int b = __clz((int)rem0);
+                rem0 &= ~(0x80000000u >> b);
+                c = centroid_of(b, 0);
+            } else if (rem1) {
+                const int b = __clz((int)rem1);
+                rem1 &= ~(0x80000000u >> b);
+                c = centroid_of(b, 1);
+            }
+            return c;
+        };
+        for (int i = 0; i < q; ++i) pop();
         double bs = __builtin_inf();
         int bc = 0x7fffffff;
-        while (rem0 | rem1) {
-            int cc[4];
-            double ss[4];
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                cc[q] = -1;
-                ss[q] = 0.0;
-                if (rem0) {
-                    const int b = __clz((int)rem0);
-                    rem0 &= ~(0x80000000u >> b);
-                    cc[q] = centroid_of(b, 0);
-                } else if (rem1) {
-                    const int b = __clz((int)rem1);
-                    rem1 &= ~(0x80000000u >> b);
-                    cc[q] = centroid_of(b, 1);
-                }
-            }
-            int ci[4];
-#pragma unroll
-            for (int q = 0; q < 4; ++q) ci[q] = cc[q] < 0 ? 0 : cc[q];
-            // knobs in groups of 8 (padded knobs are zero in x and in the centroids, so they add an
-            // exact zero); the loads of a group are independent and overlap
+        while (__ballot((rem0 | rem1) != 0u)) {
+            const int cc = pop();
+            const int ci = cc < 0 ? 0 : cc;
+            double ss = 0.0;
+            // knobs in groups of 8; the loads of a group are independent and overlap
             for (int j0 = 0; j0 < d; j0 += 8) {
                 half8 xq;
-                if (r < kRecCap) {
-                    xq = *reinterpret_cast<const half8 *>(Q.rec_x() + (size_t)r * DK + j0);
+                if (rr < kRecCap) {
+                    xq = *reinterpret_cast<const half8 *>(Q.rec_x() + (size_t)rr * DK + j0);
                 } else {
                     xq = *reinterpret_cast<const half8 *>(xh_wave + (size_t)pid * DK + j0);
                 }
                 const float4 oa = *reinterpret_cast<const float4 *>(ojf + j0);
                 const float4 ob = *reinterpret_cast<const float4 *>(ojf + j0 + 4);
                 const float of[8] = {oa.x, oa.y, oa.z, oa.w, ob.x, ob.y, ob.z, ob.w};
-                double mu[8][4];
+                double mu[8];
 #pragma unroll
-                for (int i = 0; i < 8; ++i)
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) mu[i][q] = mu64T[(size_t)(j0 + i) * KP + ci[q]];
+                for (int i = 0; i < 8; ++i) mu[i] = mu64T[(size_t)(j0 + i) * KP + ci];
 #pragma unroll
                 for (int i = 0; i < 8; ++i) {
-                    float xf = r < kRecCap ? (float)xq[i] + of[i] : (float)xq[i];
-                    if (j0 + i >= d) xf = 0.0f;          // padded knobs (one of them carries the bias)
-                    const double xv = (double)xf;
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        const double tq = xv - mu[i][q];
-                        ss[q] = ss[q] + tq * tq;
-                    }
+                    // queued copies are centred; padded knobs are skipped (one of them carries the bias)
+                    float xf = rr < kRecCap ? (float)xq[i] + of[i] : (float)xq[i];
+                    if (j0 + i >= d) xf = 0.0f;
+                    const double tq = (double)xf - mu[i];
+                    ss = ss + tq * tq;
                 }
             }
+            if (cc >= 0 && (ss < bs || (ss == bs && cc < bc))) {
+                bs = ss;
+                bc = cc;
+            }
+            pop();
+            pop();
+            pop();
+        }
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                if (cc[q] >= 0 && (ss[q] < bs || (ss[q] == bs && cc[q] < bc))) {
-                    bs = ss[q];
-                    bc = cc[q];
-                }
+        for (int off = 1; off <= 2; off <<= 1) {
+            const double os = __shfl_xor(bs, off, 64);
+            const int oc = __shfl_xor(bc, off, 64);
+            if (os < bs || (os == bs && oc < bc)) {
+                bs = os;
+                bc = oc;
             }
         }
-        Q.lab_res()[pid] = (unsigned char)(bc < k ? bc : 0);
+        if (have && q == 0) Q.lab_res()[pid] = (unsigned char)(bc < k ? bc : 0);
     }
     __builtin_amdgcn_wave_barrier();
 }
@@ -239,43 +250,61 @@ __device__ __forceinline__ void apply_changes(const WaveQueue<DK> &Q, int cnt, i
 
 // Centroid update for the clusters touched in this pass, all threads: item (c, q) owns knobs
 // 4q..4q+3 of centroid c: mean = (double)S / (double)n, then the f16 hi/lo fragments of
-// w = -2 (mu - o) (one 8-byte store each) and the partial sum of (mu - o)^2.  The last knob
-// slot (the bias slot) is left zero here; each wave fills it in its register copy.
+// w = -2 (mu - o) (one 8-byte store each).  The DK/4 items of a centroid sit in adjacent lanes and
+// add up |mu - o|^2 among themselves; the last of them owns the bias slot (knob slot DK - 1) and
+// stores the sum / 256 there as hi/lo, and its rounded-up value for the error bound.
 template <int DK>
 __device__ __forceinline__ void update_centroids(const MfmaLds<DK> &U, int k, int KP, int d, int stamp, bool all)
 {
     constexpr int NS = DK / 16, NS2 = 2 * NS, QN = DK / 4;
     typedef _Float16 half4 __attribute__((ext_vector_type(4)));
-    for (int item = threadIdx.x; item < k * QN; item += blockDim.x) {
+    const int items = k * QN;
+    for (int base = 0; base < items; base += blockDim.x) {      // uniform trip count: every lane shuffles
+        const int item = base + (int)threadIdx.x;
         const int c = item / QN, q = item % QN;
-        if (4 * q >= d) continue;
-        if (!all && U.dirty[c] != stamp) continue;
-        const int cnt = U.n[c];
-        if (!all && cnt == 0) continue;          // an empty cluster keeps its centroid
-        half4 hi4, lo4;
-        double b = 0.0;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int j = 4 * q + i;
-            double mu = U.mu64T[(size_t)j * KP + c];
-            if (!all && j < d) {
-                mu = (double)U.S[c * DK + j] / (double)cnt;
-                U.mu64T[(size_t)j * KP + c] = mu;
-            }
-            const double m = j < d ? mu - (double)U.ojf[j] : 0.0;
-            b = __builtin_fma(m, m, b);
-            const float w = (float)(-2.0 * m);
-            const _Float16 hi = (_Float16)w;
-            hi4[i] = hi;
-            lo4[i] = (_Float16)(w - (float)hi);
+        bool act = item < items;
+        int cnt = 0;
+        if (act) {
+            cnt = U.n[c];
+            if (!all && (U.dirty[c] != stamp || cnt == 0)) act = false;   // an empty cluster keeps its centroid
         }
-        const int mt = c >> 5, m32 = c & 31;
-        const int g = q >> 1, hh = g & 1, fstep = g >> 1, sub = q & 1;
-        half4 *fh = reinterpret_cast<half4 *>(U.afrag + (mt * NS2 + fstep) * 64 + 32 * hh + m32) + sub;
-        half4 *fl = reinterpret_cast<half4 *>(U.afrag + (mt * NS2 + NS + fstep) * 64 + 32 * hh + m32) + sub;
-        *fh = hi4;
-        *fl = lo4;
-        U.bpart[c * 8 + q] = b;
+        half4 hi4 = {(_Float16)0.0f, (_Float16)0.0f, (_Float16)0.0f, (_Float16)0.0f};
+        half4 lo4 = hi4;
+        double b = 0.0;
+        if (act && 4 * q < d) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int j = 4 * q + i;
+                double mu = U.mu64T[(size_t)j * KP + c];
+                if (!all && j < d) {
+                    mu = (double)U.S[c * DK + j] / (double)cnt;
+                    U.mu64T[(size_t)j * KP + c] = mu;
+                }
+                const double m = j < d ? mu - (double)U.ojf[j] : 0.0;
+                b = __builtin_fma(m, m, b);
+                const float w = (float)(-2.0 * m);
+                const _Float16 hi = (_Float16)w;
+                hi4[i] = hi;
+                lo4[i] = (_Float16)(w - (float)hi);
+            }
+        }
+#pragma unroll
+        for (int off = 1; off < QN; off <<= 1) b = b + __shfl_xor(b, off, 64);
+        if (act && (4 * q < d || q == QN - 1)) {
+            if (q == QN - 1) {
+                const float bs = (float)b * (1.0f / kBiasScale);
+                const _Float16 bhi = (_Float16)bs;
+                hi4[3] = bhi;
+                lo4[3] = (_Float16)(bs - (float)bhi);
+                U.bias[c] = __double2float_ru(b) * 1.0000005f;
+            }
+            const int mt = c >> 5, m32 = c & 31;
+            const int g = q >> 1, hh = g & 1, fstep = g >> 1, sub = q & 1;
+            half4 *fh = reinterpret_cast<half4 *>(U.afrag + (mt * NS2 + fstep) * 64 + 32 * hh + m32) + sub;
+            half4 *fl = reinterpret_cast<half4 *>(U.afrag + (mt * NS2 + NS + fstep) * 64 + 32 * hh + m32) + sub;
+            *fh = hi4;
+            *fl = lo4;
+        }
     }
 }
 
@@ -319,7 +348,7 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
         U.n[c] = 0;
         U.dirty[c] = -1;
     }
-    for (int e = tid; e < KP * 8; e += blockDim.x) U.bpart[e] = 0.0;
+    for (int c = tid; c < KP; c += blockDim.x) U.bias[c] = 0.0f;
     {
         half8 z;
 #pragma unroll
@@ -327,6 +356,11 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
         for (int e = tid; e < (KP / 32) * NS2 * 64; e += blockDim.x) U.afrag[e] = z;
     }
     __syncthreads();
+    // padding centroid rows (beyond k) carry a huge bias so that they never win
+    for (int c = k + tid; c < KP; c += blockDim.x) {
+        _Float16 *slot = reinterpret_cast<_Float16 *>(U.afrag + ((c >> 5) * NS2 + bstep) * 64 + 32 * bhalf + (c & 31)) + belem;
+        *slot = (_Float16)kPadBiasHi;
+    }
     for (int e = tid; e < k * d; e += blockDim.x) {
         const int c = e / d, j = e % d;
         double v;
@@ -407,7 +441,7 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
 
     double loss = 0.0;
 #ifdef CHAM_KERNEL_TIMING
-    unsigned long long tacc[10] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+    unsigned long long tacc[16] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
 #endif
     for (int it = 0; it <= a.n_iter; ++it) {
         const bool final_pass = (it == a.n_iter);
@@ -421,48 +455,19 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
         int nrec = 0;
 
         if (wave_live) {
-            // A fragments of this pass, the bias slot filled in from the partial sums, and the
-            // bound m2 (every wave for itself)
+            // A fragments of this pass (the bias slot included) and the bound m2
             half8 A0[NS2], A1[NS2];
 #pragma unroll
             for (int s = 0; s < NS2; ++s) {
                 A0[s] = U.afrag[s * 64 + lane];
                 A1[s] = two ? U.afrag[(NS2 + s) * 64 + lane] : A0[s];
             }
-            float m2 = 0.0f;
-#pragma unroll
-            for (int mt = 0; mt < 2; ++mt) {
-                if (mt == 1 && !two) break;
-                const int c = 32 * mt + n32;
-                _Float16 bhi = (_Float16)kPadBiasHi, blo = (_Float16)0.0f;
-                if (c < k) {
-                    double b = U.bpart[c * 8];
-#pragma unroll
-                    for (int q = 1; q < 8; ++q) b = b + U.bpart[c * 8 + q];
-                    const float bs = (float)b * (1.0f / kBiasScale);
-                    bhi = (_Float16)bs;
-                    blo = (_Float16)(bs - (float)bhi);
-                    m2 = __builtin_fmaxf(m2, __double2float_ru(b) * 1.0000005f);
-                }
-                if (h == bhalf) {
-#pragma unroll
-                    for (int s = 0; s < NS; ++s)
-#pragma unroll
-                        for (int i = 0; i < 8; ++i)
-                            if (s == bstep && i == belem) {
-                                if (mt == 0) {
-                                    A0[s][i] = bhi;
-                                    A0[NS + s][i] = blo;
-                                } else {
-                                    A1[s][i] = bhi;
-                                    A1[NS + s][i] = blo;
-                                }
-                            }
-                }
-            }
+            float m2 = lane < KP ? U.bias[lane] : 0.0f;
 #pragma unroll
             for (int off = 32; off >= 1; off >>= 1) m2 = __builtin_fmaxf(m2, __shfl_xor(m2, off, 64));
 
+            CHAM_T(t_a2);
+            CHAM_TADD(10, t_a, t_a2);   // pass prologue (inside "tiles")
             float16v accA, accB;
             const float16v zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 
@@ -589,6 +594,7 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
         CHAM_T(t_b);
         CHAM_TCOUNT(8, nrec);
         if (nrec) resolve_queue<DK>(Q, nrec, U.mu64T, U.ojf, KP, k, d, xh_wave);
+        CHAM_TCOUNT(11, nrec ? 1 : 0);
         CHAM_T(t_c);
 
         // Labels of the rows that went through the queue replace their placeholders.
@@ -647,7 +653,11 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
                     }
                 }
                 CHAM_TCOUNT(7, cnt);
+                CHAM_T(t_p0);
                 if (cnt) apply_changes<DK>(Q, cnt, U.S, U.n, U.dirty, U.ojf, d, it);
+                CHAM_T(t_p1);
+                CHAM_TADD(12, t_p0, t_p1);   // apply (inside "sums")
+                CHAM_TCOUNT(13, cnt ? 1 : 0);
                 start = next_start;
             }
 #pragma unroll
@@ -704,7 +714,7 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
 
 #ifdef CHAM_KERNEL_TIMING
     if (lane == 0)
-        for (int q = 0; q < 10; ++q) atomicAdd(&g_timing[q], tacc[q]);
+        for (int q = 0; q < 16; ++q) atomicAdd(&g_timing[q], tacc[q]);
 #endif
     for (int e = tid; e < k * d; e += blockDim.x) {
         const int c = e / d, j = e % d;
