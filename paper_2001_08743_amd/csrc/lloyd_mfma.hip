@@ -46,14 +46,15 @@ struct MfmaLds {
     int *n;             // [KP]       cluster sizes
     int *dirty;         // [KP]       pass in which the cluster last changed
     float *ojf;         // [DK]       centring offsets
+    int *upd_stamp;     // [1]        1 + pass whose update last rewrote a centroid
     unsigned char *wave_base;   // per-wave regions follow
     static constexpr size_t kWaveBytes =
-        ((size_t)kRecCap * DK * 2 + 512 * 8 + 512 * 2 + 512 + 512 * 4 + 15) / 16 * 16;
+        ((size_t)kRecCap * DK * 2 + 512 * 8 + 512 * 2 + 512 + 512 * 4 + 512 * 4 + 15) / 16 * 16;
     __host__ __device__ static size_t bytes(int KP, int nwaves)
     {
         size_t b = sizeof(double) * DK * KP + sizeof(double) * 16 + sizeof(float) * KP;
         b += 16 * (size_t)(KP / 32) * (2 * DK / 16) * 64;
-        b += sizeof(int) * (size_t)KP * DK + sizeof(int) * KP * 2 + sizeof(float) * DK;
+        b += sizeof(int) * (size_t)KP * DK + sizeof(int) * KP * 2 + sizeof(float) * DK + 16;
         b = (b + 15) & ~(size_t)15;
         return b + kWaveBytes * nwaves;
     }
@@ -69,6 +70,7 @@ struct MfmaLds {
         n = reinterpret_cast<int *>(base + o);         o += sizeof(int) * KP;
         dirty = reinterpret_cast<int *>(base + o);     o += sizeof(int) * KP;
         ojf = reinterpret_cast<float *>(base + o);     o += sizeof(float) * DK;
+        upd_stamp = reinterpret_cast<int *>(base + o); o += 16;
         o = (o + 15) & ~(size_t)15;
         wave_base = base + o;
     }
@@ -91,7 +93,8 @@ struct WaveQueue {
     __device__ unsigned *rec_mask() const { return reinterpret_cast<unsigned *>(base + kOffMask); }      // [kRows][2]
     __device__ unsigned short *rec_pid() const { return reinterpret_cast<unsigned short *>(base + kOffPid); }
     __device__ unsigned char *lab_res() const { return base + kOffLab; }                                  // [kRows]
-    __device__ float *x2() const { return reinterpret_cast<float *>(base + kOffX2); }                     // [kRows]
+    __device__ float *x2() const { return reinterpret_cast<float *>(base + kOffX2); }                     // [kRows] bound scale: at least |x'|^2 + |tau|
+    __device__ float *best() const { return reinterpret_cast<float *>(base + kOffX2 + (size_t)kRows * 4); }     // [kRows] smallest score of the measuring pass
 };
 
 // Resolve the queued rows of this wave: four lanes per row, each lane takes every fourth marked
@@ -160,7 +163,7 @@ __device__ __forceinline__ void resolve_queue(const WaveQueue<DK> &Q, int nrec, 
                     ss = ss + tq * tq;
                 }
             }
-            if (cc >= 0 && (ss < bs || (ss == bs && cc < bc))) {
+            if (cc >= 0 && cc < k && (ss < bs || (ss == bs && cc < bc))) {
                 bs = ss;
                 bc = cc;
             }
@@ -251,8 +254,10 @@ __device__ __forceinline__ void apply_changes(const WaveQueue<DK> &Q, int cnt, i
 // Centroid update for the clusters touched in this pass, all threads: item (c, q) owns knobs
 // 4q..4q+3 of centroid c: mean = (double)S / (double)n, then the f16 hi/lo fragments of
 // w = -2 (mu - o) (one 8-byte store each).  The DK/4 items of a centroid sit in adjacent lanes and
-// add up |mu - o|^2 among themselves; the last of them owns the bias slot (knob slot DK - 1) and
-// stores the sum / 256 there as hi/lo, and its rounded-up value for the error bound.
+// add up |mu - o|^2 among themselves; the last of them owns the bias slot (knob slot DK - 3) and
+// stores the sum / 256 there as hi/lo, and its rounded-up value for the error bound.  The two
+// threshold slots (DK - 2, DK - 1) hold the constant 256.  A rewritten centroid is recorded in
+// upd_stamp.
 template <int DK>
 __device__ __forceinline__ void update_centroids(const MfmaLds<DK> &U, int k, int KP, int d, int stamp, bool all)
 {
@@ -294,9 +299,12 @@ __device__ __forceinline__ void update_centroids(const MfmaLds<DK> &U, int k, in
             if (q == QN - 1) {
                 const float bs = (float)b * (1.0f / kBiasScale);
                 const _Float16 bhi = (_Float16)bs;
-                hi4[3] = bhi;
-                lo4[3] = (_Float16)(bs - (float)bhi);
+                hi4[1] = bhi;
+                lo4[1] = (_Float16)(bs - (float)bhi);
+                hi4[2] = hi4[3] = (_Float16)kBiasScale;      // the two threshold slots
+                lo4[2] = lo4[3] = (_Float16)0.0f;
                 U.bias[c] = __double2float_ru(b) * 1.0000005f;
+                if (!all) *U.upd_stamp = stamp + 1;
             }
             const int mt = c >> 5, m32 = c & 31;
             const int g = q >> 1, hh = g & 1, fstep = g >> 1, sub = q & 1;
@@ -338,8 +346,10 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
     const int wave_row0 = wave * NTW * 32;                 // first row (task-relative) of this wave
     const bool wave_live = wave_row0 < nrows;              // the wave owns at least one row
 
-    // the bias slot is the last knob slot of the fragments (knob index DK - 1 >= d)
-    constexpr int bstep = NS - 1, bhalf = 1, belem = 7;
+    // The last three knob slots of the fragments are reserved (d <= DK - 3): slot DK - 3 carries the
+    // bias (256 in B, |mu'|^2 / 256 as hi/lo in A), slots DK - 2 and DK - 1 a per-row threshold
+    // (-tau / 256 as hi/lo in B, 256 in A), so that the scores come out as score - tau.
+    constexpr int bstep = NS - 1, bhalf = 1, belem = 5;
 
     // ---- set-up
     for (int e = tid; e < DK * KP; e += blockDim.x) U.mu64T[e] = 0.0;
@@ -359,8 +369,10 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
     // padding centroid rows (beyond k) carry a huge bias so that they never win
     for (int c = k + tid; c < KP; c += blockDim.x) {
         _Float16 *slot = reinterpret_cast<_Float16 *>(U.afrag + ((c >> 5) * NS2 + bstep) * 64 + 32 * bhalf + (c & 31)) + belem;
-        *slot = (_Float16)kPadBiasHi;
+        slot[0] = (_Float16)kPadBiasHi;
+        slot[1] = slot[2] = (_Float16)kBiasScale;
     }
+    if (tid == 0) *U.upd_stamp = -1;
     for (int e = tid; e < k * d; e += blockDim.x) {
         const int c = e / d, j = e % d;
         double v;
@@ -440,6 +452,7 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
     __syncthreads();
 
     double loss = 0.0;
+    bool have_tau = false;      // the rows' threshold slots are valid for the current centroids
 #ifdef CHAM_KERNEL_TIMING
     unsigned long long tacc[16] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
 #endif
@@ -454,6 +467,26 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
         uint32_t flagged_tiles = 0;
         int nrec = 0;
 
+        // How this pass decides its rows (the same for every wave of the workgroup):
+        //   kScreen   best score, threshold best + bound, one mark per score (always valid);
+        //   kMeasure  the same, and every row's threshold tau = best + margin goes into its B slots;
+        //   kCount    no centroid has changed since the thresholds were measured: a row keeps its
+        //             label iff exactly one score lies below its tau (one sign bit per score);
+        //             tiles with any other row are redone the kScreen way.
+        enum { kScreen = 0, kMeasure = 1, kCount = 2 };
+        const bool changed_prev = it == 0 || __builtin_amdgcn_readfirstlane(*U.upd_stamp) == it;
+        int mode;
+        if (changed_prev) {
+            mode = kScreen;
+            have_tau = false;
+        } else if (!have_tau) {
+            mode = kMeasure;
+            have_tau = true;
+        } else {
+            mode = kCount;
+        }
+
+        CHAM_TCOUNT(14, mode == kCount ? 1 : 0);
         if (wave_live) {
             // A fragments of this pass (the bias slot included) and the bound m2
             half8 A0[NS2], A1[NS2];
@@ -475,27 +508,22 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
             auto mma = [&](float16v &acc, const half8 (&Af)[NS2], const half8 (&Bt)[NS], int s) {
                 acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(Af[s], Bt[s % NS], s == 0 ? zero16 : acc, 0, 0, 0);
             };
-            // Scores come in groups of 4 registers = 8 centroid rows (4 per lane half).  Groups that
-            // hold only padding rows (beyond k) are skipped: ng = number of groups in use.
-            // mark scores of groups [g0, g0 + CH/4): bit set = above the threshold (or padding)
-            auto mark = [&](uint32_t &far, const float16v &acc, float thr, int i0, int ng) {
+            // mark scores [i0, i0 + CH): bit set = above the threshold (or padding)
+            auto mark = [&](uint32_t &far, const float16v &acc, float thr, int i0) {
 #pragma unroll
-                for (int g = 0; g < CH / 4; ++g) {
-                    const int gi = i0 / 4 + g;
-                    if (gi < ng) {
-#pragma unroll
-                        for (int i = 0; i < 4; ++i)
-                            far = __builtin_amdgcn_alignbit(far, __float_as_uint(thr - acc[4 * gi + i]), 31);
-                    } else {
-                        far = (far << 4) | 0xFu;
-                    }
-                }
+                for (int i = 0; i < CH; ++i)
+                    far = __builtin_amdgcn_alignbit(far, __float_as_uint(thr - acc[i0 + i]), 31);
             };
-            auto min16 = [&](const float16v &acc, int ng) {
+            // sign bits of scores [i0, i0 + CH): bit set = score - tau below zero
+            auto signs = [&](uint32_t &neg, const float16v &acc, int i0) {
+#pragma unroll
+                for (int i = 0; i < CH; ++i) neg = __builtin_amdgcn_alignbit(neg, __float_as_uint(acc[i0 + i]), 31);
+            };
+            auto min16 = [&](const float16v &acc) {
                 float b = __builtin_fminf(min3f(acc[0], acc[1], acc[2]), acc[3]);
-                if (ng > 1) b = min3f(min3f(b, acc[4], acc[5]), acc[6], acc[7]);
-                if (ng > 2) b = min3f(min3f(b, acc[8], acc[9]), acc[10], acc[11]);
-                if (ng > 3) b = min3f(min3f(b, acc[12], acc[13]), acc[14], acc[15]);
+                b = min3f(min3f(b, acc[4], acc[5]), acc[6], acc[7]);
+                b = min3f(min3f(b, acc[8], acc[9]), acc[10], acc[11]);
+                b = min3f(min3f(b, acc[12], acc[13]), acc[14], acc[15]);
                 return b;
             };
             // decide or queue the rows of tile nt from the candidate mask of this lane half
@@ -510,6 +538,9 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
                 const int q = __clz((int)(cand_lo ? cand_lo : cand_hi));
                 const int lab = centroid_of(q & 31, hh);
                 newpack[nt >> 2] |= (uint32_t)(!live ? 0xFF : (flagged ? 0xFE : lab)) << (8 * (nt & 3));
+                // the label is packed here and now: left to itself the compiler defers all of this to
+                // the end of the pass and keeps both candidate masks of every tile live until then
+                asm volatile("" : "+v"(newpack[nt >> 2]));
                 const uint64_t fm = __ballot(flagged) & 0xFFFFFFFFull;
                 if (fm) {
                     flagged_tiles |= flagged ? (1u << nt) : 0u;
@@ -521,73 +552,154 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
                                 *reinterpret_cast<half8 *>(Q.rec_x() + (size_t)rs * DK + 16 * f + 8 * h) = B[nt][f];
                             }
                         }
-                        Q.rec_mask()[rs * 2 + h] = cand;
+                        // no candidate at all cannot happen with valid thresholds; if it does, every centroid is one
+                        Q.rec_mask()[rs * 2 + h] = total ? cand : (two ? 0xFFFFFFFFu : 0xFFFF0000u);
                         if (h == 0) Q.rec_pid()[rs] = (unsigned short)(nt * 32 + n32);
                     }
                     nrec += __popcll(fm);
                 }
             };
-
-            constexpr int ng0 = 4;                                // score groups evaluated per m-tile (all)
-            constexpr int ng1 = 4;
-            float x2cur = Q.x2()[n32];
-            if (two) {
-                // accA = centroids 0..31, accB = centroids 32..63 of the current tile
+            if (mode == kCount) {
+                // The scores come out as score - tau.  A row whose only negative score is its
+                // centroid's keeps its label; a row with several is queued with exactly those
+                // centroids as candidates (the nearest centroid is always among them).
+                if (two) {
 #pragma unroll
-                for (int s = 0; s < NS2; ++s) mma(accA, A0, B[0], s);
+                    for (int s = 0; s < NS2; ++s) mma(accA, A0, B[0], s);
 #pragma unroll
-                for (int s = 0; s < NS2; ++s) mma(accB, A1, B[0], s);
+                    for (int s = 0; s < NS2; ++s) mma(accB, A1, B[0], s);
 #pragma unroll
-                for (int nt = 0; nt < NTW; ++nt) {
-                    constexpr int kLast = NTW - 1;
-                    const int nx = nt < kLast ? nt + 1 : nt;
-                    float best = min_halves(__builtin_fminf(min16(accA, 4), min16(accB, ng1)));
-                    const float thr = best + mfma_bound<NS2>(x2cur, m2);
-                    if (nt < kLast) x2cur = Q.x2()[nx * 32 + n32];
-                    uint32_t far = 0;
+                    for (int nt = 0; nt < NTW; ++nt) {
+                        constexpr int kLast = NTW - 1;
+                        const int nx = nt < kLast ? nt + 1 : nt;
+                        uint32_t neg = 0;
 #pragma unroll
-                    for (int s = 0; s < NS2; ++s) mark(far, accA, thr, s * CH, 4);
-                    // accA is consumed: its next chain runs under the marking of accB
+                        for (int s = 0; s < NS2; ++s) signs(neg, accA, s * CH);
+                        // accA is consumed: its next chain runs under the sign collection of accB
 #pragma unroll
-                    for (int s = 0; s < NS2; ++s) {
+                        for (int s = 0; s < NS2; ++s) {
+                            __builtin_amdgcn_sched_barrier(0);
+                            if (nt < kLast) mma(accA, A0, B[nx], s);
+                            __builtin_amdgcn_sched_barrier(0);
+                            signs(neg, accB, s * CH);
+                        }
                         __builtin_amdgcn_sched_barrier(0);
-                        if (nt < kLast) mma(accA, A0, B[nx], s);
-                        __builtin_amdgcn_sched_barrier(0);
-                        mark(far, accB, thr, s * CH, ng1);
-                    }
-                    __builtin_amdgcn_sched_barrier(0);
-                    if (nt < kLast) {
+                        if (nt < kLast) {
 #pragma unroll
-                        for (int s = 0; s < NS2; ++s) mma(accB, A1, B[nx], s);
+                            for (int s = 0; s < NS2; ++s) mma(accB, A1, B[nx], s);
+                        }
+                        decide(~neg, nt);
+                        __builtin_amdgcn_sched_barrier(0);
                     }
-                    decide(far, nt);
-                    __builtin_amdgcn_sched_barrier(0);   // labels of this tile are packed before the next tile
+                } else {
+#pragma unroll
+                    for (int s = 0; s < NS2; ++s) mma(accA, A0, B[0], s);
+#pragma unroll
+                    for (int nt = 0; nt < NTW; ++nt) {
+                        constexpr int kLast = NTW - 1;
+                        const int nx = nt < kLast ? nt + 1 : nt;
+                        float16v &cur = (nt & 1) ? accB : accA;
+                        float16v &nxt = (nt & 1) ? accA : accB;
+                        uint32_t neg = 0;
+#pragma unroll
+                        for (int s = 0; s < NS2; ++s) {
+                            __builtin_amdgcn_sched_barrier(0);
+                            if (nt < kLast) mma(nxt, A0, B[nx], s);
+                            __builtin_amdgcn_sched_barrier(0);
+                            signs(neg, cur, s * CH);
+                        }
+                        __builtin_amdgcn_sched_barrier(0);
+                        decide((~neg << 16) | 0xFFFFu, nt);
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
                 }
             } else {
-                // one m-tile: the accumulators alternate, the next tile's chain runs under this epilogue
+                float x2cur = Q.x2()[n32];
+                if (two) {
+                    // accA = centroids 0..31, accB = centroids 32..63 of the current tile
 #pragma unroll
-                for (int s = 0; s < NS2; ++s) mma(accA, A0, B[0], s);
+                    for (int s = 0; s < NS2; ++s) mma(accA, A0, B[0], s);
+#pragma unroll
+                    for (int s = 0; s < NS2; ++s) mma(accB, A1, B[0], s);
+#pragma unroll
+                    for (int nt = 0; nt < NTW; ++nt) {
+                        constexpr int kLast = NTW - 1;
+                        const int nx = nt < kLast ? nt + 1 : nt;
+                        float best = min_halves(__builtin_fminf(min16(accA), min16(accB)));
+                        const float thr = best + mfma_bound<NS2>(x2cur, m2);
+                        if (nt < kLast) x2cur = Q.x2()[nx * 32 + n32];
+                        uint32_t far = 0;
+#pragma unroll
+                        for (int s = 0; s < NS2; ++s) mark(far, accA, thr, s * CH);
+                        // accA is consumed: its next chain runs under the marking of accB
+#pragma unroll
+                        for (int s = 0; s < NS2; ++s) {
+                            __builtin_amdgcn_sched_barrier(0);
+                            if (nt < kLast) mma(accA, A0, B[nx], s);
+                            __builtin_amdgcn_sched_barrier(0);
+                            mark(far, accB, thr, s * CH);
+                        }
+                        __builtin_amdgcn_sched_barrier(0);
+                        if (nt < kLast) {
+#pragma unroll
+                            for (int s = 0; s < NS2; ++s) mma(accB, A1, B[nx], s);
+                        }
+                        decide(far, nt);
+                        if (mode == kMeasure && h == 0) Q.best()[nt * 32 + n32] = best;
+                        __builtin_amdgcn_sched_barrier(0);   // labels of this tile are packed before the next tile
+                    }
+                } else {
+                    // one m-tile: the accumulators alternate, the next tile's chain runs under this epilogue
+#pragma unroll
+                    for (int s = 0; s < NS2; ++s) mma(accA, A0, B[0], s);
+#pragma unroll
+                    for (int nt = 0; nt < NTW; ++nt) {
+                        constexpr int kLast = NTW - 1;
+                        const int nx = nt < kLast ? nt + 1 : nt;
+                        float16v &cur = (nt & 1) ? accB : accA;
+                        float16v &nxt = (nt & 1) ? accA : accB;
+                        float best = min_halves(min16(cur));
+                        const float thr = best + mfma_bound<NS2>(x2cur, m2);
+                        if (nt < kLast) x2cur = Q.x2()[nx * 32 + n32];
+                        uint32_t far = 0;
+#pragma unroll
+                        for (int s = 0; s < NS2; ++s) {
+                            __builtin_amdgcn_sched_barrier(0);
+                            if (nt < kLast) mma(nxt, A0, B[nx], s);
+                            __builtin_amdgcn_sched_barrier(0);
+                            mark(far, cur, thr, s * CH);
+                        }
+                        __builtin_amdgcn_sched_barrier(0);
+                        far = (far << 16) | 0xFFFFu;
+                        decide(far, nt);
+                        if (mode == kMeasure && h == 0) Q.best()[nt * 32 + n32] = best;
+                        __builtin_amdgcn_sched_barrier(0);   // labels of this tile are packed before the next tile
+                    }
+                }
+            }
+            if (mode == kMeasure) {
+                // Every row's threshold for the passes to come.  best = smallest computed
+                // score - tau_old, bnd = the bound it was screened with.  The new tau exceeds the true
+                // score of the row's centroid by more than the screen errors of this pass and of the
+                // passes that use it, and a centroid that is not counted later is farther than the
+                // row's centroid by more than those errors.  Lanes of the upper half own the slots.
 #pragma unroll
                 for (int nt = 0; nt < NTW; ++nt) {
-                    constexpr int kLast = NTW - 1;
-                    const int nx = nt < kLast ? nt + 1 : nt;
-                    float16v &cur = (nt & 1) ? accB : accA;
-                    float16v &nxt = (nt & 1) ? accA : accB;
-                    float best = min_halves(min16(cur, ng0));
-                    const float thr = best + mfma_bound<NS2>(x2cur, m2);
-                    if (nt < kLast) x2cur = Q.x2()[nx * 32 + n32];
-                    uint32_t far = 0;
-#pragma unroll
-                    for (int s = 0; s < NS2; ++s) {
-                        __builtin_amdgcn_sched_barrier(0);
-                        if (nt < kLast) mma(nxt, A0, B[nx], s);
-                        __builtin_amdgcn_sched_barrier(0);
-                        mark(far, cur, thr, s * CH, ng0);
+                    const float best = Q.best()[nt * 32 + n32];
+                    const float xs = Q.x2()[nt * 32 + n32];
+                    const float bnd = mfma_bound<NS2>(xs, m2);
+                    const float b6 = (float)B[nt][NS - 1][6], b7 = (float)B[nt][NS - 1][7];
+                    const float tq = best - kBiasScale * (b6 + b7);                    // score with tau_old taken out
+                    const float bnd2 = mfma_bound<NS2>(xs + 2.0f * __builtin_fabsf(tq) + 4.0f * bnd + 2.0f, m2) + 1.0e-4f;
+                    const float tau = tq + bnd + 2.0f * bnd2 + __builtin_fabsf(tq) * 9.5367431640625e-7f;
+                    const float u = -tau * (1.0f / kBiasScale);
+                    const _Float16 h6 = (_Float16)u;
+                    const _Float16 h7 = (_Float16)(u - (float)h6);
+                    if (h == bhalf) {
+                        B[nt][NS - 1][6] = h6;
+                        B[nt][NS - 1][7] = h7;
+                        Q.x2()[nt * 32 + n32] = xs + __builtin_fabsf(tau) * 1.000001f + 1.0f;
                     }
-                    __builtin_amdgcn_sched_barrier(0);
-                    far = (far << 16) | 0xFFFFu;
-                    decide(far, nt);
-                    __builtin_amdgcn_sched_barrier(0);   // labels of this tile are packed before the next tile
                 }
             }
         }
@@ -785,10 +897,10 @@ extern "C" int cham_dev_timing(unsigned long long *host16, int reset)
 }
 #endif
 
-// One knob slot must stay free for the bias, so d <= 31.
+// Three knob slots stay free for the bias and the per-row threshold, so d <= 29.
 bool mfma_path_fits(int d, int kmax, int64_t n_max)
 {
-    return d >= 1 && d <= 31 && kmax <= 64 && n_max <= 4096;
+    return d >= 1 && d <= 29 && kmax <= 64 && n_max <= 4096;
 }
 
 hipError_t launch_mfma_sweep(const SweepArgs &a, int64_t n_max, int64_t n_total, hipStream_t s)
@@ -798,7 +910,7 @@ hipError_t launch_mfma_sweep(const SweepArgs &a, int64_t n_max, int64_t n_total,
     if (nwaves < 1) nwaves = 1;
     if (nwaves > 8) nwaves = 8;
     const unsigned pb = (unsigned)((n_total + 255) / 256);
-    if (a.d <= 15) {
+    if (a.d <= 13) {
         if (pb) hipLaunchKernelGGL(pack_rows_kernel<16>, dim3(pb), dim3(256), 0, s, a.X, a.ld, a.d, n_total,
                                    reinterpret_cast<_Float16 *>(a.xh));
         return ntw == 4 ? launch_mfma_t<16, 4>(a, nwaves, s) : launch_mfma_t<16, 16>(a, nwaves, s);
