@@ -46,7 +46,7 @@ struct MfmaLds {
     int *n;             // [KP]       cluster sizes
     int *dirty;         // [KP]       pass in which the cluster last changed
     float *ojf;         // [DK]       centring offsets
-    int *upd_stamp;     // [1]        1 + pass whose update last rewrote a centroid
+    int *upd_stamp;     // [2]        1 + pass whose update last rewrote a centroid; last pass that changed a sum
     unsigned char *wave_base;   // per-wave regions follow
     static constexpr size_t kWaveBytes =
         ((size_t)kRecCap * DK * 2 + 512 * 8 + 512 * 2 + 512 + 512 * 4 + 512 * 4 + 15) / 16 * 16;
@@ -101,10 +101,10 @@ struct WaveQueue {
 // centroid of its row and evaluates the exact double distance (knobs ascending, no fused
 // multiply-add); the four lanes then agree on the smallest distance, lowest index on ties.
 // xh_wave points at the packed f16 copy of the wave's first row (uncentred values).
-template <int DK>
-__device__ __forceinline__ void resolve_queue(const WaveQueue<DK> &Q, int nrec, const double *mu64T,
-                                              const float *ojf, int KP, int k, int d,
-                                              const _Float16 *xh_wave)
+template <int DK, bool kAllInLds>
+__device__ __forceinline__ void resolve_rows(const WaveQueue<DK> &Q, int nrec, const double *mu64T,
+                                             const float *ojf, int KP, int k, int d,
+                                             const _Float16 *xh_wave)
 {
     const int lane = threadIdx.x & 63;
     const int q = lane & 3;
@@ -143,7 +143,7 @@ __device__ __forceinline__ void resolve_queue(const WaveQueue<DK> &Q, int nrec, 
             // knobs in groups of 8; the loads of a group are independent and overlap
             for (int j0 = 0; j0 < d; j0 += 8) {
                 half8 xq;
-                if (rr < kRecCap) {
+                if (kAllInLds || rr < kRecCap) {
                     xq = *reinterpret_cast<const half8 *>(Q.rec_x() + (size_t)rr * DK + j0);
                 } else {
                     xq = *reinterpret_cast<const half8 *>(xh_wave + (size_t)pid * DK + j0);
@@ -157,7 +157,7 @@ __device__ __forceinline__ void resolve_queue(const WaveQueue<DK> &Q, int nrec, 
 #pragma unroll
                 for (int i = 0; i < 8; ++i) {
                     // queued copies are centred; padded knobs are skipped (one of them carries the bias)
-                    float xf = rr < kRecCap ? (float)xq[i] + of[i] : (float)xq[i];
+                    float xf = (kAllInLds || rr < kRecCap) ? (float)xq[i] + of[i] : (float)xq[i];
                     if (j0 + i >= d) xf = 0.0f;
                     const double tq = (double)xf - mu[i];
                     ss = ss + tq * tq;
@@ -185,6 +185,102 @@ __device__ __forceinline__ void resolve_queue(const WaveQueue<DK> &Q, int nrec, 
     __builtin_amdgcn_wave_barrier();
 }
 
+// A few queued rows (the usual case): two rows at a time, two marked centroids per row at a time,
+// sixteen lanes per (row, centroid): every lane squares the differences of its one or two knobs,
+// then one lane adds the d squares up in knob order (the only part that has to be serial) and the
+// lanes of a row agree on the smallest distance, lowest index on ties.
+template <int DK>
+__device__ __forceinline__ void resolve_few(const WaveQueue<DK> &Q, int nrec, const double *mu64T,
+                                            const float *ojf, int KP, int k, int d)
+{
+    const int lane = threadIdx.x & 63;
+    const int slot = lane >> 4, jl = lane & 15;
+    double *sc = reinterpret_cast<double *>(Q.best()) + slot * 32;      // [4][32] squares of one (row, centroid)
+    __builtin_amdgcn_wave_barrier();
+    for (int r0 = 0; r0 < nrec; r0 += 2) {
+        const int r = r0 + (slot >> 1);
+        const bool have = r < nrec;
+        const int rr = have ? r : 0;
+        unsigned rem0 = 0, rem1 = 0;
+        if (have) {
+            rem0 = Q.rec_mask()[r * 2 + 0];
+            rem1 = Q.rec_mask()[r * 2 + 1];
+        }
+        const int pid = Q.rec_pid()[rr];
+        // this lane's knobs of the row (the queued copy is centred; reserved and padded slots count as zero)
+        float xa = 0.0f, xb = 0.0f;
+        if (jl < d) xa = (float)Q.rec_x()[(size_t)rr * DK + jl] + ojf[jl];
+        if (DK == 32 && jl + 16 < d) xb = (float)Q.rec_x()[(size_t)rr * DK + jl + 16] + ojf[jl + 16];
+        auto pop = [&]() -> int {
+            int c = -1;
+            if (rem0) {
+                const int b = __clz((int)rem0);
+                rem0 &= ~(0x80000000u >> b);
+                c = centroid_of(b, 0);
+            } else if (rem1) {
+                const int b = __clz((int)rem1);
+                rem1 &= ~(0x80000000u >> b);
+                c = centroid_of(b, 1);
+            }
+            return c;
+        };
+        if (slot & 1) pop();
+        double bs = __builtin_inf();
+        int bc = 0x7fffffff;
+        while (__ballot((rem0 | rem1) != 0u)) {
+            const int cc = pop();
+            const int ci = cc < 0 ? 0 : cc;
+            const double ta = (double)xa - mu64T[(size_t)jl * KP + ci];
+            sc[jl] = ta * ta;
+            if (DK == 32) {
+                const double tb = (double)xb - mu64T[(size_t)(jl + 16) * KP + ci];
+                sc[jl + 16] = tb * tb;
+            }
+            __builtin_amdgcn_wave_barrier();
+            if (jl == 0) {
+                // eight loads in flight at a time; slots from d on hold exact zeros
+                double ss = 0.0;
+                for (int j0 = 0; j0 < d; j0 += 8) {
+                    double v[8];
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) v[i] = sc[j0 + i];
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) ss = ss + v[i];
+                }
+                if (cc >= 0 && cc < k && (ss < bs || (ss == bs && cc < bc))) {
+                    bs = ss;
+                    bc = cc;
+                }
+            }
+            __builtin_amdgcn_wave_barrier();
+            pop();
+        }
+        const double os = __shfl_xor(bs, 16, 64);
+        const int oc = __shfl_xor(bc, 16, 64);
+        if (os < bs || (os == bs && oc < bc)) {
+            bs = os;
+            bc = oc;
+        }
+        if (have && (lane & 31) == 0) Q.lab_res()[pid] = (unsigned char)(bc < k ? bc : 0);
+    }
+    __builtin_amdgcn_wave_barrier();
+}
+
+// The usual case (every queued row has its LDS copy) never touches global memory.
+template <int DK>
+__device__ __forceinline__ void resolve_queue(const WaveQueue<DK> &Q, int nrec, const double *mu64T,
+                                              const float *ojf, int KP, int k, int d,
+                                              const _Float16 *xh_wave)
+{
+    if (nrec <= 8) {
+        resolve_few<DK>(Q, nrec, mu64T, ojf, KP, k, d);
+    } else if (nrec <= kRecCap) {
+        resolve_rows<DK, true>(Q, nrec, mu64T, ojf, KP, k, d, xh_wave);
+    } else {
+        resolve_rows<DK, false>(Q, nrec, mu64T, ojf, KP, k, d, xh_wave);
+    }
+}
+
 // Row-major f16 copy of X (one row = DK halfs, padded knobs zero): a lane fetches the eight knobs
 // of a B fragment with one 16-byte load.
 template <int DK>
@@ -210,7 +306,7 @@ __global__ void pack_rows_kernel(const uint8_t *__restrict__ X, int64_t ld, int 
 // row that had no label yet.
 template <int DK>
 __device__ __forceinline__ void apply_changes(const WaveQueue<DK> &Q, int cnt, int *S, int *n, int *dirty,
-                                              const float *ojf, int d, int stamp)
+                                              int *pass_dirty, const float *ojf, int d, int stamp)
 {
     constexpr int LPR = DK / 4;              // lanes per row
     constexpr int EPI = 64 / LPR;            // rows per step
@@ -218,6 +314,7 @@ __device__ __forceinline__ void apply_changes(const WaveQueue<DK> &Q, int cnt, i
     const int j0 = 4 * (lane % LPR);
     const float4 o4 = *reinterpret_cast<const float4 *>(ojf + j0);
     const float of[4] = {o4.x, o4.y, o4.z, o4.w};
+    if (lane == 0) *pass_dirty = stamp;          // this pass changes a sum: the centroids need their update
     __builtin_amdgcn_wave_barrier();
 #pragma unroll 2
     for (int e0 = 0; e0 < cnt; e0 += EPI) {
@@ -372,7 +469,10 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
         slot[0] = (_Float16)kPadBiasHi;
         slot[1] = slot[2] = (_Float16)kBiasScale;
     }
-    if (tid == 0) *U.upd_stamp = -1;
+    if (tid == 0) {
+        U.upd_stamp[0] = -1;
+        U.upd_stamp[1] = -1;      // last pass that changed a sum
+    }
     for (int e = tid; e < k * d; e += blockDim.x) {
         const int c = e / d, j = e % d;
         double v;
@@ -495,9 +595,12 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
                 A0[s] = U.afrag[s * 64 + lane];
                 A1[s] = two ? U.afrag[(NS2 + s) * 64 + lane] : A0[s];
             }
-            float m2 = lane < KP ? U.bias[lane] : 0.0f;
+            float m2 = 0.0f;
+            if (mode != kCount) {
+                m2 = lane < KP ? U.bias[lane] : 0.0f;
 #pragma unroll
-            for (int off = 32; off >= 1; off >>= 1) m2 = __builtin_fmaxf(m2, __shfl_xor(m2, off, 64));
+                for (int off = 32; off >= 1; off >>= 1) m2 = __builtin_fmaxf(m2, __shfl_xor(m2, off, 64));
+            }
 
             CHAM_T(t_a2);
             CHAM_TADD(10, t_a, t_a2);   // pass prologue (inside "tiles")
@@ -691,7 +794,9 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
                     const float b6 = (float)B[nt][NS - 1][6], b7 = (float)B[nt][NS - 1][7];
                     const float tq = best - kBiasScale * (b6 + b7);                    // score with tau_old taken out
                     const float bnd2 = mfma_bound<NS2>(xs + 2.0f * __builtin_fabsf(tq) + 4.0f * bnd + 2.0f, m2) + 1.0e-4f;
-                    const float tau = tq + bnd + 2.0f * bnd2 + __builtin_fabsf(tq) * 9.5367431640625e-7f;
+                    // one screen error is at most 0.4 of a bound (mfma_bound = 2 errors x 1.25): tau lies above
+                    // the measured best by this pass's error, the later passes' error and a quarter more
+                    const float tau = tq + 0.5f * bnd + 0.5f * bnd2 + __builtin_fabsf(tq) * 9.5367431640625e-7f;
                     const float u = -tau * (1.0f / kBiasScale);
                     const _Float16 h6 = (_Float16)u;
                     const _Float16 h7 = (_Float16)(u - (float)h6);
@@ -708,6 +813,9 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
         if (nrec) resolve_queue<DK>(Q, nrec, U.mu64T, U.ojf, KP, k, d, xh_wave);
         CHAM_TCOUNT(11, nrec ? 1 : 0);
         CHAM_T(t_c);
+#ifdef CHAM_KERNEL_TIMING
+        if (nrec > 0 && nrec <= 8) { tacc[12] += t_c - t_b; tacc[13] += 1; }
+#endif
 
         // Labels of the rows that went through the queue replace their placeholders.
         if (wave_live && __ballot(flagged_tiles != 0u)) {
@@ -766,10 +874,9 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
                 }
                 CHAM_TCOUNT(7, cnt);
                 CHAM_T(t_p0);
-                if (cnt) apply_changes<DK>(Q, cnt, U.S, U.n, U.dirty, U.ojf, d, it);
+                if (cnt) apply_changes<DK>(Q, cnt, U.S, U.n, U.dirty, U.upd_stamp + 1, U.ojf, d, it);
                 CHAM_T(t_p1);
-                CHAM_TADD(12, t_p0, t_p1);   // apply (inside "sums")
-                CHAM_TCOUNT(13, cnt ? 1 : 0);
+
                 start = next_start;
             }
 #pragma unroll
@@ -811,12 +918,16 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
             }
         }
 
-        if (!final_pass) {
+        // A pass that moved no row leaves every sum as it was: no update, and no second barrier
+        // (the flag is read after the barrier above; a wave that runs ahead can only overwrite it
+        // with a later pass number, which reads the same).
+        if (!final_pass && __builtin_amdgcn_readfirstlane(U.upd_stamp[1]) == it) {
             update_centroids<DK>(U, k, KP, d, it, false);
             __syncthreads();
         }
         CHAM_T(t_f);
         CHAM_TADD(0, t_a, t_b);   // tiles
+        if (mode == kCount) { CHAM_TADD(5, t_a, t_b); CHAM_TADD(6, t_a, t_f); }
         CHAM_TADD(1, t_b, t_c);   // resolve
         CHAM_TADD(2, t_c, t_d);   // sums
         CHAM_TADD(3, t_d, t_e);   // barrier wait
