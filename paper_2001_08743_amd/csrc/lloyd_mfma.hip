@@ -630,17 +630,24 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
                 return b;
             };
             // decide or queue the rows of tile nt from the candidate mask of this lane half
-            auto decide = [&](uint32_t far, int nt) {
+            auto decide = [&](uint32_t far, int nt, bool keep) {
                 const uint32_t cand = ~far;
                 uint32_t cand_lo, cand_hi;
                 both_halves(cand, cand_lo, cand_hi);
                 const int total = __popc(cand_lo) + __popc(cand_hi);
                 const bool live = (wave_row0 + nt * 32 + n32) < nrows;
                 const bool flagged = live && total != 1;
-                const int hh = cand_lo ? 0 : 1;
-                const int q = __clz((int)(cand_lo ? cand_lo : cand_hi));
-                const int lab = centroid_of(q & 31, hh);
-                newpack[nt >> 2] |= (uint32_t)(!live ? 0xFF : (flagged ? 0xFE : lab)) << (8 * (nt & 3));
+                if (keep) {
+                    // the single candidate is the row's centroid of the pass before (rows outside the
+                    // task carry 0xFF there already)
+                    const uint32_t prev = prevpack[nt >> 2] & (0xFFu << (8 * (nt & 3)));
+                    newpack[nt >> 2] |= flagged ? (0xFEu << (8 * (nt & 3))) : prev;
+                } else {
+                    const int hh = cand_lo ? 0 : 1;
+                    const int q = __clz((int)(cand_lo ? cand_lo : cand_hi));
+                    const int lab = centroid_of(q & 31, hh);
+                    newpack[nt >> 2] |= (uint32_t)(!live ? 0xFF : (flagged ? 0xFE : lab)) << (8 * (nt & 3));
+                }
                 // the label is packed here and now: left to itself the compiler defers all of this to
                 // the end of the pass and keeps both candidate masks of every tile live until then
                 asm volatile("" : "+v"(newpack[nt >> 2]));
@@ -691,7 +698,7 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
 #pragma unroll
                             for (int s = 0; s < NS2; ++s) mma(accB, A1, B[nx], s);
                         }
-                        decide(~neg, nt);
+                        decide(~neg, nt, true);
                         __builtin_amdgcn_sched_barrier(0);
                     }
                 } else {
@@ -712,7 +719,7 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
                             signs(neg, cur, s * CH);
                         }
                         __builtin_amdgcn_sched_barrier(0);
-                        decide((~neg << 16) | 0xFFFFu, nt);
+                        decide((~neg << 16) | 0xFFFFu, nt, true);
                         __builtin_amdgcn_sched_barrier(0);
                     }
                 }
@@ -747,7 +754,7 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
 #pragma unroll
                             for (int s = 0; s < NS2; ++s) mma(accB, A1, B[nx], s);
                         }
-                        decide(far, nt);
+                        decide(far, nt, false);
                         if (mode == kMeasure && h == 0) Q.best()[nt * 32 + n32] = best;
                         __builtin_amdgcn_sched_barrier(0);   // labels of this tile are packed before the next tile
                     }
@@ -774,7 +781,7 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
                         }
                         __builtin_amdgcn_sched_barrier(0);
                         far = (far << 16) | 0xFFFFu;
-                        decide(far, nt);
+                        decide(far, nt, false);
                         if (mode == kMeasure && h == 0) Q.best()[nt * 32 + n32] = best;
                         __builtin_amdgcn_sched_barrier(0);   // labels of this tile are packed before the next tile
                     }
@@ -813,9 +820,6 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
         if (nrec) resolve_queue<DK>(Q, nrec, U.mu64T, U.ojf, KP, k, d, xh_wave);
         CHAM_TCOUNT(11, nrec ? 1 : 0);
         CHAM_T(t_c);
-#ifdef CHAM_KERNEL_TIMING
-        if (nrec > 0 && nrec <= 8) { tacc[12] += t_c - t_b; tacc[13] += 1; }
-#endif
 
         // Labels of the rows that went through the queue replace their placeholders.
         if (wave_live && __ballot(flagged_tiles != 0u)) {
@@ -838,6 +842,8 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
         // label yet has previous = 0xFF; rows outside the task keep 0xFF and never change.  The
         // queue holds kRecCap rows; if a pass changes more (the first passes do), the tiles are
         // walked again from the first tile that did not fit.
+        CHAM_T(t_c1);
+        CHAM_TADD(13, t_c, t_c1);    // label patch (inside "sums")
         if (wave_live) {
             uint32_t diff[(NTW + 3) / 4];
             uint32_t any = 0;
@@ -876,7 +882,7 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
                 CHAM_T(t_p0);
                 if (cnt) apply_changes<DK>(Q, cnt, U.S, U.n, U.dirty, U.upd_stamp + 1, U.ojf, d, it);
                 CHAM_T(t_p1);
-
+                CHAM_TADD(12, t_p0, t_p1);   // apply (inside "sums")
                 start = next_start;
             }
 #pragma unroll

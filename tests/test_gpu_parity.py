@@ -190,10 +190,11 @@ def test_cfg5_full_size_sampled_tasks():
 
 # ------------------------------------------------------------------ matrix-core path specifics
 
-@pytest.mark.parametrize("d,k", [(15, 32), (16, 33), (31, 64), (24, 1), (2, 64)])
+@pytest.mark.parametrize("d,k", [(13, 32), (14, 33), (15, 32), (16, 33), (29, 64), (30, 64), (31, 64), (24, 1),
+                                 (2, 64)])
 def test_matrix_core_path_boundaries(d, k):
-    """Knob counts around the 16/32 fragment widths (one slot is kept for the bias) and centroid
-    counts around the 32-row tile."""
+    """Knob counts around the 16/32 fragment widths (three slots are kept for the bias and the row
+    thresholds; 30 and 31 knobs take another path) and centroid counts around the 32-row tile."""
     wl = workloads.random_task(700 + d + k, n=1500, d=d, n_blobs=max(2, k // 2), ks=(k,), n_iter=7,
                                n_visited=32, card_hi=24, sigma=1.3)
     _full(wl, threshold=1.01)
@@ -230,6 +231,26 @@ def test_every_row_on_an_exact_tie_overflows_the_queue():
                                     want_trace=True)
     torch.cuda.synchronize()
     check_sweep(wl, out, ref, dw.ld)
+
+
+@pytest.mark.parametrize("seed,d,card_hi,ks", [(801, 3, 3, (2, 5, 9)), (802, 6, 4, (7, 33, 40)), (803, 24, 8, (16, 64))])
+def test_many_passes_after_convergence_with_ties(seed, d, card_hi, ks):
+    """Few distinct values per knob: many duplicate rows and exact ties, and the sweep runs long
+    after the centroids have stopped moving, so most passes only count the scores below each row's
+    threshold and re-resolve the tied rows exactly."""
+    wl = workloads.random_task(seed, n=4096, d=d, card_hi=card_hi, n_blobs=5, sigma=2.0, ks=ks, n_iter=40,
+                               n_tasks=2, ragged=True)
+    _sweep_only(wl, 0, want_trace=True)
+
+
+def test_converged_start_counts_from_the_second_pass():
+    """Caller-supplied centroids that are already a fixed point: no pass changes a centroid."""
+    import torch
+    wl = workloads.random_task(810, n=3000, d=10, n_blobs=6, ks=(6,), n_iter=60, card_hi=12)
+    ref0 = oracle.sweep(wl.rows, wl.task_off, wl.ks, wl.n_iter)
+    init = ref0["centroids"].reshape(1, 6, 10).copy()
+    wl.n_iter = 12
+    _sweep_only(wl, 0, want_trace=True, init=init)
 
 
 def test_matrix_core_and_vector_paths_agree_on_every_task():
