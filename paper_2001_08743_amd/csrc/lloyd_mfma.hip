@@ -195,7 +195,8 @@ __device__ __forceinline__ void resolve_few(const WaveQueue<DK> &Q, int nrec, co
 {
     const int lane = threadIdx.x & 63;
     const int slot = lane >> 4, jl = lane & 15;
-    double *sc = reinterpret_cast<double *>(Q.best()) + slot * 32;      // [4][32] squares of one (row, centroid)
+    // [4][32] squares of one (row, centroid), in the upper half of the mask array (unused by <= 8 queued rows)
+    double *sc = reinterpret_cast<double *>(Q.rec_mask() + 512) + slot * 32;
     __builtin_amdgcn_wave_barrier();
     for (int r0 = 0; r0 < nrec; r0 += 2) {
         const int r = r0 + (slot >> 1);
@@ -552,6 +553,7 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
     __syncthreads();
 
     double loss = 0.0;
+    const int rows_left = nrows - wave_row0 - n32;      // this lane's row of tile nt is in the task iff 32 nt < rows_left
     bool have_tau = false;      // the rows' threshold slots are valid for the current centroids
 #ifdef CHAM_KERNEL_TIMING
     unsigned long long tacc[16] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
@@ -568,23 +570,18 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
         int nrec = 0;
 
         // How this pass decides its rows (the same for every wave of the workgroup):
-        //   kScreen   best score, threshold best + bound, one mark per score (always valid);
-        //   kMeasure  the same, and every row's threshold tau = best + margin goes into its B slots;
-        //   kCount    no centroid has changed since the thresholds were measured: a row keeps its
-        //             label iff exactly one score lies below its tau (one sign bit per score);
-        //             tiles with any other row are redone the kScreen way.
-        enum { kScreen = 0, kMeasure = 1, kCount = 2 };
+        //   kScreen   best score, threshold best + bound, one mark per score (always valid); the
+        //             best score of every row is kept for a later measurement;
+        //   kCount    no centroid has changed since the rows' thresholds tau were measured: a row
+        //             keeps its label iff exactly one score lies below its tau (one sign bit per
+        //             score); a row with several is queued with exactly those centroids.
+        // The thresholds are measured at the start of the first pass that finds the centroids of
+        // the pass before unchanged, from the best scores of that pass.
+        enum { kScreen = 0, kCount = 2 };
         const bool changed_prev = it == 0 || __builtin_amdgcn_readfirstlane(*U.upd_stamp) == it;
-        int mode;
-        if (changed_prev) {
-            mode = kScreen;
-            have_tau = false;
-        } else if (!have_tau) {
-            mode = kMeasure;
-            have_tau = true;
-        } else {
-            mode = kCount;
-        }
+        const int mode = changed_prev ? kScreen : kCount;
+        const bool measure_now = !changed_prev && !have_tau;
+        have_tau = !changed_prev;
 
         CHAM_TCOUNT(14, mode == kCount ? 1 : 0);
         if (wave_live) {
@@ -596,10 +593,39 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
                 A1[s] = two ? U.afrag[(NS2 + s) * 64 + lane] : A0[s];
             }
             float m2 = 0.0f;
-            if (mode != kCount) {
+            if (mode != kCount || measure_now) {
                 m2 = lane < KP ? U.bias[lane] : 0.0f;
 #pragma unroll
                 for (int off = 32; off >= 1; off >>= 1) m2 = __builtin_fmaxf(m2, __shfl_xor(m2, off, 64));
+            }
+
+            if (measure_now) {
+                // Every row's threshold for the passes to come.  best = smallest computed
+                // score - tau_old of the pass before (same centroids), bnd = the bound it was screened
+                // with.  The new tau exceeds the true score of the row's centroid by more than the
+                // screen errors of that pass and of the passes that use it, and a centroid that is
+                // not counted later is farther than the row's centroid by more than those errors.
+                // Lanes of the upper half own the slots.
+#pragma unroll
+                for (int nt = 0; nt < NTW; ++nt) {
+                    const float best = Q.best()[nt * 32 + n32];
+                    const float xs = Q.x2()[nt * 32 + n32];
+                    const float bnd = mfma_bound<NS2>(xs, m2);
+                    const float b6 = (float)B[nt][NS - 1][6], b7 = (float)B[nt][NS - 1][7];
+                    const float tq = best - kBiasScale * (b6 + b7);                    // score with tau_old taken out
+                    const float bnd2 = mfma_bound<NS2>(xs + 2.0f * __builtin_fabsf(tq) + 4.0f * bnd + 2.0f, m2) + 1.0e-4f;
+                    // one screen error is at most 0.4 of a bound (mfma_bound = 2 errors x 1.25): tau lies above
+                    // the measured best by this pass's error, the later passes' error and a quarter more
+                    const float tau = tq + 0.5f * bnd + 0.5f * bnd2 + __builtin_fabsf(tq) * 9.5367431640625e-7f;
+                    const float u = -tau * (1.0f / kBiasScale);
+                    const _Float16 h6 = (_Float16)u;
+                    const _Float16 h7 = (_Float16)(u - (float)h6);
+                    if (h == bhalf) {
+                        B[nt][NS - 1][6] = h6;
+                        B[nt][NS - 1][7] = h7;
+                        Q.x2()[nt * 32 + n32] = xs + __builtin_fabsf(tau) * 1.000001f + 1.0f;
+                    }
+                }
             }
 
             CHAM_T(t_a2);
@@ -635,7 +661,10 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
                 uint32_t cand_lo, cand_hi;
                 both_halves(cand, cand_lo, cand_hi);
                 const int total = __popc(cand_lo) + __popc(cand_hi);
-                const bool live = (wave_row0 + nt * 32 + n32) < nrows;
+                // compared afresh in every tile: sixteen hoisted lane masks cost more than sixteen compares
+                int rl = rows_left;
+                asm volatile("" : "+v"(rl));
+                const bool live = nt * 32 < rl;
                 const bool flagged = live && total != 1;
                 if (keep) {
                     // the single candidate is the row's centroid of the pass before (rows outside the
@@ -755,7 +784,7 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
                             for (int s = 0; s < NS2; ++s) mma(accB, A1, B[nx], s);
                         }
                         decide(far, nt, false);
-                        if (mode == kMeasure && h == 0) Q.best()[nt * 32 + n32] = best;
+                        if (h == 0) Q.best()[nt * 32 + n32] = best;
                         __builtin_amdgcn_sched_barrier(0);   // labels of this tile are packed before the next tile
                     }
                 } else {
@@ -782,35 +811,8 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
                         __builtin_amdgcn_sched_barrier(0);
                         far = (far << 16) | 0xFFFFu;
                         decide(far, nt, false);
-                        if (mode == kMeasure && h == 0) Q.best()[nt * 32 + n32] = best;
+                        if (h == 0) Q.best()[nt * 32 + n32] = best;
                         __builtin_amdgcn_sched_barrier(0);   // labels of this tile are packed before the next tile
-                    }
-                }
-            }
-            if (mode == kMeasure) {
-                // Every row's threshold for the passes to come.  best = smallest computed
-                // score - tau_old, bnd = the bound it was screened with.  The new tau exceeds the true
-                // score of the row's centroid by more than the screen errors of this pass and of the
-                // passes that use it, and a centroid that is not counted later is farther than the
-                // row's centroid by more than those errors.  Lanes of the upper half own the slots.
-#pragma unroll
-                for (int nt = 0; nt < NTW; ++nt) {
-                    const float best = Q.best()[nt * 32 + n32];
-                    const float xs = Q.x2()[nt * 32 + n32];
-                    const float bnd = mfma_bound<NS2>(xs, m2);
-                    const float b6 = (float)B[nt][NS - 1][6], b7 = (float)B[nt][NS - 1][7];
-                    const float tq = best - kBiasScale * (b6 + b7);                    // score with tau_old taken out
-                    const float bnd2 = mfma_bound<NS2>(xs + 2.0f * __builtin_fabsf(tq) + 4.0f * bnd + 2.0f, m2) + 1.0e-4f;
-                    // one screen error is at most 0.4 of a bound (mfma_bound = 2 errors x 1.25): tau lies above
-                    // the measured best by this pass's error, the later passes' error and a quarter more
-                    const float tau = tq + 0.5f * bnd + 0.5f * bnd2 + __builtin_fabsf(tq) * 9.5367431640625e-7f;
-                    const float u = -tau * (1.0f / kBiasScale);
-                    const _Float16 h6 = (_Float16)u;
-                    const _Float16 h7 = (_Float16)(u - (float)h6);
-                    if (h == bhalf) {
-                        B[nt][NS - 1][6] = h6;
-                        B[nt][NS - 1][7] = h7;
-                        Q.x2()[nt * 32 + n32] = xs + __builtin_fabsf(tau) * 1.000001f + 1.0f;
                     }
                 }
             }
@@ -843,7 +845,6 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
         // queue holds kRecCap rows; if a pass changes more (the first passes do), the tiles are
         // walked again from the first tile that did not fit.
         CHAM_T(t_c1);
-        CHAM_TADD(13, t_c, t_c1);    // label patch (inside "sums")
         if (wave_live) {
             uint32_t diff[(NTW + 3) / 4];
             uint32_t any = 0;
@@ -888,42 +889,51 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
 #pragma unroll
             for (int q = 0; q < (NTW + 3) / 4; ++q) prevpack[q] = newpack[q];
         }
+        if (want_dist) {
+            // Exact loss of this pass from the rows in registers: (x - mu)^2 in double over the knobs
+            // a lane holds (x = centred value + offset, exact), the two lanes of a row and all rows
+            // added up afterwards.  Reserved slots are left out; padded slots are zero on both sides.
+            double part = 0.0;
+            if (wave_live) {
+                float of[NS][8];
+#pragma unroll
+                for (int f = 0; f < NS; ++f)
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) of[f][i] = U.ojf[16 * f + 8 * h + i];
+#pragma unroll
+                for (int nt = 0; nt < NTW; ++nt) {
+                    const uint32_t lab = (newpack[nt >> 2] >> (8 * (nt & 3))) & 0xFFu;
+                    const bool live = lab != 0xFFu;
+                    const double *mc = U.mu64T + (live ? lab : 0u) + (size_t)(8 * h) * KP;
+                    double s = 0.0;
+#pragma unroll
+                    for (int f = 0; f < NS; ++f)
+#pragma unroll
+                        for (int i = 0; i < 8; ++i) {
+                            float xf = (float)B[nt][f][i] + of[f][i];
+                            if (f == NS - 1 && i >= belem) xf = h == bhalf ? 0.0f : xf;
+                            const double tq = (double)xf - mc[(size_t)(16 * f + i) * KP];
+                            s = s + tq * tq;
+                        }
+                    part = part + (live ? s : 0.0);
+                }
+            }
+            const double ws = wave_sum(part);
+            if (lane == 0) U.red[(it & 1) * 8 + wave] = ws;
+        }
         CHAM_T(t_d);
         __syncthreads();
         CHAM_T(t_e);
 
-        if (want_dist) {
-            // exact loss of this pass: every row against its centroid, double, knobs ascending
-            double part = 0.0;
-            const int64_t g0 = r0 & ~(int64_t)3;
-            for (int64_t g = g0 + (int64_t)tid * 4; g < r1; g += (int64_t)blockDim.x * 4) {
-                const uint32_t lw = *reinterpret_cast<const uint32_t *>(labrow + g);
-                double s4[4] = {0.0, 0.0, 0.0, 0.0};
-                for (int j = 0; j < d; ++j) {
-                    const uint32_t w = *reinterpret_cast<const uint32_t *>(a.X + (int64_t)j * a.ld + g);
-                    const double *row = U.mu64T + (size_t)j * KP;
-#pragma unroll
-                    for (int p = 0; p < 4; ++p) {
-                        const int c = (lw >> (8 * p)) & 0xFF;
-                        const double tq = (double)((w >> (8 * p)) & 0xFFu) - row[c < k ? c : 0];
-                        s4[p] = s4[p] + tq * tq;
-                    }
-                }
-#pragma unroll
-                for (int p = 0; p < 4; ++p)
-                    if (g + p >= r0 && g + p < r1) part = part + s4[p];
-            }
-            const double ws = wave_sum(part);
-            if (lane == 0) U.red[wave] = ws;
-            __syncthreads();
-            if (tid == 0) {
-                double s = 0.0;
-                for (int w = 0; w < nwaves; ++w) s = s + U.red[w];
-                loss = s;
-                if (a.trace) a.trace[slot * (a.n_iter + 1) + it] = s;
-            }
+        if (want_dist && tid == 0) {
+            double s = 0.0;
+            for (int w = 0; w < nwaves; ++w) s = s + U.red[(it & 1) * 8 + w];
+            loss = s;
+            if (a.trace) a.trace[slot * (a.n_iter + 1) + it] = s;
         }
 
+        CHAM_T(t_e2);
+        CHAM_TADD(13, t_e, t_e2);    // exact loss (inside "loss/update")
         // A pass that moved no row leaves every sum as it was: no update, and no second barrier
         // (the flag is read after the barrier above; a wave that runs ahead can only overwrite it
         // with a later pass number, which reads the same).
