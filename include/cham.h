@@ -94,7 +94,9 @@ int64_t cham_sweep_workspace_bytes(int64_t ld, int32_t d, const int64_t *task_of
  *   inertia   [T][n_k]     double  loss: sum over rows of the squared distance to the row's
  *                                  final centroid (double terms, fixed summation tree)
  *   status    [T][n_k]     int32   0 ok; 1 = task has fewer than k distinct rows (init_mode 0):
- *                                  centroids, counts, loss and labels of that (t,k) are zero
+ *                                  centroids, counts, loss and labels of that (t,k) are zero;
+ *                                  2 = internal consistency check failed (a label changed in a
+ *                                  pass whose centroids had not changed): results not to be used
  *   labels    [n_k][ld]    uint8   final labels per k (optional, may be NULL)
  *   inertia_trace [T][n_k][n_iter+1] double  loss seen by every labelling pass (optional)
  * workspace: DEVICE scratch of at least cham_sweep_workspace_bytes(...) bytes, 256-byte aligned.

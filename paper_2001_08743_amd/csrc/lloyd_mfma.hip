@@ -46,7 +46,7 @@ struct MfmaLds {
     int *n;             // [KP]       cluster sizes
     int *dirty;         // [KP]       pass in which the cluster last changed
     float *ojf;         // [DK]       centring offsets
-    int *upd_stamp;     // [2]        1 + pass whose update last rewrote a centroid; last pass that changed a sum
+    int *upd_stamp;     // [3]        1 + pass whose update last rewrote a centroid; last pass that changed a sum; broken-invariant flag
     unsigned char *wave_base;   // per-wave regions follow
     static constexpr size_t kWaveBytes =
         ((size_t)kRecCap * DK * 2 + 512 * 8 + 512 * 2 + 512 + 512 * 4 + 512 * 4 + 15) / 16 * 16;
@@ -473,6 +473,7 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
     if (tid == 0) {
         U.upd_stamp[0] = -1;
         U.upd_stamp[1] = -1;      // last pass that changed a sum
+        U.upd_stamp[2] = 0;       // set if a pass that must not change a label did
     }
     for (int e = tid; e < k * d; e += blockDim.x) {
         const int c = e / d, j = e % d;
@@ -882,6 +883,7 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
                 CHAM_TCOUNT(7, cnt);
                 CHAM_T(t_p0);
                 if (cnt) apply_changes<DK>(Q, cnt, U.S, U.n, U.dirty, U.upd_stamp + 1, U.ojf, d, it);
+                if (cnt && mode == kCount && lane == 0) U.upd_stamp[2] = 1;
                 CHAM_T(t_p1);
                 CHAM_TADD(12, t_p0, t_p1);   // apply (inside "sums")
                 start = next_start;
@@ -921,8 +923,14 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
             const double ws = wave_sum(part);
             if (lane == 0) U.red[(it & 1) * 8 + wave] = ws;
         }
+        // Once the centroids have stopped changing, a pass reads shared state only (fragments,
+        // centroids) and writes nothing that another wave reads: identical inputs give identical
+        // labels, so no sum can change and the waves need not meet until a pass that reports the
+        // loss.  A label change in such a pass would mean the invariant is broken; it is recorded
+        // and reported as status 2.
+        const bool free_run = mode == kCount && !want_dist;
         CHAM_T(t_d);
-        __syncthreads();
+        if (!free_run) __syncthreads();
         CHAM_T(t_e);
 
         if (want_dist && tid == 0) {
@@ -937,7 +945,7 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
         // A pass that moved no row leaves every sum as it was: no update, and no second barrier
         // (the flag is read after the barrier above; a wave that runs ahead can only overwrite it
         // with a later pass number, which reads the same).
-        if (!final_pass && __builtin_amdgcn_readfirstlane(U.upd_stamp[1]) == it) {
+        if (!free_run && !final_pass && __builtin_amdgcn_readfirstlane(U.upd_stamp[1]) == it) {
             update_centroids<DK>(U, k, KP, d, it, false);
             __syncthreads();
         }
@@ -961,7 +969,7 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
     }
     for (int c = tid; c < k; c += blockDim.x) a.counts[crow + c] = U.n[c];
     if (tid == 0) {
-        a.status[slot] = 0;
+        a.status[slot] = U.upd_stamp[2] ? 2 : 0;
         a.inertia[slot] = loss;
     }
 }
