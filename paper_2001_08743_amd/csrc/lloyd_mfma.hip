@@ -35,6 +35,45 @@ __device__ unsigned long long g_timing[16];
 #define CHAM_TCOUNT(slot, v)
 #endif
 
+
+// Cross-lane exchanges done in the vector ALU (DPP), no LDS round trip.
+// xor_lanes<1|2|4>: the value held by lane ^ 1, 2 or 4.
+template <int XOR>
+__device__ __forceinline__ int dpp_xor_i32(int v)
+{
+    if (XOR == 1) return __builtin_amdgcn_update_dpp(0, v, 0xB1, 0xF, 0xF, false);      // quad_perm [1,0,3,2]
+    if (XOR == 2) return __builtin_amdgcn_update_dpp(0, v, 0x4E, 0xF, 0xF, false);      // quad_perm [2,3,0,1]
+    // lane ^ 4 = mirror within each group of eight lanes, then reverse within each quad
+    const int m = __builtin_amdgcn_update_dpp(0, v, 0x141, 0xF, 0xF, false);            // row_half_mirror
+    return __builtin_amdgcn_update_dpp(0, m, 0x1B, 0xF, 0xF, false);                    // quad_perm [3,2,1,0]
+}
+template <int XOR>
+__device__ __forceinline__ double dpp_xor_f64(double v)
+{
+    const long long b = __double_as_longlong(v);
+    const int lo = dpp_xor_i32<XOR>((int)(b & 0xFFFFFFFFll));
+    const int hi = dpp_xor_i32<XOR>((int)(b >> 32));
+    return __longlong_as_double(((long long)hi << 32) | (unsigned int)lo);
+}
+// maximum of a non-negative float over the wave: rotations within the 16-lane rows, then the four
+// row results through scalar registers
+__device__ __forceinline__ float wave_max_nonneg(float v)
+{
+    int b = __float_as_int(v);          // non-negative floats order like integers
+    int o = __builtin_amdgcn_update_dpp(0, b, 0x128, 0xF, 0xF, false);    // row_ror:8
+    b = b > o ? b : o;
+    o = __builtin_amdgcn_update_dpp(0, b, 0x124, 0xF, 0xF, false);        // row_ror:4
+    b = b > o ? b : o;
+    o = __builtin_amdgcn_update_dpp(0, b, 0x122, 0xF, 0xF, false);        // row_ror:2
+    b = b > o ? b : o;
+    o = __builtin_amdgcn_update_dpp(0, b, 0x121, 0xF, 0xF, false);        // row_ror:1
+    b = b > o ? b : o;
+    const int r0 = __builtin_amdgcn_readlane(b, 0), r1 = __builtin_amdgcn_readlane(b, 16);
+    const int r2 = __builtin_amdgcn_readlane(b, 32), r3 = __builtin_amdgcn_readlane(b, 48);
+    const int m01 = r0 > r1 ? r0 : r1, m23 = r2 > r3 ? r2 : r3;
+    return __int_as_float(m01 > m23 ? m01 : m23);
+}
+
 // LDS carve-up.  DK = padded knob count (16 or 32), KP = padded centroid count (32 or 64).
 template <int DK>
 struct MfmaLds {
@@ -171,10 +210,17 @@ __device__ __forceinline__ void resolve_rows(const WaveQueue<DK> &Q, int nrec, c
             pop();
             pop();
         }
-#pragma unroll
-        for (int off = 1; off <= 2; off <<= 1) {
-            const double os = __shfl_xor(bs, off, 64);
-            const int oc = __shfl_xor(bc, off, 64);
+        {
+            const double os = dpp_xor_f64<1>(bs);
+            const int oc = dpp_xor_i32<1>(bc);
+            if (os < bs || (os == bs && oc < bc)) {
+                bs = os;
+                bc = oc;
+            }
+        }
+        {
+            const double os = dpp_xor_f64<2>(bs);
+            const int oc = dpp_xor_i32<2>(bc);
             if (os < bs || (os == bs && oc < bc)) {
                 bs = os;
                 bc = oc;
@@ -391,8 +437,9 @@ __device__ __forceinline__ void update_centroids(const MfmaLds<DK> &U, int k, in
                 lo4[i] = (_Float16)(w - (float)hi);
             }
         }
-#pragma unroll
-        for (int off = 1; off < QN; off <<= 1) b = b + __shfl_xor(b, off, 64);
+        b = b + dpp_xor_f64<1>(b);
+        b = b + dpp_xor_f64<2>(b);
+        if (QN == 8) b = b + dpp_xor_f64<4>(b);
         if (act && (4 * q < d || q == QN - 1)) {
             if (q == QN - 1) {
                 const float bs = (float)b * (1.0f / kBiasScale);
@@ -595,9 +642,7 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
             }
             float m2 = 0.0f;
             if (mode != kCount || measure_now) {
-                m2 = lane < KP ? U.bias[lane] : 0.0f;
-#pragma unroll
-                for (int off = 32; off >= 1; off >>= 1) m2 = __builtin_fmaxf(m2, __shfl_xor(m2, off, 64));
+                m2 = wave_max_nonneg(lane < KP ? U.bias[lane] : 0.0f);
             }
 
             if (measure_now) {
