@@ -98,14 +98,15 @@ def main():
     evals = wl.nominal_evals()
     value = evals / (ms_per_step * 1e-3)
     sweep_ms = float(np.mean([a.elapsed_time(b) for a, b in events]))
-    # Dominant kernel = the sweep kernel (resident_mfma_kernel when every task has <= 4096 rows, k <= 64,
-    # d <= 31; resident_sweep_kernel otherwise).  Algorithmic work per distance evaluation: d
-    # multiply-adds of the expanded form plus the bias add and the compare = 2d + 2 flops.  The
-    # contraction runs on the f16 matrix cores, so it is priced against the dense f16 MFMA peak.
+    # Dominant kernel = the sweep kernel: resident_mfma_kernel when every task has <= 4096 rows, k <= 64
+    # and d <= 29; stream_assign_kernel for larger tasks or k (d <= 31); resident_sweep_kernel for
+    # d = 32.  Algorithmic work per distance evaluation: d multiply-adds of the expanded form plus the
+    # bias add and the compare = 2d + 2 flops.  The contraction runs on the f16 matrix cores, so it is
+    # priced against the dense f16 MFMA peak.
     flops_per_eval = 2 * wl.d + 2
     achieved_tflops = evals * flops_per_eval / (sweep_ms * 1e-3) / 1e12
     n_max = int(np.diff(wl.task_off).max())
-    resident = max(wl.ks) <= 64 and n_max <= 4096
+    resident = max(wl.ks) <= 64 and n_max <= 4096 and wl.d <= 29
     uses_mfma = wl.d <= 31
     kernel = ("resident_mfma_kernel" if resident else "stream_assign_kernel") if uses_mfma else "resident_sweep_kernel"
     peak = PEAK_F16_MFMA_TFLOPS if uses_mfma else PEAK_FP32_VECTOR_TFLOPS
