@@ -26,6 +26,7 @@ namespace {
 #ifdef CHAM_KERNEL_TIMING
 // Development aid (not built into the library): per-section cycle counts summed over waves.
 __device__ unsigned long long g_timing[16];
+__device__ unsigned long long g_pass[64 * 16];   // per pass index: tiles, resolve, sums, barrier, update, count-mode, waves
 #define CHAM_T(var) const unsigned long long var = __builtin_readcyclecounter()
 #define CHAM_TADD(slot, t0, t1) tacc[slot] += (t1) - (t0)
 #define CHAM_TCOUNT(slot, v) tacc[slot] += (unsigned long long)(v)
@@ -81,7 +82,7 @@ struct MfmaLds {
     double *red;        // [16]       per-wave partial sums of the loss
     float *bias;        // [KP]       upper bound of |mu - o|^2 per centroid (0 for padding rows)
     half8 *afrag;       // [KP/32][2*DK/16][64]  A fragments: hi parts then lo parts
-    int *S;             // [KP][DK]   integer cluster sums
+    int *S;             // [KP][DK+1] integer cluster sums (row stride DK + 1: rows of different clusters fall into different banks)
     int *n;             // [KP]       cluster sizes
     int *dirty;         // [KP]       pass in which the cluster last changed
     float *ojf;         // [DK]       centring offsets
@@ -93,7 +94,7 @@ struct MfmaLds {
     {
         size_t b = sizeof(double) * DK * KP + sizeof(double) * 16 + sizeof(float) * KP;
         b += 16 * (size_t)(KP / 32) * (2 * DK / 16) * 64;
-        b += sizeof(int) * (size_t)KP * DK + sizeof(int) * KP * 2 + sizeof(float) * DK + 16;
+        b += sizeof(int) * (size_t)KP * (DK + 1) + sizeof(int) * KP * 2 + sizeof(float) * DK + 16;
         b = (b + 15) & ~(size_t)15;
         return b + kWaveBytes * nwaves;
     }
@@ -105,7 +106,7 @@ struct MfmaLds {
         red = reinterpret_cast<double *>(base + o);    o += sizeof(double) * 16;
         bias = reinterpret_cast<float *>(base + o);    o += sizeof(float) * KP;
         afrag = reinterpret_cast<half8 *>(base + o);   o += 16 * (size_t)(KP / 32) * (2 * DK / 16) * 64;
-        S = reinterpret_cast<int *>(base + o);         o += sizeof(int) * (size_t)KP * DK;
+        S = reinterpret_cast<int *>(base + o);         o += sizeof(int) * (size_t)KP * (DK + 1);
         n = reinterpret_cast<int *>(base + o);         o += sizeof(int) * KP;
         dirty = reinterpret_cast<int *>(base + o);     o += sizeof(int) * KP;
         ojf = reinterpret_cast<float *>(base + o);     o += sizeof(float) * DK;
@@ -372,8 +373,8 @@ __device__ __forceinline__ void apply_changes(const WaveQueue<DK> &Q, int cnt, i
             const half4 xq = *reinterpret_cast<const half4 *>(Q.rec_x() + (size_t)e * DK + j0);
             const int cur = w & 0xFF, prev = (w >> 8) & 0xFF;
             const bool first = prev == 0xFF;
-            int *sc = S + cur * DK + j0;
-            int *sp = S + (first ? cur : prev) * DK + j0;
+            int *sc = S + cur * (DK + 1) + j0;
+            int *sp = S + (first ? cur : prev) * (DK + 1) + j0;
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 if (j0 + i < d) {
@@ -426,7 +427,7 @@ __device__ __forceinline__ void update_centroids(const MfmaLds<DK> &U, int k, in
                 const int j = 4 * q + i;
                 double mu = U.mu64T[(size_t)j * KP + c];
                 if (!all && j < d) {
-                    mu = (double)U.S[c * DK + j] / (double)cnt;
+                    mu = (double)U.S[c * (DK + 1) + j] / (double)cnt;
                     U.mu64T[(size_t)j * KP + c] = mu;
                 }
                 const double m = j < d ? mu - (double)U.ojf[j] : 0.0;
@@ -498,7 +499,7 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
 
     // ---- set-up
     for (int e = tid; e < DK * KP; e += blockDim.x) U.mu64T[e] = 0.0;
-    for (int e = tid; e < KP * DK; e += blockDim.x) U.S[e] = 0;
+    for (int e = tid; e < KP * (DK + 1); e += blockDim.x) U.S[e] = 0;
     for (int c = tid; c < KP; c += blockDim.x) {
         U.n[c] = 0;
         U.dirty[c] = -1;
@@ -1002,6 +1003,19 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
         CHAM_TADD(3, t_d, t_e);   // barrier wait
         CHAM_TADD(4, t_e, t_f);   // loss / update
         CHAM_TCOUNT(9, 1);
+#ifdef CHAM_KERNEL_TIMING
+        if (lane == 0 && it < 64) {
+            atomicAdd(&g_pass[it * 16 + 0], t_b - t_a);
+            atomicAdd(&g_pass[it * 16 + 1], t_c - t_b);
+            atomicAdd(&g_pass[it * 16 + 2], t_d - t_c);
+            atomicAdd(&g_pass[it * 16 + 3], t_e - t_d);
+            atomicAdd(&g_pass[it * 16 + 4], t_f - t_e);
+            atomicAdd(&g_pass[it * 16 + 5], (unsigned long long)(mode == kCount ? 1 : 0));
+            atomicAdd(&g_pass[it * 16 + 6], 1ull);
+            atomicAdd(&g_pass[it * 16 + 7], (unsigned long long)nrec);
+            atomicAdd(&g_pass[it * 16 + 8], (unsigned long long)__popc(flagged_tiles));
+        }
+#endif
     }
 
 #ifdef CHAM_KERNEL_TIMING
@@ -1069,6 +1083,12 @@ hipError_t launch_mfma_t(const SweepArgs &a, int nwaves, hipStream_t s)
 }  // namespace
 
 #ifdef CHAM_KERNEL_TIMING
+extern "C" int cham_dev_pass_timing(unsigned long long *host512, int reset)
+{
+    static unsigned long long z[64 * 16] = {0};
+    if (reset) return (int)hipMemcpyToSymbol(HIP_SYMBOL(g_pass), z, sizeof(z));
+    return (int)hipMemcpyFromSymbol(host512, HIP_SYMBOL(g_pass), sizeof(z));
+}
 extern "C" int cham_dev_timing(unsigned long long *host16, int reset)
 {
     unsigned long long z[16] = {0};
