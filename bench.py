@@ -20,6 +20,11 @@ PEAK_FP32_VECTOR_TFLOPS = 157.3
 PEAK_F16_MFMA_TFLOPS = 2500.0
 PEAK_HBM_GBS = 8000.0
 
+# HBM bytes per launch of the dominant kernel, from the rocprofv3 --pmc runs (FETCH_SIZE x 2.000 and
+# WRITE_SIZE x 1.000 after calibration against a 1 GiB copy) recorded under profiles/; counters cannot be
+# read from inside this process, so only workloads that were profiled have a figure.
+MEASURED_TRAFFIC_BYTES = {("cfg5-fullmodel", 1.0): 4.63e9}
+
 
 def main():
     ap = argparse.ArgumentParser()
@@ -29,7 +34,7 @@ def main():
     ap.add_argument("--cfg", type=int, default=5, help="workload number 1..5 (default: the full-model sweep)")
     ap.add_argument("--scale", type=float, default=1.0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-tasks", type=int, default=8, help="tasks of the workload the oracle is timed on")
+    ap.add_argument("--cpu-tasks", type=int, default=48, help="tasks of the workload the oracle is timed on (about 13 s)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run only a plain 1 GiB device copy (reference for the FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
@@ -111,7 +116,8 @@ def main():
     kernel = ("resident_mfma_kernel" if resident else "stream_assign_kernel") if uses_mfma else "resident_sweep_kernel"
     peak = PEAK_F16_MFMA_TFLOPS if uses_mfma else PEAK_FP32_VECTOR_TFLOPS
     roofline = dict(bound="mfma" if uses_mfma else "alu", achieved=round(achieved_tflops, 3), peak=peak,
-                    unit="TFLOP/s", frac=round(achieved_tflops / peak, 4), traffic=None,
+                    unit="TFLOP/s", frac=round(achieved_tflops / peak, 4),
+                    traffic=MEASURED_TRAFFIC_BYTES.get((wl.name, args.scale)),
                     kernel=kernel,
                     kernel_ms=round(sweep_ms, 3), flops_per_eval=flops_per_eval,
                     frac_of_fp32_vector_peak=round(achieved_tflops / PEAK_FP32_VECTOR_TFLOPS, 4))
