@@ -110,6 +110,33 @@ int32_t cham_kmeans_sweep(const uint8_t *X, int64_t ld, int32_t d,
                           void *workspace, int64_t workspace_bytes, int32_t flags, void *stream);
 
 /*
+ * K-means sweep that stops at the knee, the loop of Algorithm 1 as printed: for k in the list,
+ * run k-means, and leave the loop at the first k with threshold * loss(k) >= previous_loss.
+ * The list is run in chunks of `chunk` consecutive entries of ks (all tasks at once); after every
+ * chunk the knee test runs on the device and the later chunks skip the tasks that have stopped,
+ * so at most chunk - 1 values of k beyond the knee are computed per task.  Arguments and outputs
+ * as for cham_kmeans_sweep, plus
+ *   threshold            the factor of the test (the paper's value is 2.5)
+ *   chunk                >= 1; values above n_k mean one chunk (the whole list)
+ *   chosen_idx [T]       DEVICE int32: index into ks of the k the loop stopped at (the last usable
+ *                        k if it never stopped, -1 if none is usable), as cham_select_k on the
+ *                        full curve would give
+ *   status               3 = not computed: the task had stopped before this k (outputs of that
+ *                        (t,k) are zero); every entry up to and including the chosen one is 0 or 1
+ * Every computed entry is identical to the one cham_kmeans_sweep produces.  Workspace:
+ * cham_sweep_knee_workspace_bytes(...) bytes.  Errors: as cham_kmeans_sweep; CHAM_E_BAD_K for
+ * chunk < 1, CHAM_E_NULL for a missing chosen_idx.
+ */
+int64_t cham_sweep_knee_workspace_bytes(int64_t ld, int32_t d, const int64_t *task_off, int32_t T,
+                                        const int32_t *ks, int32_t n_k, int32_t n_iter, int32_t flags);
+int32_t cham_kmeans_sweep_knee(const uint8_t *X, int64_t ld, int32_t d, const int64_t *task_off, int32_t T,
+                               const int32_t *ks, int32_t n_k, int32_t n_iter, int32_t init_mode,
+                               const double *init_centroids, double threshold, int32_t chunk,
+                               double *centroids, int32_t *counts, double *inertia, int32_t *status,
+                               int32_t *chosen_idx, uint8_t *labels, double *inertia_trace,
+                               void *workspace, int64_t workspace_bytes, int32_t flags, void *stream);
+
+/*
  * Knee selection (Algorithm 1: previous_loss = infinity; for each k in order: stop at the
  * first k with threshold * loss(k) >= previous_loss, and that k is the result; if no k
  * stops the loop the last k is the result).  Entries with status != 0 are skipped as if

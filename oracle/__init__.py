@@ -117,6 +117,43 @@ def select_k(loss, status=None, threshold: float = 2.5) -> int:
     return int(lib().orc_select_k(_p(loss), _p(st), C.c_int(len(loss)), C.c_double(threshold)))
 
 
+def sweep_until_knee(rows, task_off, ks: Sequence[int], n_iter: int, threshold: float = 2.5):
+    """Algorithm 1's loop, one task at a time: for k in ks run k-means from the first k distinct rows;
+    leave the loop at the first k with threshold * loss >= previous_loss (previous_loss starts at
+    infinity); a k with fewer than k distinct rows is passed over.  Returns dict(chosen_idx [T],
+    ran [T][n_k] bool, inertia [T][n_k], centroids: list per task of {ki: mu}, counts likewise)."""
+    x = _rows(rows)
+    task_off = np.ascontiguousarray(task_off, dtype=np.int64)
+    T, n_k = len(task_off) - 1, len(ks)
+    chosen = np.full(T, -1, dtype=np.int32)
+    ran = np.zeros((T, n_k), dtype=bool)
+    inertia = np.zeros((T, n_k), dtype=np.float64)
+    cents, cnts = [], []
+    for t in range(T):
+        xt = x[task_off[t]:task_off[t + 1]]
+        first = first_distinct(xt, int(max(ks))) if len(xt) else np.zeros(0, dtype=np.int64)
+        previous_loss = np.inf
+        last = -1
+        cents.append({})
+        cnts.append({})
+        for ki, k in enumerate(ks):
+            if len(first) < k:
+                continue
+            r = kmeans(xt, xt[first[:k]].astype(np.float64), n_iter)
+            ran[t, ki] = True
+            inertia[t, ki] = r["inertia"]
+            cents[t][ki] = r["mu"]
+            cnts[t][ki] = r["counts"]
+            last = ki
+            if threshold * r["inertia"] >= previous_loss:
+                chosen[t] = ki
+                break
+            previous_loss = r["inertia"]
+        if chosen[t] < 0:
+            chosen[t] = last
+    return dict(chosen_idx=chosen, ran=ran, inertia=inertia, centroids=cents, counts=cnts)
+
+
 def snap(x, mu):
     x = _rows(x)
     mu = np.ascontiguousarray(mu, dtype=np.float64)

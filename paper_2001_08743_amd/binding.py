@@ -22,7 +22,7 @@ EXPORTS = [
     "cham_version", "cham_strerror", "cham_last_hip_error", "cham_sweep_workspace_bytes",
     "cham_kmeans_sweep", "cham_select_k", "cham_select_k_host", "cham_snap_workspace_bytes",
     "cham_snap_centroids", "cham_synth_workspace_bytes", "cham_synthesize", "cham_hash_config",
-    "cham_hash_rows",
+    "cham_hash_rows", "cham_sweep_knee_workspace_bytes", "cham_kmeans_sweep_knee",
 ]
 
 
@@ -50,6 +50,11 @@ def load() -> C.CDLL:
         lib.cham_kmeans_sweep.restype = i32
         lib.cham_kmeans_sweep.argtypes = [vp, i64, i32, vp, i32, vp, i32, i32, i32, vp,
                                           vp, vp, vp, vp, vp, vp, vp, i64, i32, vp]
+        lib.cham_sweep_knee_workspace_bytes.restype = i64
+        lib.cham_sweep_knee_workspace_bytes.argtypes = [i64, i32, vp, i32, vp, i32, i32, i32]
+        lib.cham_kmeans_sweep_knee.restype = i32
+        lib.cham_kmeans_sweep_knee.argtypes = [vp, i64, i32, vp, i32, vp, i32, i32, i32, vp, f64, i32,
+                                               vp, vp, vp, vp, vp, vp, vp, vp, i64, i32, vp]
         lib.cham_select_k.restype = i32
         lib.cham_select_k.argtypes = [vp, vp, i32, i32, f64, vp, vp]
         lib.cham_select_k_host.restype = i32
@@ -147,6 +152,13 @@ def cham_sweep_workspace_bytes(ld, d, task_off, ks, n_iter, flags=0) -> int:
                                                     _hp(k), C.c_int32(len(k)), C.c_int32(n_iter), C.c_int32(flags)))
 
 
+def cham_sweep_knee_workspace_bytes(ld, d, task_off, ks, n_iter, flags=0) -> int:
+    to, k = _host_lists(task_off, ks)
+    return _check(load().cham_sweep_knee_workspace_bytes(C.c_int64(ld), C.c_int32(d), _hp(to),
+                                                         C.c_int32(len(to) - 1), _hp(k), C.c_int32(len(k)),
+                                                         C.c_int32(n_iter), C.c_int32(flags)))
+
+
 def cham_kmeans_sweep(X, ld: int, d: int, task_off, ks: Sequence[int], n_iter: int, init_centroids=None,
                       want_labels: bool = False, want_trace: bool = False, flags: int = 0,
                       out: Optional[dict] = None, workspace=None):
@@ -173,6 +185,40 @@ def cham_kmeans_sweep(X, ld: int, d: int, task_off, ks: Sequence[int], n_iter: i
                                _dp(out["inertia"]), _dp(out["status"]), _dp(out.get("labels")),
                                _dp(out.get("trace")), _dp(workspace), C.c_int64(workspace.numel()),
                                C.c_int32(flags), _stream())
+    _check(rc)
+    out["workspace"] = workspace
+    out["koff"] = np.concatenate([[0], np.cumsum(k)]).astype(np.int64)
+    return out
+
+
+def cham_kmeans_sweep_knee(X, ld: int, d: int, task_off, ks: Sequence[int], n_iter: int, threshold: float = 2.5,
+                           chunk: int = 8, init_centroids=None, want_labels: bool = False,
+                           want_trace: bool = False, flags: int = 0, out: Optional[dict] = None, workspace=None):
+    """Run the sweep in chunks and stop every task at its knee; returns the same dict plus ``chosen``."""
+    torch = _torch()
+    lib = load()
+    to, k = _host_lists(task_off, ks)
+    T, n_k, Ksum = len(to) - 1, len(k), int(k.sum())
+    dev = X.device
+    if out is None:
+        out = {}
+        out["centroids"] = torch.empty((T, Ksum, d), dtype=torch.float64, device=dev)
+        out["counts"] = torch.empty((T, Ksum), dtype=torch.int32, device=dev)
+        out["inertia"] = torch.empty((T, n_k), dtype=torch.float64, device=dev)
+        out["status"] = torch.empty((T, n_k), dtype=torch.int32, device=dev)
+        out["chosen"] = torch.empty(T, dtype=torch.int32, device=dev)
+        out["labels"] = torch.zeros((n_k, ld), dtype=torch.uint8, device=dev) if want_labels else None
+        out["trace"] = torch.empty((T, n_k, n_iter + 1), dtype=torch.float64, device=dev) if want_trace else None
+    if workspace is None:
+        nbytes = cham_sweep_knee_workspace_bytes(ld, d, to, k, n_iter, flags)
+        workspace = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=dev)
+    rc = lib.cham_kmeans_sweep_knee(_dp(X), C.c_int64(ld), C.c_int32(d), _hp(to), C.c_int32(T), _hp(k),
+                                    C.c_int32(n_k), C.c_int32(n_iter), C.c_int32(0 if init_centroids is None else 1),
+                                    _dp(init_centroids), C.c_double(threshold), C.c_int32(chunk),
+                                    _dp(out["centroids"]), _dp(out["counts"]), _dp(out["inertia"]),
+                                    _dp(out["status"]), _dp(out["chosen"]), _dp(out.get("labels")),
+                                    _dp(out.get("trace")), _dp(workspace), C.c_int64(workspace.numel()),
+                                    C.c_int32(flags), _stream())
     _check(rc)
     out["workspace"] = workspace
     out["koff"] = np.concatenate([[0], np.cumsum(k)]).astype(np.int64)

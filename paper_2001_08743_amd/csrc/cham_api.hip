@@ -210,11 +210,14 @@ int64_t cham_sweep_workspace_bytes(int64_t ld, int32_t d, const int64_t *task_of
     return sweep_ws(pl, ld, true, choose_path(pl, d, flags) == SweepPath::kStream, task_off).total;
 }
 
-int32_t cham_kmeans_sweep(const uint8_t *X, int64_t ld, int32_t d, const int64_t *task_off, int32_t T,
+// The sweep, whole (chunk <= 0) or in chunks of `chunk` values of k with the knee test between them:
+// tasks whose loss curve has reached the knee are marked done and the later chunks skip them.
+static int32_t sweep_impl(const uint8_t *X, int64_t ld, int32_t d, const int64_t *task_off, int32_t T,
                           const int32_t *ks, int32_t n_k, int32_t n_iter, int32_t init_mode,
                           const double *init_centroids, double *centroids, int32_t *counts,
                           double *inertia, int32_t *status, uint8_t *labels, double *inertia_trace,
-                          void *workspace, int64_t workspace_bytes, int32_t flags, void *stream)
+                          void *workspace, int64_t workspace_bytes, int32_t flags, void *stream,
+                          int32_t chunk, double threshold, int32_t *chosen_idx)
 {
     Plan pl;
     int32_t rc = check_common(X, ld, d, task_off, T, ks, n_k, true, pl);
@@ -226,7 +229,9 @@ int32_t cham_kmeans_sweep(const uint8_t *X, int64_t ld, int32_t d, const int64_t
     if (flags & ~(CHAM_F_FORCE_EXACT | CHAM_F_STREAMING | CHAM_F_RESIDENT | CHAM_F_NO_MFMA)) return CHAM_E_BAD_FLAG;
     const SweepPath path = choose_path(pl, d, flags);
     const SweepWs w = sweep_ws(pl, ld, labels == nullptr, path == SweepPath::kStream, task_off);
-    if (!workspace || workspace_bytes < w.total) return CHAM_E_WORKSPACE;
+    const bool chunked = chunk > 0;
+    const int64_t done_bytes = chunked ? up((int64_t)T * 4) : 0;
+    if (!workspace || workspace_bytes < w.total + done_bytes) return CHAM_E_WORKSPACE;
     if (reinterpret_cast<uintptr_t>(workspace) % kAlign) return CHAM_E_WORKSPACE;
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
     unsigned char *ws = static_cast<unsigned char *>(workspace);
@@ -258,72 +263,132 @@ int32_t cham_kmeans_sweep(const uint8_t *X, int64_t ld, int32_t d, const int64_t
     a.labbuf = labels ? labels : ws + w.labbuf;
     a.trace = inertia_trace;
     a.xh = reinterpret_cast<uint16_t *>(ws + w.xh);
+    a.ki_begin = 0;
+    a.ki_end = n_k;
+    a.done = nullptr;
+    int *done = chunked ? reinterpret_cast<int *>(ws + w.total) : nullptr;
+    if (chunked) {
+        e = launch_fill_i32(done, T, 0, s);
+        if (e != hipSuccess) return hip_fail(e);
+    }
 
     if (init_mode == 0) {
         e = launch_first_distinct(a, reinterpret_cast<int *>(ws + w.init_rows),
                                   reinterpret_cast<int *>(ws + w.ndist), s);
         if (e != hipSuccess) return hip_fail(e);
     }
-    if (path == SweepPath::kStream) {
-        // first workgroup of every unit, in launch order (largest k first)
-        std::vector<uint64_t> wo(((size_t)w.n_units + 2) / 2, 0);
-        int32_t *po = reinterpret_cast<int32_t *>(wo.data());
-        int acc = 0;
-        for (int u = 0; u < w.n_units; ++u) {
-            const int t = u % T;
-            po[u] = acc;
-            acc += (int)((task_off[t + 1] - task_off[t] + kStreamRowsPerWg - 1) / kStreamRowsPerWg);
+    const int step = chunked ? chunk : n_k;
+    for (int ki_begin = 0; ki_begin < n_k; ki_begin += step) {
+        const int ki_end = ki_begin + step < n_k ? ki_begin + step : n_k;
+        a.ki_begin = ki_begin;
+        a.ki_end = ki_end;
+        a.done = ki_begin > 0 ? done : nullptr;
+        if (path == SweepPath::kStream) {
+            // first workgroup of every unit, in launch order (largest k first)
+            const int n_units = (ki_end - ki_begin) * T;        // units of this chunk, largest k first
+            std::vector<uint64_t> wo(((size_t)n_units + 2) / 2, 0);
+            int32_t *po = reinterpret_cast<int32_t *>(wo.data());
+            int acc = 0;
+            for (int u = 0; u < n_units; ++u) {
+                const int t = u % T;
+                po[u] = acc;
+                acc += (int)((task_off[t + 1] - task_off[t] + kStreamRowsPerWg - 1) / kStreamRowsPerWg);
+            }
+            po[n_units] = acc;
+            e = stage_words(wo, reinterpret_cast<uint64_t *>(ws + w.wg_off), s);
+            if (e != hipSuccess) return hip_fail(e);
+            StreamArgs sa;
+            sa.X = X;
+            sa.ld = ld;
+            sa.d = d;
+            sa.T = T;
+            sa.n_k = n_k;
+            sa.Ksum = pl.Ksum;
+            sa.kmax = pl.kmax;
+            sa.kpm = w.kpm;
+            sa.n_iter = n_iter;
+            sa.init_mode = init_mode;
+            sa.n_units = n_units;
+            sa.u_begin = (n_k - ki_end) * T;
+            sa.prepare = ki_begin == 0 ? 1 : 0;
+            sa.done = a.done;
+            sa.rows_per_wg = kStreamRowsPerWg;
+            sa.it = 0;
+            sa.final_pass = 0;
+            sa.task_off = a.task_off;
+            sa.ks = a.ks;
+            sa.koff = a.koff;
+            sa.init_centroids = init_centroids;
+            sa.init_rows = a.init_rows;
+            sa.ndist = a.ndist;
+            sa.wg_off = reinterpret_cast<const int *>(ws + w.wg_off);
+            sa.centroids = centroids;
+            sa.counts = counts;
+            sa.inertia = inertia;
+            sa.status = status;
+            sa.labbuf = a.labbuf;
+            sa.trace = inertia_trace;
+            sa.xh = a.xh;
+            sa.x2 = reinterpret_cast<float *>(ws + w.x2);
+            sa.ojf = reinterpret_cast<float *>(ws + w.ojf);
+            sa.Sg = reinterpret_cast<int *>(ws + w.Sg);
+            sa.ng = reinterpret_cast<int *>(ws + w.ng);
+            sa.mu = reinterpret_cast<double *>(ws + w.mu);
+            sa.afrag = ws + w.afrag;
+            sa.m2 = reinterpret_cast<float *>(ws + w.m2);
+            sa.loss_part = reinterpret_cast<double *>(ws + w.loss);
+            if (stream_lds_bytes(d, w.kpm) > 160 * 1024) return CHAM_E_BAD_K;
+            e = acc > 0 ? launch_stream_sweep(sa, pl.n_total, acc, s) : hipSuccess;
+            if (acc == 0) e = launch_resident_sweep(a, pl.nt, s);   // all tasks empty: trivial path
+        } else if (path == SweepPath::kMfmaResident) {
+            e = launch_mfma_sweep(a, pl.n_max, pl.n_total, s);
+        } else {
+            e = launch_resident_sweep(a, pl.nt, s);
         }
-        po[w.n_units] = acc;
-        e = stage_words(wo, reinterpret_cast<uint64_t *>(ws + w.wg_off), s);
         if (e != hipSuccess) return hip_fail(e);
-        StreamArgs sa;
-        sa.X = X;
-        sa.ld = ld;
-        sa.d = d;
-        sa.T = T;
-        sa.n_k = n_k;
-        sa.Ksum = pl.Ksum;
-        sa.kmax = pl.kmax;
-        sa.kpm = w.kpm;
-        sa.n_iter = n_iter;
-        sa.init_mode = init_mode;
-        sa.n_units = w.n_units;
-        sa.rows_per_wg = kStreamRowsPerWg;
-        sa.it = 0;
-        sa.final_pass = 0;
-        sa.task_off = a.task_off;
-        sa.ks = a.ks;
-        sa.koff = a.koff;
-        sa.init_centroids = init_centroids;
-        sa.init_rows = a.init_rows;
-        sa.ndist = a.ndist;
-        sa.wg_off = reinterpret_cast<const int *>(ws + w.wg_off);
-        sa.centroids = centroids;
-        sa.counts = counts;
-        sa.inertia = inertia;
-        sa.status = status;
-        sa.labbuf = a.labbuf;
-        sa.trace = inertia_trace;
-        sa.xh = a.xh;
-        sa.x2 = reinterpret_cast<float *>(ws + w.x2);
-        sa.ojf = reinterpret_cast<float *>(ws + w.ojf);
-        sa.Sg = reinterpret_cast<int *>(ws + w.Sg);
-        sa.ng = reinterpret_cast<int *>(ws + w.ng);
-        sa.mu = reinterpret_cast<double *>(ws + w.mu);
-        sa.afrag = ws + w.afrag;
-        sa.m2 = reinterpret_cast<float *>(ws + w.m2);
-        sa.loss_part = reinterpret_cast<double *>(ws + w.loss);
-        if (stream_lds_bytes(d, w.kpm) > 160 * 1024) return CHAM_E_BAD_K;
-        e = w.total_wgs > 0 ? launch_stream_sweep(sa, pl.n_total, w.total_wgs, s) : hipSuccess;
-        if (w.total_wgs == 0) e = launch_resident_sweep(a, pl.nt, s);   // all tasks empty: trivial path
-    } else if (path == SweepPath::kMfmaResident) {
-        e = launch_mfma_sweep(a, pl.n_max, pl.n_total, s);
-    } else {
-        e = launch_resident_sweep(a, pl.nt, s);
+        if (chunked && ki_end < n_k) {
+            e = launch_knee_update(inertia, status, T, n_k, ki_end, threshold, done, s);
+            if (e != hipSuccess) return hip_fail(e);
+        }
     }
-    if (e != hipSuccess) return hip_fail(e);
+    if (chunked) {
+        e = launch_select_k(inertia, status, T, n_k, threshold, chosen_idx, s);
+        if (e != hipSuccess) return hip_fail(e);
+    }
     return CHAM_OK;
+}
+
+int32_t cham_kmeans_sweep(const uint8_t *X, int64_t ld, int32_t d, const int64_t *task_off, int32_t T,
+                          const int32_t *ks, int32_t n_k, int32_t n_iter, int32_t init_mode,
+                          const double *init_centroids, double *centroids, int32_t *counts,
+                          double *inertia, int32_t *status, uint8_t *labels, double *inertia_trace,
+                          void *workspace, int64_t workspace_bytes, int32_t flags, void *stream)
+{
+    return sweep_impl(X, ld, d, task_off, T, ks, n_k, n_iter, init_mode, init_centroids, centroids, counts, inertia,
+                      status, labels, inertia_trace, workspace, workspace_bytes, flags, stream, 0, 0.0, nullptr);
+}
+
+int64_t cham_sweep_knee_workspace_bytes(int64_t ld, int32_t d, const int64_t *task_off, int32_t T,
+                                        const int32_t *ks, int32_t n_k, int32_t n_iter, int32_t flags)
+{
+    const int64_t base = cham_sweep_workspace_bytes(ld, d, task_off, T, ks, n_k, n_iter, flags);
+    if (base < 0) return base;
+    return base + up((int64_t)T * 4);
+}
+
+int32_t cham_kmeans_sweep_knee(const uint8_t *X, int64_t ld, int32_t d, const int64_t *task_off, int32_t T,
+                               const int32_t *ks, int32_t n_k, int32_t n_iter, int32_t init_mode,
+                               const double *init_centroids, double threshold, int32_t chunk,
+                               double *centroids, int32_t *counts, double *inertia, int32_t *status,
+                               int32_t *chosen_idx, uint8_t *labels, double *inertia_trace,
+                               void *workspace, int64_t workspace_bytes, int32_t flags, void *stream)
+{
+    if (!chosen_idx) return CHAM_E_NULL;
+    if (chunk < 1) return CHAM_E_BAD_K;
+    if (chunk > n_k) chunk = n_k;
+    return sweep_impl(X, ld, d, task_off, T, ks, n_k, n_iter, init_mode, init_centroids, centroids, counts, inertia,
+                      status, labels, inertia_trace, workspace, workspace_bytes, flags, stream, chunk, threshold,
+                      chosen_idx);
 }
 
 int32_t cham_select_k_host(const double *curve, const int32_t *status, int32_t n_k, double threshold)

@@ -30,6 +30,8 @@ struct SweepArgs {
     uint8_t *labbuf;               // [n_k][ld] working / final labels
     double *trace;                 // [T][n_k][n_iter+1] or null
     uint16_t *xh;                  // [ld][16 or 32] f16 row-major copy of X (matrix-core path)
+    int ki_begin, ki_end;          // this launch runs ks[ki_begin .. ki_end) (the whole list by default)
+    const int *done;               // [T] or null: tasks whose sweep has already stopped; their units are skipped (status 3)
 };
 
 // LDS bytes the resident kernel needs for padded knob count DP and largest k.
@@ -58,7 +60,10 @@ struct StreamArgs {
     int kpm;                       // kmax rounded up to a multiple of 32
     int n_iter;
     int init_mode;
-    int n_units;                   // T * n_k, unit u = (ki = n_k - 1 - u / T, t = u % T)
+    int n_units;                   // units of this launch; unit u = u_begin + local index = (ki = n_k - 1 - u / T, t = u % T)
+    int u_begin;                   // first unit of this launch
+    int prepare;                   // 1: this launch also computes the centring offsets and the packed rows
+    const int *done;               // [T] or null: tasks whose sweep has already stopped (their units report status 3)
     int rows_per_wg;
     int it;                        // pass being run
     int final_pass;
@@ -150,6 +155,9 @@ bool mfma_path_fits(int d, int kmax, int64_t n_max);
 hipError_t launch_mfma_sweep(const SweepArgs &a, int64_t n_max, int64_t n_total, hipStream_t s);
 int64_t stream_lds_bytes(int d, int kpm);
 hipError_t launch_stream_sweep(const StreamArgs &a, int64_t n_total, int total_wgs, hipStream_t s);
+hipError_t launch_knee_update(const double *inertia, const int *status, int T, int n_k, int ki_end, double thr,
+                              int *done, hipStream_t s);
+hipError_t launch_fill_i32(int *dst, int64_t n, int value, hipStream_t s);
 hipError_t launch_select_k(const double *inertia, const int *status, int T, int n_k, double thr,
                            int *chosen, hipStream_t s);
 hipError_t launch_snap(const SnapArgs &a, int nt, hipStream_t s);

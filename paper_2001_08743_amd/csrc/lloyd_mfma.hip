@@ -1041,12 +1041,13 @@ __global__ __launch_bounds__(512) void resident_mfma_kernel(const SweepArgs a)
 
     // units in descending-k order so that the longest ones start first
     const int u = blockIdx.x;
-    const int ki = a.n_k - 1 - u / a.T;
+    const int ki = a.ki_end - 1 - u / a.T;
     const int t = u % a.T;
     const int k = a.ks[ki];
+    const bool skipped = a.done && a.done[t];     // the task's sweep stopped at a smaller k
 
-    if (a.init_mode == 0 && a.ndist[t] < k) {
-        // fewer than k distinct rows: the unit is reported as unusable, all outputs zero
+    if (skipped || (a.init_mode == 0 && a.ndist[t] < k)) {
+        // fewer than k distinct rows, or not needed any more: all outputs zero, status says which
         const int d = a.d;
         const int64_t r0 = a.task_off[t], r1 = a.task_off[t + 1];
         const int64_t slot = (int64_t)t * a.n_k + ki;
@@ -1056,7 +1057,7 @@ __global__ __launch_bounds__(512) void resident_mfma_kernel(const SweepArgs a)
         for (int c = tid; c < k; c += blockDim.x) a.counts[crow + c] = 0;
         for (int64_t r = r0 + tid; r < r1; r += blockDim.x) labrow[r] = 0;
         if (tid == 0) {
-            a.status[slot] = 1;
+            a.status[slot] = skipped ? 3 : 1;
             a.inertia[slot] = 0.0;
         }
         if (a.trace)
@@ -1075,7 +1076,7 @@ hipError_t launch_mfma_t(const SweepArgs &a, int nwaves, hipStream_t s)
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
-    const unsigned units = (unsigned)a.T * (unsigned)a.n_k;
+    const unsigned units = (unsigned)a.T * (unsigned)(a.ki_end - a.ki_begin);
     hipLaunchKernelGGL(kern, dim3(units), dim3(nwaves * 64), lds, s, a);
     return hipGetLastError();
 }
@@ -1103,6 +1104,7 @@ bool mfma_path_fits(int d, int kmax, int64_t n_max)
     return d >= 1 && d <= 29 && kmax <= 64 && n_max <= 4096;
 }
 
+// The packed row copy is made by the launch that starts at the first k (chunked sweeps reuse it).
 hipError_t launch_mfma_sweep(const SweepArgs &a, int64_t n_max, int64_t n_total, hipStream_t s)
 {
     const int ntw = n_max <= 1024 ? 4 : 16;
@@ -1111,11 +1113,11 @@ hipError_t launch_mfma_sweep(const SweepArgs &a, int64_t n_max, int64_t n_total,
     if (nwaves > 8) nwaves = 8;
     const unsigned pb = (unsigned)((n_total + 255) / 256);
     if (a.d <= 13) {
-        if (pb) hipLaunchKernelGGL(pack_rows_kernel<16>, dim3(pb), dim3(256), 0, s, a.X, a.ld, a.d, n_total,
+        if (pb && a.ki_begin == 0) hipLaunchKernelGGL(pack_rows_kernel<16>, dim3(pb), dim3(256), 0, s, a.X, a.ld, a.d, n_total,
                                    reinterpret_cast<_Float16 *>(a.xh));
         return ntw == 4 ? launch_mfma_t<16, 4>(a, nwaves, s) : launch_mfma_t<16, 16>(a, nwaves, s);
     }
-    if (pb) hipLaunchKernelGGL(pack_rows_kernel<32>, dim3(pb), dim3(256), 0, s, a.X, a.ld, a.d, n_total,
+    if (pb && a.ki_begin == 0) hipLaunchKernelGGL(pack_rows_kernel<32>, dim3(pb), dim3(256), 0, s, a.X, a.ld, a.d, n_total,
                                reinterpret_cast<_Float16 *>(a.xh));
     return ntw == 4 ? launch_mfma_t<32, 4>(a, nwaves, s) : launch_mfma_t<32, 16>(a, nwaves, s);
 }

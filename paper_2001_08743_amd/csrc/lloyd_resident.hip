@@ -75,10 +75,11 @@ __global__ __launch_bounds__(MAXNT) void resident_sweep_kernel(const SweepArgs a
 
     // units in descending-k order so that the longest ones start first
     const int u = blockIdx.x;
-    const int ki = a.n_k - 1 - u / a.T;
+    const int ki = a.ki_end - 1 - u / a.T;
     const int t = u % a.T;
     const int k = a.ks[ki];
     const int kp = k;
+    const bool skipped = a.done && a.done[t];     // the task's sweep stopped at a smaller k
     const int d = a.d;
     const int64_t r0 = a.task_off[t], r1 = a.task_off[t + 1];
     const int64_t slot = (int64_t)t * a.n_k + ki;
@@ -88,13 +89,13 @@ __global__ __launch_bounds__(MAXNT) void resident_sweep_kernel(const SweepArgs a
     const int tile_rows = blockDim.x * kRowsPerThread;
     const bool force_exact = (a.flags & 1) != 0;
 
-    if (a.init_mode == 0 && a.ndist[t] < k) {
-        // fewer than k distinct rows: the unit is reported as unusable, all outputs zero
+    if (skipped || (a.init_mode == 0 && a.ndist[t] < k)) {
+        // fewer than k distinct rows, or not needed any more: all outputs zero, status says which
         for (int e = tid; e < k * d; e += blockDim.x) a.centroids[crow * d + e] = 0.0;
         for (int c = tid; c < k; c += blockDim.x) a.counts[crow + c] = 0;
         for (int64_t r = r0 + tid; r < r1; r += blockDim.x) labrow[r] = 0;
         if (tid == 0) {
-            a.status[slot] = 1;
+            a.status[slot] = skipped ? 3 : 1;
             a.inertia[slot] = 0.0;
         }
         if (a.trace)
@@ -299,7 +300,7 @@ hipError_t launch_dp(const SweepArgs &a, int nt, hipStream_t s)
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
     if (nt > MAXNT) nt = MAXNT;
-    const unsigned units = (unsigned)a.T * (unsigned)a.n_k;
+    const unsigned units = (unsigned)a.T * (unsigned)(a.ki_end - a.ki_begin);
     hipLaunchKernelGGL(kern, dim3(units), dim3(nt), lds, s, a);
     return hipGetLastError();
 }

@@ -106,7 +106,8 @@ __global__ __launch_bounds__(256) void stream_update_kernel(const StreamArgs a, 
 {
     constexpr int NS = DK / 16, G = DK / 8;
     __shared__ float red[256];
-    const int u = blockIdx.x;
+    const int ul = blockIdx.x;                 // unit within this launch
+    const int u = a.u_begin + ul;
     const int ki = a.n_k - 1 - u / a.T;
     const int t = u % a.T;
     const int k = a.ks[ki];
@@ -117,7 +118,8 @@ __global__ __launch_bounds__(256) void stream_update_kernel(const StreamArgs a, 
     const int64_t r0 = a.task_off[t], r1 = a.task_off[t + 1];
     const UnitState st = unit_state(a, u);
     const int kpm = a.kpm;
-    const bool unusable = a.init_mode == 0 && a.ndist[t] < k;
+    const bool skipped = a.done && a.done[t];  // the task's sweep stopped at a smaller k
+    const bool unusable = skipped || (a.init_mode == 0 && a.ndist[t] < k);
 
     if (unusable) {
         if (mode == 0 && tid == 0) a.m2[u] = -1.0f;
@@ -127,7 +129,7 @@ __global__ __launch_bounds__(256) void stream_update_kernel(const StreamArgs a, 
             uint8_t *labrow = a.labbuf + (int64_t)ki * a.ld;
             for (int64_t r = r0 + tid; r < r1; r += blockDim.x) labrow[r] = 0;
             if (tid == 0) {
-                a.status[slot] = 1;
+                a.status[slot] = skipped ? 3 : 1;
                 a.inertia[slot] = 0.0;
             }
             if (a.trace)
@@ -138,9 +140,9 @@ __global__ __launch_bounds__(256) void stream_update_kernel(const StreamArgs a, 
 
     // loss of the pass that just ran: workgroup partials in workgroup order
     if (mode != 0 && tid == 0 && (mode == 2 || a.trace)) {
-        const int nwg = a.wg_off[u + 1] - a.wg_off[u];
+        const int nwg = a.wg_off[ul + 1] - a.wg_off[ul];
         double s = 0.0;
-        for (int w = 0; w < nwg; ++w) s = s + a.loss_part[(size_t)a.wg_off[u] + w];
+        for (int w = 0; w < nwg; ++w) s = s + a.loss_part[(size_t)a.wg_off[ul] + w];
         if (a.trace) a.trace[slot * (a.n_iter + 1) + a.it] = s;
         if (mode == 2) {
             a.inertia[slot] = s;
@@ -274,8 +276,8 @@ __global__ __launch_bounds__(512) void stream_assign_kernel(const StreamArgs a)
         unit_sh = lo;
     }
     __syncthreads();
-    const int u = unit_sh;
-    const int wgi = blockIdx.x - a.wg_off[u];
+    const int wgi = blockIdx.x - a.wg_off[unit_sh];
+    const int u = a.u_begin + unit_sh;
     const int ki = a.n_k - 1 - u / a.T;
     const int t = u % a.T;
     const int k = a.ks[ki];
@@ -610,9 +612,11 @@ hipError_t run_stream(StreamArgs a, int64_t n_total, int total_wgs, hipStream_t 
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(stream_assign_kernel<DK>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(stream_offsets_kernel, dim3(a.T), dim3(64), 0, s, a);
-    const unsigned pb = (unsigned)((n_total + 255) / 256);
-    if (pb) hipLaunchKernelGGL(stream_pack_kernel<DK>, dim3(pb), dim3(256), 0, s, a, n_total);
+    if (a.prepare) {
+        hipLaunchKernelGGL(stream_offsets_kernel, dim3(a.T), dim3(64), 0, s, a);
+        const unsigned pb = (unsigned)((n_total + 255) / 256);
+        if (pb) hipLaunchKernelGGL(stream_pack_kernel<DK>, dim3(pb), dim3(256), 0, s, a, n_total);
+    }
     a.it = 0;
     a.final_pass = 0;
     hipLaunchKernelGGL(stream_update_kernel<DK>, dim3(a.n_units), dim3(256), 0, s, a, 0);

@@ -33,6 +33,35 @@ __global__ void select_k_kernel(const double *inertia, const int *status, int T,
     chosen[t] = pick >= 0 ? pick : last;
 }
 
+// Between two chunks of a sweep that stops at the knee (Algorithm 1 breaks out of its loop over k at
+// the first k with threshold * loss >= previous_loss): tasks whose curve has reached that k are
+// marked done; the remaining chunks skip them.
+__global__ void knee_update_kernel(const double *inertia, const int *status, int T, int n_k, int ki_end,
+                                   double threshold, int *done)
+{
+    const int t = blockIdx.x * blockDim.x + threadIdx.x;
+    if (t >= T || done[t]) return;
+    const double *L = inertia + (int64_t)t * n_k;
+    const int *st = status + (int64_t)t * n_k;
+    bool have_prev = false;
+    double prev = 0.0;
+    for (int i = 0; i < ki_end; ++i) {
+        if (st[i] != 0) continue;
+        if (have_prev && threshold * L[i] >= prev) {
+            done[t] = 1;
+            return;
+        }
+        prev = L[i];
+        have_prev = true;
+    }
+}
+
+__global__ void fill_i32_kernel(int *dst, int64_t n, int value)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) dst[i] = value;
+}
+
 // ---------------------------------------------------------------------------------------------
 // Snap: one workgroup per task.  Labels under the chosen centroids (same two-stage exact
 // assignment as the sweep), then per cluster the member with the smallest exact distance,
@@ -715,6 +744,20 @@ hipError_t launch_snap_dp(const SnapArgs &a, int nt, hipStream_t s)
 }
 
 }  // namespace
+
+hipError_t launch_knee_update(const double *inertia, const int *status, int T, int n_k, int ki_end, double thr,
+                              int *done, hipStream_t s)
+{
+    hipLaunchKernelGGL(knee_update_kernel, dim3((T + 127) / 128), dim3(128), 0, s, inertia, status, T, n_k, ki_end, thr,
+                       done);
+    return hipGetLastError();
+}
+
+hipError_t launch_fill_i32(int *dst, int64_t n, int value, hipStream_t s)
+{
+    if (n > 0) hipLaunchKernelGGL(fill_i32_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, dst, n, value);
+    return hipGetLastError();
+}
 
 hipError_t launch_select_k(const double *inertia, const int *status, int T, int n_k, double thr,
                            int *chosen, hipStream_t s)

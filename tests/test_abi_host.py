@@ -102,3 +102,19 @@ def test_workspace_queries(lib):
     assert n >= 63 * 4096 and n % 256 == 0
     with pytest.raises(binding.ChamError):
         binding.cham_sweep_workspace_bytes(4095, 12, [0, 4095], [2, 3], 5)
+
+
+def test_knee_sweep_workspace_and_argument_errors(lib):
+    base = binding.cham_sweep_workspace_bytes(4096, 12, [0, 2048, 4096], list(range(2, 65)), 50)
+    knee = binding.cham_sweep_knee_workspace_bytes(4096, 12, [0, 2048, 4096], list(range(2, 65)), 50)
+    assert knee >= base + 2 * 4 and knee % 256 == 0
+    to = (C.c_int64 * 2)(0, 16)
+    ks = (C.c_int32 * 2)(2, 3)
+    one = C.c_void_p(256)                                   # non-null, never dereferenced: errors come first
+    args = lambda chunk, chosen: lib.cham_kmeans_sweep_knee(one, C.c_int64(16), C.c_int32(4), to, C.c_int32(1), ks,
+                                                            C.c_int32(2), C.c_int32(3), C.c_int32(0), None,
+                                                            C.c_double(2.5), C.c_int32(chunk), one, one, one, one,
+                                                            chosen, None, None, one, C.c_int64(1 << 20),
+                                                            C.c_int32(0), None)
+    assert args(1, None) == -1                              # missing chosen_idx
+    assert args(0, one) == -3                               # chunk < 1

@@ -352,3 +352,79 @@ def test_large_tasks_snap_and_synthesis_over_chunks(seed, d, card_hi, ks):
     check_pipeline(wl, g, c)
     flags = c["out_flag"]
     assert (flags == oracle.DROPPED).any() or (flags == oracle.SYNTH).any()
+
+
+# ------------------------------------------------------------------ sweep that stops at the knee
+
+def _check_knee_sweep(wl, thr, chunk, flags=0):
+    """Chunked sweep against the oracle: the chosen k is the one Algorithm 1's loop stops at, every
+    computed entry equals the full sweep's, and only whole chunks after the stopping chunk are left out."""
+    import torch
+    dw = binding.DeviceWorkload(wl)
+    out = binding.cham_kmeans_sweep_knee(dw.X, dw.ld, dw.d, wl.task_off, wl.ks, wl.n_iter, threshold=thr,
+                                         chunk=chunk, want_labels=True, flags=flags)
+    torch.cuda.synchronize()
+    full = oracle.sweep(wl.rows, wl.task_off, wl.ks, wl.n_iter, want_labels=True)
+    loop = oracle.sweep_until_knee(wl.rows, wl.task_off, wl.ks, wl.n_iter, thr)
+    chosen = out["chosen"].cpu().numpy()
+    status = out["status"].cpu().numpy()
+    np.testing.assert_array_equal(chosen, loop["chosen_idx"])
+    n_k = len(wl.ks)
+    koff = np.concatenate([[0], np.cumsum(wl.ks)])
+    cent, cnt = out["centroids"].cpu().numpy(), out["counts"].cpu().numpy()
+    inertia, labels = out["inertia"].cpu().numpy(), out["labels"].cpu().numpy()
+    for t in range(wl.T):
+        # the task stops in the chunk that holds its break (if the loop broke at all)
+        broke = loop["ran"][t].sum() > 0 and chosen[t] >= 0 and \
+            thr * loop["inertia"][t, chosen[t]] >= _prev_loss(loop, t, chosen[t])
+        last_run = min(n_k, (chosen[t] // chunk + 1) * chunk) if broke else n_k
+        for ki in range(n_k):
+            if ki >= last_run:
+                assert status[t, ki] == 3, (t, ki)
+                continue
+            assert status[t, ki] == full["status"][t, ki], (t, ki)
+            if status[t, ki] != 0:
+                continue
+            sl = slice(koff[ki], koff[ki + 1])
+            np.testing.assert_array_equal(cent[t, sl], full["centroids"][t, sl])
+            np.testing.assert_array_equal(cnt[t, sl], full["counts"][t, sl])
+            np.testing.assert_allclose(inertia[t, ki], full["inertia"][t, ki], rtol=1e-11, atol=0)
+            r0, r1 = wl.task_off[t], wl.task_off[t + 1]
+            np.testing.assert_array_equal(labels[ki, r0:r1].astype(np.int32), full["labels"][ki, r0:r1])
+    return out
+
+
+def _prev_loss(loop, t, ki):
+    prev = np.inf
+    for i in range(ki):
+        if loop["ran"][t, i]:
+            prev = loop["inertia"][t, i]
+    return prev
+
+
+@pytest.mark.parametrize("thr,chunk", [(2.5, 1), (2.5, 4), (1.05, 3), (1.01, 5), (1.0, 64), (1.3, 2)])
+def test_knee_sweep_resident_paths(thr, chunk):
+    wl = workloads.random_task(900 + chunk, n=1200, d=9, n_blobs=6, ks=tuple(range(1, 20)), n_iter=8, n_tasks=5,
+                               ragged=True, card_hi=10)
+    _check_knee_sweep(wl, thr, chunk)
+    _check_knee_sweep(wl, thr, chunk, flags=binding.F_NO_MFMA)
+
+
+def test_knee_sweep_with_too_few_distinct_rows_and_an_empty_task():
+    wl = workloads.random_task(930, n=40, d=2, card_hi=3, n_blobs=2, ks=(2, 4, 6, 9, 12, 40), n_iter=5, n_tasks=3)
+    wl.task_off = np.array([0, 40, 40, 120])             # the middle task has no rows
+    _check_knee_sweep(wl, 1.2, 2)
+
+
+def test_knee_sweep_streaming_path():
+    wl = workloads.random_task(940, n=20000, d=10, n_blobs=12, ks=(2, 4, 8, 16, 40, 90), n_iter=5, card_hi=16)
+    _check_knee_sweep(wl, 1.3, 2)
+    _check_knee_sweep(wl, 2.5, 1)
+
+
+def test_knee_sweep_on_the_full_model_slice():
+    """cfg 5 tasks, the paper's threshold, chunks of 8: nearly every task stops in the first chunk."""
+    wl = workloads.make_config(5, 0, scale=4 / 256)
+    out = _check_knee_sweep(wl, wl.threshold, 8)
+    status = out["status"].cpu().numpy()
+    assert (status[:, 8:] == 3).mean() > 0.5

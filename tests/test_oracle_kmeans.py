@@ -256,3 +256,42 @@ def test_batch_equals_single_tasks():
             r = oracle.kmeans(x, start_rows(x, k), wl.n_iter)
             np.testing.assert_array_equal(sw["centroids"][t, sw["koff"][ki]:sw["koff"][ki] + k], r["mu"])
             assert sw["inertia"][t, ki] == r["inertia"]
+
+
+# ------------------------------------------------------------------ the loop that stops at the knee
+
+@pytest.mark.parametrize("seed,thr", [(11, 2.5), (12, 1.05), (13, 1.01), (14, 1.0), (15, 1.3)])
+def test_early_break_loop_agrees_with_full_sweep_then_select(seed, thr):
+    """Algorithm 1 run literally (k after k, break at the knee) must pick the k that the knee rule
+    picks on the full loss curve, and every k it ran must give the full sweep's result."""
+    from paper_2001_08743_amd import workloads
+    wl = workloads.random_task(seed, n=300, d=5, n_blobs=5, ks=(1, 2, 3, 4, 6, 8, 11), n_iter=8, n_tasks=3,
+                               ragged=True, card_hi=6)
+    full = oracle.sweep(wl.rows, wl.task_off, wl.ks, wl.n_iter)
+    eb = oracle.sweep_until_knee(wl.rows, wl.task_off, wl.ks, wl.n_iter, thr)
+    koff = np.concatenate([[0], np.cumsum(wl.ks)])
+    for t in range(wl.T):
+        want = oracle.select_k(full["inertia"][t], full["status"][t], thr)
+        assert eb["chosen_idx"][t] == want
+        # nothing after the break was run, everything usable before it was
+        assert not eb["ran"][t, want + 1:].any()
+        for ki in range(want + 1):
+            assert eb["ran"][t, ki] == (full["status"][t, ki] == 0)
+            if eb["ran"][t, ki]:
+                assert eb["inertia"][t, ki] == full["inertia"][t, ki]
+                np.testing.assert_array_equal(eb["centroids"][t][ki], full["centroids"][t, koff[ki]:koff[ki + 1]])
+                np.testing.assert_array_equal(eb["counts"][t][ki], full["counts"][t, koff[ki]:koff[ki + 1]])
+
+
+def test_early_break_loop_hand_case():
+    """Two well separated pairs of points: loss(1) = 8, loss(2) = 0.5 * 4 = ... computed by hand below."""
+    rows = np.array([[0], [1], [10], [11]], dtype=np.uint8)
+    # k=1: mean 5.5, loss = 5.5^2 + 4.5^2 + 4.5^2 + 5.5^2 = 101; k=2 from starts {0, 1}: converges to
+    # {0.5, 10.5}, loss = 4 * 0.25 = 1; k=3 from starts {0, 1, 10}: {0}, {1}, {10, 11}: loss = 0.5
+    eb = oracle.sweep_until_knee(rows, [0, 4], [1, 2, 3], 10, threshold=1.5)
+    np.testing.assert_allclose(eb["inertia"][0], [101.0, 1.0, 0.5])
+    assert eb["chosen_idx"][0] == 2 and eb["ran"][0].all()          # 1.5 * 0.5 = 0.75 < 1: no break, last k
+    eb = oracle.sweep_until_knee(rows, [0, 4], [1, 2, 3], 10, threshold=2.5)
+    assert eb["chosen_idx"][0] == 2                                  # 2.5 * 0.5 = 1.25 >= 1: break at k = 3
+    eb = oracle.sweep_until_knee(rows, [0, 4], [1, 2, 3], 10, threshold=150.0)
+    assert eb["chosen_idx"][0] == 1 and not eb["ran"][0, 2]          # 150 * 1 >= 101: break at k = 2
