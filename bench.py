@@ -35,6 +35,8 @@ def main():
     ap.add_argument("--scale", type=float, default=1.0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-tasks", type=int, default=48, help="tasks of the workload the oracle is timed on (about 13 s)")
+    ap.add_argument("--knee-chunk", type=int, default=8,
+                    help="also time the sweep that stops at the knee, in chunks of this many k (0 = skip)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run only a plain 1 GiB device copy (reference for the FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
@@ -122,6 +124,32 @@ def main():
                     kernel_ms=round(sweep_ms, 3), flops_per_eval=flops_per_eval,
                     frac_of_fp32_vector_peak=round(achieved_tflops / PEAK_FP32_VECTOR_TFLOPS, 4))
 
+    # Not part of the metric: the same workload through the sweep that stops at the knee (Algorithm 1's
+    # loop as printed), in chunks of --knee-chunk values of k.
+    knee = None
+    if args.knee_chunk > 0:
+        kout = binding.cham_kmeans_sweep_knee(dw.X, dw.ld, dw.d, wl.task_off, wl.ks, wl.n_iter,
+                                              threshold=wl.threshold, chunk=args.knee_chunk)
+        torch.cuda.synchronize()
+        kbuf = {k: kout[k] for k in ("centroids", "counts", "inertia", "status", "chosen")}
+        kbuf["labels"] = None
+        kbuf["trace"] = None
+        kev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+        for e0, e1 in kev:
+            e0.record()
+            binding.cham_kmeans_sweep_knee(dw.X, dw.ld, dw.d, wl.task_off, wl.ks, wl.n_iter, threshold=wl.threshold,
+                                           chunk=args.knee_chunk, out=kbuf, workspace=kout["workspace"])
+            e1.record()
+        torch.cuda.synchronize()
+        knee_ms = float(np.mean([a.elapsed_time(b) for a, b in kev]))
+        st = kout["status"].cpu().numpy()
+        sizes = np.diff(wl.task_off).astype(np.float64)
+        executed = float((sizes[:, None] * np.asarray(wl.ks, dtype=np.float64)[None, :] * (st == 0)).sum()
+                         * (wl.n_iter + 1))
+        knee = dict(chunk=args.knee_chunk, sweep_ms=round(knee_ms, 3), executed_evals=executed,
+                    executed_fraction=round(executed / evals, 4),
+                    executed_evals_per_s=round(executed / (knee_ms * 1e-3), 1))
+
     cpu = None
     if not args.no_cpu_baseline:
         import oracle
@@ -145,7 +173,7 @@ def main():
                                f"k={wl.ks[0]}..{wl.ks[-1]} ({len(wl.ks)} values), {wl.n_iter} Lloyd steps + final pass, "
                                f"visited={wl.n_visited}, threshold={wl.threshold}",
                    "evals_per_step": evals, "sweep_ms": round(sweep_ms, 3)},
-        "roofline": roofline, "cpu_baseline": cpu,
+        "roofline": roofline, "cpu_baseline": cpu, "knee_sweep": knee,
     }
     print(json.dumps(line), flush=True)
 
