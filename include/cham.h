@@ -195,6 +195,41 @@ int32_t cham_synthesize(const uint8_t *X, int64_t ld, int32_t d,
                         void *workspace, int64_t workspace_bytes, void *stream);
 
 /*
+ * Visited set kept on the device across calls (the outer loop of the search calls the sampling
+ * step again and again with a growing set of measured configurations; Sec. 3.1 / 4.1, 16
+ * iterations per task): an open-addressing table of `slots` uint64 (a power of two, >= 2; DEVICE,
+ * 8-byte aligned, caller-owned, slots * 8 bytes).  Membership is by the same 64-bit hash as in
+ * cham_synthesize; an empty slot holds all ones and the one hash with that value is stored as
+ * the value below it.  Keep the load below about one half.
+ *   cham_visited_table_clear            empties the table
+ *   cham_visited_table_insert_hashes    inserts n hashes (DEVICE); duplicates are no-ops
+ *   cham_visited_table_insert_configs   hashes and inserts rows of cfgs (DEVICE row-major [n][d]):
+ *                                       row i iff flags is NULL or flags[i] is CHAM_OUT_KEPT or
+ *                                       CHAM_OUT_SYNTH (so out_cfg / out_flag of cham_synthesize,
+ *                                       n = T * k_max, go in directly); its salt is
+ *                                       salts[i / rows_per_salt] (DEVICE; NULL: i / rows_per_salt)
+ *   overflow (DEVICE int32, may be NULL) is set to 1 if an insert finds no free slot; it is never
+ *   cleared by the library.
+ *   cham_synthesize_table               cham_synthesize with the table in place of the sorted array
+ * Errors: CHAM_E_NULL for a missing table / input, CHAM_E_BAD_DIM for slots not a power of two,
+ * a misaligned table, n < 0, d outside [1,32], rows_per_salt < 1.
+ */
+int32_t cham_visited_table_clear(uint64_t *table, int64_t slots, void *stream);
+int32_t cham_visited_table_insert_hashes(uint64_t *table, int64_t slots, const uint64_t *hashes, int64_t n,
+                                         int32_t *overflow, void *stream);
+int32_t cham_visited_table_insert_configs(uint64_t *table, int64_t slots, const uint8_t *cfgs, int64_t n, int32_t d,
+                                          const uint8_t *flags, const uint64_t *salts, int64_t rows_per_salt,
+                                          int32_t *overflow, void *stream);
+int32_t cham_synthesize_table(const uint8_t *X, int64_t ld, int32_t d,
+                              const int64_t *task_off, int32_t T, const uint16_t *cards,
+                              const uint8_t *valid, const int32_t *ks, int32_t n_k,
+                              const int32_t *chosen_idx, const uint8_t *labels_sel,
+                              const int32_t *pick_row, const uint8_t *pick_cfg,
+                              const uint64_t *table, int64_t slots, const uint64_t *task_salt,
+                              uint8_t *out_cfg, uint8_t *out_flag, int32_t *out_count,
+                              void *workspace, int64_t workspace_bytes, void *stream);
+
+/*
  * Configuration hash used for the visited set: 64-bit FNV-1a over the d knob bytes, the
  * offset basis first XORed with salt * 0x9E3779B97F4A7C15 (mod 2^64).  salt 0 gives plain
  * FNV-1a.  cfg is HOST memory.

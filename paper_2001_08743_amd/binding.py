@@ -22,7 +22,8 @@ EXPORTS = [
     "cham_version", "cham_strerror", "cham_last_hip_error", "cham_sweep_workspace_bytes",
     "cham_kmeans_sweep", "cham_select_k", "cham_select_k_host", "cham_snap_workspace_bytes",
     "cham_snap_centroids", "cham_synth_workspace_bytes", "cham_synthesize", "cham_hash_config",
-    "cham_hash_rows", "cham_sweep_knee_workspace_bytes", "cham_kmeans_sweep_knee",
+    "cham_hash_rows", "cham_sweep_knee_workspace_bytes", "cham_kmeans_sweep_knee", "cham_synthesize_table",
+    "cham_visited_table_clear", "cham_visited_table_insert_hashes", "cham_visited_table_insert_configs",
 ]
 
 
@@ -55,6 +56,15 @@ def load() -> C.CDLL:
         lib.cham_kmeans_sweep_knee.restype = i32
         lib.cham_kmeans_sweep_knee.argtypes = [vp, i64, i32, vp, i32, vp, i32, i32, i32, vp, f64, i32,
                                                vp, vp, vp, vp, vp, vp, vp, vp, i64, i32, vp]
+        lib.cham_synthesize_table.restype = i32
+        lib.cham_synthesize_table.argtypes = [vp, i64, i32, vp, i32, vp, vp, vp, i32, vp, vp, vp, vp, vp, i64, vp,
+                                              vp, vp, vp, vp, i64, vp]
+        lib.cham_visited_table_clear.restype = i32
+        lib.cham_visited_table_clear.argtypes = [vp, i64, vp]
+        lib.cham_visited_table_insert_hashes.restype = i32
+        lib.cham_visited_table_insert_hashes.argtypes = [vp, i64, vp, i64, vp, vp]
+        lib.cham_visited_table_insert_configs.restype = i32
+        lib.cham_visited_table_insert_configs.argtypes = [vp, i64, vp, i64, i32, vp, vp, i64, vp, vp]
         lib.cham_select_k.restype = i32
         lib.cham_select_k.argtypes = [vp, vp, i32, i32, f64, vp, vp]
         lib.cham_select_k_host.restype = i32
@@ -282,6 +292,51 @@ def cham_synthesize(X, ld: int, d: int, task_off, cards, valid, ks, chosen_idx, 
                                   _dp(out["out_count"]), _dp(workspace), C.c_int64(workspace.numel()), _stream()))
     out["workspace"] = workspace
     return out
+
+
+def cham_synthesize_table(X, ld: int, d: int, task_off, cards, valid, ks, chosen_idx, labels_sel, pick_row,
+                          pick_cfg, table, task_salt=None, out: Optional[dict] = None, workspace=None):
+    """cham_synthesize with the visited set held in a device table (int64/uint64 tensor of 2^m slots)."""
+    torch = _torch()
+    to, k = _host_lists(task_off, ks)
+    T, n_k, kmax = len(to) - 1, len(k), int(k[-1])
+    cards = np.ascontiguousarray(cards, dtype=np.uint16).reshape(T, d)
+    salts = None if task_salt is None else np.ascontiguousarray(task_salt, dtype=np.uint64)
+    dev = X.device
+    if out is None:
+        out = dict(out_cfg=torch.empty((T, kmax, d), dtype=torch.uint8, device=dev),
+                   out_flag=torch.empty((T, kmax), dtype=torch.uint8, device=dev),
+                   out_count=torch.empty(T, dtype=torch.int32, device=dev))
+    if workspace is None:
+        nbytes = _check(load().cham_synth_workspace_bytes(C.c_int64(ld), C.c_int32(d), _hp(to), C.c_int32(T),
+                                                          _hp(k), C.c_int32(n_k)))
+        workspace = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=dev)
+    _check(load().cham_synthesize_table(_dp(X), C.c_int64(ld), C.c_int32(d), _hp(to), C.c_int32(T), _hp(cards),
+                                        _dp(valid), _hp(k), C.c_int32(n_k), _dp(chosen_idx), _dp(labels_sel),
+                                        _dp(pick_row), _dp(pick_cfg), _dp(table), C.c_int64(table.numel()),
+                                        _hp(salts), _dp(out["out_cfg"]), _dp(out["out_flag"]),
+                                        _dp(out["out_count"]), _dp(workspace), C.c_int64(workspace.numel()),
+                                        _stream()))
+    out["workspace"] = workspace
+    return out
+
+
+def cham_visited_table_clear(table):
+    _check(load().cham_visited_table_clear(_dp(table), C.c_int64(table.numel()), _stream()))
+    return table
+
+
+def cham_visited_table_insert_hashes(table, hashes, overflow=None):
+    _check(load().cham_visited_table_insert_hashes(_dp(table), C.c_int64(table.numel()), _dp(hashes),
+                                                   C.c_int64(hashes.numel()), _dp(overflow), _stream()))
+
+
+def cham_visited_table_insert_configs(table, cfgs, d: int, flags=None, salts=None, rows_per_salt: int = 1,
+                                      overflow=None):
+    n = cfgs.numel() // d
+    _check(load().cham_visited_table_insert_configs(_dp(table), C.c_int64(table.numel()), _dp(cfgs), C.c_int64(n),
+                                                    C.c_int32(d), _dp(flags), _dp(salts), C.c_int64(rows_per_salt),
+                                                    _dp(overflow), _stream()))
 
 
 class DeviceWorkload:

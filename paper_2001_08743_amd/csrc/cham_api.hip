@@ -533,19 +533,20 @@ int64_t cham_synth_workspace_bytes(int64_t ld, int32_t d, const int64_t *task_of
     return up(((int64_t)pl.blob.size() + synth_blob_extra_words(T, d)) * 8) + wide_synth_bytes(pl, d);
 }
 
-int32_t cham_synthesize(const uint8_t *X, int64_t ld, int32_t d, const int64_t *task_off, int32_t T,
-                        const uint16_t *cards, const uint8_t *valid, const int32_t *ks, int32_t n_k,
-                        const int32_t *chosen_idx, const uint8_t *labels_sel, const int32_t *pick_row,
-                        const uint8_t *pick_cfg, const uint64_t *visited, int64_t n_visited,
-                        const uint64_t *task_salt, uint8_t *out_cfg, uint8_t *out_flag,
-                        int32_t *out_count, void *workspace, int64_t workspace_bytes, void *stream)
+// n_visited >= 0: sorted array of that many hashes; n_visited < 0: table of -n_visited slots.
+static int32_t synth_impl(const uint8_t *X, int64_t ld, int32_t d, const int64_t *task_off, int32_t T,
+                          const uint16_t *cards, const uint8_t *valid, const int32_t *ks, int32_t n_k,
+                          const int32_t *chosen_idx, const uint8_t *labels_sel, const int32_t *pick_row,
+                          const uint8_t *pick_cfg, const uint64_t *visited, int64_t n_visited,
+                          const uint64_t *task_salt, uint8_t *out_cfg, uint8_t *out_flag,
+                          int32_t *out_count, void *workspace, int64_t workspace_bytes, void *stream)
 {
     Plan pl;
     int32_t rc = check_common(X, ld, d, task_off, T, ks, n_k, true, pl);
     if (rc != CHAM_OK) return rc;
     if (!cards || !chosen_idx || !labels_sel || !pick_row || !pick_cfg || !out_cfg || !out_flag || !out_count)
         return CHAM_E_NULL;
-    if (n_visited < 0 || (n_visited > 0 && !visited)) return CHAM_E_NULL;
+    if (n_visited != 0 && !visited) return CHAM_E_NULL;
     int cmax = 1;
     for (int64_t i = 0; i < (int64_t)T * d; ++i) {
         if (cards[i] < 1 || cards[i] > 256) return CHAM_E_CARD;
@@ -619,6 +620,64 @@ int32_t cham_synthesize(const uint8_t *X, int64_t ld, int32_t d, const int64_t *
     }
     if (e != hipSuccess) return hip_fail(e);
     return CHAM_OK;
+}
+
+int32_t cham_synthesize(const uint8_t *X, int64_t ld, int32_t d, const int64_t *task_off, int32_t T,
+                        const uint16_t *cards, const uint8_t *valid, const int32_t *ks, int32_t n_k,
+                        const int32_t *chosen_idx, const uint8_t *labels_sel, const int32_t *pick_row,
+                        const uint8_t *pick_cfg, const uint64_t *visited, int64_t n_visited,
+                        const uint64_t *task_salt, uint8_t *out_cfg, uint8_t *out_flag,
+                        int32_t *out_count, void *workspace, int64_t workspace_bytes, void *stream)
+{
+    if (n_visited < 0) return CHAM_E_NULL;
+    return synth_impl(X, ld, d, task_off, T, cards, valid, ks, n_k, chosen_idx, labels_sel, pick_row, pick_cfg,
+                      visited, n_visited, task_salt, out_cfg, out_flag, out_count, workspace, workspace_bytes, stream);
+}
+
+static bool table_ok(const void *table, int64_t slots)
+{
+    return table && slots >= 2 && (slots & (slots - 1)) == 0 && reinterpret_cast<uintptr_t>(table) % 8 == 0;
+}
+
+int32_t cham_synthesize_table(const uint8_t *X, int64_t ld, int32_t d, const int64_t *task_off, int32_t T,
+                              const uint16_t *cards, const uint8_t *valid, const int32_t *ks, int32_t n_k,
+                              const int32_t *chosen_idx, const uint8_t *labels_sel, const int32_t *pick_row,
+                              const uint8_t *pick_cfg, const uint64_t *table, int64_t slots,
+                              const uint64_t *task_salt, uint8_t *out_cfg, uint8_t *out_flag,
+                              int32_t *out_count, void *workspace, int64_t workspace_bytes, void *stream)
+{
+    if (!table_ok(table, slots)) return table ? CHAM_E_BAD_DIM : CHAM_E_NULL;
+    return synth_impl(X, ld, d, task_off, T, cards, valid, ks, n_k, chosen_idx, labels_sel, pick_row, pick_cfg,
+                      table, -slots, task_salt, out_cfg, out_flag, out_count, workspace, workspace_bytes, stream);
+}
+
+int32_t cham_visited_table_clear(uint64_t *table, int64_t slots, void *stream)
+{
+    if (!table_ok(table, slots)) return table ? CHAM_E_BAD_DIM : CHAM_E_NULL;
+    hipError_t e = launch_table_clear(table, slots, reinterpret_cast<hipStream_t>(stream));
+    return e == hipSuccess ? CHAM_OK : hip_fail(e);
+}
+
+int32_t cham_visited_table_insert_hashes(uint64_t *table, int64_t slots, const uint64_t *hashes, int64_t n,
+                                         int32_t *overflow, void *stream)
+{
+    if (!table_ok(table, slots)) return table ? CHAM_E_BAD_DIM : CHAM_E_NULL;
+    if (n < 0) return CHAM_E_BAD_DIM;
+    if (n > 0 && !hashes) return CHAM_E_NULL;
+    hipError_t e = launch_table_insert_hashes(table, slots, hashes, n, overflow, reinterpret_cast<hipStream_t>(stream));
+    return e == hipSuccess ? CHAM_OK : hip_fail(e);
+}
+
+int32_t cham_visited_table_insert_configs(uint64_t *table, int64_t slots, const uint8_t *cfgs, int64_t n, int32_t d,
+                                          const uint8_t *flags, const uint64_t *salts, int64_t rows_per_salt,
+                                          int32_t *overflow, void *stream)
+{
+    if (!table_ok(table, slots)) return table ? CHAM_E_BAD_DIM : CHAM_E_NULL;
+    if (n < 0 || d < 1 || d > 32 || rows_per_salt < 1) return CHAM_E_BAD_DIM;
+    if (n > 0 && !cfgs) return CHAM_E_NULL;
+    hipError_t e = launch_table_insert_configs(table, slots, cfgs, n, d, flags, salts, rows_per_salt, overflow,
+                                               reinterpret_cast<hipStream_t>(stream));
+    return e == hipSuccess ? CHAM_OK : hip_fail(e);
 }
 
 uint64_t cham_hash_config(const uint8_t *cfg, int32_t d, uint64_t salt)

@@ -134,7 +134,7 @@ struct SynthArgs {
     const uint8_t *labels_sel;  // [ld]
     const int *pick_row;        // [T][kmax]
     const uint8_t *pick_cfg;    // [T][kmax][d]
-    const uint64_t *visited;    // sorted
+    const uint64_t *visited;    // sorted array of n_visited hashes, or (n_visited < 0) a table of -n_visited slots
     int64_t n_visited;
     uint8_t *out_cfg;           // [T][kmax][d]
     uint8_t *out_flag;          // [T][kmax]
@@ -165,6 +165,12 @@ hipError_t launch_snap_wide(const SnapArgs &a, int total_wgs, hipStream_t s);
 hipError_t launch_synth_wide(const SynthArgs &a, int total_wgs, hipStream_t s);
 size_t synth_lds_bytes(int d, int kmax, int hist_words);
 hipError_t launch_synth(const SynthArgs &a, int nt, hipStream_t s);
+hipError_t launch_table_clear(uint64_t *v, int64_t slots, hipStream_t s);
+hipError_t launch_table_insert_hashes(uint64_t *v, int64_t slots, const uint64_t *hashes, int64_t n, int *overflow,
+                                      hipStream_t s);
+hipError_t launch_table_insert_configs(uint64_t *v, int64_t slots, const uint8_t *cfgs, int64_t n, int d,
+                                       const uint8_t *flags, const uint64_t *salts, int64_t rows_per_salt,
+                                       int *overflow, hipStream_t s);
 hipError_t launch_hash_rows(const uint8_t *rows, int64_t n, int d, const uint64_t *salts,
                             uint64_t salt_all, uint64_t *out, hipStream_t s);
 

@@ -204,14 +204,75 @@ __global__ __launch_bounds__(MAXNT) void snap_kernel(const SnapArgs a)
 }
 
 // ---------------------------------------------------------------------------------------------
+// Membership in the visited set.  n >= 0: v is a sorted array of n hashes (binary search).
+// n < 0: v is an open-addressing table of -n slots (a power of two, linear probing, empty slots
+// hold all ones; the one hash that equals the empty mark is stored as the value below it).
+constexpr uint64_t kEmptySlot = ~0ull;
+__device__ __forceinline__ uint64_t table_key(uint64_t h) { return h == kEmptySlot ? h - 1 : h; }
+
 __device__ __forceinline__ bool visited_has(const uint64_t *v, int64_t n, uint64_t key)
 {
+    if (n < 0) {
+        const uint64_t mask = (uint64_t)(-n) - 1;
+        const uint64_t k = table_key(key);
+        uint64_t pos = k & mask;
+        for (uint64_t probes = 0; probes <= mask; ++probes) {       // a full table ends the walk
+            const uint64_t cur = v[pos];
+            if (cur == k) return true;
+            if (cur == kEmptySlot) return false;
+            pos = (pos + 1) & mask;
+        }
+        return false;
+    }
     int64_t lo = 0, hi = n;
     while (lo < hi) {
         const int64_t mid = lo + ((hi - lo) >> 1);
         if (v[mid] < key) lo = mid + 1; else hi = mid;
     }
     return lo < n && v[lo] == key;
+}
+
+// Insert one hash; returns false if the table is full.
+__device__ __forceinline__ bool table_insert(uint64_t *v, uint64_t mask, uint64_t h)
+{
+    const uint64_t k = table_key(h);
+    uint64_t pos = k & mask;
+    for (uint64_t probes = 0; probes <= mask; ++probes) {
+        const unsigned long long seen = atomicCAS(reinterpret_cast<unsigned long long *>(v + pos),
+                                                  (unsigned long long)kEmptySlot, (unsigned long long)k);
+        if (seen == kEmptySlot || seen == k) return true;
+        pos = (pos + 1) & mask;
+    }
+    return false;
+}
+
+__global__ void table_clear_kernel(uint64_t *v, int64_t slots)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < slots) v[i] = kEmptySlot;
+}
+
+__global__ void table_insert_hashes_kernel(uint64_t *v, int64_t slots, const uint64_t *hashes, int64_t n,
+                                           int *overflow)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    if (!table_insert(v, (uint64_t)slots - 1, hashes[i]) && overflow) *overflow = 1;
+}
+
+// Hash and insert configurations: row i of cfgs [n][d] is inserted iff flags is null or flags[i] is
+// KEPT (1) or SYNTH (2); its salt is salts[i / rows_per_salt] (salts null: i / rows_per_salt itself).
+__global__ void table_insert_configs_kernel(uint64_t *v, int64_t slots, const uint8_t *cfgs, int64_t n, int d,
+                                            const uint8_t *flags, const uint64_t *salts, int64_t rows_per_salt,
+                                            int *overflow)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    if (flags && flags[i] != 1 && flags[i] != 2) return;
+    const uint64_t g = (uint64_t)(i / rows_per_salt);
+    uint64_t h = fnv_begin(salts ? salts[g] : g);
+    for (int j = 0; j < d; ++j) h = fnv_step(h, cfgs[i * d + j]);
+    if (!table_insert(v, (uint64_t)slots - 1, h) && overflow) *overflow = 1;
 }
 
 // Synthesis: one workgroup per task.
@@ -821,6 +882,31 @@ hipError_t launch_synth(const SynthArgs &a, int nt, hipStream_t s)
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(synth_kernel, dim3(a.T), dim3(nt), lds, s, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_table_clear(uint64_t *v, int64_t slots, hipStream_t s)
+{
+    hipLaunchKernelGGL(table_clear_kernel, dim3((unsigned)((slots + 255) / 256)), dim3(256), 0, s, v, slots);
+    return hipGetLastError();
+}
+
+hipError_t launch_table_insert_hashes(uint64_t *v, int64_t slots, const uint64_t *hashes, int64_t n, int *overflow,
+                                      hipStream_t s)
+{
+    if (n > 0)
+        hipLaunchKernelGGL(table_insert_hashes_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, v, slots,
+                           hashes, n, overflow);
+    return hipGetLastError();
+}
+
+hipError_t launch_table_insert_configs(uint64_t *v, int64_t slots, const uint8_t *cfgs, int64_t n, int d,
+                                       const uint8_t *flags, const uint64_t *salts, int64_t rows_per_salt,
+                                       int *overflow, hipStream_t s)
+{
+    if (n > 0)
+        hipLaunchKernelGGL(table_insert_configs_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, v, slots,
+                           cfgs, n, d, flags, salts, rows_per_salt, overflow);
     return hipGetLastError();
 }
 

@@ -118,3 +118,15 @@ def test_knee_sweep_workspace_and_argument_errors(lib):
                                                             C.c_int32(0), None)
     assert args(1, None) == -1                              # missing chosen_idx
     assert args(0, one) == -3                               # chunk < 1
+
+
+def test_visited_table_argument_errors(lib):
+    one = C.c_void_p(256)
+    assert lib.cham_visited_table_clear(None, C.c_int64(16), None) == -1
+    assert lib.cham_visited_table_clear(one, C.c_int64(12), None) == -2          # not a power of two
+    assert lib.cham_visited_table_clear(C.c_void_p(260), C.c_int64(16), None) == -2   # misaligned
+    assert lib.cham_visited_table_insert_hashes(one, C.c_int64(16), None, C.c_int64(3), None, None) == -1
+    assert lib.cham_visited_table_insert_configs(one, C.c_int64(16), one, C.c_int64(3), C.c_int32(40), None, None,
+                                                 C.c_int64(1), None, None) == -2
+    assert lib.cham_visited_table_insert_configs(one, C.c_int64(16), one, C.c_int64(3), C.c_int32(4), None, None,
+                                                 C.c_int64(0), None, None) == -2

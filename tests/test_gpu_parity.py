@@ -4,7 +4,7 @@ import pytest
 
 import oracle
 from paper_2001_08743_amd import binding, workloads
-from parity_util import check_pipeline, check_sweep, knee_margin, run_both
+from parity_util import check_pipeline, check_sweep, knee_margin, oracle_visited, run_both
 
 pytestmark = pytest.mark.gpu
 
@@ -428,3 +428,92 @@ def test_knee_sweep_on_the_full_model_slice():
     out = _check_knee_sweep(wl, wl.threshold, 8)
     status = out["status"].cpu().numpy()
     assert (status[:, 8:] == 3).mean() > 0.5
+
+
+# ------------------------------------------------------------------ visited set as a device table
+
+def _table_for(dw, slots):
+    import torch
+    table = torch.empty(slots, dtype=torch.int64, device=dw.device)
+    binding.cham_visited_table_clear(table)
+    ovf = torch.zeros(1, dtype=torch.int32, device=dw.device)
+    binding.cham_visited_table_insert_hashes(table, dw.visited, overflow=ovf)
+    return table, ovf
+
+
+def test_synthesis_with_the_visited_table_equals_the_sorted_array():
+    import torch
+    wl = workloads.make_config(3, 1, scale=8 / 64)
+    dw, g, c = run_both(wl)
+    table, ovf = _table_for(dw, 1 << 15)
+    sy = binding.cham_synthesize_table(dw.X, dw.ld, dw.d, wl.task_off, wl.cards, dw.valid, wl.ks, g["chosen"],
+                                       g["snap"]["labels_sel"], g["snap"]["pick_row"], g["snap"]["pick_cfg"], table,
+                                       task_salt=wl.salts)
+    torch.cuda.synchronize()
+    assert int(ovf.item()) == 0
+    for key in ("out_cfg", "out_flag", "out_count"):
+        np.testing.assert_array_equal(sy[key].cpu().numpy(), c[key])
+    # the table holds exactly the visited hashes (the empty mark aside)
+    held = table.cpu().numpy().view(np.uint64)
+    held = np.sort(held[held != np.uint64(0xFFFFFFFFFFFFFFFF)])
+    np.testing.assert_array_equal(held, np.unique(dw.visited_host))
+
+
+def test_outer_loop_with_a_growing_visited_table():
+    """Four rounds of choose k / snap / synthesize on one sweep, with different thresholds; what a
+    round returns is inserted into the table and must be treated as visited by the next rounds."""
+    import torch
+    wl = workloads.make_config(3, 2, scale=6 / 64)
+    dw = binding.DeviceWorkload(wl)
+    dw.build_visited()
+    vis = set(int(v) for v in oracle_visited(wl))
+    np.testing.assert_array_equal(np.sort(np.array(sorted(vis), dtype=np.uint64)), np.unique(dw.visited_host))
+    table, ovf = _table_for(dw, 1 << 15)
+    salts_dev = torch.from_numpy(wl.salts.astype(np.int64)).to(dw.device)
+    sw = binding.cham_kmeans_sweep(dw.X, dw.ld, dw.d, wl.task_off, wl.ks, wl.n_iter)
+    sw_cpu = oracle.sweep(wl.rows, wl.task_off, wl.ks, wl.n_iter)
+    kmax = max(wl.ks)
+    grew = 0
+    for thr in (1.0, 1.02, 1.3, 2.5, 2.5):
+        chosen = binding.cham_select_k(sw["inertia"], sw["status"], thr)
+        sn = binding.cham_snap_centroids(dw.X, dw.ld, dw.d, wl.task_off, wl.ks, chosen, sw["centroids"])
+        sy = binding.cham_synthesize_table(dw.X, dw.ld, dw.d, wl.task_off, wl.cards, dw.valid, wl.ks, chosen,
+                                           sn["labels_sel"], sn["pick_row"], sn["pick_cfg"], table,
+                                           task_salt=wl.salts)
+        binding.cham_visited_table_insert_configs(table, sy["out_cfg"], dw.d, flags=sy["out_flag"], salts=salts_dev,
+                                                  rows_per_salt=kmax, overflow=ovf)
+        torch.cuda.synchronize()
+        ref = oracle.pipeline(wl, np.array(sorted(vis), dtype=np.uint64), threshold=thr, sweep_out=sw_cpu)
+        for key in ("out_cfg", "out_flag", "out_count"):
+            np.testing.assert_array_equal(sy[key].cpu().numpy(), ref[key], err_msg=f"{key} at threshold {thr}")
+        before = len(vis)
+        for t in range(wl.T):
+            for cc in range(kmax):
+                if ref["out_flag"][t, cc] in (oracle.KEPT, oracle.SYNTH):
+                    vis.add(oracle.hash_config(ref["out_cfg"][t, cc], int(wl.salts[t])))
+        grew += len(vis) - before
+    assert grew > 0 and int(ovf.item()) == 0
+    # the last round repeats the threshold of the one before: everything it could return is visited now
+    assert (sy["out_flag"].cpu().numpy() != oracle.KEPT).all()
+
+
+def test_visited_table_overflow_is_reported_and_lookups_end():
+    import torch
+    table = torch.empty(4, dtype=torch.int64, device="cuda:0")
+    binding.cham_visited_table_clear(table)
+    ovf = torch.zeros(1, dtype=torch.int32, device="cuda:0")
+    hashes = torch.arange(1, 11, dtype=torch.int64, device="cuda:0") * 7919
+    binding.cham_visited_table_insert_hashes(table, hashes, overflow=ovf)
+    torch.cuda.synchronize()
+    assert int(ovf.item()) == 1
+    assert (table.cpu().numpy() != -1).all()             # full
+    # a lookup in the full table must terminate: a tiny synthesis call against it
+    wl = workloads.random_task(5, n=64, d=3, ks=(2,), n_iter=2)
+    dw = binding.DeviceWorkload(wl)
+    sw = binding.cham_kmeans_sweep(dw.X, dw.ld, dw.d, wl.task_off, wl.ks, wl.n_iter)
+    chosen = binding.cham_select_k(sw["inertia"], sw["status"], 2.5)
+    sn = binding.cham_snap_centroids(dw.X, dw.ld, dw.d, wl.task_off, wl.ks, chosen, sw["centroids"])
+    sy = binding.cham_synthesize_table(dw.X, dw.ld, dw.d, wl.task_off, wl.cards, dw.valid, wl.ks, chosen,
+                                       sn["labels_sel"], sn["pick_row"], sn["pick_cfg"], table, task_salt=wl.salts)
+    torch.cuda.synchronize()
+    assert int(sy["out_count"].sum().item()) >= 0
