@@ -150,6 +150,26 @@ def main():
                     executed_fraction=round(executed / evals, 4),
                     executed_evals_per_s=round(executed / (knee_ms * 1e-3), 1))
 
+    # Not part of the metric either: the visited set as a device table (what the outer loop of the search
+    # keeps between calls): insert the workload's visited hashes into a table at load <= 1/4.
+    vtab = None
+    if dw.visited is not None and dw.visited.numel() > 0:
+        n_h = int(dw.visited.numel())
+        slots = 1 << max(4, int(np.ceil(np.log2(4 * n_h))))
+        table = torch.empty(slots, dtype=torch.int64, device="cuda:0")
+        tev = []
+        for _ in range(3):
+            binding.cham_visited_table_clear(table)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            binding.cham_visited_table_insert_hashes(table, dw.visited)
+            e1.record()
+            tev.append((e0, e1))
+        torch.cuda.synchronize()
+        ins_ms = min(a.elapsed_time(b) for a, b in tev)
+        vtab = dict(slots=slots, inserted=n_h, insert_ms=round(ins_ms, 4),
+                    inserts_per_s=round(n_h / (ins_ms * 1e-3), 1))
+
     cpu = None
     if not args.no_cpu_baseline:
         import oracle
@@ -174,6 +194,7 @@ def main():
                                f"visited={wl.n_visited}, threshold={wl.threshold}",
                    "evals_per_step": evals, "sweep_ms": round(sweep_ms, 3)},
         "roofline": roofline, "cpu_baseline": cpu, "knee_sweep": knee,
+        "visited_table": vtab,
     }
     print(json.dumps(line), flush=True)
 
