@@ -170,6 +170,31 @@ def main():
         vtab = dict(slots=slots, inserted=n_h, insert_ms=round(ins_ms, 4),
                     inserts_per_s=round(n_h / (ins_ms * 1e-3), 1))
 
+    # The configuration updater that feeds the path (128 episodes x 500 steps, the paper's values), with the
+    # trajectory's distinct configurations collected on the device.
+    g = torch.Generator(device="cpu").manual_seed(1)
+    B_u, S_u = 128, 500
+    cards_u = torch.from_numpy(wl.cards[0].astype(np.int16)).to("cuda:0")
+    theta_u = torch.zeros((B_u, wl.d), dtype=torch.uint8, device="cuda:0")
+    act_u = torch.randint(-1, 2, (S_u, B_u, wl.d), generator=g, dtype=torch.int8).to("cuda:0")
+    seen_u = torch.empty(1 << 18, dtype=torch.int64, device="cuda:0")
+    uniq_u = torch.empty((B_u * S_u, wl.d), dtype=torch.uint8, device="cuda:0")
+    n_u = torch.zeros(1, dtype=torch.int32, device="cuda:0")
+    best_u = None
+    for _ in range(3):
+        binding.cham_visited_table_clear(seen_u)
+        theta_u.zero_()
+        n_u.zero_()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        binding.cham_update_configs(theta_u, act_u, cards_u, salt=0, seen_table=seen_u, unique_rows=uniq_u, n_unique=n_u)
+        e1.record()
+        torch.cuda.synchronize()
+        t_u = e0.elapsed_time(e1)
+        best_u = t_u if best_u is None else min(best_u, t_u)
+    updater = dict(episodes=B_u, steps=S_u, d=wl.d, ms=round(best_u, 4), distinct=int(n_u.item()),
+                   config_steps_per_s=round(B_u * S_u / (best_u * 1e-3), 1))
+
     cpu = None
     if not args.no_cpu_baseline:
         import oracle
@@ -194,7 +219,7 @@ def main():
                                f"visited={wl.n_visited}, threshold={wl.threshold}",
                    "evals_per_step": evals, "sweep_ms": round(sweep_ms, 3)},
         "roofline": roofline, "cpu_baseline": cpu, "knee_sweep": knee,
-        "visited_table": vtab,
+        "visited_table": vtab, "config_updater": updater,
     }
     print(json.dumps(line), flush=True)
 

@@ -230,6 +230,30 @@ int32_t cham_synthesize_table(const uint8_t *X, int64_t ld, int32_t d,
                               void *workspace, int64_t workspace_bytes, void *stream);
 
 /*
+ * Configuration updater of the exploration step that feeds the sampling step (Sec. 3.2, the
+ * action figure: the agent emits increment / decrement / stay per knob, the updater applies it;
+ * hyper-parameter table: 128 episodes of up to 500 steps).  The policy network is not part of this
+ * library: the actions are an input.
+ *   theta   DEVICE uint8 [B][d]           configurations, updated in place through n_steps steps:
+ *                                         theta <- clip(theta + a, 0, card - 1) per knob
+ *   actions DEVICE int8 [n_steps][B][d]   each -1, 0 or +1
+ *   cards   DEVICE uint16 [d]             cardinalities (one design space for the whole batch)
+ *   seen_table / slots                    table as for cham_visited_table_* (NULL: no bookkeeping);
+ *                                         every configuration reached is entered under `salt`
+ *   unique_rows DEVICE uint8 [capacity][d], n_unique DEVICE int32 (caller zeroes it, or keeps it
+ *                                         running across calls): the distinct configurations in
+ *                                         the order in which they were first entered (unspecified
+ *                                         between threads) - the set S_Theta handed to the
+ *                                         sampling step
+ *   overflow DEVICE int32 (may be NULL)   set to 1 if the table or the list is full
+ * Errors: CHAM_E_NULL, CHAM_E_BAD_DIM (B < 0, d outside [1,32], n_steps < 0, bad table).
+ */
+int32_t cham_update_configs(uint8_t *theta, const int8_t *actions, int64_t B, int32_t d, int32_t n_steps,
+                            const uint16_t *cards, uint64_t salt, uint64_t *seen_table, int64_t slots,
+                            uint8_t *unique_rows, int64_t capacity, int32_t *n_unique, int32_t *overflow,
+                            void *stream);
+
+/*
  * Configuration hash used for the visited set: 64-bit FNV-1a over the d knob bytes, the
  * offset basis first XORed with salt * 0x9E3779B97F4A7C15 (mod 2^64).  salt 0 gives plain
  * FNV-1a.  cfg is HOST memory.

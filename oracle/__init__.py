@@ -154,6 +154,30 @@ def sweep_until_knee(rows, task_off, ks: Sequence[int], n_iter: int, threshold: 
     return dict(chosen_idx=chosen, ran=ran, inertia=inertia, centroids=cents, counts=cnts)
 
 
+def update_configs(theta, actions, cards):
+    """Configuration updater (Sec. 3.2): theta [B][d], actions [S][B][d] in {-1, 0, +1}, cards [d].
+    Step after step theta <- clip(theta + a, 0, card - 1); returns (final theta, list of the distinct
+    configurations reached, in order of first appearance: step by step, configuration by configuration)."""
+    th = np.array(theta, dtype=np.int64, copy=True)
+    acts = np.asarray(actions, dtype=np.int64)
+    hi = np.asarray(cards, dtype=np.int64) - 1
+    seen, order = set(), []
+    for s in range(acts.shape[0]):
+        for b in range(th.shape[0]):
+            for j in range(th.shape[1]):
+                v = th[b, j] + acts[s, b, j]
+                if v < 0:
+                    v = 0
+                if v > hi[j]:
+                    v = hi[j]
+                th[b, j] = v
+            key = tuple(int(v) for v in th[b])
+            if key not in seen:
+                seen.add(key)
+                order.append(key)
+    return th.astype(np.uint8), order
+
+
 def snap(x, mu):
     x = _rows(x)
     mu = np.ascontiguousarray(mu, dtype=np.float64)

@@ -24,6 +24,7 @@ EXPORTS = [
     "cham_snap_centroids", "cham_synth_workspace_bytes", "cham_synthesize", "cham_hash_config",
     "cham_hash_rows", "cham_sweep_knee_workspace_bytes", "cham_kmeans_sweep_knee", "cham_synthesize_table",
     "cham_visited_table_clear", "cham_visited_table_insert_hashes", "cham_visited_table_insert_configs",
+    "cham_update_configs",
 ]
 
 
@@ -65,6 +66,8 @@ def load() -> C.CDLL:
         lib.cham_visited_table_insert_hashes.argtypes = [vp, i64, vp, i64, vp, vp]
         lib.cham_visited_table_insert_configs.restype = i32
         lib.cham_visited_table_insert_configs.argtypes = [vp, i64, vp, i64, i32, vp, vp, i64, vp, vp]
+        lib.cham_update_configs.restype = i32
+        lib.cham_update_configs.argtypes = [vp, vp, i64, i32, i32, vp, u64, vp, i64, vp, i64, vp, vp, vp]
         lib.cham_select_k.restype = i32
         lib.cham_select_k.argtypes = [vp, vp, i32, i32, f64, vp, vp]
         lib.cham_select_k_host.restype = i32
@@ -337,6 +340,19 @@ def cham_visited_table_insert_configs(table, cfgs, d: int, flags=None, salts=Non
     _check(load().cham_visited_table_insert_configs(_dp(table), C.c_int64(table.numel()), _dp(cfgs), C.c_int64(n),
                                                     C.c_int32(d), _dp(flags), _dp(salts), C.c_int64(rows_per_salt),
                                                     _dp(overflow), _stream()))
+
+
+def cham_update_configs(theta, actions, cards, salt: int = 0, seen_table=None, unique_rows=None, n_unique=None,
+                        overflow=None):
+    """theta [B][d] uint8 (in place), actions [S][B][d] int8, cards [d] (device int16/uint16 tensor)."""
+    B, d = theta.shape
+    n_steps = actions.shape[0] if actions.dim() == 3 else 1
+    _check(load().cham_update_configs(_dp(theta), _dp(actions), C.c_int64(B), C.c_int32(d), C.c_int32(n_steps),
+                                      _dp(cards), C.c_uint64(salt), _dp(seen_table),
+                                      C.c_int64(0 if seen_table is None else seen_table.numel()), _dp(unique_rows),
+                                      C.c_int64(0 if unique_rows is None else unique_rows.shape[0]), _dp(n_unique),
+                                      _dp(overflow), _stream()))
+    return theta
 
 
 class DeviceWorkload:

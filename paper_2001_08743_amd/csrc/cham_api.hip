@@ -680,6 +680,22 @@ int32_t cham_visited_table_insert_configs(uint64_t *table, int64_t slots, const 
     return e == hipSuccess ? CHAM_OK : hip_fail(e);
 }
 
+int32_t cham_update_configs(uint8_t *theta, const int8_t *actions, int64_t B, int32_t d, int32_t n_steps,
+                            const uint16_t *cards, uint64_t salt, uint64_t *seen_table, int64_t slots,
+                            uint8_t *unique_rows, int64_t capacity, int32_t *n_unique, int32_t *overflow,
+                            void *stream)
+{
+    if (!theta || !actions || !cards) return CHAM_E_NULL;
+    if (B < 0 || d < 1 || d > 32 || n_steps < 0) return CHAM_E_BAD_DIM;
+    if (seen_table) {
+        if (!table_ok(seen_table, slots)) return CHAM_E_BAD_DIM;
+        if (!unique_rows || !n_unique || capacity < 0) return CHAM_E_NULL;
+    }
+    hipError_t e = launch_update_configs(theta, actions, B, d, n_steps, cards, salt, seen_table, slots, unique_rows,
+                                         capacity, n_unique, overflow, reinterpret_cast<hipStream_t>(stream));
+    return e == hipSuccess ? CHAM_OK : hip_fail(e);
+}
+
 uint64_t cham_hash_config(const uint8_t *cfg, int32_t d, uint64_t salt)
 {
     uint64_t h = 0xCBF29CE484222325ULL ^ (salt * 0x9E3779B97F4A7C15ULL);

@@ -171,6 +171,9 @@ hipError_t launch_table_insert_hashes(uint64_t *v, int64_t slots, const uint64_t
 hipError_t launch_table_insert_configs(uint64_t *v, int64_t slots, const uint8_t *cfgs, int64_t n, int d,
                                        const uint8_t *flags, const uint64_t *salts, int64_t rows_per_salt,
                                        int *overflow, hipStream_t s);
+hipError_t launch_update_configs(uint8_t *theta, const int8_t *actions, int64_t B, int d, int n_steps,
+                                 const uint16_t *cards, uint64_t salt, uint64_t *seen, int64_t slots,
+                                 uint8_t *unique_rows, int64_t cap, int *n_unique, int *overflow, hipStream_t s);
 hipError_t launch_hash_rows(const uint8_t *rows, int64_t n, int d, const uint64_t *salts,
                             uint64_t salt_all, uint64_t *out, hipStream_t s);
 

@@ -232,18 +232,70 @@ __device__ __forceinline__ bool visited_has(const uint64_t *v, int64_t n, uint64
     return lo < n && v[lo] == key;
 }
 
-// Insert one hash; returns false if the table is full.
-__device__ __forceinline__ bool table_insert(uint64_t *v, uint64_t mask, uint64_t h)
+// Insert one hash: 1 = newly inserted, 2 = was there already, 0 = the table is full.
+__device__ __forceinline__ int table_insert_new(uint64_t *v, uint64_t mask, uint64_t h)
 {
     const uint64_t k = table_key(h);
     uint64_t pos = k & mask;
     for (uint64_t probes = 0; probes <= mask; ++probes) {
         const unsigned long long seen = atomicCAS(reinterpret_cast<unsigned long long *>(v + pos),
                                                   (unsigned long long)kEmptySlot, (unsigned long long)k);
-        if (seen == kEmptySlot || seen == k) return true;
+        if (seen == kEmptySlot) return 1;
+        if (seen == k) return 2;
         pos = (pos + 1) & mask;
     }
-    return false;
+    return 0;
+}
+__device__ __forceinline__ bool table_insert(uint64_t *v, uint64_t mask, uint64_t h)
+{
+    return table_insert_new(v, mask, h) != 0;
+}
+
+// Configuration updater of the exploration step (Sec. 3.2: the agent emits increment / decrement /
+// stay per knob and the updater applies it): one thread carries one configuration through n_steps
+// steps, theta <- clip(theta + a, 0, card - 1) per knob.  Every configuration reached is entered
+// into the table of configurations seen; the first thread to enter one also appends it to the list
+// of distinct configurations (the set S_Theta that the sampling step receives; order unspecified).
+__global__ void update_configs_kernel(uint8_t *theta, const int8_t *actions, int64_t B, int d, int n_steps,
+                                      const uint16_t *cards, uint64_t salt, uint64_t *seen, int64_t slots,
+                                      uint8_t *unique_rows, int64_t cap, int *n_unique, int *overflow)
+{
+    const int64_t b = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= B) return;
+    int cur[32];
+#pragma unroll
+    for (int j = 0; j < 32; ++j) cur[j] = j < d ? theta[b * d + j] : 0;
+    for (int s = 0; s < n_steps; ++s) {
+        const int8_t *a = actions + ((int64_t)s * B + b) * d;
+        uint64_t h = fnv_begin(salt);
+#pragma unroll
+        for (int j = 0; j < 32; ++j) {
+            if (j < d) {
+                int v = cur[j] + (int)a[j];
+                const int hi = (int)cards[j] - 1;
+                v = v < 0 ? 0 : (v > hi ? hi : v);
+                cur[j] = v;
+                h = fnv_step(h, (uint8_t)v);
+            }
+        }
+        if (seen) {
+            const int r = table_insert_new(seen, (uint64_t)slots - 1, h);
+            if (r == 0 && overflow) *overflow = 1;
+            if (r == 1) {
+                const int idx = atomicAdd(n_unique, 1);
+                if (idx < cap) {
+#pragma unroll
+                    for (int j = 0; j < 32; ++j)
+                        if (j < d) unique_rows[(int64_t)idx * d + j] = (uint8_t)cur[j];
+                } else if (overflow) {
+                    *overflow = 1;
+                }
+            }
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < 32; ++j)
+        if (j < d) theta[b * d + j] = (uint8_t)cur[j];
 }
 
 __global__ void table_clear_kernel(uint64_t *v, int64_t slots)
@@ -907,6 +959,16 @@ hipError_t launch_table_insert_configs(uint64_t *v, int64_t slots, const uint8_t
     if (n > 0)
         hipLaunchKernelGGL(table_insert_configs_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, v, slots,
                            cfgs, n, d, flags, salts, rows_per_salt, overflow);
+    return hipGetLastError();
+}
+
+hipError_t launch_update_configs(uint8_t *theta, const int8_t *actions, int64_t B, int d, int n_steps,
+                                 const uint16_t *cards, uint64_t salt, uint64_t *seen, int64_t slots,
+                                 uint8_t *unique_rows, int64_t cap, int *n_unique, int *overflow, hipStream_t s)
+{
+    if (B > 0)
+        hipLaunchKernelGGL(update_configs_kernel, dim3((unsigned)((B + 63) / 64)), dim3(64), 0, s, theta, actions, B, d,
+                           n_steps, cards, salt, seen, slots, unique_rows, cap, n_unique, overflow);
     return hipGetLastError();
 }
 

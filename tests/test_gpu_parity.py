@@ -517,3 +517,40 @@ def test_visited_table_overflow_is_reported_and_lookups_end():
                                        sn["labels_sel"], sn["pick_row"], sn["pick_cfg"], table, task_salt=wl.salts)
     torch.cuda.synchronize()
     assert int(sy["out_count"].sum().item()) >= 0
+
+
+# ------------------------------------------------------------------ configuration updater
+
+@pytest.mark.parametrize("B,d,steps,card_hi", [(128, 8, 60, 6), (37, 24, 25, 32), (1, 1, 10, 2), (300, 32, 12, 256)])
+def test_configuration_updater_matches_the_oracle(B, d, steps, card_hi):
+    import torch
+    rng = np.random.default_rng(1000 + B + d)
+    cards = rng.integers(1 if d == 1 else 2, card_hi + 1, size=d).astype(np.uint16)
+    theta = (rng.random((B, d)) * cards).astype(np.uint8)
+    actions = rng.integers(-1, 2, size=(steps, B, d)).astype(np.int8)
+    final, order = oracle.update_configs(theta, actions, cards)
+    dev = "cuda:0"
+    th = torch.from_numpy(theta.copy()).to(dev)
+    table = torch.empty(1 << 16, dtype=torch.int64, device=dev)
+    binding.cham_visited_table_clear(table)
+    uniq = torch.zeros((B * steps, d), dtype=torch.uint8, device=dev)
+    n_unique = torch.zeros(1, dtype=torch.int32, device=dev)
+    ovf = torch.zeros(1, dtype=torch.int32, device=dev)
+    # the walk in two calls: the running state (theta, table, list, counter) carries over
+    half = steps // 2
+    cards_dev = torch.from_numpy(cards.astype(np.int16)).to(dev)
+    for a in (actions[:half], actions[half:]):
+        binding.cham_update_configs(th, torch.from_numpy(np.ascontiguousarray(a)).to(dev), cards_dev, salt=7,
+                                    seen_table=table, unique_rows=uniq, n_unique=n_unique, overflow=ovf)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(th.cpu().numpy(), final)
+    assert int(ovf.item()) == 0
+    n = int(n_unique.item())
+    assert n == len(order)
+    got = sorted(map(tuple, uniq[:n].cpu().numpy().tolist()))
+    assert got == sorted(order)
+    # and without bookkeeping
+    th2 = torch.from_numpy(theta.copy()).to(dev)
+    binding.cham_update_configs(th2, torch.from_numpy(actions).to(dev), cards_dev)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(th2.cpu().numpy(), final)

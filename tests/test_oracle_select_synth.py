@@ -214,3 +214,31 @@ def test_adversarial_visited_flags_every_cluster():
                 counts = np.bincount(members[:, j], minlength=int(wl.cards[0, j]))
                 assert cfg[c, j] == int(np.argmax(counts))      # argmax = first maximum = smallest value
             assert H(cfg[c], 0) not in set(int(v) for v in visited)
+
+
+# ------------------------------------------------------------------ configuration updater
+
+def test_updater_hand_worked_walk_with_clipping():
+    theta = np.array([[0, 2], [3, 0]], dtype=np.uint8)
+    cards = [4, 3]                                       # values 0..3 and 0..2
+    actions = np.array([[[-1, +1], [+1, 0]],             # step 0: (0,2)->(0,2) both clipped; (3,0)->(3,0) clipped
+                        [[+1, -1], [-1, +1]],            # step 1: (1,1); (2,1)
+                        [[+1, 0], [0, 0]]], dtype=np.int8)   # step 2: (2,1) seen already; (2,1) again
+    final, order = oracle.update_configs(theta, actions, cards)
+    np.testing.assert_array_equal(final, [[2, 1], [2, 1]])
+    assert order == [(0, 2), (3, 0), (1, 1), (2, 1)]
+
+
+def test_updater_invariants():
+    rng = np.random.default_rng(5)
+    cards = rng.integers(1, 9, size=6)
+    theta = (rng.random((10, 6)) * cards).astype(np.uint8)
+    zero = np.zeros((4, 10, 6), dtype=np.int8)
+    final, order = oracle.update_configs(theta, zero, cards)
+    np.testing.assert_array_equal(final, theta)          # staying put changes nothing
+    assert set(order) == set(map(tuple, theta.tolist()))
+    up = np.ones((9, 10, 6), dtype=np.int8)              # enough steps up: everything ends at card - 1
+    final, _ = oracle.update_configs(theta, up, cards)
+    np.testing.assert_array_equal(final, np.broadcast_to(cards - 1, (10, 6)))
+    final, _ = oracle.update_configs(theta, -up, cards)
+    np.testing.assert_array_equal(final, np.zeros((10, 6)))
