@@ -253,6 +253,23 @@ def test_converged_start_counts_from_the_second_pass():
     _sweep_only(wl, 0, want_trace=True, init=init)
 
 
+def test_full_model_sweep_matrix_core_equals_vector_path_and_reports_no_broken_invariant():
+    """The whole benchmark workload (256 tasks, every k): both exact paths must agree bit for bit on
+    every unit, and no unit may report status 2 (a label change in a pass whose centroids had not
+    changed)."""
+    import torch
+    wl = workloads.make_config(5, 0)
+    dw = binding.DeviceWorkload(wl)
+    a = binding.cham_kmeans_sweep(dw.X, dw.ld, dw.d, wl.task_off, wl.ks, wl.n_iter, want_labels=True)
+    b = binding.cham_kmeans_sweep(dw.X, dw.ld, dw.d, wl.task_off, wl.ks, wl.n_iter, want_labels=True,
+                                  flags=binding.F_NO_MFMA)
+    torch.cuda.synchronize()
+    assert int(a["status"].abs().sum().item()) == 0
+    for key in ("centroids", "counts", "status", "labels"):
+        assert torch.equal(a[key], b[key]), key
+    np.testing.assert_allclose(a["inertia"].cpu().numpy(), b["inertia"].cpu().numpy(), rtol=1e-12, atol=0)
+
+
 def test_matrix_core_and_vector_paths_agree_on_every_task():
     """The two screens must lead to identical results (both are exact); this covers all tasks of a
     slice of the full-model workload, beyond what the oracle samples."""
