@@ -409,35 +409,58 @@ __global__ __launch_bounds__(512) void stream_assign_kernel(const StreamArgs a)
                 candq[tt] = __clz((int)cand) & 31;
             }
         } else {
-            // sweep 1: minimum score of every row over all chunks of 64 centroids
-            float best[kTiles];
+            // One sweep over the chunks of 64 centroids.  Every chunk leaves its own minimum (over both
+            // lane halves) and the marks within the bound of that minimum; afterwards a chunk's marks
+            // count iff its minimum lies within the bound of the overall minimum.  The centroids
+            // within the bound of the overall minimum are all among them (their chunk's minimum is
+            // no larger than their score), at worst joined by some up to two bounds away, which
+            // only sends a few more rows to the exact evaluation.
+            constexpr int kMaxCh = 4;                    // k <= 256
+            float bch[kTiles][kMaxCh];
+            uint32_t mch[kTiles][kMaxCh];
+            float bnd[kTiles];
 #pragma unroll
-            for (int tt = 0; tt < kTiles; ++tt) best[tt] = __builtin_inff();
-            for (int ch = 0; ch < nch; ++ch) {
-                const bool has1 = (2 * ch + 1) * 32 < kpu;
-                half8 A0[NS2], A1[NS2];
-                load_a(ch, has1, A0, A1);
+            for (int tt = 0; tt < kTiles; ++tt) bnd[tt] = mfma_bound<NS2>(cur.x2[tt], m2);
 #pragma unroll
-                for (int tt = 0; tt < kTiles; ++tt) {
-                    float m = min16(chain(A0, cur.B[tt]));
-                    if (has1) m = __builtin_fminf(m, min16(chain(A1, cur.B[tt])));
-                    best[tt] = __builtin_fminf(best[tt], m);
+            for (int ch = 0; ch < kMaxCh; ++ch) {
+                if (ch < nch) {
+                    const bool has1 = (2 * ch + 1) * 32 < kpu;
+                    half8 A0[NS2], A1[NS2];
+                    load_a(ch, has1, A0, A1);
+#pragma unroll
+                    for (int tt = 0; tt < kTiles; ++tt) {
+                        const float16v acc0 = chain(A0, cur.B[tt]);
+                        float16v acc1 = zero16;
+                        float m = min16(acc0);
+                        if (has1) {
+                            acc1 = chain(A1, cur.B[tt]);
+                            m = __builtin_fminf(m, min16(acc1));
+                        }
+                        m = min_halves(m);
+                        const float thr = m + bnd[tt];
+                        uint32_t far = mark16(0, acc0, thr);
+                        if (has1) far = mark16(far, acc1, thr);
+                        else far = (far << 16) | 0xFFFFu;
+                        bch[tt][ch] = m;
+                        mch[tt][ch] = ~far;
+                    }
+                } else {
+#pragma unroll
+                    for (int tt = 0; tt < kTiles; ++tt) {
+                        bch[tt][ch] = __builtin_inff();
+                        mch[tt][ch] = 0u;
+                    }
                 }
             }
-            float thr[kTiles];
 #pragma unroll
-            for (int tt = 0; tt < kTiles; ++tt) thr[tt] = min_halves(best[tt]) + mfma_bound<NS2>(cur.x2[tt], m2);
-            // sweep 2: count the scores within the bound and remember where one is
-            for (int ch = 0; ch < nch; ++ch) {
-                const bool has1 = (2 * ch + 1) * 32 < kpu;
-                half8 A0[NS2], A1[NS2];
-                load_a(ch, has1, A0, A1);
+            for (int tt = 0; tt < kTiles; ++tt) {
+                float best = bch[tt][0];
 #pragma unroll
-                for (int tt = 0; tt < kTiles; ++tt) {
-                    uint32_t far = mark16(0, chain(A0, cur.B[tt]), thr[tt]);
-                    if (has1) far = mark16(far, chain(A1, cur.B[tt]), thr[tt]);
-                    else far = (far << 16) | 0xFFFFu;
-                    const uint32_t cand = ~far;
+                for (int ch = 1; ch < kMaxCh; ++ch) best = __builtin_fminf(best, bch[tt][ch]);
+                const float lim = best + bnd[tt];
+#pragma unroll
+                for (int ch = 0; ch < kMaxCh; ++ch) {
+                    const uint32_t cand = bch[tt][ch] <= lim ? mch[tt][ch] : 0u;
                     cnt[tt] += __popc(cand);
                     candq[tt] = cand ? (ch * 32 + __clz((int)cand)) : candq[tt];
                 }
