@@ -51,7 +51,7 @@ def _p(a):
 
 
 def _rows(x) -> np.ndarray:
-    x = np.ascontiguousarray(x, dtype=np.uint8)
+    x = np.ascontiguousarray(x, dtype=np.uint16)
     assert x.ndim == 2
     return x
 
@@ -189,7 +189,7 @@ def snap(x, mu):
 
 
 def hash_config(cfg, salt: int = 0) -> int:
-    cfg = np.ascontiguousarray(cfg, dtype=np.uint8)
+    cfg = np.ascontiguousarray(cfg, dtype=np.uint16)
     return int(lib().orc_hash(_p(cfg), C.c_int(cfg.shape[0]), C.c_uint64(int(salt))))
 
 
@@ -220,7 +220,7 @@ def synthesize(x, cards, valid, labels, pick_row, visited_sorted, salt: int):
     k = len(pick_row)
     vis = np.ascontiguousarray(visited_sorted, dtype=np.uint64)
     assert (vis[1:] >= vis[:-1]).all()
-    out_cfg = np.zeros((k, d), dtype=np.uint8)
+    out_cfg = np.zeros((k, d), dtype=np.uint16)
     out_flag = np.zeros(k, dtype=np.uint8)
     out_count = np.zeros(1, dtype=np.int32)
     lib().orc_synthesize(_p(x), C.c_int64(x.shape[0]), C.c_int(d), _p(cards), _p(v), C.c_int(k),
@@ -249,8 +249,8 @@ def pipeline(wl, visited_sorted, threshold: Optional[float] = None, sweep_out=No
     chosen = np.full(T, -1, dtype=np.int32)
     labels_sel = np.zeros(wl.n_total, dtype=np.int32)
     pick_row = np.full((T, kmax), -1, dtype=np.int64)
-    pick_cfg = np.zeros((T, kmax, d), dtype=np.uint8)
-    out_cfg = np.zeros((T, kmax, d), dtype=np.uint8)
+    pick_cfg = np.zeros((T, kmax, d), dtype=np.uint16)
+    out_cfg = np.zeros((T, kmax, d), dtype=np.uint16)
     out_flag = np.zeros((T, kmax), dtype=np.uint8)
     out_count = np.zeros(T, dtype=np.int32)
     for t in range(T):

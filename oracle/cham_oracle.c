@@ -12,7 +12,9 @@
  *
  * Arithmetic: IEEE double, no fused multiply-add (build with
  * -ffp-contract=off), loops in the order written.  Rows are row-major
- * uint8 [n][d]; knob values are small non-negative integers (indices).
+ * knob_t [n][d]; knob values are non-negative integers (indices into each
+ * knob's list of choices; Sec. 2: a design space is the product of such lists,
+ * and a split-factor knob can have hundreds of choices), held in 16 bits.
  *
  * Where the paper is silent the readings are (each repeated at its function):
  *   - feature space: raw knob indices, unscaled squared Euclidean distance;
@@ -39,6 +41,8 @@
 #include <omp.h>
 #endif
 
+typedef uint16_t knob_t;
+
 enum { ORC_EMPTY = 0, ORC_KEPT = 1, ORC_SYNTH = 2, ORC_DROPPED = 3 };
 
 int orc_num_threads(void)
@@ -53,7 +57,7 @@ int orc_num_threads(void)
 /* Squared Euclidean distance between an integer row and a real centroid,
  * knobs in ascending order (Sec. 3.3: clustering of configurations; the
  * distance itself is the k-means one). */
-static double sqdist(const uint8_t *x, const double *mu, int d)
+static double sqdist(const knob_t *x, const double *mu, int d)
 {
     double s = 0.0;
     for (int j = 0; j < d; ++j) {
@@ -64,7 +68,7 @@ static double sqdist(const uint8_t *x, const double *mu, int d)
 }
 
 /* Nearest centroid of one row; ties go to the smallest cluster index. */
-static int nearest(const uint8_t *x, const double *mu, int k, int d, double *dmin)
+static int nearest(const knob_t *x, const double *mu, int k, int d, double *dmin)
 {
     int best = 0;
     double bd = sqdist(x, mu, d);
@@ -79,20 +83,20 @@ static int nearest(const uint8_t *x, const double *mu, int k, int d, double *dmi
 /* Indices of the first kmax distinct rows, scanning rows in order; a row equal
  * to one already taken is skipped.  Returns how many were found (<= kmax).
  * (The paper does not say how k-means is started; this is the benchmark's rule.) */
-int orc_first_distinct(const uint8_t *x, int64_t n, int d, int kmax, int64_t *rows_out)
+int orc_first_distinct(const knob_t *x, int64_t n, int d, int kmax, int64_t *rows_out)
 {
     int found = 0;
     for (int64_t i = 0; i < n && found < kmax; ++i) {
         int dup = 0;
         for (int q = 0; q < found && !dup; ++q)
-            if (memcmp(x + (size_t)rows_out[q] * d, x + (size_t)i * d, (size_t)d) == 0) dup = 1;
+            if (memcmp(x + (size_t)rows_out[q] * d, x + (size_t)i * d, sizeof(knob_t) * (size_t)d) == 0) dup = 1;
         if (!dup) rows_out[found++] = i;
     }
     return found;
 }
 
 /* One assignment pass: label and distance of every row (rows are independent). */
-static void assign_all(const uint8_t *x, int64_t n, int d, int k, const double *mu,
+static void assign_all(const knob_t *x, int64_t n, int d, int k, const double *mu,
                        int32_t *lab, double *dmin)
 {
 #pragma omp parallel for schedule(static) if (n >= 32768)
@@ -113,7 +117,7 @@ static double sum_in_order(const double *v, int64_t n)
  * cluster sizes and the loss.  mu holds the start on entry and the final
  * centroids on return.  trace (optional, n_iter + 1 values) receives the loss
  * seen by every assignment pass; the last one is the returned loss. */
-void orc_kmeans(const uint8_t *x, int64_t n, int d, int k, int n_iter, double *mu,
+void orc_kmeans(const knob_t *x, int64_t n, int d, int k, int n_iter, double *mu,
                 int64_t *counts, int32_t *labels, double *inertia, double *trace)
 {
     double *dmin = (double *)malloc(sizeof(double) * (size_t)(n > 0 ? n : 1));
@@ -156,7 +160,7 @@ void orc_kmeans(const uint8_t *x, int64_t n, int d, int k, int n_iter, double *m
  *   trace     [T][n_k][n_iter+1] (optional)
  * init_mode 0: centroids start at the first k distinct rows;
  * init_mode 1: they start at init[...] (same layout as centroids). */
-void orc_sweep(const uint8_t *x, int d, const int64_t *task_off, int T, const int32_t *ks,
+void orc_sweep(const knob_t *x, int d, const int64_t *task_off, int T, const int32_t *ks,
                int n_k, int n_iter, int init_mode, const double *init, double *centroids,
                int64_t *counts, double *inertia, int32_t *status, int32_t *labels,
                double *trace)
@@ -187,7 +191,7 @@ void orc_sweep(const uint8_t *x, int d, const int64_t *task_off, int T, const in
         int t = (int)(u % T);
         int k = ks[ki];
         int64_t r0 = task_off[t], n = task_off[t + 1] - task_off[t];
-        const uint8_t *xt = x + (size_t)r0 * d;
+        const knob_t *xt = x + (size_t)r0 * d;
         double *mu = centroids + ((size_t)t * Ksum + koff[ki]) * d;
         int64_t *cn = counts + (size_t)t * Ksum + koff[ki];
         size_t slot = (size_t)t * n_k + ki;
@@ -243,7 +247,7 @@ int orc_select_k(const double *loss, const int32_t *status, int n_k, double thre
  * centroid, smallest row index on ties; pick_row = -1 for an empty cluster.
  * (Sec. 3.3 uses the centroids as representatives; a centroid is real-valued,
  * so the benchmark's rule is to take the nearest member configuration.) */
-void orc_snap(const uint8_t *x, int64_t n, int d, int k, const double *mu,
+void orc_snap(const knob_t *x, int64_t n, int d, int k, const double *mu,
               int32_t *labels, int64_t *pick_row)
 {
     double *dmin = (double *)malloc(sizeof(double) * (size_t)(n > 0 ? n : 1));
@@ -257,10 +261,11 @@ void orc_snap(const uint8_t *x, int64_t n, int d, int k, const double *mu,
     free(dmin); free(bd);
 }
 
-/* 64-bit FNV-1a over the knob bytes; the offset basis is first mixed with the
- * task salt so that equal vectors of different tasks hash apart.  With salt 0
- * this is exactly FNV-1a of the byte string. */
-uint64_t orc_hash(const uint8_t *cfg, int d, uint64_t salt)
+/* 64-bit FNV-1a over the knob values, one xor-multiply step per knob; the
+ * offset basis is first mixed with the task salt so that equal vectors of
+ * different tasks hash apart.  With salt 0 and every value below 256 this is
+ * exactly FNV-1a of the byte string; a larger value enters its step whole. */
+uint64_t orc_hash(const knob_t *cfg, int d, uint64_t salt)
 {
     uint64_t h = 0xCBF29CE484222325ULL ^ (salt * 0x9E3779B97F4A7C15ULL);
     for (int j = 0; j < d; ++j) {
@@ -270,7 +275,7 @@ uint64_t orc_hash(const uint8_t *cfg, int d, uint64_t salt)
     return h;
 }
 
-void orc_hash_rows(const uint8_t *x, int64_t n, int d, const uint64_t *salt_per_row,
+void orc_hash_rows(const knob_t *x, int64_t n, int d, const uint64_t *salt_per_row,
                    uint64_t salt_all, uint64_t *out)
 {
     for (int64_t i = 0; i < n; ++i)
@@ -296,24 +301,24 @@ static int in_sorted(const uint64_t *v, int64_t n, uint64_t key)
  * valid member, when its hash is visited, when it equals a kept pick, or when it
  * equals a replacement accepted for a lower cluster; otherwise it is SYNTH.
  * Empty clusters are EMPTY.  Rows of out_cfg for DROPPED / EMPTY are zero. */
-void orc_synthesize(const uint8_t *x, int64_t n, int d, const uint16_t *cards,
+void orc_synthesize(const knob_t *x, int64_t n, int d, const uint16_t *cards,
                     const uint8_t *valid, int k, const int32_t *labels,
                     const int64_t *pick_row, const uint64_t *visited, int64_t n_visited,
-                    uint64_t salt, uint8_t *out_cfg, uint8_t *out_flag, int32_t *out_count)
+                    uint64_t salt, knob_t *out_cfg, uint8_t *out_flag, int32_t *out_count)
 {
     int cmax = 0;
     for (int j = 0; j < d; ++j) if (cards[j] > cmax) cmax = cards[j];
     int64_t *hist = (int64_t *)malloc(sizeof(int64_t) * (size_t)d * (size_t)(cmax > 0 ? cmax : 1));
     uint8_t *flagged = (uint8_t *)calloc((size_t)k, 1);
-    uint8_t *m = (uint8_t *)malloc((size_t)d);
-    memset(out_cfg, 0, (size_t)k * d);
+    knob_t *m = (knob_t *)malloc(sizeof(knob_t) * (size_t)d);
+    memset(out_cfg, 0, sizeof(knob_t) * (size_t)k * d);
     int count = 0;
     for (int c = 0; c < k; ++c) {
         if (pick_row[c] < 0) { out_flag[c] = ORC_EMPTY; continue; }
-        const uint8_t *p = x + (size_t)pick_row[c] * d;
+        const knob_t *p = x + (size_t)pick_row[c] * d;
         int bad = (valid && !valid[pick_row[c]]) || in_sorted(visited, n_visited, orc_hash(p, d, salt));
         if (bad) { flagged[c] = 1; out_flag[c] = ORC_DROPPED; }
-        else { out_flag[c] = ORC_KEPT; memcpy(out_cfg + (size_t)c * d, p, (size_t)d); ++count; }
+        else { out_flag[c] = ORC_KEPT; memcpy(out_cfg + (size_t)c * d, p, sizeof(knob_t) * (size_t)d); ++count; }
     }
     for (int c = 0; c < k; ++c) {
         if (!flagged[c]) continue;
@@ -329,16 +334,16 @@ void orc_synthesize(const uint8_t *x, int64_t n, int d, const uint16_t *cards,
             int bv = 0;
             for (int v = 1; v < cards[j]; ++v)
                 if (hist[(size_t)j * cmax + v] > hist[(size_t)j * cmax + bv]) bv = v;
-            m[j] = (uint8_t)bv;
+            m[j] = (knob_t)bv;
         }
         int dup = in_sorted(visited, n_visited, orc_hash(m, d, salt));
         for (int q = 0; q < k && !dup; ++q) {
             int use = (out_flag[q] == ORC_KEPT) || (q < c && out_flag[q] == ORC_SYNTH);
-            if (use && memcmp(out_cfg + (size_t)q * d, m, (size_t)d) == 0) dup = 1;
+            if (use && memcmp(out_cfg + (size_t)q * d, m, sizeof(knob_t) * (size_t)d) == 0) dup = 1;
         }
         if (dup) continue;
         out_flag[c] = ORC_SYNTH;
-        memcpy(out_cfg + (size_t)c * d, m, (size_t)d);
+        memcpy(out_cfg + (size_t)c * d, m, sizeof(knob_t) * (size_t)d);
         ++count;
     }
     *out_count = count;

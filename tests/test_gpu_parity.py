@@ -514,6 +514,36 @@ def test_outer_loop_with_a_growing_visited_table():
     assert (sy["out_flag"].cpu().numpy() != oracle.KEPT).all()
 
 
+@pytest.mark.parametrize("flags", [0, binding.F_NO_MFMA, binding.F_STREAMING])
+def test_warm_start_from_the_previous_round_on_a_changed_sample(flags):
+    """Outer loop, next round: the explorer returns a changed sample (here: a third of the rows
+    moved by one step in some knobs, a tenth redrawn) and the sweep starts from the centroids the
+    previous round ended with.  Some of those centroids may attract no row any more; such a cluster
+    keeps its centroid."""
+    import torch
+    wl = workloads.make_config(3, 1, scale=5 / 64)
+    wl.ks, wl.n_iter = [1, 2, 7, 16, 31, 32], 6
+    dw = binding.DeviceWorkload(wl)
+    first = binding.cham_kmeans_sweep(dw.X, dw.ld, dw.d, wl.task_off, wl.ks, wl.n_iter, flags=flags)
+    first_cpu = oracle.sweep(wl.rows, wl.task_off, wl.ks, wl.n_iter)
+    np.testing.assert_array_equal(first["centroids"].cpu().numpy(), first_cpu["centroids"])
+    rng = np.random.default_rng(99)
+    rows = wl.rows.astype(np.int64)
+    hi = np.repeat(wl.cards.astype(np.int64), np.diff(wl.task_off), axis=0) - 1
+    moved = rng.random(rows.shape[0]) < 1 / 3
+    rows[moved] += rng.integers(-1, 2, size=(int(moved.sum()), wl.rows.shape[1]))
+    redrawn = rng.random(rows.shape[0]) < 0.1
+    rows[redrawn] = (rng.random((int(redrawn.sum()), wl.rows.shape[1])) * (hi[redrawn] + 1)).astype(np.int64)
+    wl.rows = np.clip(rows, 0, hi).astype(np.uint8)
+    ref = oracle.sweep(wl.rows, wl.task_off, wl.ks, wl.n_iter, init=first_cpu["centroids"], want_labels=True)
+    dw2 = binding.DeviceWorkload(wl)
+    out = binding.cham_kmeans_sweep(dw2.X, dw2.ld, dw2.d, wl.task_off, wl.ks, wl.n_iter, want_labels=True,
+                                    init_centroids=first["centroids"], flags=flags)
+    torch.cuda.synchronize()
+    check_sweep(wl, out, ref, dw2.ld)
+    assert (ref["status"] == 0).all()
+
+
 def test_visited_table_overflow_is_reported_and_lookups_end():
     import torch
     table = torch.empty(4, dtype=torch.int64, device="cuda:0")
