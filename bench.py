@@ -37,6 +37,8 @@ def main():
     ap.add_argument("--cpu-tasks", type=int, default=48, help="tasks of the workload the oracle is timed on (about 13 s)")
     ap.add_argument("--knee-chunk", type=int, default=8,
                     help="also time the sweep that stops at the knee, in chunks of this many k (0 = skip)")
+    ap.add_argument("--no-wide-knobs", dest="wide_knobs", action="store_false",
+                    help="skip the timing of the two-byte-knob path")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run only a plain 1 GiB device copy (reference for the FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
@@ -195,6 +197,39 @@ def main():
     updater = dict(episodes=B_u, steps=S_u, d=wl.d, ms=round(best_u, 4), distinct=int(n_u.item()),
                    config_steps_per_s=round(B_u * S_u / (best_u * 1e-3), 1))
 
+    # Design spaces with two-byte knobs and more than 32 knobs (the *_u16 entry points): 64 tasks x 2048
+    # configurations x 40 knobs with cardinalities up to 600, k = 2..32, 30 Lloyd steps; whole path.
+    wide = None
+    if args.wide_knobs:
+        ww = workloads.wide_space(0)
+        dww = binding.DeviceWorkload(ww, "cuda:0")
+        dww.build_visited()
+        wfirst = dww.run()
+        wbufs = dict(sweep={k: wfirst["sweep"][k] for k in ("centroids", "counts", "inertia", "status")},
+                     sweep_ws=wfirst["sweep"]["workspace"], chosen=wfirst["chosen"],
+                     snap={k: wfirst["snap"][k] for k in ("labels_sel", "pick_row", "pick_cfg")},
+                     snap_ws=wfirst["snap"]["workspace"],
+                     synth={k: wfirst["synth"][k] for k in ("out_cfg", "out_flag", "out_count")},
+                     synth_ws=wfirst["synth"]["workspace"])
+        wbufs["sweep"]["labels"] = None
+        wbufs["sweep"]["trace"] = None
+        torch.cuda.synchronize()
+        wev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(5)]
+        for e0, e1 in wev:
+            e0.record()
+            dww.run(bufs=wbufs)
+            e1.record()
+        torch.cuda.synchronize()
+        w_ms = float(np.mean([a.elapsed_time(b) for a, b in wev]))
+        w_evals = ww.nominal_evals()
+        wide = dict(workload=f"{ww.name}: T={ww.T} tasks x N={ww.n_total // ww.T} rows x d={ww.d} two-byte knobs "
+                             f"(cardinalities up to {int(ww.cards.max())}), k={ww.ks[0]}..{ww.ks[-1]}, "
+                             f"{ww.n_iter} Lloyd steps + final pass, visited={ww.n_visited}",
+                    ms_per_step=round(w_ms, 3), evals_per_step=w_evals,
+                    evals_per_s=round(w_evals / (w_ms * 1e-3), 1),
+                    frac_of_fp32_vector_peak=round(w_evals * (2 * ww.d + 2) / (w_ms * 1e-3) / 1e12
+                                                   / PEAK_FP32_VECTOR_TFLOPS, 4))
+
     cpu = None
     if not args.no_cpu_baseline:
         import oracle
@@ -219,7 +254,7 @@ def main():
                                f"visited={wl.n_visited}, threshold={wl.threshold}",
                    "evals_per_step": evals, "sweep_ms": round(sweep_ms, 3)},
         "roofline": roofline, "cpu_baseline": cpu, "knee_sweep": knee,
-        "visited_table": vtab, "config_updater": updater,
+        "visited_table": vtab, "config_updater": updater, "wide_knobs": wide,
     }
     print(json.dumps(line), flush=True)
 

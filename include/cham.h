@@ -13,7 +13,9 @@
  *                         dedupe against the visited set (Algorithm 1, second loop)
  *
  * Conventions
- *   - A configuration is one small integer per knob (Sec. 2.2): a uint8 knob index.
+ *   - A configuration is one small integer per knob (Sec. 2.2): a uint8 knob index.  Design
+ *     spaces whose knobs have more than 256 choices, or more than 32 knobs, go through the
+ *     *_u16 entry points at the end of this header.
  *   - X is a structure-of-arrays matrix in DEVICE memory: knob j of row i is X[j*ld + i].
  *     ld >= total rows, ld % 4 == 0, X 4-byte aligned.  All tasks share X; task t owns
  *     rows [task_off[t], task_off[t+1]).
@@ -41,10 +43,10 @@ extern "C" {
 
 #define CHAM_OK              0
 #define CHAM_E_NULL         (-1)   /* a required pointer is NULL */
-#define CHAM_E_BAD_DIM      (-2)   /* d outside [1,32], ld < rows, ld % 4 != 0, misaligned X, n_iter < 0, T < 1 */
-#define CHAM_E_BAD_K        (-3)   /* ks empty, not strictly increasing, k < 1 or k > 256 */
+#define CHAM_E_BAD_DIM      (-2)   /* d outside [1,32] ([1,64] for *_u16), ld < rows, ld % 4 != 0, misaligned X, n_iter < 0, T < 1 */
+#define CHAM_E_BAD_K        (-3)   /* ks empty, not strictly increasing, k < 1 or k > 256; *_u16: k_max too large for d */
 #define CHAM_E_BAD_OFFSETS  (-4)   /* task_off not non-decreasing from >= 0, a task larger than 2^23 rows */
-#define CHAM_E_CARD         (-5)   /* a cardinality is 0 or above 256 */
+#define CHAM_E_CARD         (-5)   /* a cardinality is 0 or above 256 (above 16384 for *_u16) */
 #define CHAM_E_WORKSPACE    (-6)   /* workspace NULL or smaller than cham_*_workspace_bytes says */
 #define CHAM_E_HIP          (-7)   /* a HIP runtime call failed; see cham_last_hip_error() */
 #define CHAM_E_BAD_FLAG     (-8)   /* unknown bits in flags / unknown init_mode */
@@ -254,7 +256,7 @@ int32_t cham_update_configs(uint8_t *theta, const int8_t *actions, int64_t B, in
                             void *stream);
 
 /*
- * Configuration hash used for the visited set: 64-bit FNV-1a over the d knob bytes, the
+ * Configuration hash used for the visited set: 64-bit FNV-1a over the d knob values, the
  * offset basis first XORed with salt * 0x9E3779B97F4A7C15 (mod 2^64).  salt 0 gives plain
  * FNV-1a.  cfg is HOST memory.
  */
@@ -263,6 +265,78 @@ uint64_t cham_hash_config(const uint8_t *cfg, int32_t d, uint64_t salt);
  * (then salt_all is used for every row); out DEVICE [n]. */
 int32_t cham_hash_rows(const uint8_t *rows, int64_t n, int32_t d, const uint64_t *salts,
                        uint64_t salt_all, uint64_t *out, void *stream);
+
+/*
+ * Two-byte knobs.  The design spaces of Sec. 2 are products of the knobs' choice lists (10^10
+ * points and more); a split knob of a large loop alone has hundreds of choices, and templates
+ * with many loops have more than 32 knobs.  Every entry point above that reads or writes
+ * configurations has a twin that takes uint16 knob values and up to 64 knobs; what is computed,
+ * every rule, tie-break, output layout and error code is that of the function without the
+ * suffix, with these differences:
+ *   - X is uint16 [d][ld] (DEVICE), 8-byte aligned, ld % 4 == 0; pick_cfg, out_cfg, cfgs and
+ *     rows are uint16; 1 <= d <= 64; knob values up to 65535.
+ *   - The sweep and the snap run one workgroup per (task, k) whatever the task size (built for
+ *     tasks of up to some ten thousand rows; larger ones are correct but slow).  Cluster sums
+ *     are 64-bit integers.  flags: CHAM_F_FORCE_EXACT is honoured, CHAM_F_RESIDENT and
+ *     CHAM_F_NO_MFMA are accepted (they name what this path does anyway), CHAM_F_STREAMING
+ *     gives CHAM_E_BAD_FLAG.
+ *   - k_max * (20 * dp + 20) + 4 * dp + 192 must not exceed 160 KiB, dp = d rounded up to 8,
+ *     16, 24, 32, 48 or 64 (k_max up to 256 for d <= 24, 247 for d <= 32, 166 for d <= 48,
+ *     125 for d <= 64); beyond that: CHAM_E_BAD_K, also from the sweep's workspace queries.
+ *   - cham_synthesize*_u16: cardinalities up to 16384 (the value histogram of one knob of one
+ *     cluster has to fit in LDS); above: CHAM_E_CARD.
+ *   - The hash takes one FNV-1a step per knob value, the whole value in the step: equal to the
+ *     byte hash for a configuration whose values are all below 256, so a visited set can be
+ *     shared between the two families.
+ */
+int64_t cham_sweep_workspace_bytes_u16(int64_t ld, int32_t d, const int64_t *task_off, int32_t T,
+                                       const int32_t *ks, int32_t n_k, int32_t n_iter, int32_t flags);
+int32_t cham_kmeans_sweep_u16(const uint16_t *X, int64_t ld, int32_t d,
+                              const int64_t *task_off, int32_t T,
+                              const int32_t *ks, int32_t n_k,
+                              int32_t n_iter, int32_t init_mode, const double *init_centroids,
+                              double *centroids, int32_t *counts, double *inertia, int32_t *status,
+                              uint8_t *labels, double *inertia_trace,
+                              void *workspace, int64_t workspace_bytes, int32_t flags, void *stream);
+int64_t cham_sweep_knee_workspace_bytes_u16(int64_t ld, int32_t d, const int64_t *task_off, int32_t T,
+                                            const int32_t *ks, int32_t n_k, int32_t n_iter, int32_t flags);
+int32_t cham_kmeans_sweep_knee_u16(const uint16_t *X, int64_t ld, int32_t d, const int64_t *task_off, int32_t T,
+                                   const int32_t *ks, int32_t n_k, int32_t n_iter, int32_t init_mode,
+                                   const double *init_centroids, double threshold, int32_t chunk,
+                                   double *centroids, int32_t *counts, double *inertia, int32_t *status,
+                                   int32_t *chosen_idx, uint8_t *labels, double *inertia_trace,
+                                   void *workspace, int64_t workspace_bytes, int32_t flags, void *stream);
+int64_t cham_snap_workspace_bytes_u16(int64_t ld, int32_t d, const int64_t *task_off, int32_t T,
+                                      const int32_t *ks, int32_t n_k);
+int32_t cham_snap_centroids_u16(const uint16_t *X, int64_t ld, int32_t d,
+                                const int64_t *task_off, int32_t T, const int32_t *ks, int32_t n_k,
+                                const int32_t *chosen_idx, const double *centroids,
+                                uint8_t *labels_sel, int32_t *pick_row, uint16_t *pick_cfg,
+                                void *workspace, int64_t workspace_bytes, int32_t flags, void *stream);
+int64_t cham_synth_workspace_bytes_u16(int64_t ld, int32_t d, const int64_t *task_off, int32_t T,
+                                       const int32_t *ks, int32_t n_k);
+int32_t cham_synthesize_u16(const uint16_t *X, int64_t ld, int32_t d,
+                            const int64_t *task_off, int32_t T, const uint16_t *cards,
+                            const uint8_t *valid, const int32_t *ks, int32_t n_k,
+                            const int32_t *chosen_idx, const uint8_t *labels_sel,
+                            const int32_t *pick_row, const uint16_t *pick_cfg,
+                            const uint64_t *visited, int64_t n_visited, const uint64_t *task_salt,
+                            uint16_t *out_cfg, uint8_t *out_flag, int32_t *out_count,
+                            void *workspace, int64_t workspace_bytes, void *stream);
+int32_t cham_synthesize_table_u16(const uint16_t *X, int64_t ld, int32_t d,
+                                  const int64_t *task_off, int32_t T, const uint16_t *cards,
+                                  const uint8_t *valid, const int32_t *ks, int32_t n_k,
+                                  const int32_t *chosen_idx, const uint8_t *labels_sel,
+                                  const int32_t *pick_row, const uint16_t *pick_cfg,
+                                  const uint64_t *table, int64_t slots, const uint64_t *task_salt,
+                                  uint16_t *out_cfg, uint8_t *out_flag, int32_t *out_count,
+                                  void *workspace, int64_t workspace_bytes, void *stream);
+int32_t cham_visited_table_insert_configs_u16(uint64_t *table, int64_t slots, const uint16_t *cfgs, int64_t n,
+                                              int32_t d, const uint8_t *flags, const uint64_t *salts,
+                                              int64_t rows_per_salt, int32_t *overflow, void *stream);
+uint64_t cham_hash_config_u16(const uint16_t *cfg, int32_t d, uint64_t salt);
+int32_t cham_hash_rows_u16(const uint16_t *rows, int64_t n, int32_t d, const uint64_t *salts,
+                           uint64_t salt_all, uint64_t *out, void *stream);
 
 #ifdef __cplusplus
 }

@@ -25,6 +25,10 @@ EXPORTS = [
     "cham_hash_rows", "cham_sweep_knee_workspace_bytes", "cham_kmeans_sweep_knee", "cham_synthesize_table",
     "cham_visited_table_clear", "cham_visited_table_insert_hashes", "cham_visited_table_insert_configs",
     "cham_update_configs",
+    "cham_sweep_workspace_bytes_u16", "cham_kmeans_sweep_u16", "cham_sweep_knee_workspace_bytes_u16",
+    "cham_kmeans_sweep_knee_u16", "cham_snap_workspace_bytes_u16", "cham_snap_centroids_u16",
+    "cham_synth_workspace_bytes_u16", "cham_synthesize_u16", "cham_synthesize_table_u16",
+    "cham_visited_table_insert_configs_u16", "cham_hash_config_u16", "cham_hash_rows_u16",
 ]
 
 
@@ -85,8 +89,27 @@ def load() -> C.CDLL:
         lib.cham_hash_config.argtypes = [vp, i32, u64]
         lib.cham_hash_rows.restype = i32
         lib.cham_hash_rows.argtypes = [vp, i64, i32, vp, u64, vp, vp]
+        # the entry points for two-byte knobs take the same argument lists
+        for name in EXPORTS:
+            if name.endswith("_u16"):
+                base = getattr(lib, name[:-4])
+                getattr(lib, name).restype = base.restype
+                getattr(lib, name).argtypes = base.argtypes
         _lib = lib
     return _lib
+
+
+def _knob_dtypes(sfx: str):
+    """(numpy dtype of host rows, torch dtype of device knob buffers) for an entry-point suffix.
+    Two-byte knobs live in int16 tensors (same bits as uint16)."""
+    torch = _torch()
+    return (np.uint8, torch.uint8) if sfx == "" else (np.uint16, torch.int16)
+
+
+def knobs_to_host(t) -> np.ndarray:
+    """Device knob tensor (uint8, or int16 holding uint16 bits) as a numpy array of unsigned values."""
+    a = t.cpu().numpy()
+    return a.view(np.uint16) if a.dtype == np.int16 else a
 
 
 def _check(rc: int):
@@ -124,13 +147,17 @@ def _host_lists(task_off, ks):
 
 
 def to_soa(rows: np.ndarray, device="cuda:0", pad_to: int = 64):
-    """Upload row-major uint8 rows [N, d] as the structure-of-arrays matrix X [d, ld] the library reads."""
+    """Upload row-major rows [N, d] (uint8, or uint16 for two-byte knobs) as the structure-of-arrays
+    matrix X [d, ld] the library reads."""
     torch = _torch()
-    rows = np.ascontiguousarray(rows, dtype=np.uint8)
+    dt = np.uint16 if np.asarray(rows).dtype == np.uint16 else np.uint8
+    rows = np.ascontiguousarray(rows, dtype=dt)
     n, d = rows.shape
     ld = max(pad_to, (n + pad_to - 1) // pad_to * pad_to)
-    host = np.zeros((d, ld), dtype=np.uint8)
+    host = np.zeros((d, ld), dtype=dt)
     host[:, :n] = rows.T
+    if dt == np.uint16:
+        host = host.view(np.int16)
     return torch.from_numpy(host).to(device), ld
 
 
@@ -143,41 +170,62 @@ def cham_hash_config(cfg, salt: int = 0) -> int:
     return int(load().cham_hash_config(_hp(cfg), C.c_int32(cfg.shape[0]), C.c_uint64(int(salt))))
 
 
+def cham_hash_config_u16(cfg, salt: int = 0) -> int:
+    cfg = np.ascontiguousarray(cfg, dtype=np.uint16)
+    return int(load().cham_hash_config_u16(_hp(cfg), C.c_int32(cfg.shape[0]), C.c_uint64(int(salt))))
+
+
 def cham_select_k_host(curve, status=None, threshold: float = 2.5) -> int:
     curve = np.ascontiguousarray(curve, dtype=np.float64)
     st = None if status is None else np.ascontiguousarray(status, dtype=np.int32)
     return int(load().cham_select_k_host(_hp(curve), _hp(st), C.c_int32(len(curve)), C.c_double(threshold)))
 
 
-def cham_hash_rows(rows_dev, salts_dev=None, salt_all: int = 0):
+def cham_hash_rows(rows_dev, salts_dev=None, salt_all: int = 0, _sfx: str = ""):
     """rows_dev: device uint8 [n, d] row-major; salts_dev: device int64/uint64 [n] or None."""
     torch = _torch()
+    assert rows_dev.dtype == _knob_dtypes(_sfx)[1]
     n, d = rows_dev.shape
     out = torch.empty(n, dtype=torch.int64, device=rows_dev.device)
-    _check(load().cham_hash_rows(_dp(rows_dev), C.c_int64(n), C.c_int32(d), _dp(salts_dev),
-                                 C.c_uint64(int(salt_all)), _dp(out), _stream()))
+    _check(getattr(load(), "cham_hash_rows" + _sfx)(_dp(rows_dev), C.c_int64(n), C.c_int32(d), _dp(salts_dev),
+                                                    C.c_uint64(int(salt_all)), _dp(out), _stream()))
     return out
 
 
-def cham_sweep_workspace_bytes(ld, d, task_off, ks, n_iter, flags=0) -> int:
-    to, k = _host_lists(task_off, ks)
-    return _check(load().cham_sweep_workspace_bytes(C.c_int64(ld), C.c_int32(d), _hp(to), C.c_int32(len(to) - 1),
-                                                    _hp(k), C.c_int32(len(k)), C.c_int32(n_iter), C.c_int32(flags)))
+def cham_hash_rows_u16(rows_dev, salts_dev=None, salt_all: int = 0):
+    """rows_dev: device int16 tensor [n, d] holding uint16 knob values, row-major."""
+    return cham_hash_rows(rows_dev, salts_dev, salt_all, _sfx="_u16")
 
 
-def cham_sweep_knee_workspace_bytes(ld, d, task_off, ks, n_iter, flags=0) -> int:
+def cham_sweep_workspace_bytes(ld, d, task_off, ks, n_iter, flags=0, _sfx: str = "") -> int:
     to, k = _host_lists(task_off, ks)
-    return _check(load().cham_sweep_knee_workspace_bytes(C.c_int64(ld), C.c_int32(d), _hp(to),
-                                                         C.c_int32(len(to) - 1), _hp(k), C.c_int32(len(k)),
-                                                         C.c_int32(n_iter), C.c_int32(flags)))
+    fn = getattr(load(), "cham_sweep_workspace_bytes" + _sfx)
+    return _check(fn(C.c_int64(ld), C.c_int32(d), _hp(to), C.c_int32(len(to) - 1),
+                     _hp(k), C.c_int32(len(k)), C.c_int32(n_iter), C.c_int32(flags)))
+
+
+def cham_sweep_knee_workspace_bytes(ld, d, task_off, ks, n_iter, flags=0, _sfx: str = "") -> int:
+    to, k = _host_lists(task_off, ks)
+    fn = getattr(load(), "cham_sweep_knee_workspace_bytes" + _sfx)
+    return _check(fn(C.c_int64(ld), C.c_int32(d), _hp(to), C.c_int32(len(to) - 1), _hp(k), C.c_int32(len(k)),
+                     C.c_int32(n_iter), C.c_int32(flags)))
+
+
+def cham_sweep_workspace_bytes_u16(ld, d, task_off, ks, n_iter, flags=0) -> int:
+    return cham_sweep_workspace_bytes(ld, d, task_off, ks, n_iter, flags, _sfx="_u16")
+
+
+def cham_sweep_knee_workspace_bytes_u16(ld, d, task_off, ks, n_iter, flags=0) -> int:
+    return cham_sweep_knee_workspace_bytes(ld, d, task_off, ks, n_iter, flags, _sfx="_u16")
 
 
 def cham_kmeans_sweep(X, ld: int, d: int, task_off, ks: Sequence[int], n_iter: int, init_centroids=None,
                       want_labels: bool = False, want_trace: bool = False, flags: int = 0,
-                      out: Optional[dict] = None, workspace=None):
+                      out: Optional[dict] = None, workspace=None, _sfx: str = ""):
     """Run the sweep; returns a dict of device tensors (centroids, counts, inertia, status, labels, trace)."""
     torch = _torch()
     lib = load()
+    assert X.dtype == _knob_dtypes(_sfx)[1]
     to, k = _host_lists(task_off, ks)
     T, n_k, Ksum = len(to) - 1, len(k), int(k.sum())
     dev = X.device
@@ -190,9 +238,9 @@ def cham_kmeans_sweep(X, ld: int, d: int, task_off, ks: Sequence[int], n_iter: i
         out["labels"] = torch.zeros((n_k, ld), dtype=torch.uint8, device=dev) if want_labels else None
         out["trace"] = torch.empty((T, n_k, n_iter + 1), dtype=torch.float64, device=dev) if want_trace else None
     if workspace is None:
-        nbytes = cham_sweep_workspace_bytes(ld, d, to, k, n_iter, flags)
+        nbytes = cham_sweep_workspace_bytes(ld, d, to, k, n_iter, flags, _sfx=_sfx)
         workspace = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=dev)
-    rc = lib.cham_kmeans_sweep(_dp(X), C.c_int64(ld), C.c_int32(d), _hp(to), C.c_int32(T), _hp(k), C.c_int32(n_k),
+    rc = getattr(lib, "cham_kmeans_sweep" + _sfx)(_dp(X), C.c_int64(ld), C.c_int32(d), _hp(to), C.c_int32(T), _hp(k), C.c_int32(n_k),
                                C.c_int32(n_iter), C.c_int32(0 if init_centroids is None else 1),
                                _dp(init_centroids), _dp(out["centroids"]), _dp(out["counts"]),
                                _dp(out["inertia"]), _dp(out["status"]), _dp(out.get("labels")),
@@ -204,12 +252,19 @@ def cham_kmeans_sweep(X, ld: int, d: int, task_off, ks: Sequence[int], n_iter: i
     return out
 
 
+def cham_kmeans_sweep_u16(X, ld: int, d: int, task_off, ks: Sequence[int], n_iter: int, **kw):
+    """cham_kmeans_sweep for two-byte knobs: X is a device int16 tensor [d, ld] holding uint16 values."""
+    return cham_kmeans_sweep(X, ld, d, task_off, ks, n_iter, _sfx="_u16", **kw)
+
+
 def cham_kmeans_sweep_knee(X, ld: int, d: int, task_off, ks: Sequence[int], n_iter: int, threshold: float = 2.5,
                            chunk: int = 8, init_centroids=None, want_labels: bool = False,
-                           want_trace: bool = False, flags: int = 0, out: Optional[dict] = None, workspace=None):
+                           want_trace: bool = False, flags: int = 0, out: Optional[dict] = None, workspace=None,
+                           _sfx: str = ""):
     """Run the sweep in chunks and stop every task at its knee; returns the same dict plus ``chosen``."""
     torch = _torch()
     lib = load()
+    assert X.dtype == _knob_dtypes(_sfx)[1]
     to, k = _host_lists(task_off, ks)
     T, n_k, Ksum = len(to) - 1, len(k), int(k.sum())
     dev = X.device
@@ -223,9 +278,9 @@ def cham_kmeans_sweep_knee(X, ld: int, d: int, task_off, ks: Sequence[int], n_it
         out["labels"] = torch.zeros((n_k, ld), dtype=torch.uint8, device=dev) if want_labels else None
         out["trace"] = torch.empty((T, n_k, n_iter + 1), dtype=torch.float64, device=dev) if want_trace else None
     if workspace is None:
-        nbytes = cham_sweep_knee_workspace_bytes(ld, d, to, k, n_iter, flags)
+        nbytes = cham_sweep_knee_workspace_bytes(ld, d, to, k, n_iter, flags, _sfx=_sfx)
         workspace = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=dev)
-    rc = lib.cham_kmeans_sweep_knee(_dp(X), C.c_int64(ld), C.c_int32(d), _hp(to), C.c_int32(T), _hp(k),
+    rc = getattr(lib, "cham_kmeans_sweep_knee" + _sfx)(_dp(X), C.c_int64(ld), C.c_int32(d), _hp(to), C.c_int32(T), _hp(k),
                                     C.c_int32(n_k), C.c_int32(n_iter), C.c_int32(0 if init_centroids is None else 1),
                                     _dp(init_centroids), C.c_double(threshold), C.c_int32(chunk),
                                     _dp(out["centroids"]), _dp(out["counts"]), _dp(out["inertia"]),
@@ -236,6 +291,10 @@ def cham_kmeans_sweep_knee(X, ld: int, d: int, task_off, ks: Sequence[int], n_it
     out["workspace"] = workspace
     out["koff"] = np.concatenate([[0], np.cumsum(k)]).astype(np.int64)
     return out
+
+
+def cham_kmeans_sweep_knee_u16(X, ld: int, d: int, task_off, ks: Sequence[int], n_iter: int, **kw):
+    return cham_kmeans_sweep_knee(X, ld, d, task_off, ks, n_iter, _sfx="_u16", **kw)
 
 
 def cham_select_k(inertia, status, threshold: float = 2.5, chosen=None):
@@ -249,20 +308,21 @@ def cham_select_k(inertia, status, threshold: float = 2.5, chosen=None):
 
 
 def cham_snap_centroids(X, ld: int, d: int, task_off, ks, chosen_idx, centroids, flags: int = 0,
-                        out: Optional[dict] = None, workspace=None):
+                        out: Optional[dict] = None, workspace=None, _sfx: str = ""):
     torch = _torch()
+    assert X.dtype == _knob_dtypes(_sfx)[1]
     to, k = _host_lists(task_off, ks)
     T, n_k, kmax = len(to) - 1, len(k), int(k[-1])
     dev = X.device
     if out is None:
         out = dict(labels_sel=torch.zeros(ld, dtype=torch.uint8, device=dev),
                    pick_row=torch.empty((T, kmax), dtype=torch.int32, device=dev),
-                   pick_cfg=torch.empty((T, kmax, d), dtype=torch.uint8, device=dev))
+                   pick_cfg=torch.empty((T, kmax, d), dtype=_knob_dtypes(_sfx)[1], device=dev))
     if workspace is None:
-        nbytes = _check(load().cham_snap_workspace_bytes(C.c_int64(ld), C.c_int32(d), _hp(to), C.c_int32(T),
-                                                         _hp(k), C.c_int32(n_k)))
+        nbytes = _check(getattr(load(), "cham_snap_workspace_bytes" + _sfx)(
+            C.c_int64(ld), C.c_int32(d), _hp(to), C.c_int32(T), _hp(k), C.c_int32(n_k)))
         workspace = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=dev)
-    _check(load().cham_snap_centroids(_dp(X), C.c_int64(ld), C.c_int32(d), _hp(to), C.c_int32(T), _hp(k),
+    _check(getattr(load(), "cham_snap_centroids" + _sfx)(_dp(X), C.c_int64(ld), C.c_int32(d), _hp(to), C.c_int32(T), _hp(k),
                                       C.c_int32(n_k), _dp(chosen_idx), _dp(centroids), _dp(out["labels_sel"]),
                                       _dp(out["pick_row"]), _dp(out["pick_cfg"]), _dp(workspace),
                                       C.c_int64(workspace.numel()), C.c_int32(flags), _stream()))
@@ -270,25 +330,30 @@ def cham_snap_centroids(X, ld: int, d: int, task_off, ks, chosen_idx, centroids,
     return out
 
 
+def cham_snap_centroids_u16(X, ld: int, d: int, task_off, ks, chosen_idx, centroids, **kw):
+    return cham_snap_centroids(X, ld, d, task_off, ks, chosen_idx, centroids, _sfx="_u16", **kw)
+
+
 def cham_synthesize(X, ld: int, d: int, task_off, cards, valid, ks, chosen_idx, labels_sel, pick_row, pick_cfg,
-                    visited, task_salt=None, out: Optional[dict] = None, workspace=None):
+                    visited, task_salt=None, out: Optional[dict] = None, workspace=None, _sfx: str = ""):
     """visited: device int64/uint64 tensor, sorted ascending as unsigned 64-bit words."""
     torch = _torch()
+    assert X.dtype == _knob_dtypes(_sfx)[1] and pick_cfg.dtype == X.dtype
     to, k = _host_lists(task_off, ks)
     T, n_k, kmax = len(to) - 1, len(k), int(k[-1])
     cards = np.ascontiguousarray(cards, dtype=np.uint16).reshape(T, d)
     salts = None if task_salt is None else np.ascontiguousarray(task_salt, dtype=np.uint64)
     dev = X.device
     if out is None:
-        out = dict(out_cfg=torch.empty((T, kmax, d), dtype=torch.uint8, device=dev),
+        out = dict(out_cfg=torch.empty((T, kmax, d), dtype=_knob_dtypes(_sfx)[1], device=dev),
                    out_flag=torch.empty((T, kmax), dtype=torch.uint8, device=dev),
                    out_count=torch.empty(T, dtype=torch.int32, device=dev))
     if workspace is None:
-        nbytes = _check(load().cham_synth_workspace_bytes(C.c_int64(ld), C.c_int32(d), _hp(to), C.c_int32(T),
-                                                          _hp(k), C.c_int32(n_k)))
+        nbytes = _check(getattr(load(), "cham_synth_workspace_bytes" + _sfx)(
+            C.c_int64(ld), C.c_int32(d), _hp(to), C.c_int32(T), _hp(k), C.c_int32(n_k)))
         workspace = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=dev)
     n_vis = 0 if visited is None else int(visited.numel())
-    _check(load().cham_synthesize(_dp(X), C.c_int64(ld), C.c_int32(d), _hp(to), C.c_int32(T), _hp(cards),
+    _check(getattr(load(), "cham_synthesize" + _sfx)(_dp(X), C.c_int64(ld), C.c_int32(d), _hp(to), C.c_int32(T), _hp(cards),
                                   _dp(valid), _hp(k), C.c_int32(n_k), _dp(chosen_idx), _dp(labels_sel),
                                   _dp(pick_row), _dp(pick_cfg), _dp(visited) if n_vis else None,
                                   C.c_int64(n_vis), _hp(salts), _dp(out["out_cfg"]), _dp(out["out_flag"]),
@@ -297,24 +362,32 @@ def cham_synthesize(X, ld: int, d: int, task_off, cards, valid, ks, chosen_idx, 
     return out
 
 
+def cham_synthesize_u16(X, ld: int, d: int, task_off, cards, valid, ks, chosen_idx, labels_sel, pick_row,
+                        pick_cfg, visited, **kw):
+    return cham_synthesize(X, ld, d, task_off, cards, valid, ks, chosen_idx, labels_sel, pick_row, pick_cfg,
+                           visited, _sfx="_u16", **kw)
+
+
 def cham_synthesize_table(X, ld: int, d: int, task_off, cards, valid, ks, chosen_idx, labels_sel, pick_row,
-                          pick_cfg, table, task_salt=None, out: Optional[dict] = None, workspace=None):
+                          pick_cfg, table, task_salt=None, out: Optional[dict] = None, workspace=None,
+                          _sfx: str = ""):
     """cham_synthesize with the visited set held in a device table (int64/uint64 tensor of 2^m slots)."""
     torch = _torch()
+    assert X.dtype == _knob_dtypes(_sfx)[1] and pick_cfg.dtype == X.dtype
     to, k = _host_lists(task_off, ks)
     T, n_k, kmax = len(to) - 1, len(k), int(k[-1])
     cards = np.ascontiguousarray(cards, dtype=np.uint16).reshape(T, d)
     salts = None if task_salt is None else np.ascontiguousarray(task_salt, dtype=np.uint64)
     dev = X.device
     if out is None:
-        out = dict(out_cfg=torch.empty((T, kmax, d), dtype=torch.uint8, device=dev),
+        out = dict(out_cfg=torch.empty((T, kmax, d), dtype=_knob_dtypes(_sfx)[1], device=dev),
                    out_flag=torch.empty((T, kmax), dtype=torch.uint8, device=dev),
                    out_count=torch.empty(T, dtype=torch.int32, device=dev))
     if workspace is None:
-        nbytes = _check(load().cham_synth_workspace_bytes(C.c_int64(ld), C.c_int32(d), _hp(to), C.c_int32(T),
-                                                          _hp(k), C.c_int32(n_k)))
+        nbytes = _check(getattr(load(), "cham_synth_workspace_bytes" + _sfx)(
+            C.c_int64(ld), C.c_int32(d), _hp(to), C.c_int32(T), _hp(k), C.c_int32(n_k)))
         workspace = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=dev)
-    _check(load().cham_synthesize_table(_dp(X), C.c_int64(ld), C.c_int32(d), _hp(to), C.c_int32(T), _hp(cards),
+    _check(getattr(load(), "cham_synthesize_table" + _sfx)(_dp(X), C.c_int64(ld), C.c_int32(d), _hp(to), C.c_int32(T), _hp(cards),
                                         _dp(valid), _hp(k), C.c_int32(n_k), _dp(chosen_idx), _dp(labels_sel),
                                         _dp(pick_row), _dp(pick_cfg), _dp(table), C.c_int64(table.numel()),
                                         _hp(salts), _dp(out["out_cfg"]), _dp(out["out_flag"]),
@@ -322,6 +395,12 @@ def cham_synthesize_table(X, ld: int, d: int, task_off, cards, valid, ks, chosen
                                         _stream()))
     out["workspace"] = workspace
     return out
+
+
+def cham_synthesize_table_u16(X, ld: int, d: int, task_off, cards, valid, ks, chosen_idx, labels_sel, pick_row,
+                              pick_cfg, table, **kw):
+    return cham_synthesize_table(X, ld, d, task_off, cards, valid, ks, chosen_idx, labels_sel, pick_row, pick_cfg,
+                                 table, _sfx="_u16", **kw)
 
 
 def cham_visited_table_clear(table):
@@ -334,10 +413,15 @@ def cham_visited_table_insert_hashes(table, hashes, overflow=None):
                                                    C.c_int64(hashes.numel()), _dp(overflow), _stream()))
 
 
+def cham_visited_table_insert_configs_u16(table, cfgs, d: int, **kw):
+    return cham_visited_table_insert_configs(table, cfgs, d, _sfx="_u16", **kw)
+
+
 def cham_visited_table_insert_configs(table, cfgs, d: int, flags=None, salts=None, rows_per_salt: int = 1,
-                                      overflow=None):
+                                      overflow=None, _sfx: str = ""):
+    assert cfgs.dtype == _knob_dtypes(_sfx)[1]
     n = cfgs.numel() // d
-    _check(load().cham_visited_table_insert_configs(_dp(table), C.c_int64(table.numel()), _dp(cfgs), C.c_int64(n),
+    _check(getattr(load(), "cham_visited_table_insert_configs" + _sfx)(_dp(table), C.c_int64(table.numel()), _dp(cfgs), C.c_int64(n),
                                                     C.c_int32(d), _dp(flags), _dp(salts), C.c_int64(rows_per_salt),
                                                     _dp(overflow), _stream()))
 
@@ -363,6 +447,7 @@ class DeviceWorkload:
         self.wl = wl
         self.device = device
         self.X, self.ld = to_soa(wl.rows, device)
+        self.sfx = "_u16" if wl.rows.dtype == np.uint16 else ""      # which family of entry points
         self.d = wl.d
         v = np.zeros(self.ld, dtype=np.uint8)
         v[:wl.n_total] = wl.valid
@@ -375,9 +460,10 @@ class DeviceWorkload:
         from . import workloads
         wl = self.wl
         if len(wl.visited_cfg):
-            rows = torch.from_numpy(np.ascontiguousarray(wl.visited_cfg)).to(self.device)
+            host = np.ascontiguousarray(wl.visited_cfg)
+            rows = torch.from_numpy(host.view(np.int16) if self.sfx else host).to(self.device)
             salts = torch.from_numpy(wl.salts[wl.visited_task].astype(np.int64)).to(self.device)
-            h = cham_hash_rows(rows, salts).cpu().numpy().view(np.uint64)
+            h = cham_hash_rows(rows, salts, _sfx=self.sfx).cpu().numpy().view(np.uint64)
         else:
             h = np.zeros(0, dtype=np.uint64)
         arr = workloads.finalize_visited(h, wl.visited_raw, wl.n_visited)
@@ -395,11 +481,11 @@ class DeviceWorkload:
         b = bufs or {}
         sw = cham_kmeans_sweep(self.X, self.ld, self.d, wl.task_off, wl.ks, wl.n_iter, flags=flags,
                                want_labels=want_labels, want_trace=want_trace,
-                               out=b.get("sweep"), workspace=b.get("sweep_ws"))
+                               out=b.get("sweep"), workspace=b.get("sweep_ws"), _sfx=self.sfx)
         chosen = cham_select_k(sw["inertia"], sw["status"], thr, chosen=b.get("chosen"))
         sn = cham_snap_centroids(self.X, self.ld, self.d, wl.task_off, wl.ks, chosen, sw["centroids"],
-                                 flags=flags, out=b.get("snap"), workspace=b.get("snap_ws"))
+                                 flags=flags, out=b.get("snap"), workspace=b.get("snap_ws"), _sfx=self.sfx)
         sy = cham_synthesize(self.X, self.ld, self.d, wl.task_off, wl.cards, self.valid, wl.ks, chosen,
                              sn["labels_sel"], sn["pick_row"], sn["pick_cfg"], self.visited,
-                             task_salt=wl.salts, out=b.get("synth"), workspace=b.get("synth_ws"))
+                             task_salt=wl.salts, out=b.get("synth"), workspace=b.get("synth_ws"), _sfx=self.sfx)
         return dict(sweep=sw, chosen=chosen, snap=sn, synth=sy)

@@ -57,12 +57,13 @@ struct Plan {
     int64_t off_task = 0, off_ks = 0, off_koff = 0, off_extra = 0;   // byte offsets in the blob
 };
 
+// xbytes: bytes per knob value (1, or 2 for the *_u16 entry points).
 int32_t check_common(const void *X, int64_t ld, int32_t d, const int64_t *task_off, int32_t T,
-                     const int32_t *ks, int32_t n_k, bool need_x, Plan &pl)
+                     const int32_t *ks, int32_t n_k, bool need_x, Plan &pl, int xbytes = 1)
 {
     if ((need_x && !X) || !task_off || !ks) return CHAM_E_NULL;
-    if (d < 1 || d > 32 || T < 1 || ld < 0 || (ld % 4) != 0) return CHAM_E_BAD_DIM;
-    if (need_x && (reinterpret_cast<uintptr_t>(X) % 4) != 0) return CHAM_E_BAD_DIM;
+    if (d < 1 || d > (xbytes == 1 ? 32 : 64) || T < 1 || ld < 0 || (ld % 4) != 0) return CHAM_E_BAD_DIM;
+    if (need_x && (reinterpret_cast<uintptr_t>(X) % (4 * xbytes)) != 0) return CHAM_E_BAD_DIM;
     if (n_k < 1 || n_k > 256) return CHAM_E_BAD_K;
     int64_t ksum = 0;
     for (int i = 0; i < n_k; ++i) {
@@ -82,11 +83,12 @@ int32_t check_common(const void *X, int64_t ld, int32_t d, const int64_t *task_o
     pl.n_k = n_k;
     pl.Ksum = (int)ksum;
     pl.kmax = ks[n_k - 1];
-    pl.DP = (d + 3) / 4 * 4;
+    pl.DP = xbytes == 1 ? (d + 3) / 4 * 4 : resident_dp16(d);
     pl.n_total = task_off[T];
     pl.n_max = nmax;
-    const int maxnt = pl.DP <= 24 ? 1024 : 512;
-    int64_t nt = ((nmax + 3 + 3) / 4 + 63) / 64 * 64;
+    const int maxnt = (xbytes == 1 && pl.DP <= 24) ? 1024 : 512;
+    const int rpt = (xbytes == 2 && pl.DP > 32) ? 2 : 4;           // rows per lane and pass
+    int64_t nt = ((nmax + 2 * (rpt - 1)) / rpt + 63) / 64 * 64;
     if (nt < 64) nt = 64;
     if (nt > maxnt) nt = maxnt;
     pl.nt = (int)nt;
@@ -136,7 +138,8 @@ struct SweepWs {
     int kpm = 0, n_units = 0, total_wgs = 0;
 };
 
-SweepWs sweep_ws(const Plan &pl, int64_t ld, bool own_labels, bool stream, const int64_t *task_off)
+SweepWs sweep_ws(const Plan &pl, int64_t ld, bool own_labels, bool stream, const int64_t *task_off,
+                 bool need_xh = true)
 {
     SweepWs w;
     int64_t o = 0;
@@ -147,7 +150,7 @@ SweepWs sweep_ws(const Plan &pl, int64_t ld, bool own_labels, bool stream, const
     w.ndist = o;
     o += up((int64_t)pl.T * 4);
     w.xh = o;
-    o += up(ld * 32 * 2);
+    if (need_xh) o += up(ld * 32 * 2);
     w.labbuf = o;
     if (own_labels) o += up((int64_t)pl.n_k * ld);
     if (stream) {
@@ -189,10 +192,10 @@ const char *cham_strerror(int32_t code)
     switch (code) {
     case CHAM_OK: return "ok";
     case CHAM_E_NULL: return "a required pointer is NULL";
-    case CHAM_E_BAD_DIM: return "bad dimension (d outside [1,32], ld < rows or not a multiple of 4, misaligned X, n_iter < 0, T < 1)";
-    case CHAM_E_BAD_K: return "bad k list (empty, not strictly increasing, or outside [1,256])";
+    case CHAM_E_BAD_DIM: return "bad dimension (d outside [1,32], or [1,64] for two-byte knobs; ld < rows or not a multiple of 4; misaligned X; n_iter < 0; T < 1)";
+    case CHAM_E_BAD_K: return "bad k list (empty, not strictly increasing, outside [1,256], or too large for the knob count of two-byte knobs)";
     case CHAM_E_BAD_OFFSETS: return "bad task offsets (negative, decreasing, or a task above 2^23 rows)";
-    case CHAM_E_CARD: return "bad cardinality (0 or above 256)";
+    case CHAM_E_CARD: return "bad cardinality (0, above 256, or above 16384 for two-byte knobs)";
     case CHAM_E_WORKSPACE: return "workspace missing or too small";
     case CHAM_E_HIP: return "HIP runtime error (see cham_last_hip_error)";
     case CHAM_E_BAD_FLAG: return "unknown flag bits or init mode";
@@ -200,35 +203,55 @@ const char *cham_strerror(int32_t code)
     }
 }
 
+// Two-byte knobs always run the vector resident kernel; its LDS need bounds k * padded knob count.
+static bool u16_fits(const Plan &pl) { return resident_lds_bytes(pl.DP, pl.kmax, 8) <= 160 * 1024; }
+
+static int64_t sweep_ws_bytes(int xbytes, int64_t ld, int32_t d, const int64_t *task_off, int32_t T,
+                              const int32_t *ks, int32_t n_k, int32_t flags)
+{
+    Plan pl;
+    const int32_t rc = check_common(nullptr, ld, d, task_off, T, ks, n_k, false, pl, xbytes);
+    if (rc != CHAM_OK) return rc;
+    if (xbytes == 2) return u16_fits(pl) ? sweep_ws(pl, ld, true, false, task_off, false).total : CHAM_E_BAD_K;
+    return sweep_ws(pl, ld, true, choose_path(pl, d, flags) == SweepPath::kStream, task_off).total;
+}
+
 int64_t cham_sweep_workspace_bytes(int64_t ld, int32_t d, const int64_t *task_off, int32_t T,
                                    const int32_t *ks, int32_t n_k, int32_t n_iter, int32_t flags)
 {
     (void)n_iter;
-    Plan pl;
-    const int32_t rc = check_common(nullptr, ld, d, task_off, T, ks, n_k, false, pl);
-    if (rc != CHAM_OK) return rc;
-    return sweep_ws(pl, ld, true, choose_path(pl, d, flags) == SweepPath::kStream, task_off).total;
+    return sweep_ws_bytes(1, ld, d, task_off, T, ks, n_k, flags);
+}
+
+int64_t cham_sweep_workspace_bytes_u16(int64_t ld, int32_t d, const int64_t *task_off, int32_t T,
+                                       const int32_t *ks, int32_t n_k, int32_t n_iter, int32_t flags)
+{
+    (void)n_iter;
+    return sweep_ws_bytes(2, ld, d, task_off, T, ks, n_k, flags);
 }
 
 // The sweep, whole (chunk <= 0) or in chunks of `chunk` values of k with the knee test between them:
 // tasks whose loss curve has reached the knee are marked done and the later chunks skip them.
-static int32_t sweep_impl(const uint8_t *X, int64_t ld, int32_t d, const int64_t *task_off, int32_t T,
+static int32_t sweep_impl(const void *Xv, int xbytes, int64_t ld, int32_t d, const int64_t *task_off, int32_t T,
                           const int32_t *ks, int32_t n_k, int32_t n_iter, int32_t init_mode,
                           const double *init_centroids, double *centroids, int32_t *counts,
                           double *inertia, int32_t *status, uint8_t *labels, double *inertia_trace,
                           void *workspace, int64_t workspace_bytes, int32_t flags, void *stream,
                           int32_t chunk, double threshold, int32_t *chosen_idx)
 {
+    const uint8_t *X = static_cast<const uint8_t *>(Xv);
     Plan pl;
-    int32_t rc = check_common(X, ld, d, task_off, T, ks, n_k, true, pl);
+    int32_t rc = check_common(X, ld, d, task_off, T, ks, n_k, true, pl, xbytes);
     if (rc != CHAM_OK) return rc;
     if (!centroids || !counts || !inertia || !status) return CHAM_E_NULL;
     if (n_iter < 0) return CHAM_E_BAD_DIM;
     if (init_mode != 0 && init_mode != 1) return CHAM_E_BAD_FLAG;
     if (init_mode == 1 && !init_centroids) return CHAM_E_NULL;
     if (flags & ~(CHAM_F_FORCE_EXACT | CHAM_F_STREAMING | CHAM_F_RESIDENT | CHAM_F_NO_MFMA)) return CHAM_E_BAD_FLAG;
-    const SweepPath path = choose_path(pl, d, flags);
-    const SweepWs w = sweep_ws(pl, ld, labels == nullptr, path == SweepPath::kStream, task_off);
+    if (xbytes == 2 && (flags & CHAM_F_STREAMING)) return CHAM_E_BAD_FLAG;
+    if (xbytes == 2 && !u16_fits(pl)) return CHAM_E_BAD_K;
+    const SweepPath path = xbytes == 2 ? SweepPath::kVectorResident : choose_path(pl, d, flags);
+    const SweepWs w = sweep_ws(pl, ld, labels == nullptr, path == SweepPath::kStream, task_off, xbytes == 1);
     const bool chunked = chunk > 0;
     const int64_t done_bytes = chunked ? up((int64_t)T * 4) : 0;
     if (!workspace || workspace_bytes < w.total + done_bytes) return CHAM_E_WORKSPACE;
@@ -241,6 +264,7 @@ static int32_t sweep_impl(const uint8_t *X, int64_t ld, int32_t d, const int64_t
 
     SweepArgs a;
     a.X = X;
+    a.xbytes = xbytes;
     a.ld = ld;
     a.d = d;
     a.T = T;
@@ -364,7 +388,17 @@ int32_t cham_kmeans_sweep(const uint8_t *X, int64_t ld, int32_t d, const int64_t
                           double *inertia, int32_t *status, uint8_t *labels, double *inertia_trace,
                           void *workspace, int64_t workspace_bytes, int32_t flags, void *stream)
 {
-    return sweep_impl(X, ld, d, task_off, T, ks, n_k, n_iter, init_mode, init_centroids, centroids, counts, inertia,
+    return sweep_impl(X, 1, ld, d, task_off, T, ks, n_k, n_iter, init_mode, init_centroids, centroids, counts, inertia,
+                      status, labels, inertia_trace, workspace, workspace_bytes, flags, stream, 0, 0.0, nullptr);
+}
+
+int32_t cham_kmeans_sweep_u16(const uint16_t *X, int64_t ld, int32_t d, const int64_t *task_off, int32_t T,
+                              const int32_t *ks, int32_t n_k, int32_t n_iter, int32_t init_mode,
+                              const double *init_centroids, double *centroids, int32_t *counts,
+                              double *inertia, int32_t *status, uint8_t *labels, double *inertia_trace,
+                              void *workspace, int64_t workspace_bytes, int32_t flags, void *stream)
+{
+    return sweep_impl(X, 2, ld, d, task_off, T, ks, n_k, n_iter, init_mode, init_centroids, centroids, counts, inertia,
                       status, labels, inertia_trace, workspace, workspace_bytes, flags, stream, 0, 0.0, nullptr);
 }
 
@@ -386,7 +420,30 @@ int32_t cham_kmeans_sweep_knee(const uint8_t *X, int64_t ld, int32_t d, const in
     if (!chosen_idx) return CHAM_E_NULL;
     if (chunk < 1) return CHAM_E_BAD_K;
     if (chunk > n_k) chunk = n_k;
-    return sweep_impl(X, ld, d, task_off, T, ks, n_k, n_iter, init_mode, init_centroids, centroids, counts, inertia,
+    return sweep_impl(X, 1, ld, d, task_off, T, ks, n_k, n_iter, init_mode, init_centroids, centroids, counts, inertia,
+                      status, labels, inertia_trace, workspace, workspace_bytes, flags, stream, chunk, threshold,
+                      chosen_idx);
+}
+
+int64_t cham_sweep_knee_workspace_bytes_u16(int64_t ld, int32_t d, const int64_t *task_off, int32_t T,
+                                            const int32_t *ks, int32_t n_k, int32_t n_iter, int32_t flags)
+{
+    const int64_t base = cham_sweep_workspace_bytes_u16(ld, d, task_off, T, ks, n_k, n_iter, flags);
+    if (base < 0) return base;
+    return base + up((int64_t)T * 4);
+}
+
+int32_t cham_kmeans_sweep_knee_u16(const uint16_t *X, int64_t ld, int32_t d, const int64_t *task_off, int32_t T,
+                                   const int32_t *ks, int32_t n_k, int32_t n_iter, int32_t init_mode,
+                                   const double *init_centroids, double threshold, int32_t chunk,
+                                   double *centroids, int32_t *counts, double *inertia, int32_t *status,
+                                   int32_t *chosen_idx, uint8_t *labels, double *inertia_trace,
+                                   void *workspace, int64_t workspace_bytes, int32_t flags, void *stream)
+{
+    if (!chosen_idx) return CHAM_E_NULL;
+    if (chunk < 1) return CHAM_E_BAD_K;
+    if (chunk > n_k) chunk = n_k;
+    return sweep_impl(X, 2, ld, d, task_off, T, ks, n_k, n_iter, init_mode, init_centroids, centroids, counts, inertia,
                       status, labels, inertia_trace, workspace, workspace_bytes, flags, stream, chunk, threshold,
                       chosen_idx);
 }
@@ -452,28 +509,43 @@ static int64_t wide_synth_bytes(const Plan &pl, int d)
            up((int64_t)pl.T * pl.kmax * d * 256 * 4);
 }
 
+static int64_t snap_ws_bytes(int xbytes, int64_t ld, int32_t d, const int64_t *task_off, int32_t T,
+                             const int32_t *ks, int32_t n_k)
+{
+    Plan pl;
+    const int32_t rc = check_common(nullptr, ld, d, task_off, T, ks, n_k, false, pl, xbytes);
+    if (rc != CHAM_OK) return rc;
+    return up((int64_t)pl.blob.size() * 8) + up(ld * 8) + (xbytes == 1 ? wide_snap_bytes(pl) : 0);
+}
+
 int64_t cham_snap_workspace_bytes(int64_t ld, int32_t d, const int64_t *task_off, int32_t T,
                                   const int32_t *ks, int32_t n_k)
 {
-    Plan pl;
-    const int32_t rc = check_common(nullptr, ld, d, task_off, T, ks, n_k, false, pl);
-    if (rc != CHAM_OK) return rc;
-    return up((int64_t)pl.blob.size() * 8) + up(ld * 8) + wide_snap_bytes(pl);
+    return snap_ws_bytes(1, ld, d, task_off, T, ks, n_k);
 }
 
-int32_t cham_snap_centroids(const uint8_t *X, int64_t ld, int32_t d, const int64_t *task_off, int32_t T,
-                            const int32_t *ks, int32_t n_k, const int32_t *chosen_idx,
-                            const double *centroids, uint8_t *labels_sel, int32_t *pick_row,
-                            uint8_t *pick_cfg, void *workspace, int64_t workspace_bytes, int32_t flags,
-                            void *stream)
+int64_t cham_snap_workspace_bytes_u16(int64_t ld, int32_t d, const int64_t *task_off, int32_t T,
+                                      const int32_t *ks, int32_t n_k)
 {
+    return snap_ws_bytes(2, ld, d, task_off, T, ks, n_k);
+}
+
+static int32_t snap_impl(const void *Xv, int xbytes, int64_t ld, int32_t d, const int64_t *task_off, int32_t T,
+                         const int32_t *ks, int32_t n_k, const int32_t *chosen_idx,
+                         const double *centroids, uint8_t *labels_sel, int32_t *pick_row,
+                         void *pick_cfg, void *workspace, int64_t workspace_bytes, int32_t flags,
+                         void *stream)
+{
+    const uint8_t *X = static_cast<const uint8_t *>(Xv);
     Plan pl;
-    int32_t rc = check_common(X, ld, d, task_off, T, ks, n_k, true, pl);
+    int32_t rc = check_common(X, ld, d, task_off, T, ks, n_k, true, pl, xbytes);
     if (rc != CHAM_OK) return rc;
     if (!chosen_idx || !centroids || !labels_sel || !pick_row || !pick_cfg) return CHAM_E_NULL;
     if (flags & ~(CHAM_F_FORCE_EXACT | CHAM_F_STREAMING | CHAM_F_RESIDENT | CHAM_F_NO_MFMA)) return CHAM_E_BAD_FLAG;
+    if (xbytes == 2 && resident_lds_bytes(pl.DP, pl.kmax) > 160 * 1024) return CHAM_E_BAD_K;
+    const bool wide = xbytes == 1 && wide_tasks(pl);
     const int64_t blob_bytes = up((int64_t)pl.blob.size() * 8);
-    if (!workspace || workspace_bytes < blob_bytes + up(ld * 8) + wide_snap_bytes(pl)) return CHAM_E_WORKSPACE;
+    if (!workspace || workspace_bytes < blob_bytes + up(ld * 8) + (wide ? wide_snap_bytes(pl) : 0)) return CHAM_E_WORKSPACE;
     if (reinterpret_cast<uintptr_t>(workspace) % kAlign) return CHAM_E_WORKSPACE;
     hipStream_t s = reinterpret_cast<hipStream_t>(stream);
     unsigned char *ws = static_cast<unsigned char *>(workspace);
@@ -481,6 +553,7 @@ int32_t cham_snap_centroids(const uint8_t *X, int64_t ld, int32_t d, const int64
     if (e != hipSuccess) return hip_fail(e);
     SnapArgs a;
     a.X = X;
+    a.xbytes = xbytes;
     a.ld = ld;
     a.d = d;
     a.T = T;
@@ -495,12 +568,12 @@ int32_t cham_snap_centroids(const uint8_t *X, int64_t ld, int32_t d, const int64
     a.centroids = centroids;
     a.labels_sel = labels_sel;
     a.pick_row = pick_row;
-    a.pick_cfg = pick_cfg;
+    a.pick_cfg = static_cast<uint8_t *>(pick_cfg);
     a.dist_ws = reinterpret_cast<double *>(ws + blob_bytes);
     a.wg_off = nullptr;
     a.wide_best = nullptr;
     a.wide_row = nullptr;
-    if (wide_tasks(pl)) {
+    if (wide) {
         unsigned char *p = ws + blob_bytes + up(ld * 8);
         std::vector<uint64_t> wo;
         const int total = wide_offsets(task_off, T, wo);
@@ -519,42 +592,79 @@ int32_t cham_snap_centroids(const uint8_t *X, int64_t ld, int32_t d, const int64
     return CHAM_OK;
 }
 
+int32_t cham_snap_centroids(const uint8_t *X, int64_t ld, int32_t d, const int64_t *task_off, int32_t T,
+                            const int32_t *ks, int32_t n_k, const int32_t *chosen_idx,
+                            const double *centroids, uint8_t *labels_sel, int32_t *pick_row,
+                            uint8_t *pick_cfg, void *workspace, int64_t workspace_bytes, int32_t flags,
+                            void *stream)
+{
+    return snap_impl(X, 1, ld, d, task_off, T, ks, n_k, chosen_idx, centroids, labels_sel, pick_row, pick_cfg,
+                     workspace, workspace_bytes, flags, stream);
+}
+
+int32_t cham_snap_centroids_u16(const uint16_t *X, int64_t ld, int32_t d, const int64_t *task_off, int32_t T,
+                                const int32_t *ks, int32_t n_k, const int32_t *chosen_idx,
+                                const double *centroids, uint8_t *labels_sel, int32_t *pick_row,
+                                uint16_t *pick_cfg, void *workspace, int64_t workspace_bytes, int32_t flags,
+                                void *stream)
+{
+    return snap_impl(X, 2, ld, d, task_off, T, ks, n_k, chosen_idx, centroids, labels_sel, pick_row, pick_cfg,
+                     workspace, workspace_bytes, flags, stream);
+}
+
 static int64_t synth_blob_extra_words(int32_t T, int32_t d)
 {
     return (int64_t)T + ((int64_t)T * d + 3) / 4;      // salts (u64) + cards (u16)
 }
 
+static int64_t synth_ws_bytes(int xbytes, int64_t ld, int32_t d, const int64_t *task_off, int32_t T,
+                              const int32_t *ks, int32_t n_k)
+{
+    Plan pl;
+    const int32_t rc = check_common(nullptr, ld, d, task_off, T, ks, n_k, false, pl, xbytes);
+    if (rc != CHAM_OK) return rc;
+    return up(((int64_t)pl.blob.size() + synth_blob_extra_words(T, d)) * 8) + (xbytes == 1 ? wide_synth_bytes(pl, d) : 0);
+}
+
 int64_t cham_synth_workspace_bytes(int64_t ld, int32_t d, const int64_t *task_off, int32_t T,
                                    const int32_t *ks, int32_t n_k)
 {
-    Plan pl;
-    const int32_t rc = check_common(nullptr, ld, d, task_off, T, ks, n_k, false, pl);
-    if (rc != CHAM_OK) return rc;
-    return up(((int64_t)pl.blob.size() + synth_blob_extra_words(T, d)) * 8) + wide_synth_bytes(pl, d);
+    return synth_ws_bytes(1, ld, d, task_off, T, ks, n_k);
 }
 
+int64_t cham_synth_workspace_bytes_u16(int64_t ld, int32_t d, const int64_t *task_off, int32_t T,
+                                       const int32_t *ks, int32_t n_k)
+{
+    return synth_ws_bytes(2, ld, d, task_off, T, ks, n_k);
+}
+
+// Largest cardinality of a two-byte knob: the value histogram of one knob has to fit in LDS.
+constexpr int kMaxCard16 = 16384;
+
 // n_visited >= 0: sorted array of that many hashes; n_visited < 0: table of -n_visited slots.
-static int32_t synth_impl(const uint8_t *X, int64_t ld, int32_t d, const int64_t *task_off, int32_t T,
+static int32_t synth_impl(const void *Xv, int xbytes, int64_t ld, int32_t d, const int64_t *task_off, int32_t T,
                           const uint16_t *cards, const uint8_t *valid, const int32_t *ks, int32_t n_k,
                           const int32_t *chosen_idx, const uint8_t *labels_sel, const int32_t *pick_row,
-                          const uint8_t *pick_cfg, const uint64_t *visited, int64_t n_visited,
-                          const uint64_t *task_salt, uint8_t *out_cfg, uint8_t *out_flag,
+                          const void *pick_cfg, const uint64_t *visited, int64_t n_visited,
+                          const uint64_t *task_salt, void *out_cfg, uint8_t *out_flag,
                           int32_t *out_count, void *workspace, int64_t workspace_bytes, void *stream)
 {
+    const uint8_t *X = static_cast<const uint8_t *>(Xv);
     Plan pl;
-    int32_t rc = check_common(X, ld, d, task_off, T, ks, n_k, true, pl);
+    int32_t rc = check_common(X, ld, d, task_off, T, ks, n_k, true, pl, xbytes);
     if (rc != CHAM_OK) return rc;
     if (!cards || !chosen_idx || !labels_sel || !pick_row || !pick_cfg || !out_cfg || !out_flag || !out_count)
         return CHAM_E_NULL;
     if (n_visited != 0 && !visited) return CHAM_E_NULL;
     int cmax = 1;
     for (int64_t i = 0; i < (int64_t)T * d; ++i) {
-        if (cards[i] < 1 || cards[i] > 256) return CHAM_E_CARD;
+        if (cards[i] < 1 || cards[i] > (xbytes == 1 ? 256 : kMaxCard16)) return CHAM_E_CARD;
         if (cards[i] > cmax) cmax = cards[i];
     }
     const int64_t base_words = (int64_t)pl.blob.size();
     const int64_t need = up((base_words + synth_blob_extra_words(T, d)) * 8);
-    if (!workspace || workspace_bytes < need + wide_synth_bytes(pl, d)) return CHAM_E_WORKSPACE;
+    const bool wide = xbytes == 1 && wide_tasks(pl);
+    if (!workspace || workspace_bytes < need + (wide ? wide_synth_bytes(pl, d) : 0)) return CHAM_E_WORKSPACE;
     if (reinterpret_cast<uintptr_t>(workspace) % kAlign) return CHAM_E_WORKSPACE;
     // extend the blob: salts then cards
     pl.blob.resize((size_t)(base_words + synth_blob_extra_words(T, d)), 0);
@@ -569,15 +679,21 @@ static int32_t synth_impl(const uint8_t *X, int64_t ld, int32_t d, const int64_t
 
     SynthArgs a;
     a.X = X;
+    a.xbytes = xbytes;
     a.ld = ld;
     a.d = d;
     a.T = T;
     a.n_k = n_k;
     a.kmax = pl.kmax;
-    // LDS histogram: room for every cluster if that fits in 96 KiB, never less than one cluster
+    // LDS histogram: room for every cluster if that fits in 96 KiB and beside the kernel's other
+    // arrays; byte knobs: never less than one cluster (all knobs, which always fits); two-byte
+    // knobs: never less than one knob of one cluster
     int64_t words = (int64_t)pl.kmax * d * cmax;
     if (words > 24576) words = 24576;
-    if (words < (int64_t)d * cmax) words = (int64_t)d * cmax;
+    const int64_t avail = (160 * 1024 - (int64_t)synth_lds_bytes(d, pl.kmax, 0, xbytes)) / 4;
+    if (words > avail) words = avail;
+    if (xbytes == 1 && words < (int64_t)d * cmax) words = (int64_t)d * cmax;
+    if (words < cmax) return CHAM_E_CARD;
     a.hist_words = (int)words;
     a.task_off = reinterpret_cast<const int64_t *>(ws + pl.off_task);
     a.ks = reinterpret_cast<const int *>(ws + pl.off_ks);
@@ -587,17 +703,17 @@ static int32_t synth_impl(const uint8_t *X, int64_t ld, int32_t d, const int64_t
     a.chosen = chosen_idx;
     a.labels_sel = labels_sel;
     a.pick_row = pick_row;
-    a.pick_cfg = pick_cfg;
+    a.pick_cfg = static_cast<const uint8_t *>(pick_cfg);
     a.visited = visited;
     a.n_visited = n_visited;
-    a.out_cfg = out_cfg;
+    a.out_cfg = static_cast<uint8_t *>(out_cfg);
     a.out_flag = out_flag;
     a.out_count = out_count;
     a.wg_off = nullptr;
     a.wide_cmax = cmax;
     a.wide_slot = a.wide_list = a.wide_nf = nullptr;
     a.wide_hist = nullptr;
-    if (wide_tasks(pl)) {
+    if (wide) {
         unsigned char *p = ws + need;
         std::vector<uint64_t> wo;
         const int total = wide_offsets(task_off, T, wo);
@@ -630,7 +746,7 @@ int32_t cham_synthesize(const uint8_t *X, int64_t ld, int32_t d, const int64_t *
                         int32_t *out_count, void *workspace, int64_t workspace_bytes, void *stream)
 {
     if (n_visited < 0) return CHAM_E_NULL;
-    return synth_impl(X, ld, d, task_off, T, cards, valid, ks, n_k, chosen_idx, labels_sel, pick_row, pick_cfg,
+    return synth_impl(X, 1, ld, d, task_off, T, cards, valid, ks, n_k, chosen_idx, labels_sel, pick_row, pick_cfg,
                       visited, n_visited, task_salt, out_cfg, out_flag, out_count, workspace, workspace_bytes, stream);
 }
 
@@ -647,7 +763,31 @@ int32_t cham_synthesize_table(const uint8_t *X, int64_t ld, int32_t d, const int
                               int32_t *out_count, void *workspace, int64_t workspace_bytes, void *stream)
 {
     if (!table_ok(table, slots)) return table ? CHAM_E_BAD_DIM : CHAM_E_NULL;
-    return synth_impl(X, ld, d, task_off, T, cards, valid, ks, n_k, chosen_idx, labels_sel, pick_row, pick_cfg,
+    return synth_impl(X, 1, ld, d, task_off, T, cards, valid, ks, n_k, chosen_idx, labels_sel, pick_row, pick_cfg,
+                      table, -slots, task_salt, out_cfg, out_flag, out_count, workspace, workspace_bytes, stream);
+}
+
+int32_t cham_synthesize_u16(const uint16_t *X, int64_t ld, int32_t d, const int64_t *task_off, int32_t T,
+                            const uint16_t *cards, const uint8_t *valid, const int32_t *ks, int32_t n_k,
+                            const int32_t *chosen_idx, const uint8_t *labels_sel, const int32_t *pick_row,
+                            const uint16_t *pick_cfg, const uint64_t *visited, int64_t n_visited,
+                            const uint64_t *task_salt, uint16_t *out_cfg, uint8_t *out_flag,
+                            int32_t *out_count, void *workspace, int64_t workspace_bytes, void *stream)
+{
+    if (n_visited < 0) return CHAM_E_NULL;
+    return synth_impl(X, 2, ld, d, task_off, T, cards, valid, ks, n_k, chosen_idx, labels_sel, pick_row, pick_cfg,
+                      visited, n_visited, task_salt, out_cfg, out_flag, out_count, workspace, workspace_bytes, stream);
+}
+
+int32_t cham_synthesize_table_u16(const uint16_t *X, int64_t ld, int32_t d, const int64_t *task_off, int32_t T,
+                                  const uint16_t *cards, const uint8_t *valid, const int32_t *ks, int32_t n_k,
+                                  const int32_t *chosen_idx, const uint8_t *labels_sel, const int32_t *pick_row,
+                                  const uint16_t *pick_cfg, const uint64_t *table, int64_t slots,
+                                  const uint64_t *task_salt, uint16_t *out_cfg, uint8_t *out_flag,
+                                  int32_t *out_count, void *workspace, int64_t workspace_bytes, void *stream)
+{
+    if (!table_ok(table, slots)) return table ? CHAM_E_BAD_DIM : CHAM_E_NULL;
+    return synth_impl(X, 2, ld, d, task_off, T, cards, valid, ks, n_k, chosen_idx, labels_sel, pick_row, pick_cfg,
                       table, -slots, task_salt, out_cfg, out_flag, out_count, workspace, workspace_bytes, stream);
 }
 
@@ -675,7 +815,19 @@ int32_t cham_visited_table_insert_configs(uint64_t *table, int64_t slots, const 
     if (!table_ok(table, slots)) return table ? CHAM_E_BAD_DIM : CHAM_E_NULL;
     if (n < 0 || d < 1 || d > 32 || rows_per_salt < 1) return CHAM_E_BAD_DIM;
     if (n > 0 && !cfgs) return CHAM_E_NULL;
-    hipError_t e = launch_table_insert_configs(table, slots, cfgs, n, d, flags, salts, rows_per_salt, overflow,
+    hipError_t e = launch_table_insert_configs(table, slots, cfgs, 1, n, d, flags, salts, rows_per_salt, overflow,
+                                               reinterpret_cast<hipStream_t>(stream));
+    return e == hipSuccess ? CHAM_OK : hip_fail(e);
+}
+
+int32_t cham_visited_table_insert_configs_u16(uint64_t *table, int64_t slots, const uint16_t *cfgs, int64_t n,
+                                              int32_t d, const uint8_t *flags, const uint64_t *salts,
+                                              int64_t rows_per_salt, int32_t *overflow, void *stream)
+{
+    if (!table_ok(table, slots)) return table ? CHAM_E_BAD_DIM : CHAM_E_NULL;
+    if (n < 0 || d < 1 || d > 64 || rows_per_salt < 1) return CHAM_E_BAD_DIM;
+    if (n > 0 && !cfgs) return CHAM_E_NULL;
+    hipError_t e = launch_table_insert_configs(table, slots, cfgs, 2, n, d, flags, salts, rows_per_salt, overflow,
                                                reinterpret_cast<hipStream_t>(stream));
     return e == hipSuccess ? CHAM_OK : hip_fail(e);
 }
@@ -710,7 +862,26 @@ int32_t cham_hash_rows(const uint8_t *rows, int64_t n, int32_t d, const uint64_t
     if (n < 0 || d < 0) return CHAM_E_BAD_DIM;
     if (n == 0) return CHAM_OK;
     if (!rows || !out) return CHAM_E_NULL;
-    hipError_t e = launch_hash_rows(rows, n, d, salts, salt_all, out, reinterpret_cast<hipStream_t>(stream));
+    hipError_t e = launch_hash_rows(rows, 1, n, d, salts, salt_all, out, reinterpret_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return hip_fail(e);
+    return CHAM_OK;
+}
+
+uint64_t cham_hash_config_u16(const uint16_t *cfg, int32_t d, uint64_t salt)
+{
+    uint64_t h = 0xCBF29CE484222325ULL ^ (salt * 0x9E3779B97F4A7C15ULL);
+    if (!cfg) return h;
+    for (int32_t j = 0; j < d; ++j) h = (h ^ (uint64_t)cfg[j]) * 0x100000001B3ULL;
+    return h;
+}
+
+int32_t cham_hash_rows_u16(const uint16_t *rows, int64_t n, int32_t d, const uint64_t *salts,
+                           uint64_t salt_all, uint64_t *out, void *stream)
+{
+    if (n < 0 || d < 0) return CHAM_E_BAD_DIM;
+    if (n == 0) return CHAM_OK;
+    if (!rows || !out) return CHAM_E_NULL;
+    hipError_t e = launch_hash_rows(rows, 2, n, d, salts, salt_all, out, reinterpret_cast<hipStream_t>(stream));
     if (e != hipSuccess) return hip_fail(e);
     return CHAM_OK;
 }

@@ -15,7 +15,7 @@
 namespace cham {
 
 constexpr int kWave = 64;
-constexpr int kRowsPerThread = 4;          // one 32-bit load holds knob j of 4 consecutive rows
+constexpr int kRowsPerThread = 4;          // byte knobs: one 32-bit load holds knob j of 4 consecutive rows
 
 // LDS-resident description of the k centroids of one clustering.
 struct CentroidView {
@@ -65,30 +65,51 @@ __device__ __forceinline__ float screen_bound(float x2, float m2)
     return kE * (x2 + 2.0f * m2);
 }
 
-// Load knob values of 4 consecutive rows (rows g..g+3, g % 4 == 0) and centre them.
-// Padded knobs (j >= d) and rows of a group that is out of range read as zero.
+// Load knob values of R consecutive rows (rows g..g+R-1, g % R == 0) and centre them.  XT is the
+// storage type of a knob value (one or two bytes); one load of R * sizeof(XT) bytes holds knob j
+// of the R rows.  Padded knobs (j >= d) and rows of a group that is out of range read as zero.
+template <typename XT, int DP, int R>
+__device__ __forceinline__ void load_rows(const XT *__restrict__ X, int64_t ld, int d, int64_t g,
+                                          bool in_range, const float *ojf, float (&xf)[R][DP],
+                                          float (&x2)[R])
+{
+    constexpr int kBits = 8 * (int)sizeof(XT);
+    constexpr int kWords = R * (int)sizeof(XT) / 4;      // 32-bit words per load: 1 or 2
+    static_assert(kWords == 1 || kWords == 2, "a load is 4 or 8 bytes");
+#pragma unroll
+    for (int p = 0; p < R; ++p) x2[p] = 0.0f;
+#pragma unroll
+    for (int j = 0; j < DP; ++j) {
+        uint32_t w[2] = {0u, 0u};
+        float o = 0.0f;
+        if (j < d) {
+            o = ojf[j];
+            if (in_range) {
+                if constexpr (kWords == 1) {
+                    w[0] = *reinterpret_cast<const uint32_t *>(X + (int64_t)j * ld + g);
+                } else {
+                    const uint2 v = *reinterpret_cast<const uint2 *>(X + (int64_t)j * ld + g);
+                    w[0] = v.x;
+                    w[1] = v.y;
+                }
+            }
+        }
+#pragma unroll
+        for (int p = 0; p < R; ++p) {
+            constexpr int kPerWord = 32 / kBits;
+            const uint32_t raw = (w[p / kPerWord] >> (kBits * (p % kPerWord))) & ((1u << kBits) - 1u);
+            float v = (float)raw - o;
+            xf[p][j] = v;
+            x2[p] = __builtin_fmaf(v, v, x2[p]);
+        }
+    }
+}
 template <int DP>
 __device__ __forceinline__ void load_rows(const uint8_t *__restrict__ X, int64_t ld, int d, int64_t g,
                                           bool in_range, const float *ojf, float (&xf)[4][DP],
                                           float (&x2)[4])
 {
-#pragma unroll
-    for (int p = 0; p < 4; ++p) x2[p] = 0.0f;
-#pragma unroll
-    for (int j = 0; j < DP; ++j) {
-        uint32_t w = 0;
-        float o = 0.0f;
-        if (j < d) {
-            o = ojf[j];
-            if (in_range) w = *reinterpret_cast<const uint32_t *>(X + (int64_t)j * ld + g);
-        }
-#pragma unroll
-        for (int p = 0; p < 4; ++p) {
-            float v = (float)((w >> (8 * p)) & 0xFFu) - o;
-            xf[p][j] = v;
-            x2[p] = __builtin_fmaf(v, v, x2[p]);
-        }
-    }
+    load_rows<uint8_t, DP, 4>(X, ld, d, g, in_range, ojf, xf, x2);
 }
 
 // Exact squared distance of this lane's row p to centroid c (the oracle's operation order).
@@ -105,35 +126,35 @@ __device__ __forceinline__ double exact_dist(const float (&x)[DP], const Centroi
     return s;
 }
 
-// Nearest centroid of 4 rows per lane.  rowmask bit p = row p takes part.
+// Nearest centroid of R rows per lane.  rowmask bit p = row p takes part.
 // Returns labels; dist[p] is the exact distance to the assigned centroid when want_dist.
-template <int DP>
-__device__ __forceinline__ void assign_rows(const float (&xf)[4][DP], const float (&x2)[4],
+template <int DP, int R = 4>
+__device__ __forceinline__ void assign_rows(const float (&xf)[R][DP], const float (&x2)[R],
                                             uint32_t rowmask, const CentroidView &L, bool force_exact,
-                                            bool want_dist, int (&lab)[4], double (&dist)[4])
+                                            bool want_dist, int (&lab)[R], double (&dist)[R])
 {
     const int lane = threadIdx.x & (kWave - 1);
     const int k = L.k;
-    bool flag[4];
+    bool flag[R];
     if (!force_exact) {
-        float best[4], second[4];
+        float best[R], second[R];
 #pragma unroll
-        for (int p = 0; p < 4; ++p) {
+        for (int p = 0; p < R; ++p) {
             best[p] = __builtin_inff();
             second[p] = __builtin_inff();
             lab[p] = 0;
         }
         for (int c = 0; c < k; ++c) {
             const float4 *wrow = reinterpret_cast<const float4 *>(L.wf + (size_t)c * (DP + 4));
-            float acc[4];
+            float acc[R];
             const float b = wrow[DP / 4].x;
 #pragma unroll
-            for (int p = 0; p < 4; ++p) acc[p] = b;
+            for (int p = 0; p < R; ++p) acc[p] = b;
 #pragma unroll
             for (int q = 0; q < DP / 4; ++q) {
                 const float4 w = wrow[q];
 #pragma unroll
-                for (int p = 0; p < 4; ++p) {
+                for (int p = 0; p < R; ++p) {
                     acc[p] = __builtin_fmaf(xf[p][4 * q + 0], w.x, acc[p]);
                     acc[p] = __builtin_fmaf(xf[p][4 * q + 1], w.y, acc[p]);
                     acc[p] = __builtin_fmaf(xf[p][4 * q + 2], w.z, acc[p]);
@@ -141,20 +162,20 @@ __device__ __forceinline__ void assign_rows(const float (&xf)[4][DP], const floa
                 }
             }
 #pragma unroll
-            for (int p = 0; p < 4; ++p) {
+            for (int p = 0; p < R; ++p) {
                 second[p] = __builtin_amdgcn_fmed3f(best[p], second[p], acc[p]);
                 lab[p] = acc[p] < best[p] ? c : lab[p];
                 best[p] = fminf(best[p], acc[p]);
             }
         }
 #pragma unroll
-        for (int p = 0; p < 4; ++p) {
+        for (int p = 0; p < R; ++p) {
             const float e = screen_bound<DP>(x2[p], L.m2);
             flag[p] = ((rowmask >> p) & 1u) && !((second[p] - best[p]) > e);
         }
     } else {
 #pragma unroll
-        for (int p = 0; p < 4; ++p) {
+        for (int p = 0; p < R; ++p) {
             flag[p] = (rowmask >> p) & 1u;
             lab[p] = 0;
         }
@@ -162,7 +183,7 @@ __device__ __forceinline__ void assign_rows(const float (&xf)[4][DP], const floa
 
     // wave-cooperative exact re-evaluation of the flagged rows
 #pragma unroll
-    for (int p = 0; p < 4; ++p) {
+    for (int p = 0; p < R; ++p) {
         uint64_t m = __ballot(flag[p]);
         while (m) {
             const int l = __ffsll((unsigned long long)m) - 1;
@@ -199,12 +220,12 @@ __device__ __forceinline__ void assign_rows(const float (&xf)[4][DP], const floa
 
     if (want_dist) {
 #pragma unroll
-        for (int p = 0; p < 4; ++p)
+        for (int p = 0; p < R; ++p)
             if (((rowmask >> p) & 1u) && !flag[p]) dist[p] = exact_dist<DP>(xf[p], L, lab[p]);
     }
 }
 
-// 64-bit FNV-1a of d knob bytes with the salted offset basis.
+// 64-bit FNV-1a over d knob values (one step per value) with the salted offset basis.
 __device__ __forceinline__ uint64_t fnv_begin(uint64_t salt)
 {
     return 0xCBF29CE484222325ULL ^ (salt * 0x9E3779B97F4A7C15ULL);

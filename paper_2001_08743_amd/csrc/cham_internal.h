@@ -7,7 +7,8 @@ namespace cham {
 
 // Arguments of the sweep kernels.  Pointers are device pointers.
 struct SweepArgs {
-    const uint8_t *X;
+    const uint8_t *X;              // knob values, [d][ld] items of xbytes bytes each
+    int xbytes;                    // 1: byte knobs; 2: two-byte knobs (vector resident kernel only)
     int64_t ld;
     int d;
     int T;
@@ -35,12 +36,12 @@ struct SweepArgs {
 };
 
 // LDS bytes the resident kernel needs for padded knob count DP and largest k.
-inline size_t resident_lds_bytes(int DP, int kmax)
+inline size_t resident_lds_bytes(int DP, int kmax, int sum_bytes = 4)
 {
     size_t b = 0;
     b += sizeof(double) * (size_t)DP * kmax;          // mu64T
     b += sizeof(float) * (size_t)kmax * (DP + 4);     // wf
-    b += sizeof(int) * (size_t)kmax * DP;             // S
+    b += (size_t)sum_bytes * (size_t)kmax * DP;       // S
     b += sizeof(int) * (size_t)kmax;                  // n
     b += sizeof(float) * (size_t)DP;                  // ojf
     b += sizeof(double) * 16;                         // per-wave partials
@@ -93,7 +94,8 @@ struct StreamArgs {
 
 // Arguments of the snap kernel.
 struct SnapArgs {
-    const uint8_t *X;
+    const uint8_t *X;           // knob values, [d][ld] items of xbytes bytes each
+    int xbytes;                 // 1 or 2; pick_cfg holds items of the same size
     int64_t ld;
     int d;
     int T;
@@ -118,7 +120,8 @@ struct SnapArgs {
 
 // Arguments of the synthesis kernel.
 struct SynthArgs {
-    const uint8_t *X;
+    const uint8_t *X;           // knob values, [d][ld] items of xbytes bytes each
+    int xbytes;                 // 1 or 2; pick_cfg and out_cfg hold items of the same size
     int64_t ld;
     int d;
     int T;
@@ -150,6 +153,7 @@ struct SynthArgs {
 
 hipError_t launch_first_distinct(const SweepArgs &a, int *init_rows, int *ndist, hipStream_t s);
 hipError_t launch_resident_sweep(const SweepArgs &a, int nt, hipStream_t s);
+int resident_dp16(int d);      // padded knob count the two-byte kernels use for d knobs
 // Matrix-core resident kernel: usable when every task has at most 4096 rows and k <= 64.
 bool mfma_path_fits(int d, int kmax, int64_t n_max);
 hipError_t launch_mfma_sweep(const SweepArgs &a, int64_t n_max, int64_t n_total, hipStream_t s);
@@ -163,18 +167,18 @@ hipError_t launch_select_k(const double *inertia, const int *status, int T, int 
 hipError_t launch_snap(const SnapArgs &a, int nt, hipStream_t s);
 hipError_t launch_snap_wide(const SnapArgs &a, int total_wgs, hipStream_t s);
 hipError_t launch_synth_wide(const SynthArgs &a, int total_wgs, hipStream_t s);
-size_t synth_lds_bytes(int d, int kmax, int hist_words);
+size_t synth_lds_bytes(int d, int kmax, int hist_words, int xbytes);
 hipError_t launch_synth(const SynthArgs &a, int nt, hipStream_t s);
 hipError_t launch_table_clear(uint64_t *v, int64_t slots, hipStream_t s);
 hipError_t launch_table_insert_hashes(uint64_t *v, int64_t slots, const uint64_t *hashes, int64_t n, int *overflow,
                                       hipStream_t s);
-hipError_t launch_table_insert_configs(uint64_t *v, int64_t slots, const uint8_t *cfgs, int64_t n, int d,
+hipError_t launch_table_insert_configs(uint64_t *v, int64_t slots, const void *cfgs, int xbytes, int64_t n, int d,
                                        const uint8_t *flags, const uint64_t *salts, int64_t rows_per_salt,
                                        int *overflow, hipStream_t s);
 hipError_t launch_update_configs(uint8_t *theta, const int8_t *actions, int64_t B, int d, int n_steps,
                                  const uint16_t *cards, uint64_t salt, uint64_t *seen, int64_t slots,
                                  uint8_t *unique_rows, int64_t cap, int *n_unique, int *overflow, hipStream_t s);
-hipError_t launch_hash_rows(const uint8_t *rows, int64_t n, int d, const uint64_t *salts,
+hipError_t launch_hash_rows(const void *rows, int xbytes, int64_t n, int d, const uint64_t *salts,
                             uint64_t salt_all, uint64_t *out, hipStream_t s);
 
 }  // namespace cham

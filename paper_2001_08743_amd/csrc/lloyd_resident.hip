@@ -5,6 +5,8 @@
 // are read from global memory (L2-resident after the first pass) four rows per lane and pass.
 // Cluster sums are kept incrementally: a row touches the sums only when its label changes,
 // which is exact because the sums are integers.
+#include <type_traits>
+
 #include "cham_device.h"
 #include "cham_internal.h"
 
@@ -12,11 +14,13 @@ namespace cham {
 
 namespace {
 
-template <int DP>
+// SumT: type of the integer cluster sums.  32 bits hold the sums of byte knobs (at most 2^23 rows of
+// values below 256); two-byte knobs need 64.
+template <int DP, typename SumT>
 struct UnitLds {
     double *mu64T;
     float *wf;
-    int *S;
+    SumT *S;
     int *n;
     float *ojf;
     double *red;
@@ -27,10 +31,16 @@ struct UnitLds {
         base += sizeof(double) * (size_t)DP * kmax;
         red = reinterpret_cast<double *>(base);
         base += sizeof(double) * 16;
+        if (sizeof(SumT) == 8) {            // 8-byte items first
+            S = reinterpret_cast<SumT *>(base);
+            base += sizeof(SumT) * (size_t)kmax * DP;
+        }
         wf = reinterpret_cast<float *>(base);
         base += sizeof(float) * (size_t)kmax * (DP + 4);
-        S = reinterpret_cast<int *>(base);
-        base += sizeof(int) * (size_t)kmax * DP;
+        if (sizeof(SumT) == 4) {
+            S = reinterpret_cast<SumT *>(base);
+            base += sizeof(SumT) * (size_t)kmax * DP;
+        }
         n = reinterpret_cast<int *>(base);
         base += sizeof(int) * (size_t)kmax;
         ojf = reinterpret_cast<float *>(base);
@@ -41,8 +51,14 @@ struct UnitLds {
 
 // From the exact centroids build the fp32 screening form: w = -2*(mu - o), b = |mu - o|^2,
 // and the bound m2 >= max_c b.  Caller synchronises before and after.
-template <int DP>
-__device__ __forceinline__ void derive_screen(const UnitLds<DP> &U, int k, int kp)
+__device__ __forceinline__ void lds_add(int *p, int v) { atomicAdd(p, v); }
+__device__ __forceinline__ void lds_add(long long *p, int v)
+{
+    atomicAdd(reinterpret_cast<unsigned long long *>(p), (unsigned long long)(long long)v);
+}
+
+template <int DP, typename SumT>
+__device__ __forceinline__ void derive_screen(const UnitLds<DP, SumT> &U, int k, int kp)
 {
     for (int c = threadIdx.x; c < k; c += blockDim.x) {
         double b = 0.0;
@@ -62,11 +78,16 @@ __device__ __forceinline__ void derive_screen(const UnitLds<DP> &U, int k, int k
     }
 }
 
-template <int DP, int MAXNT>
+// XT: storage type of a knob value (uint8_t or uint16_t); R: rows per lane and pass (one load of
+// R * sizeof(XT) bytes holds knob j of R consecutive rows).
+template <typename XT, int DP, int R, int MAXNT>
 __global__ __launch_bounds__(MAXNT) void resident_sweep_kernel(const SweepArgs a)
 {
+    using SumT = typename std::conditional<sizeof(XT) == 1, int, long long>::type;
+    constexpr double kMaxValue = sizeof(XT) == 1 ? 255.0 : 65535.0;
     extern __shared__ __align__(16) unsigned char smem[];
-    UnitLds<DP> U(smem, a.kmax);
+    UnitLds<DP, SumT> U(smem, a.kmax);
+    const XT *X = reinterpret_cast<const XT *>(a.X);
 
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
@@ -85,8 +106,8 @@ __global__ __launch_bounds__(MAXNT) void resident_sweep_kernel(const SweepArgs a
     const int64_t slot = (int64_t)t * a.n_k + ki;
     const int64_t crow = (int64_t)t * a.Ksum + a.koff[ki];
     uint8_t *labrow = a.labbuf + (int64_t)ki * a.ld;
-    const int64_t g0 = r0 & ~(int64_t)3;
-    const int tile_rows = blockDim.x * kRowsPerThread;
+    const int64_t g0 = r0 & ~(int64_t)(R - 1);
+    const int tile_rows = blockDim.x * R;
     const bool force_exact = (a.flags & 1) != 0;
 
     if (skipped || (a.init_mode == 0 && a.ndist[t] < k)) {
@@ -114,7 +135,7 @@ __global__ __launch_bounds__(MAXNT) void resident_sweep_kernel(const SweepArgs a
         double v;
         if (a.init_mode == 0) {
             const int row = a.init_rows[(int64_t)t * a.kmax + c];
-            v = (double)a.X[(int64_t)j * a.ld + r0 + row];
+            v = (double)X[(int64_t)j * a.ld + r0 + row];
         } else {
             v = a.init_centroids[(crow + c) * d + j];
         }
@@ -127,7 +148,7 @@ __global__ __launch_bounds__(MAXNT) void resident_sweep_kernel(const SweepArgs a
             double s = 0.0;
             for (int c = 0; c < k; ++c) s += U.mu64T[(size_t)tid * kp + c];
             double m = rint(s / (double)k);
-            m = m < 0.0 ? 0.0 : (m > 255.0 ? 255.0 : m);
+            m = m < 0.0 ? 0.0 : (m > kMaxValue ? kMaxValue : m);
             o = (float)m;
         }
         U.ojf[tid] = o;
@@ -153,27 +174,32 @@ __global__ __launch_bounds__(MAXNT) void resident_sweep_kernel(const SweepArgs a
         double part = 0.0;
 
         for (int tile = 0; tile < ntiles; ++tile) {
-            const int64_t g = g0 + (int64_t)tile * tile_rows + (int64_t)tid * kRowsPerThread;
+            const int64_t g = g0 + (int64_t)tile * tile_rows + (int64_t)tid * R;
             const bool in_range = g < r1;
             uint32_t rowmask = 0;
 #pragma unroll
-            for (int p = 0; p < 4; ++p)
+            for (int p = 0; p < R; ++p)
                 if (g + p >= r0 && g + p < r1) rowmask |= 1u << p;
 
-            float xf[4][DP];
-            float x2[4];
-            load_rows<DP>(a.X, a.ld, d, g, in_range, U.ojf, xf, x2);
+            float xf[R][DP];
+            float x2[R];
+            load_rows<XT, DP, R>(X, a.ld, d, g, in_range, U.ojf, xf, x2);
 
-            int lab[4];
-            double dist[4] = {0.0, 0.0, 0.0, 0.0};
-            assign_rows<DP>(xf, x2, rowmask, L, force_exact, want_dist, lab, dist);
+            int lab[R];
+            double dist[R];
+#pragma unroll
+            for (int p = 0; p < R; ++p) dist[p] = 0.0;
+            assign_rows<DP, R>(xf, x2, rowmask, L, force_exact, want_dist, lab, dist);
 
             uint32_t prevpack = 0;
-            if (it > 0 && in_range) prevpack = *reinterpret_cast<const uint32_t *>(labrow + g);
+            if (it > 0 && in_range) {
+                if (R == 4) prevpack = *reinterpret_cast<const uint32_t *>(labrow + g);
+                else prevpack = *reinterpret_cast<const uint16_t *>(labrow + g);
+            }
             uint32_t newpack = 0;
             bool changed = false;
 #pragma unroll
-            for (int p = 0; p < 4; ++p) {
+            for (int p = 0; p < R; ++p) {
                 const int prev = (prevpack >> (8 * p)) & 0xFF;
                 const bool on = (rowmask >> p) & 1u;
                 const int cur = on ? lab[p] : prev;
@@ -182,8 +208,8 @@ __global__ __launch_bounds__(MAXNT) void resident_sweep_kernel(const SweepArgs a
                     changed = true;
                     for (int j = 0; j < d; ++j) {
                         const int xi = (int)(xf[p][j] + U.ojf[j]);
-                        atomicAdd(&U.S[cur * DP + j], xi);
-                        if (it > 0) atomicSub(&U.S[prev * DP + j], xi);
+                        lds_add(&U.S[cur * DP + j], xi);
+                        if (it > 0) lds_add(&U.S[prev * DP + j], -xi);
                     }
                     atomicAdd(&U.n[cur], 1);
                     if (it > 0) atomicSub(&U.n[prev], 1);
@@ -191,11 +217,12 @@ __global__ __launch_bounds__(MAXNT) void resident_sweep_kernel(const SweepArgs a
                 if (on && want_dist) part = part + dist[p];
             }
             if (changed) {
-                if (rowmask == 0xFu) {
-                    *reinterpret_cast<uint32_t *>(labrow + g) = newpack;
+                if (rowmask == (1u << R) - 1u) {
+                    if (R == 4) *reinterpret_cast<uint32_t *>(labrow + g) = newpack;
+                    else *reinterpret_cast<uint16_t *>(labrow + g) = (uint16_t)newpack;
                 } else {
 #pragma unroll
-                    for (int p = 0; p < 4; ++p)
+                    for (int p = 0; p < R; ++p)
                         if ((rowmask >> p) & 1u) labrow[g + p] = (uint8_t)lab[p];
                 }
             }
@@ -241,8 +268,10 @@ __global__ __launch_bounds__(MAXNT) void resident_sweep_kernel(const SweepArgs a
 
 // First kmax distinct rows of each task, in row order: one wave per task walks the rows 64 at a
 // time; a row is taken unless it equals a row taken before it.
+template <typename XT>
 __global__ __launch_bounds__(64) void first_distinct_kernel(const SweepArgs a, int *init_rows, int *ndist)
 {
+    const XT *X = reinterpret_cast<const XT *>(a.X);
     __shared__ uint64_t taken_hash[256];
     __shared__ int taken_row[256];
     const int t = blockIdx.x;
@@ -256,7 +285,7 @@ __global__ __launch_bounds__(64) void first_distinct_kernel(const SweepArgs a, i
         const bool live = r < r1;
         uint64_t h = fnv_begin(0);
         if (live)
-            for (int j = 0; j < d; ++j) h = fnv_step(h, a.X[(int64_t)j * a.ld + r]);
+            for (int j = 0; j < d; ++j) h = fnv_step(h, X[(int64_t)j * a.ld + r]);
         bool fresh = live;
         // against rows already taken
         for (int q = 0; q < found && fresh; ++q) {
@@ -264,7 +293,7 @@ __global__ __launch_bounds__(64) void first_distinct_kernel(const SweepArgs a, i
             bool same = true;
             const int64_t rq = r0 + taken_row[q];
             for (int j = 0; j < d && same; ++j)
-                same = a.X[(int64_t)j * a.ld + rq] == a.X[(int64_t)j * a.ld + r];
+                same = X[(int64_t)j * a.ld + rq] == X[(int64_t)j * a.ld + r];
             if (same) fresh = false;
         }
         // against earlier rows of this batch of 64
@@ -273,7 +302,7 @@ __global__ __launch_bounds__(64) void first_distinct_kernel(const SweepArgs a, i
             if (q < lane && fresh && hq == h && base + q < r1) {
                 bool same = true;
                 for (int j = 0; j < d && same; ++j)
-                    same = a.X[(int64_t)j * a.ld + base + q] == a.X[(int64_t)j * a.ld + r];
+                    same = X[(int64_t)j * a.ld + base + q] == X[(int64_t)j * a.ld + r];
                 if (same) fresh = false;
             }
         }
@@ -291,11 +320,11 @@ __global__ __launch_bounds__(64) void first_distinct_kernel(const SweepArgs a, i
     if (lane == 0) ndist[t] = found;
 }
 
-template <int DP, int MAXNT>
+template <typename XT, int DP, int R, int MAXNT>
 hipError_t launch_dp(const SweepArgs &a, int nt, hipStream_t s)
 {
-    const size_t lds = resident_lds_bytes(DP, a.kmax);
-    auto kern = resident_sweep_kernel<DP, MAXNT>;
+    const size_t lds = resident_lds_bytes(DP, a.kmax, sizeof(XT) == 1 ? 4 : 8);
+    auto kern = resident_sweep_kernel<XT, DP, R, MAXNT>;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
@@ -309,21 +338,35 @@ hipError_t launch_dp(const SweepArgs &a, int nt, hipStream_t s)
 
 hipError_t launch_first_distinct(const SweepArgs &a, int *init_rows, int *ndist, hipStream_t s)
 {
-    hipLaunchKernelGGL(first_distinct_kernel, dim3(a.T), dim3(64), 0, s, a, init_rows, ndist);
+    if (a.xbytes == 2)
+        hipLaunchKernelGGL(first_distinct_kernel<uint16_t>, dim3(a.T), dim3(64), 0, s, a, init_rows, ndist);
+    else
+        hipLaunchKernelGGL(first_distinct_kernel<uint8_t>, dim3(a.T), dim3(64), 0, s, a, init_rows, ndist);
     return hipGetLastError();
 }
+
+// Padded knob count of the two-byte instantiations.
+int resident_dp16(int d) { return d <= 32 ? (d + 7) / 8 * 8 : (d <= 48 ? 48 : 64); }
 
 hipError_t launch_resident_sweep(const SweepArgs &a, int nt, hipStream_t s)
 {
     const int d = a.d;
-    if (d <= 4) return launch_dp<4, 1024>(a, nt, s);
-    if (d <= 8) return launch_dp<8, 1024>(a, nt, s);
-    if (d <= 12) return launch_dp<12, 1024>(a, nt, s);
-    if (d <= 16) return launch_dp<16, 1024>(a, nt, s);
-    if (d <= 20) return launch_dp<20, 1024>(a, nt, s);
-    if (d <= 24) return launch_dp<24, 1024>(a, nt, s);
-    if (d <= 28) return launch_dp<28, 512>(a, nt, s);
-    return launch_dp<32, 512>(a, nt, s);
+    if (a.xbytes == 2) {
+        if (d <= 8) return launch_dp<uint16_t, 8, 4, 512>(a, nt, s);
+        if (d <= 16) return launch_dp<uint16_t, 16, 4, 512>(a, nt, s);
+        if (d <= 24) return launch_dp<uint16_t, 24, 4, 512>(a, nt, s);
+        if (d <= 32) return launch_dp<uint16_t, 32, 4, 512>(a, nt, s);
+        if (d <= 48) return launch_dp<uint16_t, 48, 2, 512>(a, nt, s);
+        return launch_dp<uint16_t, 64, 2, 512>(a, nt, s);
+    }
+    if (d <= 4) return launch_dp<uint8_t, 4, 4, 1024>(a, nt, s);
+    if (d <= 8) return launch_dp<uint8_t, 8, 4, 1024>(a, nt, s);
+    if (d <= 12) return launch_dp<uint8_t, 12, 4, 1024>(a, nt, s);
+    if (d <= 16) return launch_dp<uint8_t, 16, 4, 1024>(a, nt, s);
+    if (d <= 20) return launch_dp<uint8_t, 20, 4, 1024>(a, nt, s);
+    if (d <= 24) return launch_dp<uint8_t, 24, 4, 1024>(a, nt, s);
+    if (d <= 28) return launch_dp<uint8_t, 28, 4, 512>(a, nt, s);
+    return launch_dp<uint8_t, 32, 4, 512>(a, nt, s);
 }
 
 }  // namespace cham

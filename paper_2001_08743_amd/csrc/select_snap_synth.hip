@@ -94,9 +94,13 @@ struct SnapLds {
     }
 };
 
-template <int DP, int MAXNT>
+// XT: storage type of a knob value; R: rows per lane and pass (as in the sweep kernel).
+template <typename XT, int DP, int R, int MAXNT>
 __global__ __launch_bounds__(MAXNT) void snap_kernel(const SnapArgs a)
 {
+    constexpr double kMaxValue = sizeof(XT) == 1 ? 255.0 : 65535.0;
+    const XT *X = reinterpret_cast<const XT *>(a.X);
+    XT *pick_cfg = reinterpret_cast<XT *>(a.pick_cfg);
     extern __shared__ __align__(16) unsigned char smem[];
     SnapLds<DP> U(smem, a.kmax);
     const int tid = threadIdx.x;
@@ -104,10 +108,10 @@ __global__ __launch_bounds__(MAXNT) void snap_kernel(const SnapArgs a)
     const int d = a.d;
     const int64_t r0 = a.task_off[t], r1 = a.task_off[t + 1];
     const int ci = a.chosen[t];
-    const int tile_rows = blockDim.x * kRowsPerThread;
+    const int tile_rows = blockDim.x * R;
 
     for (int c = tid; c < a.kmax; c += blockDim.x) a.pick_row[(int64_t)t * a.kmax + c] = -1;
-    for (int e = tid; e < a.kmax * d; e += blockDim.x) a.pick_cfg[(int64_t)t * a.kmax * d + e] = 0;
+    for (int e = tid; e < a.kmax * d; e += blockDim.x) pick_cfg[(int64_t)t * a.kmax * d + e] = 0;
     if (ci < 0 || ci >= a.n_k) return;
     const int k = a.ks[ci];
     const int kp = k;
@@ -131,7 +135,7 @@ __global__ __launch_bounds__(MAXNT) void snap_kernel(const SnapArgs a)
             double s = 0.0;
             for (int c = 0; c < k; ++c) s += U.mu64T[(size_t)tid * kp + c];
             double m = rint(s / (double)k);
-            m = m < 0.0 ? 0.0 : (m > 255.0 ? 255.0 : m);
+            m = m < 0.0 ? 0.0 : (m > kMaxValue ? kMaxValue : m);
             o = (float)m;
         }
         U.ojf[tid] = o;
@@ -160,24 +164,26 @@ __global__ __launch_bounds__(MAXNT) void snap_kernel(const SnapArgs a)
     L.kp = kp;
     L.k = k;
     const bool force_exact = (a.flags & 1) != 0;
-    const int64_t g0 = r0 & ~(int64_t)3;
+    const int64_t g0 = r0 & ~(int64_t)(R - 1);
     const int ntiles = (int)((r1 - g0 + tile_rows - 1) / tile_rows);
 
     for (int tile = 0; tile < ntiles; ++tile) {
-        const int64_t g = g0 + (int64_t)tile * tile_rows + (int64_t)tid * kRowsPerThread;
+        const int64_t g = g0 + (int64_t)tile * tile_rows + (int64_t)tid * R;
         const bool in_range = g < r1;
         uint32_t rowmask = 0;
 #pragma unroll
-        for (int p = 0; p < 4; ++p)
+        for (int p = 0; p < R; ++p)
             if (g + p >= r0 && g + p < r1) rowmask |= 1u << p;
-        float xf[4][DP];
-        float x2[4];
-        load_rows<DP>(a.X, a.ld, d, g, in_range, U.ojf, xf, x2);
-        int lab[4];
-        double dist[4] = {0.0, 0.0, 0.0, 0.0};
-        assign_rows<DP>(xf, x2, rowmask, L, force_exact, true, lab, dist);
+        float xf[R][DP];
+        float x2[R];
+        load_rows<XT, DP, R>(X, a.ld, d, g, in_range, U.ojf, xf, x2);
+        int lab[R];
+        double dist[R];
 #pragma unroll
-        for (int p = 0; p < 4; ++p) {
+        for (int p = 0; p < R; ++p) dist[p] = 0.0;
+        assign_rows<DP, R>(xf, x2, rowmask, L, force_exact, true, lab, dist);
+#pragma unroll
+        for (int p = 0; p < R; ++p) {
             if (!((rowmask >> p) & 1u)) continue;
             a.labels_sel[g + p] = (uint8_t)lab[p];
             a.dist_ws[g + p] = dist[p];
@@ -199,7 +205,7 @@ __global__ __launch_bounds__(MAXNT) void snap_kernel(const SnapArgs a)
         const int c = e / d, j = e % d;
         const int row = U.brow[c];
         if (row != 0x7fffffff)
-            a.pick_cfg[((int64_t)t * a.kmax + c) * d + j] = a.X[(int64_t)j * a.ld + r0 + row];
+            pick_cfg[((int64_t)t * a.kmax + c) * d + j] = X[(int64_t)j * a.ld + r0 + row];
     }
 }
 
@@ -314,7 +320,8 @@ __global__ void table_insert_hashes_kernel(uint64_t *v, int64_t slots, const uin
 
 // Hash and insert configurations: row i of cfgs [n][d] is inserted iff flags is null or flags[i] is
 // KEPT (1) or SYNTH (2); its salt is salts[i / rows_per_salt] (salts null: i / rows_per_salt itself).
-__global__ void table_insert_configs_kernel(uint64_t *v, int64_t slots, const uint8_t *cfgs, int64_t n, int d,
+template <typename XT>
+__global__ void table_insert_configs_kernel(uint64_t *v, int64_t slots, const XT *cfgs, int64_t n, int d,
                                             const uint8_t *flags, const uint64_t *salts, int64_t rows_per_salt,
                                             int *overflow)
 {
@@ -332,8 +339,10 @@ __global__ void table_insert_configs_kernel(uint64_t *v, int64_t slots, const ui
 //  B. histograms value counts per (flagged cluster, knob) over the cluster's valid members, a
 //     chunk of clusters at a time (as many as fit the LDS histogram), and takes the mode.
 //  C. one wave walks the flagged clusters in ascending order and accepts or drops each mode.
+template <typename XT>
 __global__ __launch_bounds__(1024) void synth_kernel(const SynthArgs a)
 {
+    const XT *X = reinterpret_cast<const XT *>(a.X);
     extern __shared__ __align__(16) unsigned char smem[];
     const int tid = threadIdx.x;
     const int t = blockIdx.x;
@@ -341,7 +350,7 @@ __global__ __launch_bounds__(1024) void synth_kernel(const SynthArgs a)
     const int kmax = a.kmax;
     const int64_t r0 = a.task_off[t], r1 = a.task_off[t + 1];
     const int ci = a.chosen[t];
-    uint8_t *ocfg = a.out_cfg + (int64_t)t * kmax * d;
+    XT *ocfg = reinterpret_cast<XT *>(a.out_cfg) + (int64_t)t * kmax * d;
     uint8_t *oflag = a.out_flag + (int64_t)t * kmax;
 
     // LDS carve
@@ -350,8 +359,8 @@ __global__ __launch_bounds__(1024) void synth_kernel(const SynthArgs a)
     int *slot_of = reinterpret_cast<int *>(p8);           p8 += sizeof(int) * (size_t)kmax;      // [kmax]
     int *flagged = reinterpret_cast<int *>(p8);           p8 += sizeof(int) * (size_t)kmax;      // compact list
     int *misc = reinterpret_cast<int *>(p8);              p8 += sizeof(int) * 8;
-    uint8_t *cfg = p8;                                    p8 += (size_t)kmax * d;                // [kmax][d] kept / accepted
-    uint8_t *mode = p8;                                   p8 += (size_t)kmax * d;                // [kmax][d] candidate modes
+    XT *cfg = reinterpret_cast<XT *>(p8);                 p8 += sizeof(XT) * (size_t)kmax * d;   // [kmax][d] kept / accepted
+    XT *mode = reinterpret_cast<XT *>(p8);                p8 += sizeof(XT) * (size_t)kmax * d;   // [kmax][d] candidate modes
     uint8_t *fl = p8;                                     p8 += (size_t)kmax;                    // [kmax] flags
     uint8_t *hasv = p8;                                                                           // [kmax] cluster has a valid member
 
@@ -370,7 +379,7 @@ __global__ __launch_bounds__(1024) void synth_kernel(const SynthArgs a)
     for (int c = tid; c < k; c += blockDim.x) {
         const int row = a.pick_row[(int64_t)t * kmax + c];
         if (row < 0) continue;
-        const uint8_t *pc = a.pick_cfg + ((int64_t)t * kmax + c) * d;
+        const XT *pc = reinterpret_cast<const XT *>(a.pick_cfg) + ((int64_t)t * kmax + c) * d;
         uint64_t h = fnv_begin(salt);
         for (int j = 0; j < d; ++j) h = fnv_step(h, pc[j]);
         const bool invalid = a.valid && a.valid[r0 + row] == 0;
@@ -392,47 +401,53 @@ __global__ __launch_bounds__(1024) void synth_kernel(const SynthArgs a)
     __syncthreads();
     const int nf = misc[0];
 
-    // B. modes, a chunk of flagged clusters at a time
+    // B. modes, a window of knobs and a chunk of flagged clusters at a time (all knobs at once when
+    // the histogram of a whole cluster fits)
     int cmax = 1;
     for (int j = 0; j < d; ++j) cmax = card[j] > cmax ? card[j] : cmax;
-    const int per_cluster = d * cmax;
-    const int chunk = a.hist_words / per_cluster;       // >= 1 by construction on the host
-    for (int f0 = 0; f0 < nf; f0 += chunk) {
-        const int fn = (nf - f0) < chunk ? (nf - f0) : chunk;
-        for (int e = tid; e < fn * per_cluster; e += blockDim.x) hist[e] = 0u;
-        for (int q = tid; q < fn; q += blockDim.x) slot_of[flagged[f0 + q]] = q;
-        __syncthreads();
-        for (int64_t r = r0 + tid; r < r1; r += blockDim.x) {
-            const int s = slot_of[a.labels_sel[r]];
-            if (s < 0) continue;
-            if (a.valid && a.valid[r] == 0) continue;
-            unsigned *hrow = hist + (size_t)s * per_cluster;
-            for (int j = 0; j < d; ++j) {
-                const unsigned v = a.X[(int64_t)j * a.ld + r];
-                if (v < (unsigned)cmax) atomicAdd(&hrow[j * cmax + v], 1u);
-            }
-        }
-        __syncthreads();
-        for (int e = tid; e < fn * d; e += blockDim.x) {
-            const int q = e / d, j = e % d;
-            const unsigned *hv = hist + (size_t)q * per_cluster + (size_t)j * cmax;
-            int bv = 0;
-            unsigned bc = hv[0];
-            unsigned total = hv[0];
-            for (int v = 1; v < cmax; ++v) {
-                total += hv[v];
-                if (v < card[j] && hv[v] > bc) {
-                    bc = hv[v];
-                    bv = v;
+    int jn = a.hist_words / cmax;                       // >= 1 by construction on the host
+    jn = jn > d ? d : jn;
+    const int per_cluster = jn * cmax;
+    const int chunk = a.hist_words / per_cluster;
+    for (int j0 = 0; j0 < d; j0 += jn) {
+        const int jw = (d - j0) < jn ? (d - j0) : jn;
+        for (int f0 = 0; f0 < nf; f0 += chunk) {
+            const int fn = (nf - f0) < chunk ? (nf - f0) : chunk;
+            for (int e = tid; e < fn * per_cluster; e += blockDim.x) hist[e] = 0u;
+            for (int q = tid; q < fn; q += blockDim.x) slot_of[flagged[f0 + q]] = q;
+            __syncthreads();
+            for (int64_t r = r0 + tid; r < r1; r += blockDim.x) {
+                const int s = slot_of[a.labels_sel[r]];
+                if (s < 0) continue;
+                if (a.valid && a.valid[r] == 0) continue;
+                unsigned *hrow = hist + (size_t)s * per_cluster;
+                for (int j = 0; j < jw; ++j) {
+                    const unsigned v = X[(int64_t)(j0 + j) * a.ld + r];
+                    if (v < (unsigned)cmax) atomicAdd(&hrow[j * cmax + v], 1u);
                 }
             }
-            const int c = flagged[f0 + q];
-            mode[c * d + j] = (uint8_t)bv;
-            if (j == 0) hasv[c] = total > 0 ? 1 : 0;
+            __syncthreads();
+            for (int e = tid; e < fn * jw; e += blockDim.x) {
+                const int q = e / jw, j = e % jw;
+                const unsigned *hv = hist + (size_t)q * per_cluster + (size_t)j * cmax;
+                int bv = 0;
+                unsigned bc = hv[0];
+                unsigned total = hv[0];
+                for (int v = 1; v < cmax; ++v) {
+                    total += hv[v];
+                    if (v < card[j0 + j] && hv[v] > bc) {
+                        bc = hv[v];
+                        bv = v;
+                    }
+                }
+                const int c = flagged[f0 + q];
+                mode[c * d + j0 + j] = (XT)bv;
+                if (j0 + j == 0) hasv[c] = total > 0 ? 1 : 0;
+            }
+            __syncthreads();
+            for (int q = tid; q < fn; q += blockDim.x) slot_of[flagged[f0 + q]] = -1;
+            __syncthreads();
         }
-        __syncthreads();
-        for (int q = tid; q < fn; q += blockDim.x) slot_of[flagged[f0 + q]] = -1;
-        __syncthreads();
     }
 
     // C. accept or drop, in ascending cluster order, by the first wave
@@ -441,7 +456,7 @@ __global__ __launch_bounds__(1024) void synth_kernel(const SynthArgs a)
         for (int f = 0; f < nf; ++f) {
             const int c = flagged[f];
             if (!hasv[c]) continue;
-            const uint8_t *m = mode + c * d;
+            const XT *m = mode + c * d;
             bool dup = false;
             for (int q = lane; q < k; q += kWave) {
                 const int fq = fl[q];
@@ -473,7 +488,8 @@ __global__ __launch_bounds__(1024) void synth_kernel(const SynthArgs a)
     }
 }
 
-__global__ void hash_rows_kernel(const uint8_t *rows, int64_t n, int d, const uint64_t *salts,
+template <typename XT>
+__global__ void hash_rows_kernel(const XT *rows, int64_t n, int d, const uint64_t *salts,
                                  uint64_t salt_all, uint64_t *out)
 {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -843,11 +859,11 @@ hipError_t launch_snap_wide_dp(const SnapArgs &a, int total_wgs, hipStream_t s)
     return hipGetLastError();
 }
 
-template <int DP, int MAXNT>
+template <typename XT, int DP, int R, int MAXNT>
 hipError_t launch_snap_dp(const SnapArgs &a, int nt, hipStream_t s)
 {
     const size_t lds = resident_lds_bytes(DP, a.kmax);
-    auto kern = snap_kernel<DP, MAXNT>;
+    auto kern = snap_kernel<XT, DP, R, MAXNT>;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
@@ -883,14 +899,22 @@ hipError_t launch_select_k(const double *inertia, const int *status, int T, int 
 hipError_t launch_snap(const SnapArgs &a, int nt, hipStream_t s)
 {
     const int d = a.d;
-    if (d <= 4) return launch_snap_dp<4, 1024>(a, nt, s);
-    if (d <= 8) return launch_snap_dp<8, 1024>(a, nt, s);
-    if (d <= 12) return launch_snap_dp<12, 1024>(a, nt, s);
-    if (d <= 16) return launch_snap_dp<16, 1024>(a, nt, s);
-    if (d <= 20) return launch_snap_dp<20, 1024>(a, nt, s);
-    if (d <= 24) return launch_snap_dp<24, 1024>(a, nt, s);
-    if (d <= 28) return launch_snap_dp<28, 512>(a, nt, s);
-    return launch_snap_dp<32, 512>(a, nt, s);
+    if (a.xbytes == 2) {
+        if (d <= 8) return launch_snap_dp<uint16_t, 8, 4, 512>(a, nt, s);
+        if (d <= 16) return launch_snap_dp<uint16_t, 16, 4, 512>(a, nt, s);
+        if (d <= 24) return launch_snap_dp<uint16_t, 24, 4, 512>(a, nt, s);
+        if (d <= 32) return launch_snap_dp<uint16_t, 32, 4, 512>(a, nt, s);
+        if (d <= 48) return launch_snap_dp<uint16_t, 48, 2, 512>(a, nt, s);
+        return launch_snap_dp<uint16_t, 64, 2, 512>(a, nt, s);
+    }
+    if (d <= 4) return launch_snap_dp<uint8_t, 4, 4, 1024>(a, nt, s);
+    if (d <= 8) return launch_snap_dp<uint8_t, 8, 4, 1024>(a, nt, s);
+    if (d <= 12) return launch_snap_dp<uint8_t, 12, 4, 1024>(a, nt, s);
+    if (d <= 16) return launch_snap_dp<uint8_t, 16, 4, 1024>(a, nt, s);
+    if (d <= 20) return launch_snap_dp<uint8_t, 20, 4, 1024>(a, nt, s);
+    if (d <= 24) return launch_snap_dp<uint8_t, 24, 4, 1024>(a, nt, s);
+    if (d <= 28) return launch_snap_dp<uint8_t, 28, 4, 512>(a, nt, s);
+    return launch_snap_dp<uint8_t, 32, 4, 512>(a, nt, s);
 }
 
 hipError_t launch_snap_wide(const SnapArgs &a, int total_wgs, hipStream_t s)
@@ -919,21 +943,22 @@ hipError_t launch_synth_wide(const SynthArgs &a, int total_wgs, hipStream_t s)
     return hipGetLastError();
 }
 
-size_t synth_lds_bytes(int d, int kmax, int hist_words)
+size_t synth_lds_bytes(int d, int kmax, int hist_words, int xbytes)
 {
     size_t b = sizeof(unsigned) * (size_t)hist_words;
     b += sizeof(int) * (size_t)kmax * 2 + sizeof(int) * 8;
-    b += (size_t)kmax * d * 2 + (size_t)kmax * 2;
+    b += (size_t)xbytes * kmax * d * 2 + (size_t)kmax * 2;
     return (b + 15) & ~(size_t)15;
 }
 
 hipError_t launch_synth(const SynthArgs &a, int nt, hipStream_t s)
 {
-    const size_t lds = synth_lds_bytes(a.d, a.kmax, a.hist_words);
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(synth_kernel),
+    const size_t lds = synth_lds_bytes(a.d, a.kmax, a.hist_words, a.xbytes);
+    auto kern = a.xbytes == 2 ? synth_kernel<uint16_t> : synth_kernel<uint8_t>;
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(synth_kernel, dim3(a.T), dim3(nt), lds, s, a);
+    hipLaunchKernelGGL(kern, dim3(a.T), dim3(nt), lds, s, a);
     return hipGetLastError();
 }
 
@@ -952,13 +977,18 @@ hipError_t launch_table_insert_hashes(uint64_t *v, int64_t slots, const uint64_t
     return hipGetLastError();
 }
 
-hipError_t launch_table_insert_configs(uint64_t *v, int64_t slots, const uint8_t *cfgs, int64_t n, int d,
+hipError_t launch_table_insert_configs(uint64_t *v, int64_t slots, const void *cfgs, int xbytes, int64_t n, int d,
                                        const uint8_t *flags, const uint64_t *salts, int64_t rows_per_salt,
                                        int *overflow, hipStream_t s)
 {
-    if (n > 0)
-        hipLaunchKernelGGL(table_insert_configs_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, v, slots,
-                           cfgs, n, d, flags, salts, rows_per_salt, overflow);
+    if (n <= 0) return hipSuccess;
+    const dim3 grid((unsigned)((n + 255) / 256));
+    if (xbytes == 2)
+        hipLaunchKernelGGL(table_insert_configs_kernel<uint16_t>, grid, dim3(256), 0, s, v, slots,
+                           static_cast<const uint16_t *>(cfgs), n, d, flags, salts, rows_per_salt, overflow);
+    else
+        hipLaunchKernelGGL(table_insert_configs_kernel<uint8_t>, grid, dim3(256), 0, s, v, slots,
+                           static_cast<const uint8_t *>(cfgs), n, d, flags, salts, rows_per_salt, overflow);
     return hipGetLastError();
 }
 
@@ -972,12 +1002,17 @@ hipError_t launch_update_configs(uint8_t *theta, const int8_t *actions, int64_t 
     return hipGetLastError();
 }
 
-hipError_t launch_hash_rows(const uint8_t *rows, int64_t n, int d, const uint64_t *salts,
+hipError_t launch_hash_rows(const void *rows, int xbytes, int64_t n, int d, const uint64_t *salts,
                             uint64_t salt_all, uint64_t *out, hipStream_t s)
 {
     if (n <= 0) return hipSuccess;
-    hipLaunchKernelGGL(hash_rows_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, rows, n, d,
-                       salts, salt_all, out);
+    const dim3 grid((unsigned)((n + 255) / 256));
+    if (xbytes == 2)
+        hipLaunchKernelGGL(hash_rows_kernel<uint16_t>, grid, dim3(256), 0, s, static_cast<const uint16_t *>(rows), n, d,
+                           salts, salt_all, out);
+    else
+        hipLaunchKernelGGL(hash_rows_kernel<uint8_t>, grid, dim3(256), 0, s, static_cast<const uint8_t *>(rows), n, d,
+                           salts, salt_all, out);
     return hipGetLastError();
 }
 

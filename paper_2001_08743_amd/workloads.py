@@ -120,8 +120,9 @@ def conv_cards(rng: np.random.Generator) -> np.ndarray:
     return c
 
 
-def _blob_rows(rng, n, cards, n_blobs, sigma):
-    """n integer rows from a non-uniform mixture of n_blobs Gaussian blobs in knob-index space."""
+def _blob_rows(rng, n, cards, n_blobs, sigma, dtype=np.uint8):
+    """n integer rows from a non-uniform mixture of n_blobs Gaussian blobs in knob-index space.
+    sigma is one number or one per knob."""
     d = len(cards)
     hi = cards.astype(np.float64) - 1.0
     centres = rng.random((n_blobs, d)) * hi
@@ -129,7 +130,7 @@ def _blob_rows(rng, n, cards, n_blobs, sigma):
     which = rng.choice(n_blobs, size=n, p=weights)
     pts = centres[which] + sigma * rng.standard_normal((n, d))
     pts = np.clip(np.rint(pts), 0.0, hi)
-    return pts.astype(np.uint8)
+    return pts.astype(dtype)
 
 
 def _spoil(rng, rows, valid, cards, frac):
@@ -144,13 +145,13 @@ def _spoil(rng, rows, valid, cards, frac):
     valid[idx] = 0
 
 
-def _visited(rng, rows_by_task, cards, n_visited):
+def _visited(rng, rows_by_task, cards, n_visited, dtype=np.uint8):
     """Visited inputs: per task an equal share, half sampled from the task's rows (so that
     lookups hit), half uniform-random configurations; plus spare random words for topping up."""
     T = len(rows_by_task)
     d = rows_by_task[0].shape[1]
     if n_visited <= 0:
-        return (np.zeros((0, d), np.uint8), np.zeros(0, np.int64), np.zeros(0, np.uint64))
+        return (np.zeros((0, d), dtype), np.zeros(0, np.int64), np.zeros(0, np.uint64))
     per = max(2, n_visited // T)
     cfgs, tasks = [], []
     for t in range(T):
@@ -159,7 +160,7 @@ def _visited(rng, rows_by_task, cards, n_visited):
         pick = rng.choice(r.shape[0], size=min(h, r.shape[0]), replace=False)
         cfgs.append(r[pick])
         rnd = np.stack([rng.integers(0, int(c), size=per - h) for c in cards[t]], axis=1)
-        cfgs.append(rnd.astype(np.uint8))
+        cfgs.append(rnd.astype(dtype))
         tasks.append(np.full(len(pick) + (per - h), t, dtype=np.int64))
     cfg = np.concatenate(cfgs, axis=0)
     task = np.concatenate(tasks, axis=0)
@@ -188,16 +189,18 @@ def finalize_visited(hashes: np.ndarray, raw: np.ndarray, size: int) -> np.ndarr
 
 
 def _assemble(name, rng, task_sizes, card_list, blobs, sigma, invalid_frac, ks, n_iter,
-              n_visited, threshold=2.5, meta=None):
+              n_visited, threshold=2.5, meta=None, dtype=np.uint8, sigma_rel=0.0):
+    """sigma_rel > 0: the spread of knob j is max(sigma, sigma_rel * card_j) index steps."""
     rows_by_task, valid_by_task = [], []
     for n, cards, b in zip(task_sizes, card_list, blobs):
-        r = _blob_rows(rng, n, cards, b, sigma)
+        sg = np.maximum(sigma, sigma_rel * cards.astype(np.float64)) if sigma_rel > 0 else sigma
+        r = _blob_rows(rng, n, cards, b, sg, dtype)
         v = np.ones(n, dtype=np.uint8)
         _spoil(rng, r, v, cards, invalid_frac)
         rows_by_task.append(r)
         valid_by_task.append(v)
     cards = np.stack(card_list).astype(np.uint16)
-    vcfg, vtask, vraw = _visited(rng, rows_by_task, cards, n_visited)
+    vcfg, vtask, vraw = _visited(rng, rows_by_task, cards, n_visited, dtype)
     off = np.zeros(len(task_sizes) + 1, dtype=np.int64)
     off[1:] = np.cumsum(task_sizes)
     T = len(task_sizes)
@@ -256,3 +259,26 @@ def random_task(seed: int, n: int, d: int, card_lo: int = 2, card_hi: int = 16, 
     card_list = [rng.integers(card_lo, card_hi + 1, size=d).astype(np.uint16) for _ in range(n_tasks)]
     return _assemble(f"rand-{seed}", rng, sizes, card_list, [n_blobs] * n_tasks, sigma,
                      invalid_frac, ks, n_iter, n_visited)
+
+
+def wide_space(seed: int, n_tasks: int = 64, n: int = 2048, d: int = 40, ks=range(2, 33), n_iter: int = 30,
+               n_visited: int = 4096, wide_frac: float = 0.3, card_wide=(64, 600), card_small=(2, 32),
+               ragged: bool = False) -> Workload:
+    """Tuning tasks over design spaces with two-byte knobs (Sec. 2: the product of the knobs' choice
+    lists reaches 10^10 points; a split knob of a large loop has hundreds of choices): a share
+    `wide_frac` of the knobs draws its cardinality from `card_wide`, the others from `card_small`;
+    8..24 blobs per task whose spread is max(1.5, 2 % of the cardinality) index steps per knob;
+    5 % uniform-random invalid rows.  Rows are uint16."""
+    rng = np.random.default_rng(BASE_SEED * 7 + seed)
+    sizes = [n] * n_tasks
+    if ragged:
+        sizes = [max(1, int(n * f)) for f in rng.uniform(0.3, 1.0, size=n_tasks)]
+    card_list = []
+    for _ in range(n_tasks):
+        wide = rng.random(d) < wide_frac
+        c = np.where(wide, rng.integers(card_wide[0], card_wide[1] + 1, size=d),
+                     rng.integers(card_small[0], card_small[1] + 1, size=d))
+        card_list.append(c.astype(np.uint16))
+    blobs = rng.integers(8, 25, size=n_tasks)
+    return _assemble(f"wide-{seed}", rng, sizes, card_list, blobs, 1.5, 0.05, ks, n_iter, n_visited,
+                     dtype=np.uint16, sigma_rel=0.02)

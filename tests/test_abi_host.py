@@ -64,11 +64,11 @@ def test_host_hash_matches_published_fnv1a_vectors(lib, golden_dir):
 
 
 def _sweep_rc(lib, X=1024, ld=64, d=4, task_off=(0, 10), ks=(1, 2), n_iter=1, init_mode=0, ws=4096, ws_bytes=1 << 20,
-              flags=0, outs=4096):
+              flags=0, outs=4096, fn="cham_kmeans_sweep"):
     to = np.asarray(task_off, dtype=np.int64)
     k = np.asarray(ks, dtype=np.int32)
     vp = C.c_void_p
-    return lib.cham_kmeans_sweep(vp(X), C.c_int64(ld), C.c_int32(d), to.ctypes.data_as(vp), C.c_int32(len(to) - 1),
+    return getattr(lib, fn)(vp(X), C.c_int64(ld), C.c_int32(d), to.ctypes.data_as(vp), C.c_int32(len(to) - 1),
                                  k.ctypes.data_as(vp), C.c_int32(len(k)), C.c_int32(n_iter), C.c_int32(init_mode),
                                  None, vp(outs), vp(outs), vp(outs), vp(outs), None, None, vp(ws),
                                  C.c_int64(ws_bytes), C.c_int32(flags), None)
@@ -130,3 +130,43 @@ def test_visited_table_argument_errors(lib):
                                                  C.c_int64(1), None, None) == -2
     assert lib.cham_visited_table_insert_configs(one, C.c_int64(16), one, C.c_int64(3), C.c_int32(4), None, None,
                                                  C.c_int64(0), None, None) == -2
+
+
+def test_two_byte_knob_argument_errors_and_limits(lib):
+    u16 = dict(fn="cham_kmeans_sweep_u16")
+    assert _sweep_rc(lib, X=0, **u16) == -1
+    assert _sweep_rc(lib, d=65, **u16) == -2
+    assert _sweep_rc(lib, X=1028, **u16) == -2                # 4- but not 8-byte aligned
+    assert _sweep_rc(lib, ld=62, **u16) == -2
+    assert _sweep_rc(lib, ks=(1, 257), **u16) == -3
+    assert _sweep_rc(lib, flags=binding.F_STREAMING, **u16) == -8
+    assert _sweep_rc(lib, d=64, ks=(2, 126), **u16) == -3     # centroids and sums of 126 x 64 knobs exceed LDS
+    assert _sweep_rc(lib, d=64, ks=(2, 125), ws=0, **u16) == -6   # 125 fits: the next check is the workspace
+    assert _sweep_rc(lib, d=48, ks=(167,), **u16) == -3
+    assert _sweep_rc(lib, d=32, ks=(248,), **u16) == -3
+    assert _sweep_rc(lib, d=24, ks=(256,), ws=0, **u16) == -6
+    # workspace queries follow the same limits
+    assert binding.cham_sweep_workspace_bytes_u16(4096, 64, [0, 4096], [2, 125], 5) > 0
+    with pytest.raises(binding.ChamError):
+        binding.cham_sweep_workspace_bytes_u16(4096, 64, [0, 4096], [2, 126], 5)
+    with pytest.raises(binding.ChamError):
+        binding.cham_sweep_workspace_bytes(4096, 64, [0, 4096], [2, 3], 5)        # byte knobs stop at 32
+    # no f16 copy of the rows in the two-byte workspace
+    assert binding.cham_sweep_workspace_bytes_u16(4096, 12, [0, 4096], [2, 3], 5) < \
+        binding.cham_sweep_workspace_bytes(4096, 12, [0, 4096], [2, 3], 5)
+    one = C.c_void_p(256)
+    assert lib.cham_visited_table_insert_configs_u16(one, C.c_int64(16), one, C.c_int64(3), C.c_int32(65), None, None,
+                                                     C.c_int64(1), None, None) == -2
+
+
+def test_two_byte_host_hash_equals_the_byte_hash_below_256_and_takes_whole_values_above(lib):
+    rng = np.random.default_rng(4)
+    for _ in range(20):
+        cfg = rng.integers(0, 256, size=int(rng.integers(1, 40)))
+        salt = int(rng.integers(0, 2 ** 40))
+        assert binding.cham_hash_config_u16(cfg, salt) == binding.cham_hash_config(cfg, salt)
+    M = 1 << 64
+    h = 0xCBF29CE484222325
+    for v in (300, 65535, 0, 256):
+        h = ((h ^ v) * 0x100000001B3) % M
+    assert binding.cham_hash_config_u16([300, 65535, 0, 256], 0) == h

@@ -379,7 +379,7 @@ def _check_knee_sweep(wl, thr, chunk, flags=0):
     import torch
     dw = binding.DeviceWorkload(wl)
     out = binding.cham_kmeans_sweep_knee(dw.X, dw.ld, dw.d, wl.task_off, wl.ks, wl.n_iter, threshold=thr,
-                                         chunk=chunk, want_labels=True, flags=flags)
+                                         chunk=chunk, want_labels=True, flags=flags, _sfx=dw.sfx)
     torch.cuda.synchronize()
     full = oracle.sweep(wl.rows, wl.task_off, wl.ks, wl.n_iter, want_labels=True)
     loop = oracle.sweep_until_knee(wl.rows, wl.task_off, wl.ks, wl.n_iter, thr)
