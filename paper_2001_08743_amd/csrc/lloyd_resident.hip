@@ -60,21 +60,27 @@ __device__ __forceinline__ void lds_add(long long *p, int v)
 template <int DP, typename SumT>
 __device__ __forceinline__ void derive_screen(const UnitLds<DP, SumT> &U, int k, int kp)
 {
-    for (int c = threadIdx.x; c < k; c += blockDim.x) {
+    // eight lanes per centroid, each taking every eighth knob
+    constexpr int kGroup = 8;
+    const int sub = threadIdx.x % kGroup;
+    for (int c = threadIdx.x / kGroup; c < k; c += blockDim.x / kGroup) {
         double b = 0.0;
         float *w = U.wf + (size_t)c * (DP + 4);
-#pragma unroll
-        for (int j = 0; j < DP; ++j) {
+        for (int j = sub; j < DP; j += kGroup) {
             const double m = U.mu64T[(size_t)j * kp + c] - (double)U.ojf[j];
             b = __builtin_fma(m, m, b);
             w[j] = (float)(-2.0 * m);
         }
-        w[DP] = (float)b;
-        w[DP + 1] = 0.0f;
-        w[DP + 2] = 0.0f;
-        w[DP + 3] = 0.0f;
-        const float bu = __double2float_ru(b) * 1.0000005f;
-        atomicMax(U.m2bits, __float_as_uint(bu));
+#pragma unroll
+        for (int off = kGroup / 2; off >= 1; off >>= 1) b = b + __shfl_xor(b, off, kWave);
+        if (sub == 0) {
+            w[DP] = (float)b;
+            w[DP + 1] = 0.0f;
+            w[DP + 2] = 0.0f;
+            w[DP + 3] = 0.0f;
+            const float bu = __double2float_ru(b) * 1.0000005f;
+            atomicMax(U.m2bits, __float_as_uint(bu));
+        }
     }
 }
 
@@ -206,10 +212,14 @@ __global__ __launch_bounds__(MAXNT) void resident_sweep_kernel(const SweepArgs a
                 newpack |= (uint32_t)cur << (8 * p);
                 if (on && (it == 0 || cur != prev)) {
                     changed = true;
-                    for (int j = 0; j < d; ++j) {
-                        const int xi = (int)(xf[p][j] + U.ojf[j]);
-                        lds_add(&U.S[cur * DP + j], xi);
-                        if (it > 0) lds_add(&U.S[prev * DP + j], -xi);
+                    // fully unrolled: a run-time index into xf would move the rows out of registers
+#pragma unroll
+                    for (int j = 0; j < DP; ++j) {
+                        if (j < d) {
+                            const int xi = (int)(xf[p][j] + U.ojf[j]);
+                            lds_add(&U.S[cur * DP + j], xi);
+                            if (it > 0) lds_add(&U.S[prev * DP + j], -xi);
+                        }
                     }
                     atomicAdd(&U.n[cur], 1);
                     if (it > 0) atomicSub(&U.n[prev], 1);
