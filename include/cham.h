@@ -280,9 +280,10 @@ int32_t cham_hash_rows(const uint8_t *rows, int64_t n, int32_t d, const uint64_t
  *     are 64-bit integers.  flags: CHAM_F_FORCE_EXACT is honoured, CHAM_F_RESIDENT and
  *     CHAM_F_NO_MFMA are accepted (they name what this path does anyway), CHAM_F_STREAMING
  *     gives CHAM_E_BAD_FLAG.
- *   - k_max * (20 * dp + 20) + 4 * dp + 192 must not exceed 160 KiB, dp = d rounded up to 8,
- *     16, 24, 32, 48 or 64 (k_max up to 256 for d <= 24, 247 for d <= 32, 166 for d <= 48,
- *     125 for d <= 64); beyond that: CHAM_E_BAD_K, also from the sweep's workspace queries.
+ *   - k_max * (20 * dp + 20) + 4 * dp + 192 must not exceed 160 KiB, dp = d rounded up to a
+ *     multiple of 8 (k_max up to 256 for d <= 24, 247 for d <= 32, 199 for d <= 40, 166 for
+ *     d <= 48, 143 for d <= 56, 125 for d <= 64); beyond that: CHAM_E_BAD_K, also from the
+ *     sweep's workspace queries.
  *   - cham_synthesize*_u16: cardinalities up to 16384 (the value histogram of one knob of one
  *     cluster has to fit in LDS); above: CHAM_E_CARD.
  *   - The hash takes one FNV-1a step per knob value, the whole value in the step: equal to the

@@ -356,7 +356,7 @@ hipError_t launch_first_distinct(const SweepArgs &a, int *init_rows, int *ndist,
 }
 
 // Padded knob count of the two-byte instantiations.
-int resident_dp16(int d) { return d <= 32 ? (d + 7) / 8 * 8 : (d <= 48 ? 48 : 64); }
+int resident_dp16(int d) { return (d + 7) / 8 * 8; }
 
 hipError_t launch_resident_sweep(const SweepArgs &a, int nt, hipStream_t s)
 {
@@ -366,7 +366,9 @@ hipError_t launch_resident_sweep(const SweepArgs &a, int nt, hipStream_t s)
         if (d <= 16) return launch_dp<uint16_t, 16, 4, 512>(a, nt, s);
         if (d <= 24) return launch_dp<uint16_t, 24, 4, 512>(a, nt, s);
         if (d <= 32) return launch_dp<uint16_t, 32, 4, 512>(a, nt, s);
+        if (d <= 40) return launch_dp<uint16_t, 40, 2, 512>(a, nt, s);
         if (d <= 48) return launch_dp<uint16_t, 48, 2, 512>(a, nt, s);
+        if (d <= 56) return launch_dp<uint16_t, 56, 2, 512>(a, nt, s);
         return launch_dp<uint16_t, 64, 2, 512>(a, nt, s);
     }
     if (d <= 4) return launch_dp<uint8_t, 4, 4, 1024>(a, nt, s);

@@ -904,7 +904,9 @@ hipError_t launch_snap(const SnapArgs &a, int nt, hipStream_t s)
         if (d <= 16) return launch_snap_dp<uint16_t, 16, 4, 512>(a, nt, s);
         if (d <= 24) return launch_snap_dp<uint16_t, 24, 4, 512>(a, nt, s);
         if (d <= 32) return launch_snap_dp<uint16_t, 32, 4, 512>(a, nt, s);
+        if (d <= 40) return launch_snap_dp<uint16_t, 40, 2, 512>(a, nt, s);
         if (d <= 48) return launch_snap_dp<uint16_t, 48, 2, 512>(a, nt, s);
+        if (d <= 56) return launch_snap_dp<uint16_t, 56, 2, 512>(a, nt, s);
         return launch_snap_dp<uint16_t, 64, 2, 512>(a, nt, s);
     }
     if (d <= 4) return launch_snap_dp<uint8_t, 4, 4, 1024>(a, nt, s);

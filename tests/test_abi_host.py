@@ -143,6 +143,9 @@ def test_two_byte_knob_argument_errors_and_limits(lib):
     assert _sweep_rc(lib, d=64, ks=(2, 126), **u16) == -3     # centroids and sums of 126 x 64 knobs exceed LDS
     assert _sweep_rc(lib, d=64, ks=(2, 125), ws=0, **u16) == -6   # 125 fits: the next check is the workspace
     assert _sweep_rc(lib, d=48, ks=(167,), **u16) == -3
+    assert _sweep_rc(lib, d=40, ks=(200,), **u16) == -3
+    assert _sweep_rc(lib, d=40, ks=(199,), ws=0, **u16) == -6
+    assert _sweep_rc(lib, d=56, ks=(144,), **u16) == -3
     assert _sweep_rc(lib, d=32, ks=(248,), **u16) == -3
     assert _sweep_rc(lib, d=24, ks=(256,), ws=0, **u16) == -6
     # workspace queries follow the same limits

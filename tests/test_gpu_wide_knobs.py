@@ -33,7 +33,7 @@ def test_wide_space_whole_path(seed):
     assert (flags == oracle.SYNTH).any() and (flags == oracle.KEPT).any()
 
 
-@pytest.mark.parametrize("d", [1, 5, 8, 9, 16, 24, 25, 32, 33, 48, 49, 64])
+@pytest.mark.parametrize("d", [1, 5, 8, 9, 16, 24, 25, 32, 33, 40, 41, 48, 49, 56, 57, 64])
 def test_knob_counts(d):
     wl = workloads.wide_space(10 + d, n_tasks=2, n=900, d=d, ks=(1, 2, 5, 11, 23), n_iter=6, ragged=True,
                               n_visited=512)
