@@ -86,7 +86,7 @@ int32_t check_common(const void *X, int64_t ld, int32_t d, const int64_t *task_o
     pl.DP = xbytes == 1 ? (d + 3) / 4 * 4 : resident_dp16(d);
     pl.n_total = task_off[T];
     pl.n_max = nmax;
-    const int maxnt = (xbytes == 1 && pl.DP <= 24) ? 1024 : 512;
+    const int maxnt = (xbytes == 1 && pl.DP <= 12) ? 1024 : 512;
     const int rpt = (xbytes == 2 && pl.DP > 32) ? 2 : 4;           // rows per lane and pass
     int64_t nt = ((nmax + 2 * (rpt - 1)) / rpt + 63) / 64 * 64;
     if (nt < 64) nt = 64;

@@ -374,9 +374,9 @@ hipError_t launch_resident_sweep(const SweepArgs &a, int nt, hipStream_t s)
     if (d <= 4) return launch_dp<uint8_t, 4, 4, 1024>(a, nt, s);
     if (d <= 8) return launch_dp<uint8_t, 8, 4, 1024>(a, nt, s);
     if (d <= 12) return launch_dp<uint8_t, 12, 4, 1024>(a, nt, s);
-    if (d <= 16) return launch_dp<uint8_t, 16, 4, 1024>(a, nt, s);
-    if (d <= 20) return launch_dp<uint8_t, 20, 4, 1024>(a, nt, s);
-    if (d <= 24) return launch_dp<uint8_t, 24, 4, 1024>(a, nt, s);
+    if (d <= 16) return launch_dp<uint8_t, 16, 4, 512>(a, nt, s);
+    if (d <= 20) return launch_dp<uint8_t, 20, 4, 512>(a, nt, s);
+    if (d <= 24) return launch_dp<uint8_t, 24, 4, 512>(a, nt, s);
     if (d <= 28) return launch_dp<uint8_t, 28, 4, 512>(a, nt, s);
     return launch_dp<uint8_t, 32, 4, 512>(a, nt, s);
 }

@@ -912,9 +912,9 @@ hipError_t launch_snap(const SnapArgs &a, int nt, hipStream_t s)
     if (d <= 4) return launch_snap_dp<uint8_t, 4, 4, 1024>(a, nt, s);
     if (d <= 8) return launch_snap_dp<uint8_t, 8, 4, 1024>(a, nt, s);
     if (d <= 12) return launch_snap_dp<uint8_t, 12, 4, 1024>(a, nt, s);
-    if (d <= 16) return launch_snap_dp<uint8_t, 16, 4, 1024>(a, nt, s);
-    if (d <= 20) return launch_snap_dp<uint8_t, 20, 4, 1024>(a, nt, s);
-    if (d <= 24) return launch_snap_dp<uint8_t, 24, 4, 1024>(a, nt, s);
+    if (d <= 16) return launch_snap_dp<uint8_t, 16, 4, 512>(a, nt, s);
+    if (d <= 20) return launch_snap_dp<uint8_t, 20, 4, 512>(a, nt, s);
+    if (d <= 24) return launch_snap_dp<uint8_t, 24, 4, 512>(a, nt, s);
     if (d <= 28) return launch_snap_dp<uint8_t, 28, 4, 512>(a, nt, s);
     return launch_snap_dp<uint8_t, 32, 4, 512>(a, nt, s);
 }
@@ -925,9 +925,9 @@ hipError_t launch_snap_wide(const SnapArgs &a, int total_wgs, hipStream_t s)
     if (d <= 4) return launch_snap_wide_dp<4, 1024>(a, total_wgs, s);
     if (d <= 8) return launch_snap_wide_dp<8, 1024>(a, total_wgs, s);
     if (d <= 12) return launch_snap_wide_dp<12, 1024>(a, total_wgs, s);
-    if (d <= 16) return launch_snap_wide_dp<16, 1024>(a, total_wgs, s);
-    if (d <= 20) return launch_snap_wide_dp<20, 1024>(a, total_wgs, s);
-    if (d <= 24) return launch_snap_wide_dp<24, 1024>(a, total_wgs, s);
+    if (d <= 16) return launch_snap_wide_dp<16, 512>(a, total_wgs, s);
+    if (d <= 20) return launch_snap_wide_dp<20, 512>(a, total_wgs, s);
+    if (d <= 24) return launch_snap_wide_dp<24, 512>(a, total_wgs, s);
     if (d <= 28) return launch_snap_wide_dp<28, 512>(a, total_wgs, s);
     return launch_snap_wide_dp<32, 512>(a, total_wgs, s);
 }
