@@ -544,6 +544,16 @@ def test_warm_start_from_the_previous_round_on_a_changed_sample(flags):
     assert (ref["status"] == 0).all()
 
 
+@pytest.mark.parametrize("flags", [0, binding.F_NO_MFMA, binding.F_STREAMING, binding.F_FORCE_EXACT])
+def test_zero_lloyd_steps_is_one_assignment_with_the_start(flags):
+    """n_iter = 0: no update at all, labels, counts and loss are those of the starting centroids."""
+    wl = workloads.random_task(4242, n=1500, d=11, n_blobs=9, ks=(1, 3, 17, 40), n_iter=0, card_hi=20,
+                               n_tasks=3, ragged=True)
+    out, ref = _sweep_only(wl, flags, want_trace=True)
+    first = oracle.first_distinct(wl.task_rows(0), 40)
+    np.testing.assert_array_equal(out["centroids"].cpu().numpy()[0, 21:61], wl.task_rows(0)[first].astype(np.float64))
+
+
 def test_visited_table_overflow_is_reported_and_lookups_end():
     import torch
     table = torch.empty(4, dtype=torch.int64, device="cuda:0")
