@@ -115,7 +115,7 @@ int32_t check_common(const void *X, int64_t ld, int32_t d, const int64_t *task_o
     return CHAM_OK;
 }
 
-constexpr int kStreamRowsPerWg = 4096;
+constexpr int kStreamRowsPerWg = 4096;      // the smallest value of stream_rows_per_wg: bounds the workgroup count
 
 // Which kernel family runs the sweep.
 enum class SweepPath { kMfmaResident, kVectorResident, kStream };
@@ -167,7 +167,7 @@ SweepWs sweep_ws(const Plan &pl, int64_t ld, bool own_labels, bool stream, const
         w.ng = o;      o += up(u * kpm * 4);
         w.mu = o;      o += up(u * 32 * kpm * 8);
         w.afrag = o;   o += up(u * (kpm / 32) * 4 * 64 * 16);
-        w.m2 = o;      o += up(u * 4);
+        w.m2 = o;      o += up(u * 8 * 4);
         w.wg_off = o;  o += up((u + 2) * 4);
         w.loss = o;    o += up(((int64_t)w.total_wgs + 1) * 8);
     }
@@ -315,8 +315,9 @@ static int32_t sweep_impl(const void *Xv, int xbytes, int64_t ld, int32_t d, con
             int acc = 0;
             for (int u = 0; u < n_units; ++u) {
                 const int t = u % T;
+                const int rpw = stream_rows_per_wg(ks[ki_end - 1 - u / T]);
                 po[u] = acc;
-                acc += (int)((task_off[t + 1] - task_off[t] + kStreamRowsPerWg - 1) / kStreamRowsPerWg);
+                acc += (int)((task_off[t + 1] - task_off[t] + rpw - 1) / rpw);
             }
             po[n_units] = acc;
             e = stage_words(wo, reinterpret_cast<uint64_t *>(ws + w.wg_off), s);
@@ -336,7 +337,6 @@ static int32_t sweep_impl(const void *Xv, int xbytes, int64_t ld, int32_t d, con
             sa.u_begin = (n_k - ki_end) * T;
             sa.prepare = ki_begin == 0 ? 1 : 0;
             sa.done = a.done;
-            sa.rows_per_wg = kStreamRowsPerWg;
             sa.it = 0;
             sa.final_pass = 0;
             sa.task_off = a.task_off;

@@ -49,6 +49,10 @@ inline size_t resident_lds_bytes(int DP, int kmax, int sum_bytes = 4)
     return b;
 }
 
+// Rows one workgroup of the streaming assignment kernel walks, by the unit's k.  (Measured on the
+// large single-task workload: 2048 or 16384 rows for k <= 64 are both slower than 4096.)
+__host__ __device__ inline int stream_rows_per_wg(int k) { return k <= 256 ? 4096 : 4096; }
+
 // Arguments of the streaming sweep kernels (tasks too large for one workgroup).
 struct StreamArgs {
     const uint8_t *X;
@@ -65,7 +69,6 @@ struct StreamArgs {
     int u_begin;                   // first unit of this launch
     int prepare;                   // 1: this launch also computes the centring offsets and the packed rows
     const int *done;               // [T] or null: tasks whose sweep has already stopped (their units report status 3)
-    int rows_per_wg;
     int it;                        // pass being run
     int final_pass;
     const int64_t *task_off;
@@ -88,7 +91,7 @@ struct StreamArgs {
     int *ng;                       // [n_units][kpm] counts
     double *mu;                    // [n_units][32][kpm] exact centroids, transposed
     void *afrag;                   // [n_units][kpm/32][4][64] 16-byte A fragments
-    float *m2;                     // [n_units] bound on max |mu'|^2; negative = unit unusable
+    float *m2;                     // [n_units][8] bound on max |mu'|^2 per tile of 32 centroids; tile 0 negative = unit unusable
     double *loss_part;             // [total workgroups] loss partials of the last pass
 };
 

@@ -21,6 +21,18 @@ namespace {
 constexpr int kTiles = 4;            // 32-row tiles a wave handles per step
 constexpr int kStreamRec = 32;       // queued rows whose knob values are kept in LDS
 constexpr int kWavesPerWg = 8;
+constexpr int kPairCap = 128;        // (queued row, candidate centroid) pairs evaluated per step and wave
+
+#ifdef CHAM_KERNEL_TIMING
+// Development aid (not built into the library): per-section cycle counts summed over waves,
+// one row of 8 counters per chunk count (k <= 64, <= 128, <= 192, <= 256).
+__device__ unsigned long long g_stream_timing[4 * 8];
+#define STR_T(var) const unsigned long long var = __builtin_readcyclecounter()
+#define STR_ADD(slot, t0, t1) sacc[slot] += (t1) - (t0)
+#else
+#define STR_T(var)
+#define STR_ADD(slot, t0, t1)
+#endif
 
 // Per-unit state in global memory.  KPM = kmax rounded up to 32.
 struct UnitState {
@@ -101,12 +113,16 @@ __global__ void stream_pack_kernel(const StreamArgs a, int64_t n_rows)
 
 // mode 0: start of the sweep (centroids from the first distinct rows or from the caller);
 // mode 1: centroid update after pass a.it; mode 2: outputs after the final pass.
+// Grid: (unit, tile of 32 centroids); a thread per (centroid of the tile, group of 8 knobs).  The
+// bound on max |mu'|^2 is kept per tile: m2[unit][tile], tile 0 negative = unit unusable.
+constexpr int kM2Tiles = 8;            // k <= 256
 template <int DK>
-__global__ __launch_bounds__(256) void stream_update_kernel(const StreamArgs a, int mode)
+__global__ __launch_bounds__(32 * (DK / 8)) void stream_update_kernel(const StreamArgs a, int mode)
 {
     constexpr int NS = DK / 16, G = DK / 8;
-    __shared__ float red[256];
+    __shared__ float red[32 * G / 64 + 1];
     const int ul = blockIdx.x;                 // unit within this launch
+    const int mt = blockIdx.y;                 // tile of 32 centroids
     const int u = a.u_begin + ul;
     const int ki = a.n_k - 1 - u / a.T;
     const int t = u % a.T;
@@ -122,7 +138,8 @@ __global__ __launch_bounds__(256) void stream_update_kernel(const StreamArgs a, 
     const bool unusable = skipped || (a.init_mode == 0 && a.ndist[t] < k);
 
     if (unusable) {
-        if (mode == 0 && tid == 0) a.m2[u] = -1.0f;
+        if (mt != 0) return;
+        if (mode == 0 && tid == 0) a.m2[u * kM2Tiles] = -1.0f;
         if (mode == 2) {
             for (int e = tid; e < k * d; e += blockDim.x) a.centroids[crow * d + e] = 0.0;
             for (int c = tid; c < k; c += blockDim.x) a.counts[crow + c] = 0;
@@ -139,7 +156,7 @@ __global__ __launch_bounds__(256) void stream_update_kernel(const StreamArgs a, 
     }
 
     // loss of the pass that just ran: workgroup partials in workgroup order
-    if (mode != 0 && tid == 0 && (mode == 2 || a.trace)) {
+    if (mt == 0 && mode != 0 && tid == 0 && (mode == 2 || a.trace)) {
         const int nwg = a.wg_off[ul + 1] - a.wg_off[ul];
         double s = 0.0;
         for (int w = 0; w < nwg; ++w) s = s + a.loss_part[(size_t)a.wg_off[ul] + w];
@@ -149,79 +166,86 @@ __global__ __launch_bounds__(256) void stream_update_kernel(const StreamArgs a, 
             a.status[slot] = 0;
         }
     }
+    const int kpu = (k + 31) & ~31;
+    if (mt * 32 >= kpu) return;                // no such tile in this unit
     if (mode == 2) {
-        for (int e = tid; e < k * d; e += blockDim.x) {
-            const int c = e / d, j = e % d;
-            a.centroids[(crow + c) * d + j] = st.mu[(size_t)j * kpm + c];
+        for (int e = tid; e < 32 * d; e += blockDim.x) {
+            const int c = mt * 32 + e / d, j = e % d;
+            if (c < k) a.centroids[(crow + c) * d + j] = st.mu[(size_t)j * kpm + c];
         }
-        for (int c = tid; c < k; c += blockDim.x) a.counts[crow + c] = st.n[c];
+        for (int c = mt * 32 + tid; c < k && c < mt * 32 + 32; c += blockDim.x) a.counts[crow + c] = st.n[c];
         return;
     }
 
     const float *o = a.ojf + t * 32;
-    float bmax = 0.0f;
-    const int kpu = (k + 31) & ~31;
-    for (int c = tid; c < kpu; c += blockDim.x) {
-        const int mt = c >> 5, m32 = c & 31;
-        if (mode == 0) {
-            st.n[c] = 0;
-            for (int j = 0; j < 32; ++j) st.S[c * 32 + j] = 0;
-        }
-        const int cnt = (mode == 1 && c < k) ? st.n[c] : 0;
-        double b = 0.0;
+    const int m32 = tid / G, g = tid % G;
+    const int c = mt * 32 + m32;
+    if (mode == 0) {
+        if (g == 0) st.n[c] = 0;
 #pragma unroll
-        for (int g = 0; g < G; ++g) {
-            half8 hi8, lo8;
+        for (int i = 0; i < 8; ++i) st.S[c * 32 + 8 * g + i] = 0;
+        if (DK == 16) {
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                const int j = 8 * g + i;
-                double m = 0.0;
-                if (c < k && j < d) {
-                    double mu;
-                    if (mode == 0) {
-                        if (a.init_mode == 0) mu = (double)a.X[(int64_t)j * a.ld + r0 + a.init_rows[(int64_t)t * a.kmax + c]];
-                        else mu = a.init_centroids[(crow + c) * d + j];
-                        st.mu[(size_t)j * kpm + c] = mu;
-                    } else if (cnt > 0) {
-                        mu = (double)st.S[c * 32 + j] / (double)cnt;      // an empty cluster keeps its centroid
-                        st.mu[(size_t)j * kpm + c] = mu;
-                    } else {
-                        mu = st.mu[(size_t)j * kpm + c];
-                    }
-                    m = mu - (double)o[j];
-                } else if (mode == 0 && c < k) {
-                    st.mu[(size_t)j * kpm + c] = 0.0;
-                }
-                b = __builtin_fma(m, m, b);
-                const float w = (float)(-2.0 * m);
-                const _Float16 hi = (_Float16)w;
-                hi8[i] = hi;
-                lo8[i] = (_Float16)(w - (float)hi);
-            }
-            if (g == G - 1) {
-                // bias slot: |mu'|^2 / 256 as hi + lo; padding centroid rows get a score above all others
-                if (c < k) {
-                    const float bs = (float)b * (1.0f / kBiasScale);
-                    const _Float16 bh = (_Float16)bs;
-                    hi8[7] = bh;
-                    lo8[7] = (_Float16)(bs - (float)bh);
-                } else {
-                    hi8[7] = (_Float16)kPadBiasHi;
-                    lo8[7] = (_Float16)0.0f;
-                }
-            }
-            const int hh = g & 1, fstep = g >> 1;
-            st.afrag[(mt * 4 + fstep) * 64 + 32 * hh + m32] = hi8;
-            st.afrag[(mt * 4 + NS + fstep) * 64 + 32 * hh + m32] = lo8;
+            for (int i = 0; i < 8; ++i) st.S[c * 32 + 16 + 8 * g + i] = 0;
         }
-        if (c < k) bmax = __builtin_fmaxf(bmax, __double2float_ru(b) * 1.0000005f);
     }
-    red[tid] = bmax;
+    const int cnt = (mode == 1 && c < k) ? st.n[c] : 0;
+    double b = 0.0;
+    half8 hi8, lo8;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int j = 8 * g + i;
+        double m = 0.0;
+        if (c < k && j < d) {
+            double mu;
+            if (mode == 0) {
+                if (a.init_mode == 0) mu = (double)a.X[(int64_t)j * a.ld + r0 + a.init_rows[(int64_t)t * a.kmax + c]];
+                else mu = a.init_centroids[(crow + c) * d + j];
+                st.mu[(size_t)j * kpm + c] = mu;
+            } else if (cnt > 0) {
+                mu = (double)st.S[c * 32 + j] / (double)cnt;      // an empty cluster keeps its centroid
+                st.mu[(size_t)j * kpm + c] = mu;
+            } else {
+                mu = st.mu[(size_t)j * kpm + c];
+            }
+            m = mu - (double)o[j];
+        } else if (mode == 0 && c < k) {
+            st.mu[(size_t)j * kpm + c] = 0.0;
+        }
+        b = __builtin_fma(m, m, b);
+        const float w = (float)(-2.0 * m);
+        const _Float16 hi = (_Float16)w;
+        hi8[i] = hi;
+        lo8[i] = (_Float16)(w - (float)hi);
+    }
+    // |mu'|^2 over all knob groups of the centroid (the G lanes of a centroid are neighbours)
+#pragma unroll
+    for (int off = G / 2; off >= 1; off >>= 1) b = b + __shfl_xor(b, off, 64);
+    if (g == G - 1) {
+        // bias slot: |mu'|^2 / 256 as hi + lo; padding centroid rows get a score above all others
+        if (c < k) {
+            const float bs = (float)b * (1.0f / kBiasScale);
+            const _Float16 bh = (_Float16)bs;
+            hi8[7] = bh;
+            lo8[7] = (_Float16)(bs - (float)bh);
+        } else {
+            hi8[7] = (_Float16)kPadBiasHi;
+            lo8[7] = (_Float16)0.0f;
+        }
+    }
+    const int hh = g & 1, fstep = g >> 1;
+    st.afrag[(mt * 4 + fstep) * 64 + 32 * hh + m32] = hi8;
+    st.afrag[(mt * 4 + NS + fstep) * 64 + 32 * hh + m32] = lo8;
+
+    float bmax = c < k ? __double2float_ru(b) * 1.0000005f : 0.0f;
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) bmax = __builtin_fmaxf(bmax, __shfl_xor(bmax, off, 64));
+    if ((tid & 63) == 0) red[tid >> 6] = bmax;
     __syncthreads();
     if (tid == 0) {
         float m = 0.0f;
-        for (int i = 0; i < (int)blockDim.x; ++i) m = __builtin_fmaxf(m, red[i]);
-        a.m2[u] = m;
+        for (int i = 0; i < (int)(blockDim.x + 63) / 64; ++i) m = __builtin_fmaxf(m, red[i]);
+        a.m2[u * kM2Tiles + mt] = m;
     }
 }
 
@@ -234,7 +258,10 @@ struct StreamLds {
     double *red;         // [8]
     unsigned char *wave_base;
     // per wave: knob values of queued rows, their row slots, resolved labels, labels of the step
-    static constexpr size_t kWaveBytes = (size_t)kStreamRec * DK * 2 + 128 * 2 + 128 + 128 + 128 * 4;
+    // ... and for the exact evaluation of queued rows: (record, centroid) pairs, per record the
+    // smallest distance (bits) and the lowest centroid attaining it, the pair counter
+    static constexpr size_t kWaveBytes = (size_t)kStreamRec * DK * 2 + 128 * 2 + 128 + 128 + 128 * 4 +
+                                         kPairCap * 2 + 128 * 8 + 128 * 4 + 16;
     __host__ __device__ static size_t bytes(int kpm)
     {
         size_t b = 16 * (size_t)(kpm / 32) * 4 * 64 + sizeof(int) * (size_t)kpm * DK + sizeof(int) * kpm +
@@ -267,13 +294,22 @@ __global__ __launch_bounds__(512) void stream_assign_kernel(const StreamArgs a)
     const int n32 = lane & 31;
     const int h = lane >> 5;
 
-    if (tid == 0) {
-        int lo = 0, hi = a.n_units;            // last unit with wg_off[unit] <= blockIdx.x
+    if (tid < 64) {
+        // last unit with wg_off[unit] <= blockIdx.x: a 64-way search by the first wave (one or two
+        // rounds of independent loads instead of a chain of dependent ones)
+        int lo = 0, hi = a.n_units;
         while (hi - lo > 1) {
-            const int mid = (lo + hi) >> 1;
-            if (a.wg_off[mid] <= (int)blockIdx.x) lo = mid; else hi = mid;
+            const int span = hi - lo;
+            const int stride = (span + 63) / 64;
+            const int probe = lo + tid * stride;
+            const bool le = probe < hi && a.wg_off[probe] <= (int)blockIdx.x;     // true for a prefix of the lanes
+            const int cntle = __popcll(__ballot(le));                              // >= 1: wg_off[lo] <= blockIdx.x
+            const int nlo = lo + (cntle - 1) * stride;
+            const int nhi = nlo + stride < hi ? nlo + stride : hi;
+            lo = nlo;
+            hi = nhi;
         }
-        unit_sh = lo;
+        if (tid == 0) unit_sh = lo;
     }
     __syncthreads();
     const int wgi = blockIdx.x - a.wg_off[unit_sh];
@@ -282,20 +318,26 @@ __global__ __launch_bounds__(512) void stream_assign_kernel(const StreamArgs a)
     const int t = u % a.T;
     const int k = a.ks[ki];
     const int d = a.d;
-    const float m2 = a.m2[u];
-    if (m2 < 0.0f) return;                     // unusable unit (fewer than k distinct rows)
     const int kpm = a.kpm;
     const int kpu = (k + 31) & ~31;
+    float m2 = a.m2[u * kM2Tiles];
+    if (m2 < 0.0f) return;                     // unusable unit (fewer than k distinct rows)
+    for (int i = 1; i < kpu / 32; ++i) m2 = __builtin_fmaxf(m2, a.m2[u * kM2Tiles + i]);
     const UnitState st = unit_state(a, u);
     StreamLds<DK> L(smem, kpm);
 
     const int64_t t0 = a.task_off[t], t1 = a.task_off[t + 1];
-    const int64_t r0 = t0 + (int64_t)wgi * a.rows_per_wg;
-    const int64_t r1 = (r0 + a.rows_per_wg < t1) ? r0 + a.rows_per_wg : t1;
+    const int64_t rpw = stream_rows_per_wg(k);
+    const int64_t r0 = t0 + (int64_t)wgi * rpw;
+    const int64_t r1 = (r0 + rpw < t1) ? r0 + rpw : t1;
     uint8_t *labrow = a.labbuf + (int64_t)ki * a.ld;
     const bool first = a.it == 0;
     const bool want_dist = a.final_pass || (a.trace != nullptr);
 
+#ifdef CHAM_KERNEL_TIMING
+    unsigned long long sacc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+#endif
+    STR_T(t_w0);
     for (int e = tid; e < (kpu / 32) * 4 * 64; e += blockDim.x) L.afrag[e] = st.afrag[e];
     for (int e = tid; e < k * DK; e += blockDim.x) L.S[e] = 0;
     for (int c = tid; c < k; c += blockDim.x) L.n[c] = 0;
@@ -308,6 +350,10 @@ __global__ __launch_bounds__(512) void stream_assign_kernel(const StreamArgs a)
     unsigned char *lab_res = wb + (size_t)kStreamRec * DK * 2 + 256;                              // [128]
     unsigned char *lab_new = lab_res + 128;                                                        // [128]
     unsigned *chg = reinterpret_cast<unsigned *>(lab_new + 128);                                   // [128] cur | prev << 8 | first << 16
+    unsigned short *pairs = reinterpret_cast<unsigned short *>(chg + 128);                         // [kPairCap] record << 8 | centroid
+    unsigned long long *best_bits = reinterpret_cast<unsigned long long *>(pairs + kPairCap);      // [128]
+    int *best_c = reinterpret_cast<int *>(best_bits + 128);                                        // [128]
+    unsigned *npairs = reinterpret_cast<unsigned *>(best_c + 128);
 
     const _Float16 *xh = reinterpret_cast<const _Float16 *>(a.xh);
     const int nch = (k + 63) >> 6;
@@ -344,8 +390,11 @@ __global__ __launch_bounds__(512) void stream_assign_kernel(const StreamArgs a)
 
     StepRows nxt;
     if (r0 < r1) load_step(r0 + (int64_t)wave * kTiles * 32, nxt);
+    STR_T(t_w1);
+    STR_ADD(0, t_w0, t_w1);      // set-up
     for (int64_t base = r0; base < r1; base += step_rows) {
         const int64_t wrow0 = base + (int64_t)wave * kTiles * 32;      // first row of this wave's step
+        STR_T(t_s0);
         const StepRows cur = nxt;
         if (base + step_rows < r1) load_step(wrow0 + step_rows, nxt);  // next step's rows load under this step
         if (wrow0 >= r1) continue;                                      // wave-uniform
@@ -353,12 +402,17 @@ __global__ __launch_bounds__(512) void stream_assign_kernel(const StreamArgs a)
 #pragma unroll
         for (int tt = 0; tt < kTiles; ++tt) live[tt] = (wrow0 + tt * 32 + n32) < r1;
 
+        constexpr int kMaxCh = 4;                    // chunks of 64 centroids, k <= 256
         int cnt[kTiles], candq[kTiles];
+        uint32_t cmask[kTiles][kMaxCh];             // candidate centroids of this lane half, per chunk
 #pragma unroll
         for (int tt = 0; tt < kTiles; ++tt) {
             cnt[tt] = 0;
             candq[tt] = 0;
+#pragma unroll
+            for (int ch = 0; ch < kMaxCh; ++ch) cmask[tt][ch] = 0u;
         }
+        if (lane == 0) *npairs = 0u;
         auto load_a = [&](int ch, bool has1, half8 (&A0)[NS2], half8 (&A1)[NS2]) {
 #pragma unroll
             for (int s = 0; s < NS2; ++s) {
@@ -407,6 +461,7 @@ __global__ __launch_bounds__(512) void stream_assign_kernel(const StreamArgs a)
                 const uint32_t cand = ~far;
                 cnt[tt] = __popc(cand);
                 candq[tt] = __clz((int)cand) & 31;
+                cmask[tt][0] = cand;
             }
         } else {
             // One sweep over the chunks of 64 centroids.  Every chunk leaves its own minimum (over both
@@ -415,7 +470,6 @@ __global__ __launch_bounds__(512) void stream_assign_kernel(const StreamArgs a)
             // within the bound of the overall minimum are all among them (their chunk's minimum is
             // no larger than their score), at worst joined by some up to two bounds away, which
             // only sends a few more rows to the exact evaluation.
-            constexpr int kMaxCh = 4;                    // k <= 256
             float bch[kTiles][kMaxCh];
             uint32_t mch[kTiles][kMaxCh];
             float bnd[kTiles];
@@ -463,14 +517,19 @@ __global__ __launch_bounds__(512) void stream_assign_kernel(const StreamArgs a)
                     const uint32_t cand = bch[tt][ch] <= lim ? mch[tt][ch] : 0u;
                     cnt[tt] += __popc(cand);
                     candq[tt] = cand ? (ch * 32 + __clz((int)cand)) : candq[tt];
+                    cmask[tt][ch] = cand;
                 }
             }
         }
 
+        STR_T(t_s1);
+        STR_ADD(1, t_s0, t_s1);      // sweep
         // decide, or queue for the exact evaluation
         int lab[kTiles];
         uint32_t flagged_mask = 0;
         int nrec = 0;
+        bool no_candidate = false;          // a queued row without any candidate (cannot happen with a valid bound)
+        __builtin_amdgcn_wave_barrier();    // the pair counter is zero
 #pragma unroll
         for (int tt = 0; tt < kTiles; ++tt) {
             unsigned c_lo, c_hi, q_lo, q_hi;
@@ -492,11 +551,84 @@ __global__ __launch_bounds__(512) void stream_assign_kernel(const StreamArgs a)
                             *reinterpret_cast<half8 *>(rec_x + (size_t)rs * DK + 16 * f + 8 * h) = cur.B[tt][f];
                     }
                     if (h == 0) rec_slot[rs] = (unsigned short)(tt * 32 + n32);
+                    // this lane half's candidates of the row join the list of (record, centroid) pairs
+                    unsigned pos = atomicAdd(npairs, (unsigned)cnt[tt]);
+#pragma unroll
+                    for (int ch = 0; ch < kMaxCh; ++ch) {
+                        uint32_t m = cmask[tt][ch];
+                        while (m) {
+                            const int q = __clz((int)m);
+                            m &= ~(0x80000000u >> q);
+                            if (pos < (unsigned)kPairCap)
+                                pairs[pos] = (unsigned short)((rs << 8) | (64 * ch + centroid_of(q, h)));
+                            ++pos;
+                        }
+                    }
                 }
+                no_candidate = no_candidate || (flagged && total == 0);
                 nrec += __popcll(fm);
             }
         }
-        if (nrec) {
+        __builtin_amdgcn_wave_barrier();
+        STR_T(t_s2);
+        STR_ADD(2, t_s1, t_s2);      // decide
+        const unsigned np = nrec ? *npairs : 0u;
+        const bool full_eval = nrec && (np > (unsigned)kPairCap || __ballot(no_candidate) != 0ull);
+        if (nrec && !full_eval) {
+            // Exact evaluation of the queued rows against their candidates only: one lane per
+            // (row, centroid) pair, the distance as sum_j ((double)x_j - mu_j)^2 with j ascending;
+            // per row the smallest distance, then the lowest centroid attaining it.
+            for (int r = lane; r < nrec; r += 64) {
+                best_bits[r] = ~0ull;
+                best_c[r] = 0x7fffffff;
+            }
+            __builtin_amdgcn_wave_barrier();
+            unsigned long long mine[kPairCap / 64];
+            int mine_rc[kPairCap / 64];
+#pragma unroll
+            for (int rd = 0; rd < kPairCap / 64; ++rd) {
+                const unsigned p = rd * 64 + lane;
+                mine[rd] = ~0ull;
+                mine_rc[rd] = -1;
+                if (p < np) {
+                    const int pr = pairs[p];
+                    const int r = pr >> 8, c = pr & 0xFF;
+                    const int sl = rec_slot[r];
+                    double sd = 0.0;
+                    for (int j0 = 0; j0 < d; j0 += 8) {
+                        double mu[8];
+                        half8 xq;
+                        if (r < kStreamRec) xq = *reinterpret_cast<const half8 *>(rec_x + (size_t)r * DK + j0);
+                        else xq = *reinterpret_cast<const half8 *>(xh + (wrow0 + sl) * DK + j0);
+#pragma unroll
+                        for (int i = 0; i < 8; ++i) mu[i] = (j0 + i < d) ? st.mu[(size_t)(j0 + i) * kpm + c] : 0.0;
+#pragma unroll
+                        for (int i = 0; i < 8; ++i) {
+                            if (j0 + i < d) {
+                                const double tq = (double)((float)xq[i] + L.ojf[j0 + i]) - mu[i];
+                                sd = sd + tq * tq;
+                            }
+                        }
+                    }
+                    mine[rd] = (unsigned long long)__double_as_longlong(sd);
+                    mine_rc[rd] = pr;
+                    atomicMin(&best_bits[r], mine[rd]);
+                }
+            }
+            __builtin_amdgcn_wave_barrier();
+#pragma unroll
+            for (int rd = 0; rd < kPairCap / 64; ++rd) {
+                if (mine_rc[rd] >= 0 && best_bits[mine_rc[rd] >> 8] == mine[rd])
+                    atomicMin(&best_c[mine_rc[rd] >> 8], mine_rc[rd] & 0xFF);
+            }
+            __builtin_amdgcn_wave_barrier();
+            for (int r = lane; r < nrec; r += 64) {
+                const int bc = best_c[r];
+                lab_res[rec_slot[r]] = (unsigned char)(bc < k ? bc : 0);
+            }
+            __builtin_amdgcn_wave_barrier();
+        }
+        if (nrec && full_eval) {
             // exact evaluation of the queued rows against all k centroids, one centroid per lane;
             // the centroid loads of 8 knobs are issued together
             __builtin_amdgcn_wave_barrier();
@@ -538,6 +670,12 @@ __global__ __launch_bounds__(512) void stream_assign_kernel(const StreamArgs a)
             __builtin_amdgcn_wave_barrier();
         }
 
+        STR_T(t_s3);
+        STR_ADD(3, t_s2, t_s3);      // exact evaluation
+#ifdef CHAM_KERNEL_TIMING
+        sacc[6] += (unsigned long long)nrec;
+        sacc[7] += 1;
+#endif
         // label changes -> sums of this workgroup (LDS), tile by tile
 #pragma unroll
         for (int tt = 0; tt < kTiles; ++tt) {
@@ -588,6 +726,8 @@ __global__ __launch_bounds__(512) void stream_assign_kernel(const StreamArgs a)
             }
         }
 
+        STR_T(t_s4);
+        STR_ADD(4, t_s3, t_s4);      // sums
         if (want_dist) {
             // exact loss terms of the rows of this step: one row per lane, knobs ascending
             __builtin_amdgcn_wave_barrier();
@@ -611,6 +751,7 @@ __global__ __launch_bounds__(512) void stream_assign_kernel(const StreamArgs a)
         const double ws = wave_sum(part);
         if (lane == 0) L.red[wave] = ws;
     }
+    STR_T(t_w2);
     __syncthreads();
     // changes of this workgroup -> the unit's sums
     for (int e = tid; e < k * DK; e += blockDim.x) {
@@ -626,6 +767,14 @@ __global__ __launch_bounds__(512) void stream_assign_kernel(const StreamArgs a)
         for (int w = 0; w < kWavesPerWg; ++w) s = s + (w < (int)(blockDim.x >> 6) ? L.red[w] : 0.0);
         a.loss_part[blockIdx.x] = s;
     }
+#ifdef CHAM_KERNEL_TIMING
+    {
+        const unsigned long long t_w3 = __builtin_readcyclecounter();
+        sacc[5] += t_w3 - t_w2;      // barrier + flush
+        if (lane == 0)
+            for (int q = 0; q < 8; ++q) atomicAdd(&g_stream_timing[((nch - 1) & 3) * 8 + q], sacc[q]);
+    }
+#endif
 }
 
 template <int DK>
@@ -642,17 +791,27 @@ hipError_t run_stream(StreamArgs a, int64_t n_total, int total_wgs, hipStream_t 
     }
     a.it = 0;
     a.final_pass = 0;
-    hipLaunchKernelGGL(stream_update_kernel<DK>, dim3(a.n_units), dim3(256), 0, s, a, 0);
+    const dim3 ugrid(a.n_units, a.kpm / 32), ublock(32 * (DK / 8));
+    hipLaunchKernelGGL(stream_update_kernel<DK>, ugrid, ublock, 0, s, a, 0);
     for (int it = 0; it <= a.n_iter; ++it) {
         a.it = it;
         a.final_pass = it == a.n_iter ? 1 : 0;
         hipLaunchKernelGGL(stream_assign_kernel<DK>, dim3(total_wgs), dim3(kWavesPerWg * 64), lds, s, a);
-        hipLaunchKernelGGL(stream_update_kernel<DK>, dim3(a.n_units), dim3(256), 0, s, a, a.final_pass ? 2 : 1);
+        hipLaunchKernelGGL(stream_update_kernel<DK>, ugrid, ublock, 0, s, a, a.final_pass ? 2 : 1);
     }
     return hipGetLastError();
 }
 
 }  // namespace
+
+#ifdef CHAM_KERNEL_TIMING
+extern "C" int cham_dev_stream_timing(unsigned long long *host32, int reset)
+{
+    unsigned long long z[32] = {0};
+    if (reset) return (int)hipMemcpyToSymbol(HIP_SYMBOL(g_stream_timing), z, sizeof(z));
+    return (int)hipMemcpyFromSymbol(host32, HIP_SYMBOL(g_stream_timing), sizeof(z));
+}
+#endif
 
 int64_t stream_lds_bytes(int d, int kpm)
 {
