@@ -420,12 +420,9 @@ __global__ __launch_bounds__(512) void stream_assign_kernel(const StreamArgs a)
                 A1[s] = has1 ? L.afrag[((2 * ch + 1) * 4 + s) * 64 + lane] : A0[s];
             }
         };
-        auto chain = [&](const half8 (&Af)[NS2], const half8 (&Bt)[NS]) {
-            float16v acc = zero16;
-#pragma unroll
-            for (int s = 0; s < NS2; ++s)
-                acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(Af[s], Bt[s % NS], acc, 0, 0, 0);
-            return acc;
+        // one matrix instruction of the chain of a 32x32 tile
+        auto mma = [&](float16v &acc, const half8 (&Af)[NS2], const half8 (&Bt)[NS], int s) {
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(Af[s], Bt[s % NS], s == 0 ? zero16 : acc, 0, 0, 0);
         };
         auto min16 = [&](const float16v &acc) {
             float m = min3f(acc[0], acc[1], acc[2]);
@@ -433,92 +430,106 @@ __global__ __launch_bounds__(512) void stream_assign_kernel(const StreamArgs a)
             for (int i = 3; i < 15; i += 2) m = min3f(m, acc[i], acc[i + 1]);
             return __builtin_fminf(m, acc[15]);
         };
-        auto mark16 = [&](uint32_t far, const float16v &acc, float thr) {
+        // mark scores [i0, i0 + CH): bit set = above the threshold
+        constexpr int CH = 16 / NS2;
+        auto mark = [&](uint32_t &far, const float16v &acc, float thr, int i0) {
 #pragma unroll
-            for (int i = 0; i < 16; ++i)
-                far = __builtin_amdgcn_alignbit(far, __float_as_uint(thr - acc[i]), 31);
-            return far;
+            for (int i = 0; i < CH; ++i)
+                far = __builtin_amdgcn_alignbit(far, __float_as_uint(thr - acc[i0 + i]), 31);
         };
 
-        if (nch == 1) {
-            // at most 64 centroids: one sweep, the scores stay in registers between minimum and marking
-            const bool has1 = 32 < kpu;
-            half8 A0[NS2], A1[NS2];
-            load_a(0, has1, A0, A1);
+        // One sweep over the chunks of 64 centroids.  Every chunk leaves its own minimum (over both
+        // lane halves) and the marks within the bound of that minimum; afterwards a chunk's marks
+        // count iff its minimum lies within the bound of the overall minimum.  The centroids
+        // within the bound of the overall minimum are all among them (their chunk's minimum is
+        // no larger than their score), at worst joined by some up to two bounds away, which
+        // only sends a few more rows to the exact evaluation.  Within a chunk the tiles are
+        // pipelined: the chain of the next tile is issued under the marking of the current one.
+        float bch[kTiles][kMaxCh];
+        float bnd[kTiles];
 #pragma unroll
-            for (int tt = 0; tt < kTiles; ++tt) {
-                const float16v acc0 = chain(A0, cur.B[tt]);
-                float16v acc1 = zero16;
-                float m = min16(acc0);
+        for (int tt = 0; tt < kTiles; ++tt) bnd[tt] = mfma_bound<NS2>(cur.x2[tt], m2);
+#pragma unroll
+        for (int ch = 0; ch < kMaxCh; ++ch) {
+            if (ch < nch) {
+                const bool has1 = (2 * ch + 1) * 32 < kpu;
+                half8 A0[NS2], A1[NS2];
+                load_a(ch, has1, A0, A1);
+                float16v accA, accB;
+                constexpr int kLast = kTiles - 1;
                 if (has1) {
-                    acc1 = chain(A1, cur.B[tt]);
-                    m = __builtin_fminf(m, min16(acc1));
-                }
-                const float thr = min_halves(m) + mfma_bound<NS2>(cur.x2[tt], m2);
-                uint32_t far = mark16(0, acc0, thr);
-                if (has1) far = mark16(far, acc1, thr);
-                else far = (far << 16) | 0xFFFFu;
-                const uint32_t cand = ~far;
-                cnt[tt] = __popc(cand);
-                candq[tt] = __clz((int)cand) & 31;
-                cmask[tt][0] = cand;
-            }
-        } else {
-            // One sweep over the chunks of 64 centroids.  Every chunk leaves its own minimum (over both
-            // lane halves) and the marks within the bound of that minimum; afterwards a chunk's marks
-            // count iff its minimum lies within the bound of the overall minimum.  The centroids
-            // within the bound of the overall minimum are all among them (their chunk's minimum is
-            // no larger than their score), at worst joined by some up to two bounds away, which
-            // only sends a few more rows to the exact evaluation.
-            float bch[kTiles][kMaxCh];
-            uint32_t mch[kTiles][kMaxCh];
-            float bnd[kTiles];
+                    // accA = centroids 0..31, accB = centroids 32..63 of the chunk
 #pragma unroll
-            for (int tt = 0; tt < kTiles; ++tt) bnd[tt] = mfma_bound<NS2>(cur.x2[tt], m2);
+                    for (int s = 0; s < NS2; ++s) mma(accA, A0, cur.B[0], s);
 #pragma unroll
-            for (int ch = 0; ch < kMaxCh; ++ch) {
-                if (ch < nch) {
-                    const bool has1 = (2 * ch + 1) * 32 < kpu;
-                    half8 A0[NS2], A1[NS2];
-                    load_a(ch, has1, A0, A1);
+                    for (int s = 0; s < NS2; ++s) mma(accB, A1, cur.B[0], s);
 #pragma unroll
                     for (int tt = 0; tt < kTiles; ++tt) {
-                        const float16v acc0 = chain(A0, cur.B[tt]);
-                        float16v acc1 = zero16;
-                        float m = min16(acc0);
-                        if (has1) {
-                            acc1 = chain(A1, cur.B[tt]);
-                            m = __builtin_fminf(m, min16(acc1));
-                        }
-                        m = min_halves(m);
+                        const int nx = tt < kLast ? tt + 1 : tt;
+                        const float m = min_halves(__builtin_fminf(min16(accA), min16(accB)));
                         const float thr = m + bnd[tt];
-                        uint32_t far = mark16(0, acc0, thr);
-                        if (has1) far = mark16(far, acc1, thr);
-                        else far = (far << 16) | 0xFFFFu;
+                        uint32_t far = 0;
+#pragma unroll
+                        for (int s = 0; s < NS2; ++s) mark(far, accA, thr, s * CH);
+                        // accA is consumed: its next chain runs under the marking of accB
+#pragma unroll
+                        for (int s = 0; s < NS2; ++s) {
+                            __builtin_amdgcn_sched_barrier(0);
+                            if (tt < kLast) mma(accA, A0, cur.B[nx], s);
+                            __builtin_amdgcn_sched_barrier(0);
+                            mark(far, accB, thr, s * CH);
+                        }
+                        __builtin_amdgcn_sched_barrier(0);
+                        if (tt < kLast) {
+#pragma unroll
+                            for (int s = 0; s < NS2; ++s) mma(accB, A1, cur.B[nx], s);
+                        }
                         bch[tt][ch] = m;
-                        mch[tt][ch] = ~far;
+                        cmask[tt][ch] = ~far;
+                        __builtin_amdgcn_sched_barrier(0);
                     }
                 } else {
+                    // one block of 32 centroids: the accumulators alternate
+#pragma unroll
+                    for (int s = 0; s < NS2; ++s) mma(accA, A0, cur.B[0], s);
 #pragma unroll
                     for (int tt = 0; tt < kTiles; ++tt) {
-                        bch[tt][ch] = __builtin_inff();
-                        mch[tt][ch] = 0u;
+                        const int nx = tt < kLast ? tt + 1 : tt;
+                        float16v &now = (tt & 1) ? accB : accA;
+                        float16v &nxt2 = (tt & 1) ? accA : accB;
+                        const float m = min_halves(min16(now));
+                        const float thr = m + bnd[tt];
+                        uint32_t far = 0;
+#pragma unroll
+                        for (int s = 0; s < NS2; ++s) {
+                            __builtin_amdgcn_sched_barrier(0);
+                            if (tt < kLast) mma(nxt2, A0, cur.B[nx], s);
+                            __builtin_amdgcn_sched_barrier(0);
+                            mark(far, now, thr, s * CH);
+                        }
+                        __builtin_amdgcn_sched_barrier(0);
+                        bch[tt][ch] = m;
+                        cmask[tt][ch] = ~((far << 16) | 0xFFFFu);
+                        __builtin_amdgcn_sched_barrier(0);
                     }
                 }
+            } else {
+#pragma unroll
+                for (int tt = 0; tt < kTiles; ++tt) bch[tt][ch] = __builtin_inff();
             }
+        }
 #pragma unroll
-            for (int tt = 0; tt < kTiles; ++tt) {
-                float best = bch[tt][0];
+        for (int tt = 0; tt < kTiles; ++tt) {
+            float best = bch[tt][0];
 #pragma unroll
-                for (int ch = 1; ch < kMaxCh; ++ch) best = __builtin_fminf(best, bch[tt][ch]);
-                const float lim = best + bnd[tt];
+            for (int ch = 1; ch < kMaxCh; ++ch) best = __builtin_fminf(best, bch[tt][ch]);
+            const float lim = best + bnd[tt];
 #pragma unroll
-                for (int ch = 0; ch < kMaxCh; ++ch) {
-                    const uint32_t cand = bch[tt][ch] <= lim ? mch[tt][ch] : 0u;
-                    cnt[tt] += __popc(cand);
-                    candq[tt] = cand ? (ch * 32 + __clz((int)cand)) : candq[tt];
-                    cmask[tt][ch] = cand;
-                }
+            for (int ch = 0; ch < kMaxCh; ++ch) {
+                const uint32_t cand = bch[tt][ch] <= lim ? cmask[tt][ch] : 0u;
+                cnt[tt] += __popc(cand);
+                candq[tt] = cand ? (ch * 32 + __clz((int)cand)) : candq[tt];
+                cmask[tt][ch] = cand;
             }
         }
 
