@@ -51,7 +51,7 @@ inline size_t resident_lds_bytes(int DP, int kmax, int sum_bytes = 4)
 
 // Rows one workgroup of the streaming assignment kernel walks, by the unit's k.  (Measured on the
 // large single-task workload: 2048 or 16384 rows for k <= 64 are both slower than 4096.)
-__host__ __device__ inline int stream_rows_per_wg(int k) { return k <= 256 ? 4096 : 4096; }
+__host__ __device__ inline int stream_rows_per_wg(int /*k*/) { return 4096; }
 
 // Arguments of the streaming sweep kernels (tasks too large for one workgroup).
 struct StreamArgs {
