@@ -169,6 +169,14 @@ def test_knee_sweep_and_the_visited_table():
             assert tuple(r) not in returned
 
 
+def test_a_task_far_larger_than_one_workgroup_pass():
+    """40 000 rows in one task: the two-byte path keeps one workgroup per (task, k) and per task in the
+    snap and synthesis steps, walking the rows in several passes."""
+    wl = workloads.wide_space(8, n_tasks=2, n=40000, d=9, ks=(3, 12, 31), n_iter=5, ragged=True, n_visited=2048)
+    assert int(np.diff(wl.task_off).max()) > 16384
+    _full(wl, threshold=1.2)
+
+
 def test_limits_are_reported():
     import torch
     wl = workloads.wide_space(7, n_tasks=1, n=300, d=64, ks=(2, 126), n_iter=2)
