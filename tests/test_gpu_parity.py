@@ -611,3 +611,28 @@ def test_configuration_updater_matches_the_oracle(B, d, steps, card_hi):
     binding.cham_update_configs(th2, torch.from_numpy(actions).to(dev), cards_dev)
     torch.cuda.synchronize()
     np.testing.assert_array_equal(th2.cpu().numpy(), final)
+
+
+def test_bench_prints_one_json_line_with_the_contract_fields():
+    """bench.py on the smallest workload: one JSON line on stdout carrying the metric, the roofline
+    object and the oracle baseline."""
+    import json
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--cfg", "2", "--steps", "2", "--warmup", "1",
+                        "--knee-chunk", "4", "--no-wide-knobs"], capture_output=True, text=True, timeout=600)
+    assert r.returncode == 0, r.stderr[-2000:]
+    lines = [ln for ln in r.stdout.splitlines() if ln.strip()]
+    assert len(lines) == 1
+    d = json.loads(lines[0])
+    for key in ("metric", "value", "unit", "n_gpus", "steps", "warmup", "ms_per_step", "higher_is_better", "scaling",
+                "vs_baseline", "dtype", "data", "config", "roofline", "cpu_baseline"):
+        assert key in d, key
+    assert d["n_gpus"] == 1 and d["steps"] == 2 and d["warmup"] == 1 and d["vs_baseline"] is None
+    assert d["value"] > 0 and d["unit"] == "evals/s" and "workload" in d["config"]
+    rf = d["roofline"]
+    assert rf["bound"] in ("hbm", "mfma", "alu") and rf["peak"] > 0 and abs(rf["frac"] - rf["achieved"] / rf["peak"]) < 1e-3
+    cb = d["cpu_baseline"]
+    assert cb["kind"] == "oracle" and cb["cores"] >= 1 and cb["value"] > 0 and cb["sample"]
