@@ -3,7 +3,10 @@
 
 One step = one pass of the whole path (k-means sweep over every k, knee selection, centroid
 snap, Sample Synthesis + dedupe) over one batch of synthetic tuning tasks that is already
-resident in HBM.  Prints ONE JSON line (see the design doc for how each figure is derived).
+resident in HBM.  Prints ONE JSON line: value = nominal distance evaluations (rows x sum of k x
+(Lloyd steps + 1)) per second of the whole step; roofline.achieved = evaluations x (2d + 2) flops
+over the sweep call's duration (HIP events on the launch stream) against the peak of the unit the
+dominant kernel runs on; cpu_baseline = the CPU oracle timed on a sample of the same workload.
 """
 import argparse
 import json
