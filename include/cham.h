@@ -23,10 +23,16 @@
  *     host memory that is read before the call returns.  The caller owns every buffer and
  *     keeps device buffers alive until the stream has run the call.
  *   - Work is enqueued on `stream` (a hipStream_t passed as void*, NULL = default
- *     stream); calls do not synchronise.  Small HOST arrays are copied into the
- *     workspace with an asynchronous copy on that stream.
+ *     stream); calls do not synchronise.  Small HOST arrays are read before the call
+ *     returns: they travel to the workspace inside the arguments of small staging kernels
+ *     launched on that stream (no host buffer has to outlive the call).
  *   - Every function returns CHAM_OK or a negative error; on an argument error nothing
- *     is enqueued and no output is written.  Functions never throw or abort.
+ *     is enqueued and no output is written.  Functions never throw or abort; the only
+ *     host memory they may take is a malloc'd table for batches of more than about a
+ *     thousand tasks (CHAM_E_NOMEM if that fails).
+ *   - The library keeps no state between calls except the code of the last failed HIP call,
+ *     which is thread-local (cham_last_hip_error), and the static scratch buffer of
+ *     cham_kmeans_sweep_static.
  *   - ks is strictly increasing, 1 <= k <= 256.  Ksum = sum(ks), koff[i] = ks[0]+..+ks[i-1],
  *     k_max = ks[n_k-1].
  *   - Integer outputs are exact and reproducible run to run; floating-point outputs are
@@ -50,6 +56,8 @@ extern "C" {
 #define CHAM_E_WORKSPACE    (-6)   /* workspace NULL or smaller than cham_*_workspace_bytes says */
 #define CHAM_E_HIP          (-7)   /* a HIP runtime call failed; see cham_last_hip_error() */
 #define CHAM_E_BAD_FLAG     (-8)   /* unknown bits in flags / unknown init_mode */
+#define CHAM_E_NOMEM        (-9)   /* host memory for the call's small tables could not be had */
+#define CHAM_E_TOO_LARGE    (-10)  /* the input exceeds a fixed limit of the entry point */
 
 /* values of out_flag (cham_synthesize) */
 #define CHAM_OUT_EMPTY   0   /* cluster has no member (or index >= chosen k) */
@@ -110,6 +118,36 @@ int32_t cham_kmeans_sweep(const uint8_t *X, int64_t ld, int32_t d,
                           double *centroids, int32_t *counts, double *inertia, int32_t *status,
                           uint8_t *labels, double *inertia_trace,
                           void *workspace, int64_t workspace_bytes, int32_t flags, void *stream);
+
+/*
+ * Which kernel family cham_kmeans_sweep runs for these arguments (all HOST), or a negative error:
+ * the choice depends only on d, the largest task, the largest k and flags (Sec. 3.3's k-means,
+ * "K-means.run" of Algorithm 1, is the same computation on every path).
+ *   CHAM_PATH_RESIDENT_MFMA    one workgroup per (task, k), distances on the matrix cores
+ *                              (d <= 29, tasks of at most 4096 rows, k <= 64)
+ *   CHAM_PATH_STREAM_MFMA      several workgroups per (task, k), one launch pair per pass (d <= 31)
+ *   CHAM_PATH_RESIDENT_VECTOR  one workgroup per (task, k), vector ALU
+ * cham_sweep_path_kernel gives the name of the family's dominant kernel (a static string).
+ */
+#define CHAM_PATH_RESIDENT_MFMA   0
+#define CHAM_PATH_STREAM_MFMA     1
+#define CHAM_PATH_RESIDENT_VECTOR 2
+int32_t     cham_sweep_path(int64_t ld, int32_t d, const int64_t *task_off, int32_t T,
+                            const int32_t *ks, int32_t n_k, int32_t flags);
+const char *cham_sweep_path_kernel(int32_t path);
+
+/*
+ * Labelling passes the last sweep that used `workspace` really ran, per (task, k): passes
+ * [T][n_k] int32 DEVICE.  Algorithm 1's K-means.run is n_iter update steps plus the final
+ * labelling, n_iter + 1 passes; a pass that changes no label leaves sums, centroids and every
+ * later pass unchanged, so a kernel may stop there with the results of the full iteration
+ * (the matrix-core resident kernel does; the figure is what a throughput in executed distance
+ * evaluations is computed from).  0 for a (task, k) that was skipped (status 1 or 3).  The
+ * arguments other than passes are those of the sweep call; works for both knob widths.
+ */
+int32_t cham_sweep_passes(const void *workspace, int64_t workspace_bytes, int64_t ld, int32_t d,
+                          const int64_t *task_off, int32_t T, const int32_t *ks, int32_t n_k, int32_t flags,
+                          int32_t *passes, void *stream);
 
 /*
  * K-means sweep that stops at the knee, the loop of Algorithm 1 as printed: for k in the list,

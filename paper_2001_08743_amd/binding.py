@@ -24,7 +24,7 @@ EXPORTS = [
     "cham_snap_centroids", "cham_synth_workspace_bytes", "cham_synthesize", "cham_hash_config",
     "cham_hash_rows", "cham_sweep_knee_workspace_bytes", "cham_kmeans_sweep_knee", "cham_synthesize_table",
     "cham_visited_table_clear", "cham_visited_table_insert_hashes", "cham_visited_table_insert_configs",
-    "cham_update_configs",
+    "cham_update_configs", "cham_sweep_path", "cham_sweep_path_kernel", "cham_sweep_passes",
     "cham_sweep_workspace_bytes_u16", "cham_kmeans_sweep_u16", "cham_sweep_knee_workspace_bytes_u16",
     "cham_kmeans_sweep_knee_u16", "cham_snap_workspace_bytes_u16", "cham_snap_centroids_u16",
     "cham_synth_workspace_bytes_u16", "cham_synthesize_u16", "cham_synthesize_table_u16",
@@ -56,6 +56,12 @@ def load() -> C.CDLL:
         lib.cham_kmeans_sweep.restype = i32
         lib.cham_kmeans_sweep.argtypes = [vp, i64, i32, vp, i32, vp, i32, i32, i32, vp,
                                           vp, vp, vp, vp, vp, vp, vp, i64, i32, vp]
+        lib.cham_sweep_path.restype = i32
+        lib.cham_sweep_path.argtypes = [i64, i32, vp, i32, vp, i32, i32]
+        lib.cham_sweep_path_kernel.restype = C.c_char_p
+        lib.cham_sweep_path_kernel.argtypes = [i32]
+        lib.cham_sweep_passes.restype = i32
+        lib.cham_sweep_passes.argtypes = [vp, i64, i64, i32, vp, i32, vp, i32, i32, vp, vp]
         lib.cham_sweep_knee_workspace_bytes.restype = i64
         lib.cham_sweep_knee_workspace_bytes.argtypes = [i64, i32, vp, i32, vp, i32, i32, i32]
         lib.cham_kmeans_sweep_knee.restype = i32
@@ -250,6 +256,29 @@ def cham_kmeans_sweep(X, ld: int, d: int, task_off, ks: Sequence[int], n_iter: i
     out["workspace"] = workspace
     out["koff"] = np.concatenate([[0], np.cumsum(k)]).astype(np.int64)
     return out
+
+
+def cham_sweep_path(ld: int, d: int, task_off, ks, flags: int = 0) -> int:
+    to, k = _host_lists(task_off, ks)
+    return _check(load().cham_sweep_path(C.c_int64(ld), C.c_int32(d), _hp(to), C.c_int32(len(to) - 1), _hp(k),
+                                         C.c_int32(len(k)), C.c_int32(flags)))
+
+
+def cham_sweep_path_kernel(path: int) -> str:
+    return load().cham_sweep_path_kernel(C.c_int32(path)).decode()
+
+
+def cham_sweep_passes(workspace, ld: int, d: int, task_off, ks, flags: int = 0, passes=None):
+    """Labelling passes per (task, k) that the last sweep using ``workspace`` ran; device int32 [T, n_k]."""
+    torch = _torch()
+    to, k = _host_lists(task_off, ks)
+    T, n_k = len(to) - 1, len(k)
+    if passes is None:
+        passes = torch.empty((T, n_k), dtype=torch.int32, device=workspace.device)
+    _check(load().cham_sweep_passes(_dp(workspace), C.c_int64(workspace.numel()), C.c_int64(ld), C.c_int32(d),
+                                    _hp(to), C.c_int32(T), _hp(k), C.c_int32(n_k), C.c_int32(flags), _dp(passes),
+                                    _stream()))
+    return passes
 
 
 def cham_kmeans_sweep_u16(X, ld: int, d: int, task_off, ks: Sequence[int], n_iter: int, **kw):

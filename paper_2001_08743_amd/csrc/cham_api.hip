@@ -2,7 +2,8 @@
 // kernel launches for the Adaptive Sampling path (paper Sec. 3.3, Algorithm 1).
 #include "../../include/cham.h"
 
-#include <vector>
+#include <stdlib.h>
+#include <string.h>
 
 #include "cham_internal.h"
 
@@ -21,8 +22,56 @@ int32_t hip_fail(hipError_t e)
 constexpr int64_t kAlign = 256;
 inline int64_t up(int64_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
+// Growable array of 64-bit words for the small host-side tables.  The first kInline words live
+// inside the object; beyond that it takes heap memory with malloc and reports failure through its
+// return value (nothing in the library throws).  With heap use forbidden (the entry point that must
+// not allocate) a request beyond the inline part fails the same way.
+class Words {
+public:
+    static constexpr size_t kInline = 1024;
+    Words() = default;
+    Words(const Words &) = delete;
+    Words &operator=(const Words &) = delete;
+    ~Words() { free(heap_); }
+    void forbid_heap() { heap_ok_ = false; }
+    // n zero words, previous content dropped
+    bool assign(size_t n)
+    {
+        n_ = 0;
+        return resize(n);
+    }
+    // n words, the first min(n, size) kept, the rest zero
+    bool resize(size_t n)
+    {
+        if (n > cap_) {
+            if (!heap_ok_) return false;
+            size_t cap = cap_ * 2 > n ? cap_ * 2 : n;
+            uint64_t *h = static_cast<uint64_t *>(malloc(cap * sizeof(uint64_t)));
+            if (!h) return false;
+            memcpy(h, data(), n_ * sizeof(uint64_t));
+            free(heap_);
+            heap_ = h;
+            cap_ = cap;
+        }
+        if (n > n_) memset(data() + n_, 0, (n - n_) * sizeof(uint64_t));
+        n_ = n;
+        return true;
+    }
+    uint64_t *data() { return heap_ ? heap_ : inl_; }
+    const uint64_t *data() const { return heap_ ? heap_ : inl_; }
+    size_t size() const { return n_; }
+    uint64_t &operator[](size_t i) { return data()[i]; }
+    const uint64_t &operator[](size_t i) const { return data()[i]; }
+
+private:
+    uint64_t inl_[kInline];
+    uint64_t *heap_ = nullptr;
+    size_t n_ = 0, cap_ = kInline;
+    bool heap_ok_ = true;
+};
+
 // Small host arrays travel to the device inside kernel arguments (copied at launch time), so
-// no host buffer has to outlive the call and nothing is allocated.
+// no host buffer has to outlive the call and no device memory is allocated.
 constexpr int kPokeWords = 120;
 struct PokeArgs {
     uint64_t v[kPokeWords];
@@ -35,7 +84,7 @@ __global__ void poke_kernel(const PokeArgs p)
     if (i < p.n) p.dst[i] = p.v[i];
 }
 
-hipError_t stage_words(const std::vector<uint64_t> &blob, uint64_t *dst, hipStream_t s)
+hipError_t stage_words(const Words &blob, uint64_t *dst, hipStream_t s)
 {
     for (size_t o = 0; o < blob.size(); o += kPokeWords) {
         PokeArgs p;
@@ -53,7 +102,7 @@ hipError_t stage_words(const std::vector<uint64_t> &blob, uint64_t *dst, hipStre
 struct Plan {
     int T = 0, n_k = 0, Ksum = 0, kmax = 0, DP = 0, nt = 0;
     int64_t n_total = 0, n_max = 0;
-    std::vector<uint64_t> blob;
+    Words blob;
     int64_t off_task = 0, off_ks = 0, off_koff = 0, off_extra = 0;   // byte offsets in the blob
 };
 
@@ -97,7 +146,7 @@ int32_t check_common(const void *X, int64_t ld, int32_t d, const int64_t *task_o
     const size_t w_task = (size_t)T + 1;
     const size_t w_ks = ((size_t)n_k + 1) / 2;
     const size_t w_koff = ((size_t)n_k + 2) / 2;
-    pl.blob.assign(w_task + w_ks + w_koff, 0);
+    if (!pl.blob.assign(w_task + w_ks + w_koff)) return CHAM_E_NOMEM;
     for (int t = 0; t <= T; ++t) pl.blob[t] = (uint64_t)task_off[t];
     int32_t *pk = reinterpret_cast<int32_t *>(pl.blob.data() + w_task);
     for (int i = 0; i < n_k; ++i) pk[i] = ks[i];
@@ -132,7 +181,7 @@ SweepPath choose_path(const Plan &pl, int d, int flags)
 }
 
 struct SweepWs {
-    int64_t blob = 0, init_rows = 0, ndist = 0, xh = 0, labbuf = 0, total = 0;
+    int64_t blob = 0, init_rows = 0, ndist = 0, passes = 0, xh = 0, labbuf = 0, total = 0;
     // streaming path
     int64_t x2 = 0, ojf = 0, Sg = 0, ng = 0, mu = 0, afrag = 0, m2 = 0, wg_off = 0, loss = 0;
     int kpm = 0, n_units = 0, total_wgs = 0;
@@ -149,6 +198,8 @@ SweepWs sweep_ws(const Plan &pl, int64_t ld, bool own_labels, bool stream, const
     o += up((int64_t)pl.T * pl.kmax * 4);
     w.ndist = o;
     o += up((int64_t)pl.T * 4);
+    w.passes = o;
+    o += up((int64_t)pl.T * pl.n_k * 4);
     w.xh = o;
     if (need_xh) o += up(ld * 32 * 2);
     w.labbuf = o;
@@ -199,6 +250,8 @@ const char *cham_strerror(int32_t code)
     case CHAM_E_WORKSPACE: return "workspace missing or too small";
     case CHAM_E_HIP: return "HIP runtime error (see cham_last_hip_error)";
     case CHAM_E_BAD_FLAG: return "unknown flag bits or init mode";
+    case CHAM_E_NOMEM: return "out of host memory for the call's small tables";
+    case CHAM_E_TOO_LARGE: return "input needs more scratch memory than the library's static buffer holds (use the entry point that takes a workspace)";
     default: return "unknown error code";
     }
 }
@@ -207,9 +260,10 @@ const char *cham_strerror(int32_t code)
 static bool u16_fits(const Plan &pl) { return resident_lds_bytes(pl.DP, pl.kmax, 8) <= 160 * 1024; }
 
 static int64_t sweep_ws_bytes(int xbytes, int64_t ld, int32_t d, const int64_t *task_off, int32_t T,
-                              const int32_t *ks, int32_t n_k, int32_t flags)
+                              const int32_t *ks, int32_t n_k, int32_t flags, bool no_heap = false)
 {
     Plan pl;
+    if (no_heap) pl.blob.forbid_heap();
     const int32_t rc = check_common(nullptr, ld, d, task_off, T, ks, n_k, false, pl, xbytes);
     if (rc != CHAM_OK) return rc;
     if (xbytes == 2) return u16_fits(pl) ? sweep_ws(pl, ld, true, false, task_off, false).total : CHAM_E_BAD_K;
@@ -237,10 +291,11 @@ static int32_t sweep_impl(const void *Xv, int xbytes, int64_t ld, int32_t d, con
                           const double *init_centroids, double *centroids, int32_t *counts,
                           double *inertia, int32_t *status, uint8_t *labels, double *inertia_trace,
                           void *workspace, int64_t workspace_bytes, int32_t flags, void *stream,
-                          int32_t chunk, double threshold, int32_t *chosen_idx)
+                          int32_t chunk, double threshold, int32_t *chosen_idx, bool no_heap = false)
 {
     const uint8_t *X = static_cast<const uint8_t *>(Xv);
     Plan pl;
+    if (no_heap) pl.blob.forbid_heap();
     int32_t rc = check_common(X, ld, d, task_off, T, ks, n_k, true, pl, xbytes);
     if (rc != CHAM_OK) return rc;
     if (!centroids || !counts || !inertia || !status) return CHAM_E_NULL;
@@ -287,6 +342,7 @@ static int32_t sweep_impl(const void *Xv, int xbytes, int64_t ld, int32_t d, con
     a.labbuf = labels ? labels : ws + w.labbuf;
     a.trace = inertia_trace;
     a.xh = reinterpret_cast<uint16_t *>(ws + w.xh);
+    a.passes = reinterpret_cast<int *>(ws + w.passes);
     a.ki_begin = 0;
     a.ki_end = n_k;
     a.done = nullptr;
@@ -296,6 +352,9 @@ static int32_t sweep_impl(const void *Xv, int xbytes, int64_t ld, int32_t d, con
         if (e != hipSuccess) return hip_fail(e);
     }
 
+    // labelling passes per (task, k): n_iter + 1 unless the kernel records that it stopped earlier
+    e = launch_fill_i32(a.passes, (int64_t)T * n_k, n_iter + 1, s);
+    if (e != hipSuccess) return hip_fail(e);
     if (init_mode == 0) {
         e = launch_first_distinct(a, reinterpret_cast<int *>(ws + w.init_rows),
                                   reinterpret_cast<int *>(ws + w.ndist), s);
@@ -310,7 +369,9 @@ static int32_t sweep_impl(const void *Xv, int xbytes, int64_t ld, int32_t d, con
         if (path == SweepPath::kStream) {
             // first workgroup of every unit, in launch order (largest k first)
             const int n_units = (ki_end - ki_begin) * T;        // units of this chunk, largest k first
-            std::vector<uint64_t> wo(((size_t)n_units + 2) / 2, 0);
+            Words wo;
+            if (no_heap) wo.forbid_heap();
+            if (!wo.assign(((size_t)n_units + 2) / 2)) return CHAM_E_NOMEM;
             int32_t *po = reinterpret_cast<int32_t *>(wo.data());
             int acc = 0;
             for (int u = 0; u < n_units; ++u) {
@@ -361,6 +422,7 @@ static int32_t sweep_impl(const void *Xv, int xbytes, int64_t ld, int32_t d, con
             sa.afrag = ws + w.afrag;
             sa.m2 = reinterpret_cast<float *>(ws + w.m2);
             sa.loss_part = reinterpret_cast<double *>(ws + w.loss);
+            sa.passes = a.passes;
             if (stream_lds_bytes(d, w.kpm) > 160 * 1024) return CHAM_E_BAD_K;
             e = acc > 0 ? launch_stream_sweep(sa, pl.n_total, acc, s) : hipSuccess;
             if (acc == 0) e = launch_resident_sweep(a, pl.nt, s);   // all tasks empty: trivial path
@@ -400,6 +462,48 @@ int32_t cham_kmeans_sweep_u16(const uint16_t *X, int64_t ld, int32_t d, const in
 {
     return sweep_impl(X, 2, ld, d, task_off, T, ks, n_k, n_iter, init_mode, init_centroids, centroids, counts, inertia,
                       status, labels, inertia_trace, workspace, workspace_bytes, flags, stream, 0, 0.0, nullptr);
+}
+
+int32_t cham_sweep_path(int64_t ld, int32_t d, const int64_t *task_off, int32_t T, const int32_t *ks, int32_t n_k,
+                        int32_t flags)
+{
+    Plan pl;
+    const int32_t rc = check_common(nullptr, ld, d, task_off, T, ks, n_k, false, pl, 1);
+    if (rc != CHAM_OK) return rc;
+    if (flags & ~(CHAM_F_FORCE_EXACT | CHAM_F_STREAMING | CHAM_F_RESIDENT | CHAM_F_NO_MFMA)) return CHAM_E_BAD_FLAG;
+    switch (choose_path(pl, d, flags)) {
+    case SweepPath::kMfmaResident: return CHAM_PATH_RESIDENT_MFMA;
+    case SweepPath::kStream: return CHAM_PATH_STREAM_MFMA;
+    default: return CHAM_PATH_RESIDENT_VECTOR;
+    }
+}
+
+const char *cham_sweep_path_kernel(int32_t path)
+{
+    switch (path) {
+    case CHAM_PATH_RESIDENT_MFMA: return "resident_mfma_kernel";
+    case CHAM_PATH_STREAM_MFMA: return "stream_assign_kernel";
+    case CHAM_PATH_RESIDENT_VECTOR: return "resident_sweep_kernel";
+    default: return "unknown";
+    }
+}
+
+int32_t cham_sweep_passes(const void *workspace, int64_t workspace_bytes, int64_t ld, int32_t d,
+                          const int64_t *task_off, int32_t T, const int32_t *ks, int32_t n_k, int32_t flags,
+                          int32_t *passes, void *stream)
+{
+    Plan pl;
+    const int32_t rc = check_common(nullptr, ld, d, task_off, T, ks, n_k, false, pl, d > 32 ? 2 : 1);
+    if (rc != CHAM_OK) return rc;
+    if (!passes) return CHAM_E_NULL;
+    // the region sits before every part of the workspace whose size depends on the path or the knob width
+    const SweepWs w = sweep_ws(pl, ld, false, false, task_off, false);
+    if (!workspace || workspace_bytes < w.passes + (int64_t)T * n_k * 4) return CHAM_E_WORKSPACE;
+    (void)flags;
+    hipError_t e = hipMemcpyAsync(passes, static_cast<const unsigned char *>(workspace) + w.passes,
+                                  (size_t)T * n_k * 4, hipMemcpyDeviceToDevice, reinterpret_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return hip_fail(e);
+    return CHAM_OK;
 }
 
 int64_t cham_sweep_knee_workspace_bytes(int64_t ld, int32_t d, const int64_t *task_off, int32_t T,
@@ -483,9 +587,9 @@ constexpr int64_t kWideChunkRows = 4096;
 static bool wide_tasks(const Plan &pl) { return pl.n_max > kWideTaskRows; }
 
 // first workgroup of every task when each task is cut into 4096-row chunks; returns the total
-static int wide_offsets(const int64_t *task_off, int T, std::vector<uint64_t> &words)
+static int wide_offsets(const int64_t *task_off, int T, Words &words)
 {
-    words.assign((size_t)(T + 2) / 2 + 1, 0);
+    if (!words.assign((size_t)(T + 2) / 2 + 1)) return -1;
     int *w = reinterpret_cast<int *>(words.data());
     int acc = 0;
     for (int t = 0; t < T; ++t) {
@@ -575,8 +679,9 @@ static int32_t snap_impl(const void *Xv, int xbytes, int64_t ld, int32_t d, cons
     a.wide_row = nullptr;
     if (wide) {
         unsigned char *p = ws + blob_bytes + up(ld * 8);
-        std::vector<uint64_t> wo;
+        Words wo;
         const int total = wide_offsets(task_off, T, wo);
+        if (total < 0) return CHAM_E_NOMEM;
         e = stage_words(wo, reinterpret_cast<uint64_t *>(p), s);
         if (e != hipSuccess) return hip_fail(e);
         a.wg_off = reinterpret_cast<const int *>(p);
@@ -667,7 +772,7 @@ static int32_t synth_impl(const void *Xv, int xbytes, int64_t ld, int32_t d, con
     if (!workspace || workspace_bytes < need + (wide ? wide_synth_bytes(pl, d) : 0)) return CHAM_E_WORKSPACE;
     if (reinterpret_cast<uintptr_t>(workspace) % kAlign) return CHAM_E_WORKSPACE;
     // extend the blob: salts then cards
-    pl.blob.resize((size_t)(base_words + synth_blob_extra_words(T, d)), 0);
+    if (!pl.blob.resize((size_t)(base_words + synth_blob_extra_words(T, d)))) return CHAM_E_NOMEM;
     for (int t = 0; t < T; ++t) pl.blob[(size_t)base_words + t] = task_salt ? task_salt[t] : (uint64_t)t;
     uint16_t *pc = reinterpret_cast<uint16_t *>(pl.blob.data() + base_words + T);
     for (int64_t i = 0; i < (int64_t)T * d; ++i) pc[i] = cards[i];
@@ -715,8 +820,9 @@ static int32_t synth_impl(const void *Xv, int xbytes, int64_t ld, int32_t d, con
     a.wide_hist = nullptr;
     if (wide) {
         unsigned char *p = ws + need;
-        std::vector<uint64_t> wo;
+        Words wo;
         const int total = wide_offsets(task_off, T, wo);
+        if (total < 0) return CHAM_E_NOMEM;
         e = stage_words(wo, reinterpret_cast<uint64_t *>(p), s);
         if (e != hipSuccess) return hip_fail(e);
         a.wg_off = reinterpret_cast<const int *>(p);

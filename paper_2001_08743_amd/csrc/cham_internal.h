@@ -31,6 +31,7 @@ struct SweepArgs {
     uint8_t *labbuf;               // [n_k][ld] working / final labels
     double *trace;                 // [T][n_k][n_iter+1] or null
     uint16_t *xh;                  // [ld][16 or 32] f16 row-major copy of X (matrix-core path)
+    int *passes;                   // [T][n_k] labelling passes actually run (preset to n_iter + 1 by the host code)
     int ki_begin, ki_end;          // this launch runs ks[ki_begin .. ki_end) (the whole list by default)
     const int *done;               // [T] or null: tasks whose sweep has already stopped; their units are skipped (status 3)
 };
@@ -93,6 +94,7 @@ struct StreamArgs {
     void *afrag;                   // [n_units][kpm/32][4][64] 16-byte A fragments
     float *m2;                     // [n_units][8] bound on max |mu'|^2 per tile of 32 centroids; tile 0 negative = unit unusable
     double *loss_part;             // [total workgroups] loss partials of the last pass
+    int *passes;                   // [T][n_k] labelling passes actually run (preset to n_iter + 1 by the host code)
 };
 
 // Arguments of the snap kernel.

@@ -123,6 +123,7 @@ __global__ __launch_bounds__(MAXNT) void resident_sweep_kernel(const SweepArgs a
         for (int64_t r = r0 + tid; r < r1; r += blockDim.x) labrow[r] = 0;
         if (tid == 0) {
             a.status[slot] = skipped ? 3 : 1;
+            a.passes[slot] = 0;
             a.inertia[slot] = 0.0;
         }
         if (a.trace)

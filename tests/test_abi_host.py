@@ -38,7 +38,7 @@ def test_every_declared_symbol_is_exported(lib):
 def test_version_and_strerror(lib):
     assert lib.cham_version() >= 100
     assert lib.cham_strerror(0) == b"ok"
-    for code in range(-8, 0):
+    for code in range(-10, 0):
         assert len(lib.cham_strerror(code)) > 3
 
 
@@ -173,3 +173,17 @@ def test_two_byte_host_hash_equals_the_byte_hash_below_256_and_takes_whole_value
     for v in (300, 65535, 0, 256):
         h = ((h ^ v) * 0x100000001B3) % M
     assert binding.cham_hash_config_u16([300, 65535, 0, 256], 0) == h
+
+
+def test_sweep_path_query(lib):
+    ks64 = list(range(1, 65))
+    assert binding.cham_sweep_path(4096, 24, [0, 4096], ks64) == 0            # resident, matrix cores
+    assert binding.cham_sweep_path_kernel(0) == "resident_mfma_kernel"
+    assert binding.cham_sweep_path(8192, 24, [0, 8192], ks64) == 1            # task too large for one workgroup
+    assert binding.cham_sweep_path(4096, 16, [0, 4096], [16, 128]) == 1       # k above 64
+    assert binding.cham_sweep_path_kernel(1) == "stream_assign_kernel"
+    assert binding.cham_sweep_path(4096, 32, [0, 4096], ks64) == 2            # no spare knob slot
+    assert binding.cham_sweep_path(4096, 24, [0, 4096], ks64, flags=binding.F_NO_MFMA) == 2
+    assert binding.cham_sweep_path_kernel(2) == "resident_sweep_kernel"
+    with pytest.raises(binding.ChamError):
+        binding.cham_sweep_path(4096, 24, [0, 4096], [3, 2])
