@@ -57,7 +57,7 @@ extern "C" {
 #define CHAM_E_HIP          (-7)   /* a HIP runtime call failed; see cham_last_hip_error() */
 #define CHAM_E_BAD_FLAG     (-8)   /* unknown bits in flags / unknown init_mode */
 #define CHAM_E_NOMEM        (-9)   /* host memory for the call's small tables could not be had */
-#define CHAM_E_TOO_LARGE    (-10)  /* the input exceeds a fixed limit of the entry point */
+#define CHAM_E_TOO_LARGE    (-10)  /* cham_kmeans_sweep_static: the input needs more scratch than the static buffer holds */
 
 /* values of out_flag (cham_synthesize) */
 #define CHAM_OUT_EMPTY   0   /* cluster has no member (or index >= chosen k) */
@@ -148,6 +148,30 @@ const char *cham_sweep_path_kernel(int32_t path);
 int32_t cham_sweep_passes(const void *workspace, int64_t workspace_bytes, int64_t ld, int32_t d,
                           const int64_t *task_off, int32_t T, const int32_t *ks, int32_t n_k, int32_t flags,
                           int32_t *passes, void *stream);
+
+/*
+ * cham_kmeans_sweep for callers that cannot allocate device memory or pass a workspace: code
+ * under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments
+ * (minus the workspace), same results bit for bit, same kernels; the scratch memory is a static
+ * device array of CHAM_STATIC_SCRATCH_BYTES inside the library, one per GPU, held until the
+ * process ends.  The call allocates nothing, on the device or on the host.
+ *   - Limit: cham_sweep_workspace_bytes(...) for the arguments must not exceed
+ *     CHAM_STATIC_SCRATCH_BYTES and T + n_k must stay below about a thousand (the host tables
+ *     live on the stack); beyond: CHAM_E_TOO_LARGE, nothing is enqueued.
+ *   - The array's device address is looked up on the first call on each GPU (with that GPU
+ *     current); cham_static_init() does the lookup ahead of time, e.g. before a graph capture.
+ *   - All calls on one GPU share that GPU's array, whatever the stream: calls that overlap in
+ *     time on one GPU race.  Nothing in it has to be cleared between calls: every word a call
+ *     reads it has written first.
+ */
+#define CHAM_STATIC_SCRATCH_BYTES (8 * 1024 * 1024)
+int32_t cham_static_init(void);
+int32_t cham_kmeans_sweep_static(const uint8_t *X, int64_t ld, int32_t d,
+                                 const int64_t *task_off, int32_t T,
+                                 const int32_t *ks, int32_t n_k,
+                                 int32_t n_iter, int32_t init_mode, const double *init_centroids,
+                                 double *centroids, int32_t *counts, double *inertia, int32_t *status,
+                                 uint8_t *labels, double *inertia_trace, int32_t flags, void *stream);
 
 /*
  * K-means sweep that stops at the knee, the loop of Algorithm 1 as printed: for k in the list,

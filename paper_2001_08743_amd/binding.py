@@ -25,6 +25,7 @@ EXPORTS = [
     "cham_hash_rows", "cham_sweep_knee_workspace_bytes", "cham_kmeans_sweep_knee", "cham_synthesize_table",
     "cham_visited_table_clear", "cham_visited_table_insert_hashes", "cham_visited_table_insert_configs",
     "cham_update_configs", "cham_sweep_path", "cham_sweep_path_kernel", "cham_sweep_passes",
+    "cham_static_init", "cham_kmeans_sweep_static",
     "cham_sweep_workspace_bytes_u16", "cham_kmeans_sweep_u16", "cham_sweep_knee_workspace_bytes_u16",
     "cham_kmeans_sweep_knee_u16", "cham_snap_workspace_bytes_u16", "cham_snap_centroids_u16",
     "cham_synth_workspace_bytes_u16", "cham_synthesize_u16", "cham_synthesize_table_u16",
@@ -62,6 +63,11 @@ def load() -> C.CDLL:
         lib.cham_sweep_path_kernel.argtypes = [i32]
         lib.cham_sweep_passes.restype = i32
         lib.cham_sweep_passes.argtypes = [vp, i64, i64, i32, vp, i32, vp, i32, i32, vp, vp]
+        lib.cham_static_init.restype = i32
+        lib.cham_static_init.argtypes = []
+        lib.cham_kmeans_sweep_static.restype = i32
+        lib.cham_kmeans_sweep_static.argtypes = [vp, i64, i32, vp, i32, vp, i32, i32, i32, vp,
+                                                 vp, vp, vp, vp, vp, vp, i32, vp]
         lib.cham_sweep_knee_workspace_bytes.restype = i64
         lib.cham_sweep_knee_workspace_bytes.argtypes = [i64, i32, vp, i32, vp, i32, i32, i32]
         lib.cham_kmeans_sweep_knee.restype = i32
@@ -279,6 +285,26 @@ def cham_sweep_passes(workspace, ld: int, d: int, task_off, ks, flags: int = 0, 
                                     _hp(to), C.c_int32(T), _hp(k), C.c_int32(n_k), C.c_int32(flags), _dp(passes),
                                     _stream()))
     return passes
+
+
+def cham_static_init() -> None:
+    _torch()
+    _check(load().cham_static_init())
+
+
+def cham_kmeans_sweep_static(X, ld: int, d: int, task_off, ks: Sequence[int], n_iter: int, out: dict,
+                             init_centroids=None, flags: int = 0):
+    """cham_kmeans_sweep on the library's static scratch buffer; ``out`` holds the caller's output tensors
+    (centroids, counts, inertia, status and optionally labels, trace).  Nothing is allocated here."""
+    to, k = _host_lists(task_off, ks)
+    rc = load().cham_kmeans_sweep_static(_dp(X), C.c_int64(ld), C.c_int32(d), _hp(to), C.c_int32(len(to) - 1), _hp(k),
+                                         C.c_int32(len(k)), C.c_int32(n_iter),
+                                         C.c_int32(0 if init_centroids is None else 1), _dp(init_centroids),
+                                         _dp(out["centroids"]), _dp(out["counts"]), _dp(out["inertia"]),
+                                         _dp(out["status"]), _dp(out.get("labels")), _dp(out.get("trace")),
+                                         C.c_int32(flags), _stream())
+    _check(rc)
+    return out
 
 
 def cham_kmeans_sweep_u16(X, ld: int, d: int, task_off, ks: Sequence[int], n_iter: int, **kw):

@@ -454,6 +454,59 @@ int32_t cham_kmeans_sweep(const uint8_t *X, int64_t ld, int32_t d, const int64_t
                       status, labels, inertia_trace, workspace, workspace_bytes, flags, stream, 0, 0.0, nullptr);
 }
 
+// Scratch memory of cham_kmeans_sweep_static, the entry point for callers that cannot allocate:
+// one array per GPU, inside the loaded code object, kept until the process ends.  The name below
+// is only a host-side handle of the symbol; the array's device address is looked up once per
+// device and every use in host code goes through that address.
+constexpr int64_t kStaticScratchBytes = (int64_t)CHAM_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+static void *g_scratch_addr[kMaxDevices];       // device address of `scratch` on each GPU, null until looked up
+
+static int32_t static_scratch_address(void **out)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail(e);
+    if (dev < 0 || dev >= kMaxDevices) return CHAM_E_BAD_DIM;
+    void *p = __atomic_load_n(&g_scratch_addr[dev], __ATOMIC_ACQUIRE);
+    if (!p) {
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return hip_fail(e);
+        if (!p) return hip_fail(hipErrorInvalidSymbol);
+        __atomic_store_n(&g_scratch_addr[dev], p, __ATOMIC_RELEASE);
+    }
+    *out = p;
+    return CHAM_OK;
+}
+
+int32_t cham_static_init(void)
+{
+    void *p = nullptr;
+    return static_scratch_address(&p);
+}
+
+int32_t cham_kmeans_sweep_static(const uint8_t *X, int64_t ld, int32_t d, const int64_t *task_off, int32_t T,
+                                 const int32_t *ks, int32_t n_k, int32_t n_iter, int32_t init_mode,
+                                 const double *init_centroids, double *centroids, int32_t *counts,
+                                 double *inertia, int32_t *status, uint8_t *labels, double *inertia_trace,
+                                 int32_t flags, void *stream)
+{
+    // argument errors come out of the size query exactly as they would out of the sweep
+    const int64_t need = sweep_ws_bytes(1, ld, d, task_off, T, ks, n_k, flags, true);
+    if (need == CHAM_E_NOMEM) return CHAM_E_TOO_LARGE;      // tables beyond the part kept on the stack
+    if (need < 0) return (int32_t)need;
+    if (flags & ~(CHAM_F_FORCE_EXACT | CHAM_F_STREAMING | CHAM_F_RESIDENT | CHAM_F_NO_MFMA)) return CHAM_E_BAD_FLAG;
+    if (need > kStaticScratchBytes) return CHAM_E_TOO_LARGE;
+    void *ws = nullptr;
+    int32_t rc = static_scratch_address(&ws);
+    if (rc != CHAM_OK) return rc;
+    rc = sweep_impl(X, 1, ld, d, task_off, T, ks, n_k, n_iter, init_mode, init_centroids, centroids, counts, inertia,
+                    status, labels, inertia_trace, ws, kStaticScratchBytes, flags, stream, 0, 0.0, nullptr, true);
+    // the host-side tables of this entry point live on the stack only
+    return rc == CHAM_E_NOMEM ? CHAM_E_TOO_LARGE : rc;
+}
+
 int32_t cham_kmeans_sweep_u16(const uint16_t *X, int64_t ld, int32_t d, const int64_t *task_off, int32_t T,
                               const int32_t *ks, int32_t n_k, int32_t n_iter, int32_t init_mode,
                               const double *init_centroids, double *centroids, int32_t *counts,

@@ -187,3 +187,31 @@ def test_sweep_path_query(lib):
     assert binding.cham_sweep_path_kernel(2) == "resident_sweep_kernel"
     with pytest.raises(binding.ChamError):
         binding.cham_sweep_path(4096, 24, [0, 4096], [3, 2])
+
+
+def test_static_sweep_rejects_bad_arguments_and_sizes_before_any_device_work(lib):
+    vp = C.c_void_p
+
+    def rc(X=1024, ld=64, d=4, task_off=(0, 10), ks=(1, 2), n_iter=1, init_mode=0, flags=0, outs=4096):
+        to = np.asarray(task_off, dtype=np.int64)
+        k = np.asarray(ks, dtype=np.int32)
+        return lib.cham_kmeans_sweep_static(vp(X), C.c_int64(ld), C.c_int32(d), to.ctypes.data_as(vp),
+                                            C.c_int32(len(to) - 1), k.ctypes.data_as(vp), C.c_int32(len(k)),
+                                            C.c_int32(n_iter), C.c_int32(init_mode), None, vp(outs), vp(outs),
+                                            vp(outs), vp(outs), None, None, C.c_int32(flags), None)
+
+    assert rc(d=0) == -2
+    assert rc(ks=(2, 2)) == -3
+    assert rc(task_off=(0, 10, 5)) == -4
+    assert rc(flags=1 << 20) == -8
+    # 1 Mi rows need 64 MiB of packed rows alone: beyond the static buffer
+    assert rc(ld=1 << 20, task_off=(0, 1 << 20)) == -10
+    # 2000 tasks: the host-side tables no longer fit on the stack
+    assert rc(ld=4000, task_off=tuple(range(0, 4002, 2))) == -10
+    assert len(lib.cham_strerror(-10)) > 20
+    # the documented limit and the workspace query agree
+    text = open(os.path.join(ROOT, "include", "cham.h")).read()
+    m = re.search(r"#define\s+CHAM_STATIC_SCRATCH_BYTES\s+\((\d+) \* (\d+) \* (\d+)\)", text)
+    limit = int(m.group(1)) * int(m.group(2)) * int(m.group(3))
+    ks = list(range(2, 33))
+    assert binding.cham_sweep_workspace_bytes(65536, 12, np.arange(0, 65537, 1024), ks, 30) <= limit
