@@ -7,14 +7,26 @@
 //   B (K x 32 rows)      = [ x' ; x' ]        (x' is a small integer: exact in f16)
 //   the last knob slot (always unused: d < DK) carries the bias: B = 256, A = hi/lo of |mu'_c|^2 / 256
 // so every product is exact and only the fp32 accumulation and the 22-bit splits round.
-// Each lane then holds the scores of 16 centroids for one row; the epilogue takes the minimum
-// (v_min3) and marks every centroid within the error bound of it (one subtract and one
-// v_alignbit per score).  A row with a single mark is decided; the others are queued per wave
-// and their marked centroids are re-evaluated in double in the oracle's operation order.
-// The matrix instructions of the next 32-row tile are issued between the epilogue pieces of the
-// current one.  Rows (as f16 B fragments) and previous labels stay in registers for all passes;
-// centroids, integer sums and counts stay in LDS; a row touches the sums only when its label
-// changes (exact: the sums are integers), through a dense per-wave queue.
+//
+// Centroid c sits in fragment row 8 (i / 4) + 4 (c & 1) + (i & 3), i = (c & 31) / 2, of m-tile c / 32,
+// so that accumulator register i of lane half hh holds centroid 2 i + hh: a unit with k centroids
+// has live scores in its first ceil(k / 2) registers only, and the epilogue walks live groups of
+// four registers, not all sixteen.  Per 32-row tile: minimum over the live registers (v_min3),
+// threshold = minimum + error bound of the row (a constant of the row for the whole unit: the
+// bound uses the largest squared norm that a centroid can have, that of the farthest row), one
+// subtract and one v_alignbit per score for the mask of centroids beyond the threshold.  If every
+// row's mask equals the mask it had when the tile was last decided (and none of its rows was
+// undecided then), every row keeps its label and nothing else happens for the tile.  Otherwise a
+// row with a single centroid inside the threshold takes it; the others are queued per wave and
+// their marked centroids are re-evaluated in double in the oracle's operation order.
+// The matrix instructions of the next tile are issued between the epilogue pieces of the current
+// one.  Rows (as f16 B fragments) and labels stay in registers for all passes; centroids, integer
+// sums and counts stay in LDS; a row touches the sums only when its label changes (exact: the
+// sums are integers), through a dense per-wave queue.
+//
+// A pass that changes no label leaves the sums, hence the centroids, hence every later pass as
+// they are: the iteration stops there and reports the state it has, which is what the remaining
+// passes of the fixed-length iteration would reproduce.  The number of passes run is recorded.
 #include "cham_device.h"
 #include "cham_internal.h"
 #include "mfma_common.h"
@@ -22,20 +34,6 @@
 namespace cham {
 
 namespace {
-
-#ifdef CHAM_KERNEL_TIMING
-// Development aid (not built into the library): per-section cycle counts summed over waves.
-__device__ unsigned long long g_timing[16];
-__device__ unsigned long long g_pass[64 * 16];   // per pass index: tiles, resolve, sums, barrier, update, count-mode, waves
-#define CHAM_T(var) const unsigned long long var = __builtin_readcyclecounter()
-#define CHAM_TADD(slot, t0, t1) tacc[slot] += (t1) - (t0)
-#define CHAM_TCOUNT(slot, v) tacc[slot] += (unsigned long long)(v)
-#else
-#define CHAM_T(var)
-#define CHAM_TADD(slot, t0, t1)
-#define CHAM_TCOUNT(slot, v)
-#endif
-
 
 // Cross-lane exchanges done in the vector ALU (DPP), no LDS round trip.
 // xor_lanes<1|2|4>: the value held by lane ^ 1, 2 or 4.
@@ -75,6 +73,23 @@ __device__ __forceinline__ float wave_max_nonneg(float v)
     return __int_as_float(m01 > m23 ? m01 : m23);
 }
 
+// Minimum of two / three scores.  This file is compiled with -fno-honor-nans (every score is a finite
+// sum of finite products), which spares the instruction that would otherwise quiet a possible NaN in
+// each operand coming out of a matrix instruction.  (Not inline assembly: the compiler has to see
+// these reads to keep the wait states between a matrix instruction and the use of its result.)
+__device__ __forceinline__ float vmin(float a, float b) { return __builtin_fminf(a, b); }
+__device__ __forceinline__ float vmin3(float a, float b, float c) { return __builtin_fminf(__builtin_fminf(a, b), c); }
+
+// Score position -> centroid.  Position q = 16 * m-tile + accumulator register (the order in which
+// the mask bits are collected, most significant first), hh = lane half.
+__device__ __forceinline__ int slot_centroid(int q, int hh) { return 2 * q + hh; }
+// Row of the 32-row A fragment that holds centroid c of its m-tile.
+__device__ __forceinline__ int frag_row(int c)
+{
+    const int i = (c & 31) >> 1;
+    return 8 * (i >> 2) + 4 * (c & 1) + (i & 3);
+}
+
 // LDS carve-up.  DK = padded knob count (16 or 32), KP = padded centroid count (32 or 64).
 template <int DK>
 struct MfmaLds {
@@ -86,17 +101,19 @@ struct MfmaLds {
     int *n;             // [KP]       cluster sizes
     int *dirty;         // [KP]       pass in which the cluster last changed
     float *ojf;         // [DK]       centring offsets
-    int *upd_stamp;     // [3]        1 + pass whose update last rewrote a centroid; last pass that changed a sum; broken-invariant flag
+    int *stamp;         // [4]        last pass that changed a sum; float bits of the largest squared row norm
     unsigned char *wave_base;   // per-wave regions follow
-    static constexpr size_t kWaveBytes =
-        ((size_t)kRecCap * DK * 2 + 512 * 8 + 512 * 2 + 512 + 512 * 4 + 512 * 4 + 15) / 16 * 16;
-    __host__ __device__ static size_t bytes(int KP, int nwaves)
+    __host__ __device__ static size_t wave_bytes(int ntw)
+    {
+        return ((size_t)kRecCap * DK * 2 + kRecCap * 8 + kRecCap * 2 + 4 * 32 * 8 + 512 + 512 + 512 * 4 + (size_t)ntw * 64 * 4 + 15) / 16 * 16;
+    }
+    __host__ __device__ static size_t bytes(int KP, int nwaves, int ntw)
     {
         size_t b = sizeof(double) * DK * KP + sizeof(double) * 16 + sizeof(float) * KP;
         b += 16 * (size_t)(KP / 32) * (2 * DK / 16) * 64;
         b += sizeof(int) * (size_t)KP * (DK + 1) + sizeof(int) * KP * 2 + sizeof(float) * DK + 16;
         b = (b + 15) & ~(size_t)15;
-        return b + kWaveBytes * nwaves;
+        return b + wave_bytes(ntw) * nwaves;
     }
     __device__ MfmaLds(unsigned char *base, int KP)
     {
@@ -110,41 +127,47 @@ struct MfmaLds {
         n = reinterpret_cast<int *>(base + o);         o += sizeof(int) * KP;
         dirty = reinterpret_cast<int *>(base + o);     o += sizeof(int) * KP;
         ojf = reinterpret_cast<float *>(base + o);     o += sizeof(float) * DK;
-        upd_stamp = reinterpret_cast<int *>(base + o); o += 16;
+        stamp = reinterpret_cast<int *>(base + o);     o += 16;
         o = (o + 15) & ~(size_t)15;
         wave_base = base + o;
     }
 };
 
-// Per-wave LDS region.  Every row of the wave can be queued (index + candidate masks of both lane
-// halves); the first kRecCap queued rows also carry their knob values (f16, centred), later ones
-// are re-read from the packed row copy in global memory.  The same storage then queues the label
-// changes of the pass.
+// Per-wave LDS region.  A queue of at most kRecCap rows (their centred knob values as f16, the
+// candidate masks of both lane halves, the row index), used first for the rows the screen could
+// not decide and then for the label changes of the pass, in batches; behind it the current label of
+// every row, the labels the pass arrives at, the error bound of every row and, per (tile, lane),
+// the mask the lane had when its tile was last decided.
 template <int DK>
 struct WaveQueue {
     static constexpr int kRows = 512;                       // rows a wave owns at most
     static constexpr size_t kOffMask = (size_t)kRecCap * DK * 2;
-    static constexpr size_t kOffPid = kOffMask + (size_t)kRows * 8;
-    static constexpr size_t kOffLab = kOffPid + (size_t)kRows * 2;
-    static constexpr size_t kOffX2 = kOffLab + (size_t)kRows;
+    static constexpr size_t kOffPid = kOffMask + (size_t)kRecCap * 8;
+    static constexpr size_t kOffFew = kOffPid + (size_t)kRecCap * 2;
+    static constexpr size_t kOffLab = kOffFew + 4 * 32 * 8;
+    static constexpr size_t kOffNew = kOffLab + (size_t)kRows;
+    static constexpr size_t kOffEb = kOffNew + (size_t)kRows;
+    static constexpr size_t kOffSeen = kOffEb + (size_t)kRows * 4;
+    __host__ __device__ static constexpr size_t bytes(int ntw) { return (kOffSeen + (size_t)ntw * 64 * 4 + 15) / 16 * 16; }
     unsigned char *base;
     __device__ explicit WaveQueue(unsigned char *wb) : base(wb) {}
     __device__ _Float16 *rec_x() const { return reinterpret_cast<_Float16 *>(base); }                    // [kRecCap][DK]
-    __device__ unsigned *rec_mask() const { return reinterpret_cast<unsigned *>(base + kOffMask); }      // [kRows][2]
+    __device__ unsigned *rec_mask() const { return reinterpret_cast<unsigned *>(base + kOffMask); }      // [kRecCap][2]
     __device__ unsigned short *rec_pid() const { return reinterpret_cast<unsigned short *>(base + kOffPid); }
-    __device__ unsigned char *lab_res() const { return base + kOffLab; }                                  // [kRows]
-    __device__ float *x2() const { return reinterpret_cast<float *>(base + kOffX2); }                     // [kRows] bound scale: at least |x'|^2 + |tau|
-    __device__ float *best() const { return reinterpret_cast<float *>(base + kOffX2 + (size_t)kRows * 4); }     // [kRows] smallest score of the measuring pass
+    __device__ double *few() const { return reinterpret_cast<double *>(base + kOffFew); }                 // [4][32] squares of one (row, centroid)
+    __device__ unsigned char *lab() const { return base + kOffLab; }                                      // [kRows] current labels (0xFF: none)
+    __device__ unsigned char *lab_new() const { return base + kOffNew; }                                  // [kRows] labels of the pass under way
+    __device__ float *eb() const { return reinterpret_cast<float *>(base + kOffEb); }                     // [kRows] screen bound of the row
+    __device__ unsigned *seen() const { return reinterpret_cast<unsigned *>(base + kOffSeen); }           // [tiles][64] mask at the last decision
 };
 
 // Resolve the queued rows of this wave: four lanes per row, each lane takes every fourth marked
 // centroid of its row and evaluates the exact double distance (knobs ascending, no fused
-// multiply-add); the four lanes then agree on the smallest distance, lowest index on ties.
-// xh_wave points at the packed f16 copy of the wave's first row (uncentred values).
-template <int DK, bool kAllInLds>
+// multiply-add); the four lanes then agree on the smallest distance, lowest index on ties.  The
+// result goes to the row's entry of the labels of the pass under way.
+template <int DK>
 __device__ __forceinline__ void resolve_rows(const WaveQueue<DK> &Q, int nrec, const double *mu64T,
-                                             const float *ojf, int KP, int k, int d,
-                                             const _Float16 *xh_wave)
+                                             const float *ojf, int KP, int k, int d)
 {
     const int lane = threadIdx.x & 63;
     const int q = lane & 3;
@@ -165,11 +188,11 @@ __device__ __forceinline__ void resolve_rows(const WaveQueue<DK> &Q, int nrec, c
             if (rem0) {
                 const int b = __clz((int)rem0);
                 rem0 &= ~(0x80000000u >> b);
-                c = centroid_of(b, 0);
+                c = slot_centroid(b, 0);
             } else if (rem1) {
                 const int b = __clz((int)rem1);
                 rem1 &= ~(0x80000000u >> b);
-                c = centroid_of(b, 1);
+                c = slot_centroid(b, 1);
             }
             return c;
         };
@@ -178,16 +201,11 @@ __device__ __forceinline__ void resolve_rows(const WaveQueue<DK> &Q, int nrec, c
         int bc = 0x7fffffff;
         while (__ballot((rem0 | rem1) != 0u)) {
             const int cc = pop();
-            const int ci = cc < 0 ? 0 : cc;
+            const int ci = (cc < 0 || cc >= k) ? 0 : cc;
             double ss = 0.0;
             // knobs in groups of 8; the loads of a group are independent and overlap
             for (int j0 = 0; j0 < d; j0 += 8) {
-                half8 xq;
-                if (kAllInLds || rr < kRecCap) {
-                    xq = *reinterpret_cast<const half8 *>(Q.rec_x() + (size_t)rr * DK + j0);
-                } else {
-                    xq = *reinterpret_cast<const half8 *>(xh_wave + (size_t)pid * DK + j0);
-                }
+                const half8 xq = *reinterpret_cast<const half8 *>(Q.rec_x() + (size_t)rr * DK + j0);
                 const float4 oa = *reinterpret_cast<const float4 *>(ojf + j0);
                 const float4 ob = *reinterpret_cast<const float4 *>(ojf + j0 + 4);
                 const float of[8] = {oa.x, oa.y, oa.z, oa.w, ob.x, ob.y, ob.z, ob.w};
@@ -196,8 +214,8 @@ __device__ __forceinline__ void resolve_rows(const WaveQueue<DK> &Q, int nrec, c
                 for (int i = 0; i < 8; ++i) mu[i] = mu64T[(size_t)(j0 + i) * KP + ci];
 #pragma unroll
                 for (int i = 0; i < 8; ++i) {
-                    // queued copies are centred; padded knobs are skipped (one of them carries the bias)
-                    float xf = (kAllInLds || rr < kRecCap) ? (float)xq[i] + of[i] : (float)xq[i];
+                    // queued copies are centred; padded knobs are skipped (the last one carries the bias)
+                    float xf = (float)xq[i] + of[i];
                     if (j0 + i >= d) xf = 0.0f;
                     const double tq = (double)xf - mu[i];
                     ss = ss + tq * tq;
@@ -227,7 +245,7 @@ __device__ __forceinline__ void resolve_rows(const WaveQueue<DK> &Q, int nrec, c
                 bc = oc;
             }
         }
-        if (have && q == 0) Q.lab_res()[pid] = (unsigned char)(bc < k ? bc : 0);
+        if (have && q == 0) Q.lab_new()[pid] = (unsigned char)(bc < k ? bc : 0);
     }
     __builtin_amdgcn_wave_barrier();
 }
@@ -242,8 +260,7 @@ __device__ __forceinline__ void resolve_few(const WaveQueue<DK> &Q, int nrec, co
 {
     const int lane = threadIdx.x & 63;
     const int slot = lane >> 4, jl = lane & 15;
-    // [4][32] squares of one (row, centroid), in the upper half of the mask array (unused by <= 8 queued rows)
-    double *sc = reinterpret_cast<double *>(Q.rec_mask() + 512) + slot * 32;
+    double *sc = Q.few() + slot * 32;      // squares of one (row, centroid)
     __builtin_amdgcn_wave_barrier();
     for (int r0 = 0; r0 < nrec; r0 += 2) {
         const int r = r0 + (slot >> 1);
@@ -255,7 +272,7 @@ __device__ __forceinline__ void resolve_few(const WaveQueue<DK> &Q, int nrec, co
             rem1 = Q.rec_mask()[r * 2 + 1];
         }
         const int pid = Q.rec_pid()[rr];
-        // this lane's knobs of the row (the queued copy is centred; reserved and padded slots count as zero)
+        // this lane's knobs of the row (the queued copy is centred; the bias slot and padded slots count as zero)
         float xa = 0.0f, xb = 0.0f;
         if (jl < d) xa = (float)Q.rec_x()[(size_t)rr * DK + jl] + ojf[jl];
         if (DK == 32 && jl + 16 < d) xb = (float)Q.rec_x()[(size_t)rr * DK + jl + 16] + ojf[jl + 16];
@@ -264,11 +281,11 @@ __device__ __forceinline__ void resolve_few(const WaveQueue<DK> &Q, int nrec, co
             if (rem0) {
                 const int b = __clz((int)rem0);
                 rem0 &= ~(0x80000000u >> b);
-                c = centroid_of(b, 0);
+                c = slot_centroid(b, 0);
             } else if (rem1) {
                 const int b = __clz((int)rem1);
                 rem1 &= ~(0x80000000u >> b);
-                c = centroid_of(b, 1);
+                c = slot_centroid(b, 1);
             }
             return c;
         };
@@ -277,7 +294,7 @@ __device__ __forceinline__ void resolve_few(const WaveQueue<DK> &Q, int nrec, co
         int bc = 0x7fffffff;
         while (__ballot((rem0 | rem1) != 0u)) {
             const int cc = pop();
-            const int ci = cc < 0 ? 0 : cc;
+            const int ci = (cc < 0 || cc >= k) ? 0 : cc;
             const double ta = (double)xa - mu64T[(size_t)jl * KP + ci];
             sc[jl] = ta * ta;
             if (DK == 32) {
@@ -309,23 +326,19 @@ __device__ __forceinline__ void resolve_few(const WaveQueue<DK> &Q, int nrec, co
             bs = os;
             bc = oc;
         }
-        if (have && (lane & 31) == 0) Q.lab_res()[pid] = (unsigned char)(bc < k ? bc : 0);
+        if (have && (lane & 31) == 0) Q.lab_new()[pid] = (unsigned char)(bc < k ? bc : 0);
     }
     __builtin_amdgcn_wave_barrier();
 }
 
-// The usual case (every queued row has its LDS copy) never touches global memory.
 template <int DK>
 __device__ __forceinline__ void resolve_queue(const WaveQueue<DK> &Q, int nrec, const double *mu64T,
-                                              const float *ojf, int KP, int k, int d,
-                                              const _Float16 *xh_wave)
+                                              const float *ojf, int KP, int k, int d)
 {
     if (nrec <= 8) {
         resolve_few<DK>(Q, nrec, mu64T, ojf, KP, k, d);
-    } else if (nrec <= kRecCap) {
-        resolve_rows<DK, true>(Q, nrec, mu64T, ojf, KP, k, d, xh_wave);
     } else {
-        resolve_rows<DK, false>(Q, nrec, mu64T, ojf, KP, k, d, xh_wave);
+        resolve_rows<DK>(Q, nrec, mu64T, ojf, KP, k, d);
     }
 }
 
@@ -396,68 +409,68 @@ __device__ __forceinline__ void apply_changes(const WaveQueue<DK> &Q, int cnt, i
     __builtin_amdgcn_wave_barrier();
 }
 
-// Centroid update for the clusters touched in this pass, all threads: item (c, q) owns knobs
-// 4q..4q+3 of centroid c: mean = (double)S / (double)n, then the f16 hi/lo fragments of
-// w = -2 (mu - o) (one 8-byte store each).  The DK/4 items of a centroid sit in adjacent lanes and
-// add up |mu - o|^2 among themselves; the last of them owns the bias slot (knob slot DK - 3) and
-// stores the sum / 256 there as hi/lo, and its rounded-up value for the error bound.  The two
-// threshold slots (DK - 2, DK - 1) hold the constant 256.  A rewritten centroid is recorded in
-// upd_stamp.
+// Centroid update for the clusters touched in this pass (all of them when `all` is set: the start).
+// Every wave derives the same list of touched clusters from the pass stamps and takes two of them
+// at a time, one per lane half; lane j of a half owns knob slot j: mean = (double)S / (double)n, then
+// the f16 hi/lo parts of w = -2 (mu - o) go to their places in the A fragments (two-byte stores).
+// The lanes of a half add up |mu - o|^2; the lane of the last knob slot, which is the bias slot,
+// stores the sum / 256 there as hi/lo, and its rounded-up value for the error bound.
 template <int DK>
 __device__ __forceinline__ void update_centroids(const MfmaLds<DK> &U, int k, int KP, int d, int stamp, bool all)
 {
-    constexpr int NS = DK / 16, NS2 = 2 * NS, QN = DK / 4;
-    typedef _Float16 half4 __attribute__((ext_vector_type(4)));
-    const int items = k * QN;
-    for (int base = 0; base < items; base += blockDim.x) {      // uniform trip count: every lane shuffles
-        const int item = base + (int)threadIdx.x;
-        const int c = item / QN, q = item % QN;
-        bool act = item < items;
-        int cnt = 0;
-        if (act) {
-            cnt = U.n[c];
-            if (!all && (U.dirty[c] != stamp || cnt == 0)) act = false;   // an empty cluster keeps its centroid
-        }
-        half4 hi4 = {(_Float16)0.0f, (_Float16)0.0f, (_Float16)0.0f, (_Float16)0.0f};
-        half4 lo4 = hi4;
+    constexpr int NS = DK / 16, NS2 = 2 * NS;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
+    const int nwaves = blockDim.x >> 6;
+    const int half = lane >> 5, j = lane & 31;
+    bool touched = false;
+    if (lane < k) touched = all || (U.dirty[lane] == stamp && U.n[lane] > 0);   // an empty cluster keeps its centroid
+    uint64_t todo = __ballot(touched);
+    auto strip = [](uint64_t m, int cnt) {
+        for (int i = 0; i < cnt && m; ++i) m &= m - 1;
+        return m;
+    };
+    todo = strip(todo, 2 * wave);
+    while (todo) {
+        const int c0 = __builtin_ctzll(todo);
+        todo &= todo - 1;
+        const int c1 = todo ? __builtin_ctzll(todo) : -1;
+        todo = strip(todo, 1 + 2 * (nwaves - 1));
+        const int c = half ? c1 : c0;
+        const bool act = c >= 0 && j < DK;
+        const int ci = c >= 0 ? c : 0;
         double b = 0.0;
-        if (act && 4 * q < d) {
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int j = 4 * q + i;
-                double mu = U.mu64T[(size_t)j * KP + c];
-                if (!all && j < d) {
-                    mu = (double)U.S[c * (DK + 1) + j] / (double)cnt;
-                    U.mu64T[(size_t)j * KP + c] = mu;
-                }
-                const double m = j < d ? mu - (double)U.ojf[j] : 0.0;
-                b = __builtin_fma(m, m, b);
-                const float w = (float)(-2.0 * m);
-                const _Float16 hi = (_Float16)w;
-                hi4[i] = hi;
-                lo4[i] = (_Float16)(w - (float)hi);
+        _Float16 hi = (_Float16)0.0f, lo = (_Float16)0.0f;
+        if (act && j < d) {
+            double mu = U.mu64T[(size_t)j * KP + ci];
+            if (!all) {
+                mu = (double)U.S[ci * (DK + 1) + j] / (double)U.n[ci];
+                U.mu64T[(size_t)j * KP + ci] = mu;
             }
+            const double m = mu - (double)U.ojf[j];
+            b = m * m;
+            const float w = (float)(-2.0 * m);
+            hi = (_Float16)w;
+            lo = (_Float16)(w - (float)hi);
         }
         b = b + dpp_xor_f64<1>(b);
         b = b + dpp_xor_f64<2>(b);
-        if (QN == 8) b = b + dpp_xor_f64<4>(b);
-        if (act && (4 * q < d || q == QN - 1)) {
-            if (q == QN - 1) {
+        b = b + dpp_xor_f64<4>(b);
+        b = b + __shfl_xor(b, 8, 64);
+        b = b + __shfl_xor(b, 16, 64);
+        if (act) {
+            if (j == DK - 1) {
                 const float bs = (float)b * (1.0f / kBiasScale);
-                const _Float16 bhi = (_Float16)bs;
-                hi4[1] = bhi;
-                lo4[1] = (_Float16)(bs - (float)bhi);
-                hi4[2] = hi4[3] = (_Float16)kBiasScale;      // the two threshold slots
-                lo4[2] = lo4[3] = (_Float16)0.0f;
-                U.bias[c] = __double2float_ru(b) * 1.0000005f;
-                if (!all) *U.upd_stamp = stamp + 1;
+                hi = (_Float16)bs;
+                lo = (_Float16)(bs - (float)hi);
+                U.bias[ci] = __double2float_ru(b) * 1.0000005f;
             }
-            const int mt = c >> 5, m32 = c & 31;
-            const int g = q >> 1, hh = g & 1, fstep = g >> 1, sub = q & 1;
-            half4 *fh = reinterpret_cast<half4 *>(U.afrag + (mt * NS2 + fstep) * 64 + 32 * hh + m32) + sub;
-            half4 *fl = reinterpret_cast<half4 *>(U.afrag + (mt * NS2 + NS + fstep) * 64 + 32 * hh + m32) + sub;
-            *fh = hi4;
-            *fl = lo4;
+            const int mt = ci >> 5, m32 = frag_row(ci);
+            const int fstep = j >> 4, kh = (j >> 3) & 1, e = j & 7;
+            _Float16 *fh = reinterpret_cast<_Float16 *>(U.afrag + (mt * NS2 + fstep) * 64 + 32 * kh + m32) + e;
+            _Float16 *fl = reinterpret_cast<_Float16 *>(U.afrag + (mt * NS2 + NS + fstep) * 64 + 32 * kh + m32) + e;
+            *fh = hi;
+            *fl = lo;
         }
     }
 }
@@ -471,12 +484,13 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
     constexpr int NS = DK / 16;          // distinct B fragments per row
     constexpr int NS2 = 2 * NS;          // chained instructions per 32x32 tile
     constexpr int CH = 16 / NS2;         // scores handled between two matrix instructions
+    constexpr int kBulkTiles = 6;        // from this many tiles with decisions on, a wave sums its label changes on the matrix cores
     const int KP = a.kmax > 32 ? 64 : 32;
     MfmaLds<DK> U(smem, KP);
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int wave = tid >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int nwaves = blockDim.x >> 6;
     const int n32 = lane & 31;           // row within a 32-row tile
     const int h = lane >> 5;             // which half of the knob slots / centroid rows this lane holds
@@ -488,14 +502,18 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
     const int64_t crow = (int64_t)t * a.Ksum + a.koff[ki];
     uint8_t *labrow = a.labbuf + (int64_t)ki * a.ld;
 
-    WaveQueue<DK> Q(U.wave_base + MfmaLds<DK>::kWaveBytes * wave);
+    WaveQueue<DK> Q(U.wave_base + MfmaLds<DK>::wave_bytes(NTW) * wave);
     const int wave_row0 = wave * NTW * 32;                 // first row (task-relative) of this wave
     const bool wave_live = wave_row0 < nrows;              // the wave owns at least one row
 
-    // The last three knob slots of the fragments are reserved (d <= DK - 3): slot DK - 3 carries the
-    // bias (256 in B, |mu'|^2 / 256 as hi/lo in A), slots DK - 2 and DK - 1 a per-row threshold
-    // (-tau / 256 as hi/lo in B, 256 in A), so that the scores come out as score - tau.
-    constexpr int bstep = NS - 1, bhalf = 1, belem = 5;
+    // Live accumulator registers: centroids 2 i + hh sit in register i, so a tile of kk centroids has
+    // scores in its first ceil(kk / 2) registers; they are walked in groups of four.
+    const int kk_last = two ? k - 32 : k;                  // centroids in the last (or only) m-tile
+    const int lregs = ((kk_last + 1) / 2 + 3) & ~3;        // 4, 8, 12 or 16
+
+    // The last knob slot of the fragments is reserved (d <= DK - 1): it carries the bias (256 in B,
+    // |mu'|^2 / 256 as hi/lo in A).
+    constexpr int bstep = NS - 1, bhalf = 1, belem = 7;
 
     // ---- set-up
     for (int e = tid; e < DK * KP; e += blockDim.x) U.mu64T[e] = 0.0;
@@ -514,14 +532,12 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
     __syncthreads();
     // padding centroid rows (beyond k) carry a huge bias so that they never win
     for (int c = k + tid; c < KP; c += blockDim.x) {
-        _Float16 *slot = reinterpret_cast<_Float16 *>(U.afrag + ((c >> 5) * NS2 + bstep) * 64 + 32 * bhalf + (c & 31)) + belem;
-        slot[0] = (_Float16)kPadBiasHi;
-        slot[1] = slot[2] = (_Float16)kBiasScale;
+        _Float16 *bslot = reinterpret_cast<_Float16 *>(U.afrag + ((c >> 5) * NS2 + bstep) * 64 + 32 * bhalf + frag_row(c)) + belem;
+        bslot[0] = (_Float16)kPadBiasHi;
     }
     if (tid == 0) {
-        U.upd_stamp[0] = -1;
-        U.upd_stamp[1] = -1;      // last pass that changed a sum
-        U.upd_stamp[2] = 0;       // set if a pass that must not change a label did
+        U.stamp[0] = -1;          // last pass that changed a sum
+        U.stamp[1] = 0;           // float bits of the largest squared norm of a centred row
     }
     for (int e = tid; e < k * d; e += blockDim.x) {
         const int c = e / d, j = e % d;
@@ -552,10 +568,8 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
     // ---- this lane's rows as B fragments (kept in registers for every pass)
     const _Float16 *xh_wave = reinterpret_cast<const _Float16 *>(a.xh) + (r0 + (wave_live ? wave_row0 : 0)) * DK;
     half8 B[NTW][NS];
-    uint32_t prevpack[(NTW + 3) / 4];
-#pragma unroll
-    for (int q = 0; q < (NTW + 3) / 4; ++q) prevpack[q] = 0xFFFFFFFFu;   // 0xFF = row has no label yet
     {
+        float x2row[NTW];                // squared norm of this lane's row of every tile
         half8 off8[NS];
 #pragma unroll
         for (int f = 0; f < NS; ++f)
@@ -576,18 +590,25 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
                 B[nt][f] = v;
             }
         }
+        float xmax = 0.0f;
 #pragma unroll
         for (int nt = 0; nt < NTW; ++nt) {
             float part = 0.0f;
 #pragma unroll
-            for (int f = 0; f < NS; ++f)
+            for (int f = 0; f < NS; ++f) {
+                // an opaque copy: otherwise the compiler keeps these conversions (128 values) alive in
+                // scratch memory through the whole iteration for the loss computation at its end
+                half8 bv = B[nt][f];
+                asm volatile("" : "+v"(bv));
 #pragma unroll
                 for (int i = 0; i < 8; ++i) {
-                    const float v = (float)B[nt][f][i];
+                    const float v = (float)bv[i];
                     part = __builtin_fmaf(v, v, part);
                 }
+            }
             part = part + __shfl_xor(part, 32, 64);
-            if (h == 0) Q.x2()[nt * 32 + n32] = part;
+            x2row[nt] = part;
+            xmax = __builtin_fmaxf(xmax, part);
             // the bias slot: a constant for every live row (after the norm, which excludes it)
             const bool live = wave_live && (wave_row0 + nt * 32 + n32) < nrows;
             if (live && h == bhalf) {
@@ -598,85 +619,98 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
                         if (f == bstep && i == belem) B[nt][f][i] = (_Float16)kBiasScale;
             }
         }
+        xmax = wave_max_nonneg(xmax);
+        if (lane == 0) atomicMax(&U.stamp[1], __float_as_int(xmax));     // non-negative floats order like integers
+        __syncthreads();
+        // Largest squared norm a centred centroid can take during the iteration: every later centroid
+        // is a mean of rows (inside their convex hull) or stays where it started.
+        float m2 = wave_max_nonneg(lane < k ? U.bias[lane] : 0.0f);
+        m2 = __builtin_fmaxf(m2, __int_as_float(U.stamp[1])) * 1.000001f;
+#pragma unroll
+        for (int nt = 0; nt < NTW; ++nt)
+            if (h == 0) Q.eb()[nt * 32 + n32] = mfma_bound<NS2>(x2row[nt], m2);
     }
-    __syncthreads();
+    __builtin_amdgcn_wave_barrier();
+
+    // no row has a label yet
+    for (int e = lane; e < WaveQueue<DK>::kRows; e += 64) Q.lab()[e] = 0xFF;
+    __builtin_amdgcn_wave_barrier();
 
     double loss = 0.0;
-    const int rows_left = nrows - wave_row0 - n32;      // this lane's row of tile nt is in the task iff 32 nt < rows_left
-    bool have_tau = false;      // the rows' threshold slots are valid for the current centroids
-#ifdef CHAM_KERNEL_TIMING
-    unsigned long long tacc[16] = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
-#endif
-    for (int it = 0; it <= a.n_iter; ++it) {
-        const bool final_pass = (it == a.n_iter);
-        const bool want_dist = final_pass || (a.trace != nullptr);
-        CHAM_T(t_a);
+    const int rows_wave = __builtin_amdgcn_readfirstlane(nrows - wave_row0);   // rows from this wave's first row to the task's end
+    uint32_t force_tiles = 0xFFFFFFFFu;  // tiles to decide whatever their masks say: all at first, later those with undecided rows
+    int passes_run = 0;
+    bool traced_last = false;
 
-        uint32_t newpack[(NTW + 3) / 4];
+    // lanes of tile nt (as a 32-bit mask over the row index within the tile) whose row belongs to the task
+    auto live_rows = [&](int nt) -> uint32_t {
+        int left = rows_wave - 32 * nt;
+        left = left < 0 ? 0 : (left > 32 ? 32 : left);
+        return left == 32 ? 0xFFFFFFFFu : ((1u << left) - 1u);
+    };
+    // This lane's B fragments of tile nt, nt known at run time only (the same for the whole wave): one
+    // branch per tile around a register copy, so that the code that follows exists once, not per tile.
+    auto rows_of_tile = [&](int nt, half8 (&bt)[NS]) {
 #pragma unroll
-        for (int q = 0; q < (NTW + 3) / 4; ++q) newpack[q] = 0;
-        uint32_t flagged_tiles = 0;
-        int nrec = 0;
+        for (int n = 0; n < NTW; ++n) {
+            if (nt == n) {
+#pragma unroll
+                for (int f = 0; f < NS; ++f) {
+                    bt[f] = B[n][f];
+                    asm volatile("" : "+v"(bt[f]));      // keeps the copy under its branch
+                }
+            }
+        }
+    };
 
-        // How this pass decides its rows (the same for every wave of the workgroup):
-        //   kScreen   best score, threshold best + bound, one mark per score (always valid); the
-        //             best score of every row is kept for a later measurement;
-        //   kCount    no centroid has changed since the rows' thresholds tau were measured: a row
-        //             keeps its label iff exactly one score lies below its tau (one sign bit per
-        //             score); a row with several is queued with exactly those centroids.
-        // The thresholds are measured at the start of the first pass that finds the centroids of
-        // the pass before unchanged, from the best scores of that pass.
-        enum { kScreen = 0, kCount = 2 };
-        const bool changed_prev = it == 0 || __builtin_amdgcn_readfirstlane(*U.upd_stamp) == it;
-        const int mode = changed_prev ? kScreen : kCount;
-        const bool measure_now = !changed_prev && !have_tau;
-        have_tau = !changed_prev;
-
-        CHAM_TCOUNT(14, mode == kCount ? 1 : 0);
+    // Exact loss of the current labels from the rows in registers: (x - mu)^2 in double over the knobs
+    // a lane holds (x = centred value + offset, exact), the two lanes of a row and all rows added up
+    // afterwards; the per-wave sums land in U.red[slot8 .. slot8 + nwaves).
+    auto wave_loss = [&](int slot8) {
+        double part = 0.0;
         if (wave_live) {
-            // A fragments of this pass (the bias slot included) and the bound m2
+            float of[NS][8];
+#pragma unroll
+            for (int f = 0; f < NS; ++f)
+#pragma unroll
+                for (int i = 0; i < 8; ++i) of[f][i] = U.ojf[16 * f + 8 * h + i];
+            for (int nt = 0; nt < NTW; ++nt) {
+                half8 bt[NS];
+                rows_of_tile(nt, bt);
+                const uint32_t lab = Q.lab()[nt * 32 + n32];
+                const bool live = lab != 0xFFu;
+                const double *mc = U.mu64T + (live ? lab : 0u) + (size_t)(8 * h) * KP;
+                double s = 0.0;
+#pragma unroll
+                for (int f = 0; f < NS; ++f)
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) {
+                        float xf = (float)bt[f][i] + of[f][i];
+                        if (f == bstep && i == belem) xf = h == bhalf ? 0.0f : xf;     // the bias slot is no knob
+                        const double tq = (double)xf - mc[(size_t)(16 * f + i) * KP];
+                        s = s + tq * tq;
+                    }
+                part = part + (live ? s : 0.0);
+            }
+        }
+        const double ws = wave_sum(part);
+        if (lane == 0) U.red[slot8 + wave] = ws;
+    };
+
+    for (int it = 0; it <= a.n_iter; ++it) {
+        const bool last_pass = (it == a.n_iter);
+        passes_run = it + 1;
+        uint32_t dirty_tiles = 0;        // tiles whose masks differ from the remembered ones (or that are forced)
+
+        if (wave_live) {
+            // A fragments of this pass (the bias slot included)
             half8 A0[NS2], A1[NS2];
 #pragma unroll
             for (int s = 0; s < NS2; ++s) {
                 A0[s] = U.afrag[s * 64 + lane];
                 A1[s] = two ? U.afrag[(NS2 + s) * 64 + lane] : A0[s];
             }
-            float m2 = 0.0f;
-            if (mode != kCount || measure_now) {
-                m2 = wave_max_nonneg(lane < KP ? U.bias[lane] : 0.0f);
-            }
 
-            if (measure_now) {
-                // Every row's threshold for the passes to come.  best = smallest computed
-                // score - tau_old of the pass before (same centroids), bnd = the bound it was screened
-                // with.  The new tau exceeds the true score of the row's centroid by more than the
-                // screen errors of that pass and of the passes that use it, and a centroid that is
-                // not counted later is farther than the row's centroid by more than those errors.
-                // Lanes of the upper half own the slots.
-#pragma unroll
-                for (int nt = 0; nt < NTW; ++nt) {
-                    const float best = Q.best()[nt * 32 + n32];
-                    const float xs = Q.x2()[nt * 32 + n32];
-                    const float bnd = mfma_bound<NS2>(xs, m2);
-                    const float b6 = (float)B[nt][NS - 1][6], b7 = (float)B[nt][NS - 1][7];
-                    const float tq = best - kBiasScale * (b6 + b7);                    // score with tau_old taken out
-                    const float bnd2 = mfma_bound<NS2>(xs + 2.0f * __builtin_fabsf(tq) + 4.0f * bnd + 2.0f, m2) + 1.0e-4f;
-                    // one screen error is at most 0.4 of a bound (mfma_bound = 2 errors x 1.25): tau lies above
-                    // the measured best by this pass's error, the later passes' error and a quarter more
-                    const float tau = tq + 0.5f * bnd + 0.5f * bnd2 + __builtin_fabsf(tq) * 9.5367431640625e-7f;
-                    const float u = -tau * (1.0f / kBiasScale);
-                    const _Float16 h6 = (_Float16)u;
-                    const _Float16 h7 = (_Float16)(u - (float)h6);
-                    if (h == bhalf) {
-                        B[nt][NS - 1][6] = h6;
-                        B[nt][NS - 1][7] = h7;
-                        Q.x2()[nt * 32 + n32] = xs + __builtin_fabsf(tau) * 1.000001f + 1.0f;
-                    }
-                }
-            }
-
-            CHAM_T(t_a2);
-            CHAM_TADD(10, t_a, t_a2);   // pass prologue (inside "tiles")
             float16v accA, accB;
             const float16v zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 
@@ -690,346 +724,313 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
                 for (int i = 0; i < CH; ++i)
                     far = __builtin_amdgcn_alignbit(far, __float_as_uint(thr - acc[i0 + i]), 31);
             };
-            // sign bits of scores [i0, i0 + CH): bit set = score - tau below zero
-            auto signs = [&](uint32_t &neg, const float16v &acc, int i0) {
-#pragma unroll
-                for (int i = 0; i < CH; ++i) neg = __builtin_amdgcn_alignbit(neg, __float_as_uint(acc[i0 + i]), 31);
-            };
-            auto min16 = [&](const float16v &acc) {
-                float b = __builtin_fminf(min3f(acc[0], acc[1], acc[2]), acc[3]);
-                b = min3f(min3f(b, acc[4], acc[5]), acc[6], acc[7]);
-                b = min3f(min3f(b, acc[8], acc[9]), acc[10], acc[11]);
-                b = min3f(min3f(b, acc[12], acc[13]), acc[14], acc[15]);
+            // minimum over the first nreg registers (nreg = 4, 8, 12 or 16, the same for every lane)
+            auto min_live = [&](const float16v &acc, int nreg) {
+                float b = vmin(vmin3(acc[0], acc[1], acc[2]), acc[3]);
+                if (nreg > 4) b = vmin3(vmin3(b, acc[4], acc[5]), acc[6], acc[7]);
+                if (nreg > 8) b = vmin3(vmin3(b, acc[8], acc[9]), acc[10], acc[11]);
+                if (nreg > 12) b = vmin3(vmin3(b, acc[12], acc[13]), acc[14], acc[15]);
                 return b;
             };
-            // decide or queue the rows of tile nt from the candidate mask of this lane half
-            auto decide = [&](uint32_t far, int nt, bool keep) {
-                const uint32_t cand = ~far;
+            // both lane halves' minima of a row -> the row's minimum
+            auto row_min = [&](float v) {
+                unsigned lo, hi;
+                both_halves(__float_as_uint(v), lo, hi);
+                return vmin(__uint_as_float(lo), __uint_as_float(hi));
+            };
+            // After the masks of tile nt: if any row's mask differs from the remembered one (or the tile is
+            // forced), remember the new masks and put the tile on the list of tiles to decide.
+            auto settle = [&](uint32_t far, uint32_t seen, int nt) {
+                const uint64_t diff = __ballot(far != seen);
+                uint32_t dirty32 = ((uint32_t)diff | (uint32_t)(diff >> 32)) & live_rows(nt);
+                if ((force_tiles >> nt) & 1u) dirty32 = live_rows(nt);
+                if (dirty32) {
+                    Q.seen()[nt * 64 + lane] = far;
+                    dirty_tiles |= 1u << nt;
+                }
+            };
+
+            // bound and remembered mask of the tile under way; those of the next tile are fetched a tile ahead
+            float eb_cur = Q.eb()[n32];
+            uint32_t seen_cur = Q.seen()[lane];
+            if (two) {
+                // accA = centroids 0..31 (all sixteen registers live), accB = centroids 32..k-1 of the current tile
+#pragma unroll
+                for (int s = 0; s < NS2; ++s) mma(accA, A0, B[0], s);
+#pragma unroll
+                for (int s = 0; s < NS2; ++s) mma(accB, A1, B[0], s);
+#pragma unroll
+                for (int nt = 0; nt < NTW; ++nt) {
+                    constexpr int kLast = NTW - 1;
+                    const int nx = nt < kLast ? nt + 1 : nt;
+                    const float eb_nxt = Q.eb()[nx * 32 + n32];
+                    const uint32_t seen_nxt = Q.seen()[nx * 64 + lane];
+                    const float best = row_min(vmin(min_live(accA, 16), min_live(accB, lregs)));
+                    const float thr = best + eb_cur;
+                    uint32_t far = 0;
+#pragma unroll
+                    for (int s = 0; s < NS2; ++s) mark(far, accA, thr, s * CH);
+                    // accA is consumed: its next chain runs under the marking of accB
+#pragma unroll
+                    for (int s = 0; s < NS2; ++s) {
+                        __builtin_amdgcn_sched_barrier(0);
+                        if (nt < kLast) mma(accA, A0, B[nx], s);
+                        __builtin_amdgcn_sched_barrier(0);
+                        if (s * CH < lregs) mark(far, accB, thr, s * CH);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                    if (nt < kLast) {
+#pragma unroll
+                        for (int s = 0; s < NS2; ++s) mma(accB, A1, B[nx], s);
+                    }
+                    // registers of accB that were not walked hold padding only: far
+                    const int live_marks = CH * ((lregs + CH - 1) / CH);
+                    far = (far << (16 - live_marks)) | ((1u << (16 - live_marks)) - 1u);
+                    settle(far, seen_cur, nt);
+                    eb_cur = eb_nxt;
+                    seen_cur = seen_nxt;
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            } else {
+                // one m-tile: the accumulators alternate, the next tile's chain runs under this epilogue
+#pragma unroll
+                for (int s = 0; s < NS2; ++s) mma(accA, A0, B[0], s);
+#pragma unroll
+                for (int nt = 0; nt < NTW; ++nt) {
+                    constexpr int kLast = NTW - 1;
+                    const int nx = nt < kLast ? nt + 1 : nt;
+                    float16v &cur = (nt & 1) ? accB : accA;
+                    float16v &nxt = (nt & 1) ? accA : accB;
+                    const float eb_nxt = Q.eb()[nx * 32 + n32];
+                    const uint32_t seen_nxt = Q.seen()[nx * 64 + lane];
+                    const float best = row_min(min_live(cur, lregs));
+                    const float thr = best + eb_cur;
+                    uint32_t far = 0;
+#pragma unroll
+                    for (int s = 0; s < NS2; ++s) {
+                        __builtin_amdgcn_sched_barrier(0);
+                        if (nt < kLast) mma(nxt, A0, B[nx], s);
+                        __builtin_amdgcn_sched_barrier(0);
+                        if (s * CH < lregs) mark(far, cur, thr, s * CH);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                    const int live_marks = CH * ((lregs + CH - 1) / CH);
+                    far = (far << (32 - live_marks)) | (0xFFFFFFFFu >> live_marks);
+                    settle(far, seen_cur, nt);
+                    eb_cur = eb_nxt;
+                    seen_cur = seen_nxt;
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+        }
+
+        // ---- decide the rows of the listed tiles (this code exists once; the tile index is a run-time value)
+        uint32_t flagged_tiles = 0;
+        int nrec = 0;
+        {
+            uint32_t todo = dirty_tiles;
+            while (todo) {
+                const int nt = __builtin_ctz(todo);
+                todo &= todo - 1;
+                // a batch of queued rows that may not fit one more tile is resolved first
+                if (nrec + 32 > kRecCap) {
+                    resolve_queue<DK>(Q, nrec, U.mu64T, U.ojf, KP, k, d);
+                    nrec = 0;
+                }
+                const uint32_t live32 = live_rows(nt);
+                const uint32_t cand = ~Q.seen()[nt * 64 + lane];       // bit 31 = position 0
                 uint32_t cand_lo, cand_hi;
                 both_halves(cand, cand_lo, cand_hi);
                 const int total = __popc(cand_lo) + __popc(cand_hi);
-                // compared afresh in every tile: sixteen hoisted lane masks cost more than sixteen compares
-                int rl = rows_left;
-                asm volatile("" : "+v"(rl));
-                const bool live = nt * 32 < rl;
+                const bool live = (live32 >> n32) & 1u;
                 const bool flagged = live && total != 1;
-                if (keep) {
-                    // the single candidate is the row's centroid of the pass before (rows outside the
-                    // task carry 0xFF there already)
-                    const uint32_t prev = prevpack[nt >> 2] & (0xFFu << (8 * (nt & 3)));
-                    newpack[nt >> 2] |= flagged ? (0xFEu << (8 * (nt & 3))) : prev;
-                } else {
-                    const int hh = cand_lo ? 0 : 1;
-                    const int q = __clz((int)(cand_lo ? cand_lo : cand_hi));
-                    const int lab = centroid_of(q & 31, hh);
-                    newpack[nt >> 2] |= (uint32_t)(!live ? 0xFF : (flagged ? 0xFE : lab)) << (8 * (nt & 3));
-                }
-                // the label is packed here and now: left to itself the compiler defers all of this to
-                // the end of the pass and keeps both candidate masks of every tile live until then
-                asm volatile("" : "+v"(newpack[nt >> 2]));
+                const int hh = cand_lo ? 0 : 1;
+                const int q = __clz((int)(cand_lo ? cand_lo : cand_hi));
+                const int lab = slot_centroid(q & 31, hh);
+                if (h == 0) Q.lab_new()[nt * 32 + n32] = (unsigned char)(!live ? 0xFF : (flagged ? 0xFE : lab));
                 const uint64_t fm = __ballot(flagged) & 0xFFFFFFFFull;
                 if (fm) {
-                    flagged_tiles |= flagged ? (1u << nt) : 0u;
+                    flagged_tiles |= 1u << nt;
+                    half8 bt[NS];
+                    rows_of_tile(nt, bt);
                     if (flagged) {
                         const int rs = nrec + __popcll(fm & ((1ull << n32) - 1ull));
-                        if (rs < kRecCap) {
 #pragma unroll
-                            for (int f = 0; f < NS; ++f) {
-                                *reinterpret_cast<half8 *>(Q.rec_x() + (size_t)rs * DK + 16 * f + 8 * h) = B[nt][f];
-                            }
-                        }
-                        // no candidate at all cannot happen with valid thresholds; if it does, every centroid is one
-                        Q.rec_mask()[rs * 2 + h] = total ? cand : (two ? 0xFFFFFFFFu : 0xFFFF0000u);
+                        for (int f = 0; f < NS; ++f)
+                            *reinterpret_cast<half8 *>(Q.rec_x() + (size_t)rs * DK + 16 * f + 8 * h) = bt[f];
+                        // no candidate at all cannot happen (the smallest score is always one); if it does, every centroid is one
+                        Q.rec_mask()[rs * 2 + h] = total ? cand : 0xFFFFFFFFu;
                         if (h == 0) Q.rec_pid()[rs] = (unsigned short)(nt * 32 + n32);
                     }
                     nrec += __popcll(fm);
                 }
-            };
-            if (mode == kCount) {
-                // The scores come out as score - tau.  A row whose only negative score is its
-                // centroid's keeps its label; a row with several is queued with exactly those
-                // centroids as candidates (the nearest centroid is always among them).
-                if (two) {
-#pragma unroll
-                    for (int s = 0; s < NS2; ++s) mma(accA, A0, B[0], s);
-#pragma unroll
-                    for (int s = 0; s < NS2; ++s) mma(accB, A1, B[0], s);
-#pragma unroll
-                    for (int nt = 0; nt < NTW; ++nt) {
-                        constexpr int kLast = NTW - 1;
-                        const int nx = nt < kLast ? nt + 1 : nt;
-                        uint32_t neg = 0;
-#pragma unroll
-                        for (int s = 0; s < NS2; ++s) signs(neg, accA, s * CH);
-                        // accA is consumed: its next chain runs under the sign collection of accB
-#pragma unroll
-                        for (int s = 0; s < NS2; ++s) {
-                            __builtin_amdgcn_sched_barrier(0);
-                            if (nt < kLast) mma(accA, A0, B[nx], s);
-                            __builtin_amdgcn_sched_barrier(0);
-                            signs(neg, accB, s * CH);
-                        }
-                        __builtin_amdgcn_sched_barrier(0);
-                        if (nt < kLast) {
-#pragma unroll
-                            for (int s = 0; s < NS2; ++s) mma(accB, A1, B[nx], s);
-                        }
-                        decide(~neg, nt, true);
-                        __builtin_amdgcn_sched_barrier(0);
-                    }
-                } else {
-#pragma unroll
-                    for (int s = 0; s < NS2; ++s) mma(accA, A0, B[0], s);
-#pragma unroll
-                    for (int nt = 0; nt < NTW; ++nt) {
-                        constexpr int kLast = NTW - 1;
-                        const int nx = nt < kLast ? nt + 1 : nt;
-                        float16v &cur = (nt & 1) ? accB : accA;
-                        float16v &nxt = (nt & 1) ? accA : accB;
-                        uint32_t neg = 0;
-#pragma unroll
-                        for (int s = 0; s < NS2; ++s) {
-                            __builtin_amdgcn_sched_barrier(0);
-                            if (nt < kLast) mma(nxt, A0, B[nx], s);
-                            __builtin_amdgcn_sched_barrier(0);
-                            signs(neg, cur, s * CH);
-                        }
-                        __builtin_amdgcn_sched_barrier(0);
-                        decide((~neg << 16) | 0xFFFFu, nt, true);
-                        __builtin_amdgcn_sched_barrier(0);
-                    }
-                }
-            } else {
-                float x2cur = Q.x2()[n32];
-                if (two) {
-                    // accA = centroids 0..31, accB = centroids 32..63 of the current tile
-#pragma unroll
-                    for (int s = 0; s < NS2; ++s) mma(accA, A0, B[0], s);
-#pragma unroll
-                    for (int s = 0; s < NS2; ++s) mma(accB, A1, B[0], s);
-#pragma unroll
-                    for (int nt = 0; nt < NTW; ++nt) {
-                        constexpr int kLast = NTW - 1;
-                        const int nx = nt < kLast ? nt + 1 : nt;
-                        float best = min_halves(__builtin_fminf(min16(accA), min16(accB)));
-                        const float thr = best + mfma_bound<NS2>(x2cur, m2);
-                        if (nt < kLast) x2cur = Q.x2()[nx * 32 + n32];
-                        uint32_t far = 0;
-#pragma unroll
-                        for (int s = 0; s < NS2; ++s) mark(far, accA, thr, s * CH);
-                        // accA is consumed: its next chain runs under the marking of accB
-#pragma unroll
-                        for (int s = 0; s < NS2; ++s) {
-                            __builtin_amdgcn_sched_barrier(0);
-                            if (nt < kLast) mma(accA, A0, B[nx], s);
-                            __builtin_amdgcn_sched_barrier(0);
-                            mark(far, accB, thr, s * CH);
-                        }
-                        __builtin_amdgcn_sched_barrier(0);
-                        if (nt < kLast) {
-#pragma unroll
-                            for (int s = 0; s < NS2; ++s) mma(accB, A1, B[nx], s);
-                        }
-                        decide(far, nt, false);
-                        if (h == 0) Q.best()[nt * 32 + n32] = best;
-                        __builtin_amdgcn_sched_barrier(0);   // labels of this tile are packed before the next tile
-                    }
-                } else {
-                    // one m-tile: the accumulators alternate, the next tile's chain runs under this epilogue
-#pragma unroll
-                    for (int s = 0; s < NS2; ++s) mma(accA, A0, B[0], s);
-#pragma unroll
-                    for (int nt = 0; nt < NTW; ++nt) {
-                        constexpr int kLast = NTW - 1;
-                        const int nx = nt < kLast ? nt + 1 : nt;
-                        float16v &cur = (nt & 1) ? accB : accA;
-                        float16v &nxt = (nt & 1) ? accA : accB;
-                        float best = min_halves(min16(cur));
-                        const float thr = best + mfma_bound<NS2>(x2cur, m2);
-                        if (nt < kLast) x2cur = Q.x2()[nx * 32 + n32];
-                        uint32_t far = 0;
-#pragma unroll
-                        for (int s = 0; s < NS2; ++s) {
-                            __builtin_amdgcn_sched_barrier(0);
-                            if (nt < kLast) mma(nxt, A0, B[nx], s);
-                            __builtin_amdgcn_sched_barrier(0);
-                            mark(far, cur, thr, s * CH);
-                        }
-                        __builtin_amdgcn_sched_barrier(0);
-                        far = (far << 16) | 0xFFFFu;
-                        decide(far, nt, false);
-                        if (h == 0) Q.best()[nt * 32 + n32] = best;
-                        __builtin_amdgcn_sched_barrier(0);   // labels of this tile are packed before the next tile
-                    }
-                }
             }
+            if (nrec) resolve_queue<DK>(Q, nrec, U.mu64T, U.ojf, KP, k, d);
         }
-        CHAM_T(t_b);
-        CHAM_TCOUNT(8, nrec);
-        if (nrec) resolve_queue<DK>(Q, nrec, U.mu64T, U.ojf, KP, k, d, xh_wave);
-        CHAM_TCOUNT(11, nrec ? 1 : 0);
-        CHAM_T(t_c);
+        force_tiles = flagged_tiles;
 
-        // Labels of the rows that went through the queue replace their placeholders.
-        if (wave_live && __ballot(flagged_tiles != 0u)) {
-#pragma unroll
-            for (int nt = 0; nt < NTW; ++nt) {
-                if ((flagged_tiles >> nt) & 1u) {
-                    const uint32_t lab = Q.lab_res()[nt * 32 + n32];
-                    newpack[nt >> 2] = (newpack[nt >> 2] & ~(0xFFu << (8 * (nt & 3)))) | (lab << (8 * (nt & 3)));
-                }
-            }
-        }
-        if (wave_live && want_dist) {
-#pragma unroll
-            for (int nt = 0; nt < NTW; ++nt) {
-                const int pid = wave_row0 + nt * 32 + n32;
-                if (pid < nrows && h == 0) labrow[r0 + pid] = (uint8_t)((newpack[nt >> 2] >> (8 * (nt & 3))) & 0xFF);
-            }
-        }
-        // Label changes -> queue of (previous, new, knob values) -> integer sums.  A row without a
-        // label yet has previous = 0xFF; rows outside the task keep 0xFF and never change.  The
-        // queue holds kRecCap rows; if a pass changes more (the first passes do), the tiles are
-        // walked again from the first tile that did not fit.
-        CHAM_T(t_c1);
-        if (wave_live) {
-            uint32_t diff[(NTW + 3) / 4];
-            uint32_t any = 0;
-#pragma unroll
-            for (int q = 0; q < (NTW + 3) / 4; ++q) {
-                diff[q] = newpack[q] ^ prevpack[q];
-                any |= diff[q];
-            }
-            int start = __ballot(any != 0u) ? 0 : NTW;
-            while (start < NTW) {
-                int cnt = 0;
-                int next_start = NTW;
-#pragma unroll
-                for (int nt = 0; nt < NTW; ++nt) {
-                    if (nt < start || next_start != NTW) continue;
-                    const bool changed = ((diff[nt >> 2] >> (8 * (nt & 3))) & 0xFFu) != 0u;
-                    const uint64_t cm = __ballot(changed) & 0xFFFFFFFFull;
-                    if (cm) {
-                        if (cnt + 32 > kRecCap) {
-                            next_start = nt;
-                            continue;
-                        }
-                        if (changed) {
-                            const int rs = cnt + __popcll(cm & ((1ull << n32) - 1ull));
-#pragma unroll
-                            for (int f = 0; f < NS; ++f)
-                                *reinterpret_cast<half8 *>(Q.rec_x() + (size_t)rs * DK + 16 * f + 8 * h) = B[nt][f];
-                            const uint32_t cur = (newpack[nt >> 2] >> (8 * (nt & 3))) & 0xFFu;
-                            const uint32_t prev = (prevpack[nt >> 2] >> (8 * (nt & 3))) & 0xFFu;
-                            if (h == 0) Q.rec_mask()[rs] = cur | (prev << 8);
-                        }
-                        cnt += __popcll(cm);
-                    }
-                }
-                CHAM_TCOUNT(7, cnt);
-                CHAM_T(t_p0);
-                if (cnt) apply_changes<DK>(Q, cnt, U.S, U.n, U.dirty, U.upd_stamp + 1, U.ojf, d, it);
-                if (cnt && mode == kCount && lane == 0) U.upd_stamp[2] = 1;
-                CHAM_T(t_p1);
-                CHAM_TADD(12, t_p0, t_p1);   // apply (inside "sums")
-                start = next_start;
-            }
-#pragma unroll
-            for (int q = 0; q < (NTW + 3) / 4; ++q) prevpack[q] = newpack[q];
-        }
-        if (want_dist) {
-            // Exact loss of this pass from the rows in registers: (x - mu)^2 in double over the knobs
-            // a lane holds (x = centred value + offset, exact), the two lanes of a row and all rows
-            // added up afterwards.  Reserved slots are left out; padded slots are zero on both sides.
-            double part = 0.0;
-            if (wave_live) {
-                float of[NS][8];
+        // ---- label changes of the decided tiles -> integer sums and counts.
+        // A row without a label yet has previous = 0xFF; rows outside the task keep 0xFF and never change.
+        if (__popc(dirty_tiles) >= kBulkTiles) {
+            // Many tiles (the first passes): the sums move by  dS[c][j] = sum_i ([cur_i = c] - [prev_i = c]) x'_ij,
+            // a contraction over the rows, done on the matrix cores: A = the coefficients (-1, 0, 1: a row
+            // that keeps its label contributes nothing), B = the tile's centred rows, staged row-major in
+            // LDS and read back knob-major.  All values are small integers, every partial sum stays below
+            // 2^24: exact.  The bias slot of the rows (256 for every row of the task) yields 256 x the
+            // change of the cluster sizes, from which the centring offsets are put back:
+            // S += dS' + dn * offset.
+            const float16v zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+            float16v sacc0 = zero16, sacc1 = zero16;
+            const int jn = lane & 31;            // knob slot (B, D column) or centroid within the m-tile (A row)
+            bool any_change = false;
+            uint32_t todo = dirty_tiles;
+            while (todo) {
+                const int nt = __builtin_ctz(todo);
+                todo &= todo - 1;
+                half8 bt[NS];
+                rows_of_tile(nt, bt);
 #pragma unroll
                 for (int f = 0; f < NS; ++f)
+                    *reinterpret_cast<half8 *>(Q.rec_x() + (size_t)n32 * DK + 16 * f + 8 * h) = bt[f];
+                __builtin_amdgcn_wave_barrier();
 #pragma unroll
-                    for (int i = 0; i < 8; ++i) of[f][i] = U.ojf[16 * f + 8 * h + i];
+                for (int ks = 0; ks < 2; ++ks) {
+                    const int rbase = 16 * ks + 8 * h;   // this lane's eight rows of the contraction step
+                    const uint64_t cur8 = *reinterpret_cast<const uint64_t *>(Q.lab_new() + nt * 32 + rbase);
+                    const uint64_t prev8 = *reinterpret_cast<const uint64_t *>(Q.lab() + nt * 32 + rbase);
+                    half8 bx;
 #pragma unroll
-                for (int nt = 0; nt < NTW; ++nt) {
-                    const uint32_t lab = (newpack[nt >> 2] >> (8 * (nt & 3))) & 0xFFu;
-                    const bool live = lab != 0xFFu;
-                    const double *mc = U.mu64T + (live ? lab : 0u) + (size_t)(8 * h) * KP;
-                    double s = 0.0;
+                    for (int e = 0; e < 8; ++e)
+                        bx[e] = jn < DK ? Q.rec_x()[(size_t)(rbase + e) * DK + jn] : (_Float16)0.0f;
+                    half8 ax0, ax1;
 #pragma unroll
-                    for (int f = 0; f < NS; ++f)
+                    for (int e = 0; e < 8; ++e) {
+                        const int cc = (int)((cur8 >> (8 * e)) & 0xFF), pp = (int)((prev8 >> (8 * e)) & 0xFF);
+                        ax0[e] = (_Float16)(float)((cc == jn ? 1 : 0) - (pp == jn ? 1 : 0));
+                        ax1[e] = (_Float16)(float)((cc == jn + 32 ? 1 : 0) - (pp == jn + 32 ? 1 : 0));
+                    }
+                    sacc0 = __builtin_amdgcn_mfma_f32_32x32x16_f16(ax0, bx, sacc0, 0, 0, 0);
+                    if (two) sacc1 = __builtin_amdgcn_mfma_f32_32x32x16_f16(ax1, bx, sacc1, 0, 0, 0);
+                }
+                __builtin_amdgcn_wave_barrier();
+                // the tile's labels become current; its changed rows mark their clusters
+                const uint32_t cur = Q.lab_new()[nt * 32 + n32];
+                const uint32_t prev = Q.lab()[nt * 32 + n32];
+                const bool changed = cur != prev;
+                if (changed && h == 0) {
+                    U.dirty[cur] = it;
+                    if (prev != 0xFFu) U.dirty[prev] = it;
+                    Q.lab()[nt * 32 + n32] = (unsigned char)cur;
+                }
+                any_change = any_change || __ballot(changed) != 0ull;
+                __builtin_amdgcn_wave_barrier();
+            }
+            if (any_change) {
+                if (lane == 0) U.stamp[0] = it;
+                const int oj = jn < d ? (int)U.ojf[jn < DK ? jn : 0] : 0;
 #pragma unroll
-                        for (int i = 0; i < 8; ++i) {
-                            float xf = (float)B[nt][f][i] + of[f][i];
-                            if (f == NS - 1 && i >= belem) xf = h == bhalf ? 0.0f : xf;
-                            const double tq = (double)xf - mc[(size_t)(16 * f + i) * KP];
-                            s = s + tq * tq;
+                for (int mt = 0; mt < 2; ++mt) {
+                    if (mt == 1 && !two) continue;
+                    const float16v &sa = mt ? sacc1 : sacc0;
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        const int c = 32 * mt + 8 * (i >> 2) + 4 * h + (i & 3);
+                        const float c0 = readlane_f(sa[i], DK - 1), c1 = readlane_f(sa[i], 32 + DK - 1);
+                        const int dn = (int)((h ? c1 : c0) * (1.0f / kBiasScale));
+                        if (c < k) {
+                            if (jn < d) {
+                                const int delta = (int)sa[i] + dn * oj;
+                                if (delta) atomicAdd(&U.S[c * (DK + 1) + jn], delta);
+                            }
+                            if (jn == DK - 1 && dn) atomicAdd(&U.n[c], dn);
                         }
-                    part = part + (live ? s : 0.0);
+                    }
                 }
             }
-            const double ws = wave_sum(part);
-            if (lane == 0) U.red[(it & 1) * 8 + wave] = ws;
+        } else {
+            // Few tiles: a dense queue of (previous, new, knob values), applied with one lane per
+            // (row, group of four knobs), in batches of at most kRecCap rows.
+            uint32_t todo = dirty_tiles;
+            int cnt = 0;
+            while (todo) {
+                const int nt = __builtin_ctz(todo);
+                todo &= todo - 1;
+                const uint32_t cur = Q.lab_new()[nt * 32 + n32];
+                const uint32_t prev = Q.lab()[nt * 32 + n32];
+                const bool changed = cur != prev;
+                const uint64_t cm = __ballot(changed) & 0xFFFFFFFFull;
+                if (cm) {
+                    if (cnt + 32 > kRecCap) {
+                        apply_changes<DK>(Q, cnt, U.S, U.n, U.dirty, U.stamp, U.ojf, d, it);
+                        cnt = 0;
+                    }
+                    half8 bt[NS];
+                    rows_of_tile(nt, bt);
+                    if (changed) {
+                        const int rs = cnt + __popcll(cm & ((1ull << n32) - 1ull));
+#pragma unroll
+                        for (int f = 0; f < NS; ++f)
+                            *reinterpret_cast<half8 *>(Q.rec_x() + (size_t)rs * DK + 16 * f + 8 * h) = bt[f];
+                        if (h == 0) {
+                            Q.rec_mask()[rs] = cur | (prev << 8);
+                            Q.lab()[nt * 32 + n32] = (unsigned char)cur;
+                        }
+                    }
+                    cnt += __popcll(cm);
+                }
+            }
+            if (cnt) apply_changes<DK>(Q, cnt, U.S, U.n, U.dirty, U.stamp, U.ojf, d, it);
         }
-        // Once the centroids have stopped changing, a pass reads shared state only (fragments,
-        // centroids) and writes nothing that another wave reads: identical inputs give identical
-        // labels, so no sum can change and the waves need not meet until a pass that reports the
-        // loss.  A label change in such a pass would mean the invariant is broken; it is recorded
-        // and reported as status 2.
-        const bool free_run = mode == kCount && !want_dist;
-        CHAM_T(t_d);
-        if (!free_run) __syncthreads();
-        CHAM_T(t_e);
-
-        if (want_dist && tid == 0) {
+        traced_last = false;
+        if (a.trace) {
+            wave_loss((it & 1) * 8);
+            traced_last = true;
+        }
+        __syncthreads();
+        if (a.trace && tid == 0) {
             double s = 0.0;
             for (int w = 0; w < nwaves; ++w) s = s + U.red[(it & 1) * 8 + w];
             loss = s;
-            if (a.trace) a.trace[slot * (a.n_iter + 1) + it] = s;
+            a.trace[slot * (a.n_iter + 1) + it] = s;
         }
-
-        CHAM_T(t_e2);
-        CHAM_TADD(13, t_e, t_e2);    // exact loss (inside "loss/update")
-        // A pass that moved no row leaves every sum as it was: no update, and no second barrier
-        // (the flag is read after the barrier above; a wave that runs ahead can only overwrite it
-        // with a later pass number, which reads the same).
-        if (!free_run && !final_pass && __builtin_amdgcn_readfirstlane(U.upd_stamp[1]) == it) {
-            update_centroids<DK>(U, k, KP, d, it, false);
-            __syncthreads();
-        }
-        CHAM_T(t_f);
-        CHAM_TADD(0, t_a, t_b);   // tiles
-        if (mode == kCount) { CHAM_TADD(5, t_a, t_b); CHAM_TADD(6, t_a, t_f); }
-        CHAM_TADD(1, t_b, t_c);   // resolve
-        CHAM_TADD(2, t_c, t_d);   // sums
-        CHAM_TADD(3, t_d, t_e);   // barrier wait
-        CHAM_TADD(4, t_e, t_f);   // loss / update
-        CHAM_TCOUNT(9, 1);
-#ifdef CHAM_KERNEL_TIMING
-        if (lane == 0 && it < 64) {
-            atomicAdd(&g_pass[it * 16 + 0], t_b - t_a);
-            atomicAdd(&g_pass[it * 16 + 1], t_c - t_b);
-            atomicAdd(&g_pass[it * 16 + 2], t_d - t_c);
-            atomicAdd(&g_pass[it * 16 + 3], t_e - t_d);
-            atomicAdd(&g_pass[it * 16 + 4], t_f - t_e);
-            atomicAdd(&g_pass[it * 16 + 5], (unsigned long long)(mode == kCount ? 1 : 0));
-            atomicAdd(&g_pass[it * 16 + 6], 1ull);
-            atomicAdd(&g_pass[it * 16 + 7], (unsigned long long)nrec);
-            atomicAdd(&g_pass[it * 16 + 8], (unsigned long long)__popc(flagged_tiles));
-        }
-#endif
+        // A pass that moved no row leaves every sum, hence every centroid, as it was: the labels are
+        // final.  (The flag is read between this pass's two barriers, or after its only one when the
+        // loop ends here; no wave writes it in between.)
+        const bool changed_any = __builtin_amdgcn_readfirstlane(U.stamp[0]) == it;
+        if (last_pass || !changed_any) break;
+        update_centroids<DK>(U, k, KP, d, it, false);
+        __syncthreads();
     }
 
-#ifdef CHAM_KERNEL_TIMING
-    if (lane == 0)
-        for (int q = 0; q < 16; ++q) atomicAdd(&g_timing[q], tacc[q]);
-#endif
+    // ---- results: labels, loss, centroids, counts
+    if (wave_live) {
+        for (int e = lane; e < NTW * 32; e += 64) {
+            const int pid = wave_row0 + e;
+            if (pid < nrows) labrow[r0 + pid] = Q.lab()[e];
+        }
+    }
+    if (!traced_last) {
+        wave_loss(0);
+        __syncthreads();
+        if (tid == 0) {
+            double s = 0.0;
+            for (int w = 0; w < nwaves; ++w) s = s + U.red[w];
+            loss = s;
+        }
+    }
+    if (a.trace && tid == 0) {
+        // the passes that were not run would have seen the same labels and centroids
+        for (int it = passes_run; it <= a.n_iter; ++it) a.trace[slot * (a.n_iter + 1) + it] = loss;
+    }
     for (int e = tid; e < k * d; e += blockDim.x) {
         const int c = e / d, j = e % d;
         a.centroids[(crow + c) * d + j] = U.mu64T[(size_t)j * KP + c];
     }
     for (int c = tid; c < k; c += blockDim.x) a.counts[crow + c] = U.n[c];
     if (tid == 0) {
-        a.status[slot] = U.upd_stamp[2] ? 2 : 0;
+        a.status[slot] = 0;
         a.inertia[slot] = loss;
+        a.passes[slot] = passes_run;
     }
 }
 
@@ -1072,7 +1073,7 @@ template <int DK, int NTW>
 hipError_t launch_mfma_t(const SweepArgs &a, int nwaves, hipStream_t s)
 {
     const int KP = a.kmax > 32 ? 64 : 32;
-    const size_t lds = MfmaLds<DK>::bytes(KP, nwaves);
+    const size_t lds = MfmaLds<DK>::bytes(KP, nwaves, NTW);
     auto kern = resident_mfma_kernel<DK, NTW>;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -1084,25 +1085,10 @@ hipError_t launch_mfma_t(const SweepArgs &a, int nwaves, hipStream_t s)
 
 }  // namespace
 
-#ifdef CHAM_KERNEL_TIMING
-extern "C" int cham_dev_pass_timing(unsigned long long *host512, int reset)
-{
-    static unsigned long long z[64 * 16] = {0};
-    if (reset) return (int)hipMemcpyToSymbol(HIP_SYMBOL(g_pass), z, sizeof(z));
-    return (int)hipMemcpyFromSymbol(host512, HIP_SYMBOL(g_pass), sizeof(z));
-}
-extern "C" int cham_dev_timing(unsigned long long *host16, int reset)
-{
-    unsigned long long z[16] = {0};
-    if (reset) return (int)hipMemcpyToSymbol(HIP_SYMBOL(g_timing), z, sizeof(z));
-    return (int)hipMemcpyFromSymbol(host16, HIP_SYMBOL(g_timing), sizeof(z));
-}
-#endif
-
-// Three knob slots stay free for the bias and the per-row threshold, so d <= 29.
+// One knob slot stays free for the bias, so d <= 31.
 bool mfma_path_fits(int d, int kmax, int64_t n_max)
 {
-    return d >= 1 && d <= 29 && kmax <= 64 && n_max <= 4096;
+    return d >= 1 && d <= 31 && kmax <= 64 && n_max <= 4096;
 }
 
 // The packed row copy is made by the launch that starts at the first k (chunked sweeps reuse it).
@@ -1113,7 +1099,7 @@ hipError_t launch_mfma_sweep(const SweepArgs &a, int64_t n_max, int64_t n_total,
     if (nwaves < 1) nwaves = 1;
     if (nwaves > 8) nwaves = 8;
     const unsigned pb = (unsigned)((n_total + 255) / 256);
-    if (a.d <= 13) {
+    if (a.d <= 15) {
         if (pb && a.ki_begin == 0) hipLaunchKernelGGL(pack_rows_kernel<16>, dim3(pb), dim3(256), 0, s, a.X, a.ld, a.d, n_total,
                                    reinterpret_cast<_Float16 *>(a.xh));
         return ntw == 4 ? launch_mfma_t<16, 4>(a, nwaves, s) : launch_mfma_t<16, 16>(a, nwaves, s);
