@@ -409,68 +409,63 @@ __device__ __forceinline__ void apply_changes(const WaveQueue<DK> &Q, int cnt, i
     __builtin_amdgcn_wave_barrier();
 }
 
-// Centroid update for the clusters touched in this pass (all of them when `all` is set: the start).
-// Every wave derives the same list of touched clusters from the pass stamps and takes two of them
-// at a time, one per lane half; lane j of a half owns knob slot j: mean = (double)S / (double)n, then
-// the f16 hi/lo parts of w = -2 (mu - o) go to their places in the A fragments (two-byte stores).
-// The lanes of a half add up |mu - o|^2; the lane of the last knob slot, which is the bias slot,
+// Centroid update for the clusters touched in this pass, all threads: item (c, q) owns knobs
+// 4q..4q+3 of centroid c: mean = (double)S / (double)n, then the f16 hi/lo fragments of
+// w = -2 (mu - o) (one 8-byte store each).  The DK/4 items of a centroid sit in adjacent lanes and
+// add up |mu - o|^2 among themselves; the last of them owns the bias slot (knob slot DK - 1) and
 // stores the sum / 256 there as hi/lo, and its rounded-up value for the error bound.
 template <int DK>
 __device__ __forceinline__ void update_centroids(const MfmaLds<DK> &U, int k, int KP, int d, int stamp, bool all)
 {
-    constexpr int NS = DK / 16, NS2 = 2 * NS;
-    const int lane = threadIdx.x & 63;
-    const int wave = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 6);
-    const int nwaves = blockDim.x >> 6;
-    const int half = lane >> 5, j = lane & 31;
-    bool touched = false;
-    if (lane < k) touched = all || (U.dirty[lane] == stamp && U.n[lane] > 0);   // an empty cluster keeps its centroid
-    uint64_t todo = __ballot(touched);
-    auto strip = [](uint64_t m, int cnt) {
-        for (int i = 0; i < cnt && m; ++i) m &= m - 1;
-        return m;
-    };
-    todo = strip(todo, 2 * wave);
-    while (todo) {
-        const int c0 = __builtin_ctzll(todo);
-        todo &= todo - 1;
-        const int c1 = todo ? __builtin_ctzll(todo) : -1;
-        todo = strip(todo, 1 + 2 * (nwaves - 1));
-        const int c = half ? c1 : c0;
-        const bool act = c >= 0 && j < DK;
-        const int ci = c >= 0 ? c : 0;
+    constexpr int NS = DK / 16, NS2 = 2 * NS, QN = DK / 4;
+    typedef _Float16 half4 __attribute__((ext_vector_type(4)));
+    const int items = k * QN;
+    for (int base = 0; base < items; base += blockDim.x) {      // uniform trip count: every lane shuffles
+        const int item = base + (int)threadIdx.x;
+        const int c = item / QN, q = item % QN;
+        bool act = item < items;
+        int cnt = 0;
+        if (act) {
+            cnt = U.n[c];
+            if (!all && (U.dirty[c] != stamp || cnt == 0)) act = false;   // an empty cluster keeps its centroid
+        }
+        half4 hi4 = {(_Float16)0.0f, (_Float16)0.0f, (_Float16)0.0f, (_Float16)0.0f};
+        half4 lo4 = hi4;
         double b = 0.0;
-        _Float16 hi = (_Float16)0.0f, lo = (_Float16)0.0f;
-        if (act && j < d) {
-            double mu = U.mu64T[(size_t)j * KP + ci];
-            if (!all) {
-                mu = (double)U.S[ci * (DK + 1) + j] / (double)U.n[ci];
-                U.mu64T[(size_t)j * KP + ci] = mu;
+        if (act && 4 * q < d) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int j = 4 * q + i;
+                double mu = U.mu64T[(size_t)j * KP + c];
+                if (!all && j < d) {
+                    mu = (double)U.S[c * (DK + 1) + j] / (double)cnt;
+                    U.mu64T[(size_t)j * KP + c] = mu;
+                }
+                const double m = j < d ? mu - (double)U.ojf[j] : 0.0;
+                b = __builtin_fma(m, m, b);
+                const float w = (float)(-2.0 * m);
+                const _Float16 hi = (_Float16)w;
+                hi4[i] = hi;
+                lo4[i] = (_Float16)(w - (float)hi);
             }
-            const double m = mu - (double)U.ojf[j];
-            b = m * m;
-            const float w = (float)(-2.0 * m);
-            hi = (_Float16)w;
-            lo = (_Float16)(w - (float)hi);
         }
         b = b + dpp_xor_f64<1>(b);
         b = b + dpp_xor_f64<2>(b);
-        b = b + dpp_xor_f64<4>(b);
-        b = b + __shfl_xor(b, 8, 64);
-        b = b + __shfl_xor(b, 16, 64);
-        if (act) {
-            if (j == DK - 1) {
+        if (QN == 8) b = b + dpp_xor_f64<4>(b);
+        if (act && (4 * q < d || q == QN - 1)) {
+            if (q == QN - 1) {
                 const float bs = (float)b * (1.0f / kBiasScale);
-                hi = (_Float16)bs;
-                lo = (_Float16)(bs - (float)hi);
-                U.bias[ci] = __double2float_ru(b) * 1.0000005f;
+                const _Float16 bhi = (_Float16)bs;
+                hi4[3] = bhi;
+                lo4[3] = (_Float16)(bs - (float)bhi);
+                U.bias[c] = __double2float_ru(b) * 1.0000005f;
             }
-            const int mt = ci >> 5, m32 = frag_row(ci);
-            const int fstep = j >> 4, kh = (j >> 3) & 1, e = j & 7;
-            _Float16 *fh = reinterpret_cast<_Float16 *>(U.afrag + (mt * NS2 + fstep) * 64 + 32 * kh + m32) + e;
-            _Float16 *fl = reinterpret_cast<_Float16 *>(U.afrag + (mt * NS2 + NS + fstep) * 64 + 32 * kh + m32) + e;
-            *fh = hi;
-            *fl = lo;
+            const int mt = c >> 5, m32 = frag_row(c);
+            const int g = q >> 1, kh = g & 1, fstep = g >> 1, sub = q & 1;
+            half4 *fh = reinterpret_cast<half4 *>(U.afrag + (mt * NS2 + fstep) * 64 + 32 * kh + m32) + sub;
+            half4 *fl = reinterpret_cast<half4 *>(U.afrag + (mt * NS2 + NS + fstep) * 64 + 32 * kh + m32) + sub;
+            *fh = hi4;
+            *fl = lo4;
         }
     }
 }
@@ -484,7 +479,7 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
     constexpr int NS = DK / 16;          // distinct B fragments per row
     constexpr int NS2 = 2 * NS;          // chained instructions per 32x32 tile
     constexpr int CH = 16 / NS2;         // scores handled between two matrix instructions
-    constexpr int kBulkTiles = 6;        // from this many tiles with decisions on, a wave sums its label changes on the matrix cores
+    constexpr int kBulkTiles = 3;        // first pass, at least this many tiles: the wave sums its rows on the matrix cores
     const int KP = a.kmax > 32 ? 64 : 32;
     MfmaLds<DK> U(smem, KP);
 
@@ -871,8 +866,8 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
 
         // ---- label changes of the decided tiles -> integer sums and counts.
         // A row without a label yet has previous = 0xFF; rows outside the task keep 0xFF and never change.
-        if (__popc(dirty_tiles) >= kBulkTiles) {
-            // Many tiles (the first passes): the sums move by  dS[c][j] = sum_i ([cur_i = c] - [prev_i = c]) x'_ij,
+        if (it == 0 && __popc(dirty_tiles) >= kBulkTiles) {
+            // The first pass (every row gets its first label): the sums move by  dS[c][j] = sum_i ([cur_i = c] - [prev_i = c]) x'_ij,
             // a contraction over the rows, done on the matrix cores: A = the coefficients (-1, 0, 1: a row
             // that keeps its label contributes nothing), B = the tile's centred rows, staged row-major in
             // LDS and read back knob-major.  All values are small integers, every partial sum stays below
