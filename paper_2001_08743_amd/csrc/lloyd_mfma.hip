@@ -27,6 +27,8 @@
 // A pass that changes no label leaves the sums, hence the centroids, hence every later pass as
 // they are: the iteration stops there and reports the state it has, which is what the remaining
 // passes of the fixed-length iteration would reproduce.  The number of passes run is recorded.
+#include <type_traits>
+
 #include "cham_device.h"
 #include "cham_internal.h"
 #include "mfma_common.h"
@@ -697,7 +699,10 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
         passes_run = it + 1;
         uint32_t dirty_tiles = 0;        // tiles whose masks differ from the remembered ones (or that are forced)
 
-        if (wave_live) {
+        // The tile loop, compiled once per number of live registers of the last m-tile (4, 8, 12 or 16),
+        // so that the epilogue has no branches.
+        auto tile_pass = [&](auto live_tag) {
+            constexpr int LREGS = decltype(live_tag)::value;
             // A fragments of this pass (the bias slot included)
             half8 A0[NS2], A1[NS2];
 #pragma unroll
@@ -719,8 +724,9 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
                 for (int i = 0; i < CH; ++i)
                     far = __builtin_amdgcn_alignbit(far, __float_as_uint(thr - acc[i0 + i]), 31);
             };
-            // minimum over the first nreg registers (nreg = 4, 8, 12 or 16, the same for every lane)
-            auto min_live = [&](const float16v &acc, int nreg) {
+            // minimum over the first nreg registers (nreg = 4, 8, 12 or 16)
+            auto min_live = [&](const float16v &acc, auto nreg_tag) {
+                constexpr int nreg = decltype(nreg_tag)::value;
                 float b = vmin(vmin3(acc[0], acc[1], acc[2]), acc[3]);
                 if (nreg > 4) b = vmin3(vmin3(b, acc[4], acc[5]), acc[6], acc[7]);
                 if (nreg > 8) b = vmin3(vmin3(b, acc[8], acc[9]), acc[10], acc[11]);
@@ -760,7 +766,7 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
                     const int nx = nt < kLast ? nt + 1 : nt;
                     const float eb_nxt = Q.eb()[nx * 32 + n32];
                     const uint32_t seen_nxt = Q.seen()[nx * 64 + lane];
-                    const float best = row_min(vmin(min_live(accA, 16), min_live(accB, lregs)));
+                    const float best = row_min(vmin(min_live(accA, std::integral_constant<int, 16>{}), min_live(accB, live_tag)));
                     const float thr = best + eb_cur;
                     uint32_t far = 0;
 #pragma unroll
@@ -771,7 +777,7 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
                         __builtin_amdgcn_sched_barrier(0);
                         if (nt < kLast) mma(accA, A0, B[nx], s);
                         __builtin_amdgcn_sched_barrier(0);
-                        if (s * CH < lregs) mark(far, accB, thr, s * CH);
+                        if (s * CH < LREGS) mark(far, accB, thr, s * CH);
                     }
                     __builtin_amdgcn_sched_barrier(0);
                     if (nt < kLast) {
@@ -779,7 +785,7 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
                         for (int s = 0; s < NS2; ++s) mma(accB, A1, B[nx], s);
                     }
                     // registers of accB that were not walked hold padding only: far
-                    const int live_marks = CH * ((lregs + CH - 1) / CH);
+                    constexpr int live_marks = CH * ((LREGS + CH - 1) / CH);
                     far = (far << (16 - live_marks)) | ((1u << (16 - live_marks)) - 1u);
                     settle(far, seen_cur, nt);
                     eb_cur = eb_nxt;
@@ -798,7 +804,7 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
                     float16v &nxt = (nt & 1) ? accA : accB;
                     const float eb_nxt = Q.eb()[nx * 32 + n32];
                     const uint32_t seen_nxt = Q.seen()[nx * 64 + lane];
-                    const float best = row_min(min_live(cur, lregs));
+                    const float best = row_min(min_live(cur, live_tag));
                     const float thr = best + eb_cur;
                     uint32_t far = 0;
 #pragma unroll
@@ -806,16 +812,24 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
                         __builtin_amdgcn_sched_barrier(0);
                         if (nt < kLast) mma(nxt, A0, B[nx], s);
                         __builtin_amdgcn_sched_barrier(0);
-                        if (s * CH < lregs) mark(far, cur, thr, s * CH);
+                        if (s * CH < LREGS) mark(far, cur, thr, s * CH);
                     }
                     __builtin_amdgcn_sched_barrier(0);
-                    const int live_marks = CH * ((lregs + CH - 1) / CH);
+                    constexpr int live_marks = CH * ((LREGS + CH - 1) / CH);
                     far = (far << (32 - live_marks)) | (0xFFFFFFFFu >> live_marks);
                     settle(far, seen_cur, nt);
                     eb_cur = eb_nxt;
                     seen_cur = seen_nxt;
                     __builtin_amdgcn_sched_barrier(0);
                 }
+            }
+        };
+        if (wave_live) {
+            switch (lregs) {
+            case 4: tile_pass(std::integral_constant<int, 4>{}); break;
+            case 8: tile_pass(std::integral_constant<int, 8>{}); break;
+            case 12: tile_pass(std::integral_constant<int, 12>{}); break;
+            default: tile_pass(std::integral_constant<int, 16>{}); break;
             }
         }
 
