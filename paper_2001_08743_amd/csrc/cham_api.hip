@@ -181,7 +181,7 @@ SweepPath choose_path(const Plan &pl, int d, int flags)
 }
 
 struct SweepWs {
-    int64_t blob = 0, init_rows = 0, ndist = 0, passes = 0, xh = 0, labbuf = 0, total = 0;
+    int64_t blob = 0, init_rows = 0, ndist = 0, passes = 0, counters = 0, xh = 0, labbuf = 0, total = 0;
     // streaming path
     int64_t x2 = 0, ojf = 0, Sg = 0, ng = 0, mu = 0, afrag = 0, m2 = 0, wg_off = 0, loss = 0;
     int kpm = 0, n_units = 0, total_wgs = 0;
@@ -200,6 +200,8 @@ SweepWs sweep_ws(const Plan &pl, int64_t ld, bool own_labels, bool stream, const
     o += up((int64_t)pl.T * 4);
     w.passes = o;
     o += up((int64_t)pl.T * pl.n_k * 4);
+    w.counters = o;                                   // one work counter per launch of a chunked sweep
+    o += up((int64_t)pl.n_k * 4);
     w.xh = o;
     if (need_xh) o += up(ld * 32 * 2);
     w.labbuf = o;
@@ -355,6 +357,9 @@ static int32_t sweep_impl(const void *Xv, int xbytes, int64_t ld, int32_t d, con
     // labelling passes per (task, k): n_iter + 1 unless the kernel records that it stopped earlier
     e = launch_fill_i32(a.passes, (int64_t)T * n_k, n_iter + 1, s);
     if (e != hipSuccess) return hip_fail(e);
+    // work counters of the launches (the matrix-core resident kernel hands out its units through one)
+    e = launch_fill_i32(reinterpret_cast<int *>(ws + w.counters), n_k, 0, s);
+    if (e != hipSuccess) return hip_fail(e);
     if (init_mode == 0) {
         e = launch_first_distinct(a, reinterpret_cast<int *>(ws + w.init_rows),
                                   reinterpret_cast<int *>(ws + w.ndist), s);
@@ -365,6 +370,7 @@ static int32_t sweep_impl(const void *Xv, int xbytes, int64_t ld, int32_t d, con
         const int ki_end = ki_begin + step < n_k ? ki_begin + step : n_k;
         a.ki_begin = ki_begin;
         a.ki_end = ki_end;
+        a.unit_counter = reinterpret_cast<int *>(ws + w.counters) + ki_begin;
         a.done = ki_begin > 0 ? done : nullptr;
         if (path == SweepPath::kStream) {
             // first workgroup of every unit, in launch order (largest k first)

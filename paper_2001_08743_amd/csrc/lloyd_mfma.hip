@@ -1043,39 +1043,50 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
     }
 }
 
+// Persistent workgroups (one per compute unit) take units from a counter until none is left: the
+// next unit starts as soon as the last one ends, without a new dispatch of a workgroup of this size.
+// Units are handed out in descending-k order so that the longest ones start first.
 template <int DK, int NTW>
 __global__ __launch_bounds__(512) void resident_mfma_kernel(const SweepArgs a)
 {
     extern __shared__ __align__(16) unsigned char smem[];
+    __shared__ int next_unit;
     const int tid = threadIdx.x;
+    const int n_units = a.T * (a.ki_end - a.ki_begin);
 
-    // units in descending-k order so that the longest ones start first
-    const int u = blockIdx.x;
-    const int ki = a.ki_end - 1 - u / a.T;
-    const int t = u % a.T;
-    const int k = a.ks[ki];
-    const bool skipped = a.done && a.done[t];     // the task's sweep stopped at a smaller k
+    for (;;) {
+        if (tid == 0) next_unit = atomicAdd(a.unit_counter, 1);
+        __syncthreads();
+        const int u = next_unit;
+        __syncthreads();                           // everyone has read it before it is written again
+        if (u >= n_units) break;
+        const int ki = a.ki_end - 1 - u / a.T;
+        const int t = u % a.T;
+        const int k = a.ks[ki];
+        const bool skipped = a.done && a.done[t];     // the task's sweep stopped at a smaller k
 
-    if (skipped || (a.init_mode == 0 && a.ndist[t] < k)) {
-        // fewer than k distinct rows, or not needed any more: all outputs zero, status says which
-        const int d = a.d;
-        const int64_t r0 = a.task_off[t], r1 = a.task_off[t + 1];
-        const int64_t slot = (int64_t)t * a.n_k + ki;
-        const int64_t crow = (int64_t)t * a.Ksum + a.koff[ki];
-        uint8_t *labrow = a.labbuf + (int64_t)ki * a.ld;
-        for (int e = tid; e < k * d; e += blockDim.x) a.centroids[crow * d + e] = 0.0;
-        for (int c = tid; c < k; c += blockDim.x) a.counts[crow + c] = 0;
-        for (int64_t r = r0 + tid; r < r1; r += blockDim.x) labrow[r] = 0;
-        if (tid == 0) {
-            a.status[slot] = skipped ? 3 : 1;
-            a.passes[slot] = 0;
-            a.inertia[slot] = 0.0;
+        if (skipped || (a.init_mode == 0 && a.ndist[t] < k)) {
+            // fewer than k distinct rows, or not needed any more: all outputs zero, status says which
+            const int d = a.d;
+            const int64_t r0 = a.task_off[t], r1 = a.task_off[t + 1];
+            const int64_t slot = (int64_t)t * a.n_k + ki;
+            const int64_t crow = (int64_t)t * a.Ksum + a.koff[ki];
+            uint8_t *labrow = a.labbuf + (int64_t)ki * a.ld;
+            for (int e = tid; e < k * d; e += blockDim.x) a.centroids[crow * d + e] = 0.0;
+            for (int c = tid; c < k; c += blockDim.x) a.counts[crow + c] = 0;
+            for (int64_t r = r0 + tid; r < r1; r += blockDim.x) labrow[r] = 0;
+            if (tid == 0) {
+                a.status[slot] = skipped ? 3 : 1;
+                a.passes[slot] = 0;
+                a.inertia[slot] = 0.0;
+            }
+            if (a.trace)
+                for (int e = tid; e <= a.n_iter; e += blockDim.x) a.trace[slot * (a.n_iter + 1) + e] = 0.0;
+            continue;
         }
-        if (a.trace)
-            for (int e = tid; e <= a.n_iter; e += blockDim.x) a.trace[slot * (a.n_iter + 1) + e] = 0.0;
-        return;
+        run_unit<DK, NTW>(a, smem, ki, t, k);
+        __syncthreads();                           // the unit's LDS state is dead before the next unit sets its own
     }
-    run_unit<DK, NTW>(a, smem, ki, t, k);
 }
 
 template <int DK, int NTW>
@@ -1087,8 +1098,20 @@ hipError_t launch_mfma_t(const SweepArgs &a, int nwaves, hipStream_t s)
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
+    // as many workgroups as can be resident at once
+    int dev = 0, cus = 0, per_cu = 0;
+    e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+    if (e != hipSuccess) return e;
+    e = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kern, nwaves * 64, lds);
+    if (e != hipSuccess) return e;
+    if (per_cu < 1) per_cu = 1;
     const unsigned units = (unsigned)a.T * (unsigned)(a.ki_end - a.ki_begin);
-    hipLaunchKernelGGL(kern, dim3(units), dim3(nwaves * 64), lds, s, a);
+    unsigned grid = (unsigned)cus * (unsigned)per_cu;
+    if (grid > units) grid = units;
+    if (grid < 1) grid = 1;
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(nwaves * 64), lds, s, a);
     return hipGetLastError();
 }
 
