@@ -46,6 +46,12 @@ def load() -> C.CDLL:
     if _lib is None:
         if not os.path.exists(LIB_PATH):
             raise ChamError(f"{LIB_PATH} is not built; run `python -m paper_2001_08743_amd.build`")
+        # PyTorch ships its own copy of the HIP runtime: it has to be in the process first, so that the
+        # library binds to that same runtime (its kernels then see the device and streams torch uses).
+        try:
+            import torch  # noqa: F401
+        except ImportError:
+            pass
         lib = C.CDLL(LIB_PATH)
         vp, i32, i64, u64, f64 = C.c_void_p, C.c_int32, C.c_int64, C.c_uint64, C.c_double
         lib.cham_version.restype = i32
