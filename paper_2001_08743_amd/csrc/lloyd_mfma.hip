@@ -481,7 +481,6 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
     constexpr int NS = DK / 16;          // distinct B fragments per row
     constexpr int NS2 = 2 * NS;          // chained instructions per 32x32 tile
     constexpr int CH = 16 / NS2;         // scores handled between two matrix instructions
-    constexpr int kBulkTiles = 3;        // first pass, at least this many tiles: the wave sums its rows on the matrix cores
     const int KP = a.kmax > 32 ? 64 : 32;
     MfmaLds<DK> U(smem, KP);
 
@@ -880,85 +879,9 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
 
         // ---- label changes of the decided tiles -> integer sums and counts.
         // A row without a label yet has previous = 0xFF; rows outside the task keep 0xFF and never change.
-        if (it == 0 && __popc(dirty_tiles) >= kBulkTiles) {
-            // The first pass (every row gets its first label): the sums move by  dS[c][j] = sum_i ([cur_i = c] - [prev_i = c]) x'_ij,
-            // a contraction over the rows, done on the matrix cores: A = the coefficients (-1, 0, 1: a row
-            // that keeps its label contributes nothing), B = the tile's centred rows, staged row-major in
-            // LDS and read back knob-major.  All values are small integers, every partial sum stays below
-            // 2^24: exact.  The bias slot of the rows (256 for every row of the task) yields 256 x the
-            // change of the cluster sizes, from which the centring offsets are put back:
-            // S += dS' + dn * offset.
-            const float16v zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-            float16v sacc0 = zero16, sacc1 = zero16;
-            const int jn = lane & 31;            // knob slot (B, D column) or centroid within the m-tile (A row)
-            bool any_change = false;
-            uint32_t todo = dirty_tiles;
-            while (todo) {
-                const int nt = __builtin_ctz(todo);
-                todo &= todo - 1;
-                half8 bt[NS];
-                rows_of_tile(nt, bt);
-#pragma unroll
-                for (int f = 0; f < NS; ++f)
-                    *reinterpret_cast<half8 *>(Q.rec_x() + (size_t)n32 * DK + 16 * f + 8 * h) = bt[f];
-                __builtin_amdgcn_wave_barrier();
-#pragma unroll
-                for (int ks = 0; ks < 2; ++ks) {
-                    const int rbase = 16 * ks + 8 * h;   // this lane's eight rows of the contraction step
-                    const uint64_t cur8 = *reinterpret_cast<const uint64_t *>(Q.lab_new() + nt * 32 + rbase);
-                    const uint64_t prev8 = *reinterpret_cast<const uint64_t *>(Q.lab() + nt * 32 + rbase);
-                    half8 bx;
-#pragma unroll
-                    for (int e = 0; e < 8; ++e)
-                        bx[e] = jn < DK ? Q.rec_x()[(size_t)(rbase + e) * DK + jn] : (_Float16)0.0f;
-                    half8 ax0, ax1;
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) {
-                        const int cc = (int)((cur8 >> (8 * e)) & 0xFF), pp = (int)((prev8 >> (8 * e)) & 0xFF);
-                        ax0[e] = (_Float16)(float)((cc == jn ? 1 : 0) - (pp == jn ? 1 : 0));
-                        ax1[e] = (_Float16)(float)((cc == jn + 32 ? 1 : 0) - (pp == jn + 32 ? 1 : 0));
-                    }
-                    sacc0 = __builtin_amdgcn_mfma_f32_32x32x16_f16(ax0, bx, sacc0, 0, 0, 0);
-                    if (two) sacc1 = __builtin_amdgcn_mfma_f32_32x32x16_f16(ax1, bx, sacc1, 0, 0, 0);
-                }
-                __builtin_amdgcn_wave_barrier();
-                // the tile's labels become current; its changed rows mark their clusters
-                const uint32_t cur = Q.lab_new()[nt * 32 + n32];
-                const uint32_t prev = Q.lab()[nt * 32 + n32];
-                const bool changed = cur != prev;
-                if (changed && h == 0) {
-                    U.dirty[cur] = it;
-                    if (prev != 0xFFu) U.dirty[prev] = it;
-                    Q.lab()[nt * 32 + n32] = (unsigned char)cur;
-                }
-                any_change = any_change || __ballot(changed) != 0ull;
-                __builtin_amdgcn_wave_barrier();
-            }
-            if (any_change) {
-                if (lane == 0) U.stamp[0] = it;
-                const int oj = jn < d ? (int)U.ojf[jn < DK ? jn : 0] : 0;
-#pragma unroll
-                for (int mt = 0; mt < 2; ++mt) {
-                    if (mt == 1 && !two) continue;
-                    const float16v &sa = mt ? sacc1 : sacc0;
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) {
-                        const int c = 32 * mt + 8 * (i >> 2) + 4 * h + (i & 3);
-                        const float c0 = readlane_f(sa[i], DK - 1), c1 = readlane_f(sa[i], 32 + DK - 1);
-                        const int dn = (int)((h ? c1 : c0) * (1.0f / kBiasScale));
-                        if (c < k) {
-                            if (jn < d) {
-                                const int delta = (int)sa[i] + dn * oj;
-                                if (delta) atomicAdd(&U.S[c * (DK + 1) + jn], delta);
-                            }
-                            if (jn == DK - 1 && dn) atomicAdd(&U.n[c], dn);
-                        }
-                    }
-                }
-            }
-        } else {
-            // Few tiles: a dense queue of (previous, new, knob values), applied with one lane per
-            // (row, group of four knobs), in batches of at most kRecCap rows.
+        {
+            // a dense queue of (previous, new, knob values), applied with one lane per (row, group of four
+            // knobs), in batches of at most kRecCap rows
             uint32_t todo = dirty_tiles;
             int cnt = 0;
             while (todo) {
