@@ -103,7 +103,7 @@ struct MfmaLds {
     int *n;             // [KP]       cluster sizes
     int *dirty;         // [KP]       pass in which the cluster last changed
     float *ojf;         // [DK]       centring offsets
-    int *stamp;         // [4]        last pass that changed a sum; float bits of the largest squared row norm
+    int *stamp;         // [4]        [1] float bits of the largest squared row norm, [2], [3] rows that changed in an even / odd pass
     unsigned char *wave_base;   // per-wave regions follow
     __host__ __device__ static size_t wave_bytes(int ntw)
     {
@@ -369,7 +369,7 @@ __global__ void pack_rows_kernel(const uint8_t *__restrict__ X, int64_t ld, int 
 // row that had no label yet.
 template <int DK>
 __device__ __forceinline__ void apply_changes(const WaveQueue<DK> &Q, int cnt, int *S, int *n, int *dirty,
-                                              int *pass_dirty, const float *ojf, int d, int stamp)
+                                              const float *ojf, int d, int stamp)
 {
     constexpr int LPR = DK / 4;              // lanes per row
     constexpr int EPI = 64 / LPR;            // rows per step
@@ -377,8 +377,6 @@ __device__ __forceinline__ void apply_changes(const WaveQueue<DK> &Q, int cnt, i
     const int j0 = 4 * (lane % LPR);
     const float4 o4 = *reinterpret_cast<const float4 *>(ojf + j0);
     const float of[4] = {o4.x, o4.y, o4.z, o4.w};
-    if (lane == 0) *pass_dirty = stamp;          // this pass changes a sum: the centroids need their update
-    __builtin_amdgcn_wave_barrier();
 #pragma unroll 2
     for (int e0 = 0; e0 < cnt; e0 += EPI) {
         const int e = e0 + lane / LPR;
@@ -411,13 +409,120 @@ __device__ __forceinline__ void apply_changes(const WaveQueue<DK> &Q, int cnt, i
     __builtin_amdgcn_wave_barrier();
 }
 
+// Sums and sizes of every cluster over this wave's rows, from the current labels, on the matrix
+// cores: S^T (knob x centroid) = X^T (knob x row) * onehot (row x centroid), sixteen rows per
+// instruction.  Lane (m, kh) of the A fragment holds knob m of eight consecutive rows, read straight
+// from the knob-major byte matrix (32 consecutive rows = 32 bytes per lane and group of 64 rows; the
+// same row order is used for the labels, so any order would do).  A byte b becomes the f16 value
+// 1024 + b by byte placement alone (0x6400 | b); the knob rows therefore sum to S + 1024 n, and the
+// rows of absent knobs (all bytes zero) to 1024 n, of which row 31 serves as the cluster size.  The
+// one-hot operand is clamp(1025 - (1024 + (label ^ centroid)), 0, 1).  Every product and partial sum
+// is an integer below 2^24, so the fp32 accumulation is exact.  The results are added to the sums
+// of the workgroup (still raised by 1024 n: the centroid update takes that off) and to the sizes.
+// Needs 16-byte aligned rows (xw, ld) and reads whole groups of 64 rows: the caller makes sure
+// that the last group of the task still lies inside the matrix (rows of other tasks or padding
+// read there meet the label 0xFF, which matches no centroid).  NG = groups of 64 rows a wave owns
+// at most; the loads of four groups are under way at any time.
+template <int DK, int NG>
+__device__ __forceinline__ void full_sums(const WaveQueue<DK> &Q, int *S, int *n, const uint8_t *xw, int64_t ld,
+                                          int d, int k, int rows_here, int lane)
+{
+    typedef unsigned uint4v __attribute__((ext_vector_type(4)));
+    typedef _Float16 half2v __attribute__((ext_vector_type(2)));
+    constexpr int kDepth = NG < 4 ? NG : 4;
+    const int m32 = lane & 31, kh = lane >> 5;
+    const bool two = k > 32;
+    const bool knob = m32 < d;
+    const uint8_t *xp = xw + (int64_t)(knob ? m32 : 0) * ld + 32 * kh;
+    const unsigned char *lp = Q.lab() + 32 * kh;
+    const unsigned c4a = (unsigned)m32 * 0x01010101u, c4b = c4a + 0x20202020u;
+    const float16v zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    float16v acc0 = zero16, acc1 = zero16;
+    const int ngroups = (rows_here + 63) >> 6;
+
+    // this lane's 32 bytes of group g (zero where the knob or the group does not exist)
+    auto fetch = [&](int g, uint4v &w0, uint4v &w1) {
+        w0 = uint4v{0u, 0u, 0u, 0u};
+        w1 = w0;
+        if (knob && g < ngroups) {
+            w0 = *reinterpret_cast<const uint4v *>(xp + 64 * g);
+            w1 = *reinterpret_cast<const uint4v *>(xp + 64 * g + 16);
+        }
+    };
+    // eight bytes -> eight f16 values 1024 + byte
+    auto widen = [](unsigned lo4, unsigned hi4) {
+        uint4v r;
+        r[0] = __builtin_amdgcn_perm(0x64646464u, lo4, 0x04010400u);
+        r[1] = __builtin_amdgcn_perm(0x64646464u, lo4, 0x04030402u);
+        r[2] = __builtin_amdgcn_perm(0x64646464u, hi4, 0x04010400u);
+        r[3] = __builtin_amdgcn_perm(0x64646464u, hi4, 0x04030402u);
+        return r;
+    };
+    // eight (label ^ centroid) bytes -> eight f16 values: 1 where the byte is zero, else 0
+    auto onehot = [&](unsigned lo4, unsigned hi4) {
+        const uint4v r = widen(lo4, hi4);
+        uint4v o;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const unsigned re = r[e];           // (a scalar copy: a bit cast of the vector element itself reads element 0)
+            half2v v = __builtin_bit_cast(half2v, re);
+            v = half2v{(_Float16)1025.0f, (_Float16)1025.0f} - v;
+            v = __builtin_elementwise_min(__builtin_elementwise_max(v, half2v{(_Float16)0.0f, (_Float16)0.0f}),
+                                          half2v{(_Float16)1.0f, (_Float16)1.0f});
+            o[e] = __builtin_bit_cast(unsigned, v);
+        }
+        return __builtin_bit_cast(half8, o);
+    };
+
+    uint4v w0[kDepth], w1[kDepth];
+#pragma unroll
+    for (int g = 0; g < kDepth; ++g) fetch(g, w0[g], w1[g]);
+#pragma unroll
+    for (int g = 0; g < NG; ++g) {
+        if (g < ngroups) {
+            const uint4v c0 = w0[g % kDepth], c1 = w1[g % kDepth];
+            const uint4v l0 = *reinterpret_cast<const uint4v *>(lp + 64 * g);
+            const uint4v l1 = *reinterpret_cast<const uint4v *>(lp + 64 * g + 16);
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const unsigned xa = t < 2 ? c0[(2 * t) & 3] : c1[(2 * t) & 3];
+                const unsigned xb = t < 2 ? c0[(2 * t + 1) & 3] : c1[(2 * t + 1) & 3];
+                const unsigned la = t < 2 ? l0[(2 * t) & 3] : l1[(2 * t) & 3];
+                const unsigned lb = t < 2 ? l0[(2 * t + 1) & 3] : l1[(2 * t + 1) & 3];
+                const half8 A = __builtin_bit_cast(half8, widen(xa, xb));
+                acc0 = __builtin_amdgcn_mfma_f32_32x32x16_f16(A, onehot(la ^ c4a, lb ^ c4a), acc0, 0, 0, 0);
+                if (two) acc1 = __builtin_amdgcn_mfma_f32_32x32x16_f16(A, onehot(la ^ c4b, lb ^ c4b), acc1, 0, 0, 0);
+            }
+            if (g + kDepth < NG) fetch(g + kDepth, w0[g % kDepth], w1[g % kDepth]);
+        }
+    }
+    // accumulator register i of lane (c, kh) = knob (i & 3) + 8 (i >> 2) + 4 kh of centroid c (or 32 + c)
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const int m = (i & 3) + 8 * (i >> 2) + 4 * kh;
+        if (m < d) {
+            if (m32 < k) atomicAdd(&S[m32 * (DK + 1) + m], (int)acc0[i]);
+            if (two && m32 + 32 < k) atomicAdd(&S[(m32 + 32) * (DK + 1) + m], (int)acc1[i]);
+        }
+        if (i == 15 && kh == 1) {                              // knob row 31: 1024 per row of the cluster
+            if (m32 < k) atomicAdd(&n[m32], (int)acc0[i] >> 10);
+            if (two && m32 + 32 < k) atomicAdd(&n[m32 + 32], (int)acc1[i] >> 10);
+        }
+    }
+}
+
 // Centroid update for the clusters touched in this pass, all threads: item (c, q) owns knobs
 // 4q..4q+3 of centroid c: mean = (double)S / (double)n, then the f16 hi/lo fragments of
 // w = -2 (mu - o) (one 8-byte store each).  The DK/4 items of a centroid sit in adjacent lanes and
 // add up |mu - o|^2 among themselves; the last of them owns the bias slot (knob slot DK - 1) and
 // stores the sum / 256 there as hi/lo, and its rounded-up value for the error bound.
+// all: fragments from the centroids as they are (no sums yet).  raw: the sums were rebuilt by
+// full_sums for every cluster (each still raised by 1024 n): every cluster is updated, and the sums
+// are left either corrected (the next pass applies label changes to them) or, with zero_after,
+// cleared together with the sizes (the next pass rebuilds them).
 template <int DK>
-__device__ __forceinline__ void update_centroids(const MfmaLds<DK> &U, int k, int KP, int d, int stamp, bool all)
+__device__ __forceinline__ void update_centroids(const MfmaLds<DK> &U, int k, int KP, int d, int stamp, bool all,
+                                                 bool raw = false, bool zero_after = false)
 {
     constexpr int NS = DK / 16, NS2 = 2 * NS, QN = DK / 4;
     typedef _Float16 half4 __attribute__((ext_vector_type(4)));
@@ -429,7 +534,7 @@ __device__ __forceinline__ void update_centroids(const MfmaLds<DK> &U, int k, in
         int cnt = 0;
         if (act) {
             cnt = U.n[c];
-            if (!all && (U.dirty[c] != stamp || cnt == 0)) act = false;   // an empty cluster keeps its centroid
+            if (!all && ((!raw && U.dirty[c] != stamp) || cnt == 0)) act = false;   // an empty cluster keeps its centroid
         }
         half4 hi4 = {(_Float16)0.0f, (_Float16)0.0f, (_Float16)0.0f, (_Float16)0.0f};
         half4 lo4 = hi4;
@@ -440,7 +545,12 @@ __device__ __forceinline__ void update_centroids(const MfmaLds<DK> &U, int k, in
                 const int j = 4 * q + i;
                 double mu = U.mu64T[(size_t)j * KP + c];
                 if (!all && j < d) {
-                    mu = (double)U.S[c * (DK + 1) + j] / (double)cnt;
+                    int sv = U.S[c * (DK + 1) + j];
+                    if (raw) {
+                        sv -= 1024 * cnt;
+                        U.S[c * (DK + 1) + j] = sv;
+                    }
+                    mu = (double)sv / (double)cnt;
                     U.mu64T[(size_t)j * KP + c] = mu;
                 }
                 const double m = j < d ? mu - (double)U.ojf[j] : 0.0;
@@ -469,6 +579,14 @@ __device__ __forceinline__ void update_centroids(const MfmaLds<DK> &U, int k, in
             *fh = hi4;
             *fl = lo4;
         }
+        if (zero_after && item < items) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                if (4 * q + i < d) U.S[c * (DK + 1) + 4 * q + i] = 0;
+            // every item of a cluster sits in this wave and has read the size by now
+            __builtin_amdgcn_wave_barrier();
+            if (q == 0) U.n[c] = 0;
+        }
     }
 }
 
@@ -490,6 +608,14 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
     const int nwaves = blockDim.x >> 6;
     const int n32 = lane & 31;           // row within a 32-row tile
     const int h = lane >> 5;             // which half of the knob slots / centroid rows this lane holds
+    // The phases of a pass take the lane index through this: values derived from it (addresses into
+    // the wave's tables) are then computed where they are used instead of living, or being spilled,
+    // across the whole iteration next to the 128 registers of rows.
+    const int lane_id = lane;
+    auto opaque = [](int v) {
+        asm volatile("" : "+v"(v));
+        return v;
+    };
 
     const int d = a.d;
     const int64_t r0 = a.task_off[t], r1 = a.task_off[t + 1];
@@ -510,6 +636,7 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
     // The last knob slot of the fragments is reserved (d <= DK - 1): it carries the bias (256 in B,
     // |mu'|^2 / 256 as hi/lo in A).
     constexpr int bstep = NS - 1, bhalf = 1, belem = 7;
+    constexpr int kFullDivisor = 8;
 
     // ---- set-up
     for (int e = tid; e < DK * KP; e += blockDim.x) U.mu64T[e] = 0.0;
@@ -532,8 +659,10 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
         bslot[0] = (_Float16)kPadBiasHi;
     }
     if (tid == 0) {
-        U.stamp[0] = -1;          // last pass that changed a sum
+        U.stamp[0] = 0;           // (unused)
         U.stamp[1] = 0;           // float bits of the largest squared norm of a centred row
+        U.stamp[2] = 0;           // rows that changed their label in an even pass
+        U.stamp[3] = 0;           // ... in an odd pass
     }
     for (int e = tid; e < k * d; e += blockDim.x) {
         const int c = e / d, j = e % d;
@@ -632,10 +761,16 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
     for (int e = lane; e < WaveQueue<DK>::kRows; e += 64) Q.lab()[e] = 0xFF;
     __builtin_amdgcn_wave_barrier();
 
-    double loss = 0.0;
     const int rows_wave = __builtin_amdgcn_readfirstlane(nrows - wave_row0);   // rows from this wave's first row to the task's end
     uint32_t force_tiles = 0xFFFFFFFFu;  // tiles to decide whatever their masks say: all at first, later those with undecided rows
     int passes_run = 0;
+    // A pass after one that moved many rows rebuilds the sums from the labels on the matrix cores
+    // instead of applying the changes one by one; the first pass (every row is new) always does.
+    const uint8_t *xw = a.X + r0 + (wave_live ? wave_row0 : 0);
+    const bool x_aligned = ((reinterpret_cast<uintptr_t>(a.X) | (uintptr_t)a.ld | (uintptr_t)r0) & 15) == 0 &&
+                           r0 + ((nrows + 63) & ~63) <= a.ld;       // ... and its last group of 64 rows lies inside the matrix
+    bool full_mode = x_aligned;
+    const int full_above = nrows / kFullDivisor;      // changed rows of a pass above which the next one rebuilds
     bool traced_last = false;
 
     // lanes of tile nt (as a 32-bit mask over the row index within the tile) whose row belongs to the task
@@ -664,6 +799,7 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
     // afterwards; the per-wave sums land in U.red[slot8 .. slot8 + nwaves).
     auto wave_loss = [&](int slot8) {
         double part = 0.0;
+        const int lane = opaque(lane_id), n32 = lane & 31, h = lane >> 5;
         if (wave_live) {
             float of[NS][8];
 #pragma unroll
@@ -689,7 +825,15 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
                 part = part + (live ? s : 0.0);
             }
         }
-        const double ws = wave_sum(part);
+        // the wave's total in the fixed order lane ^ 32, 16, ..., 1 (partner indices from the local lane index)
+        double ws = part;
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) {
+            const long long b = __double_as_longlong(ws);
+            const int plo = __builtin_amdgcn_ds_bpermute((lane ^ off) << 2, (int)(b & 0xFFFFFFFFll));
+            const int phi = __builtin_amdgcn_ds_bpermute((lane ^ off) << 2, (int)(b >> 32));
+            ws = ws + __longlong_as_double(((long long)phi << 32) | (unsigned int)plo);
+        }
         if (lane == 0) U.red[slot8 + wave] = ws;
     };
 
@@ -702,6 +846,7 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
         // so that the epilogue has no branches.
         auto tile_pass = [&](auto live_tag) {
             constexpr int LREGS = decltype(live_tag)::value;
+            const int lane = opaque(lane_id), n32 = lane & 31;
             // A fragments of this pass (the bias slot included)
             half8 A0[NS2], A1[NS2];
 #pragma unroll
@@ -836,6 +981,7 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
         uint32_t flagged_tiles = 0;
         int nrec = 0;
         {
+            const int lane = opaque(lane_id), n32 = lane & 31, h = lane >> 5;
             uint32_t todo = dirty_tiles;
             while (todo) {
                 const int nt = __builtin_ctz(todo);
@@ -879,9 +1025,30 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
 
         // ---- label changes of the decided tiles -> integer sums and counts.
         // A row without a label yet has previous = 0xFF; rows outside the task keep 0xFF and never change.
-        {
+        int wave_changed = 0;
+        if (full_mode) {
+            // the new labels become the current ones; the sums are rebuilt from all of them
+            const int lane = opaque(lane_id), n32 = lane & 31, h = lane >> 5;
+            uint32_t todo = dirty_tiles;
+            while (todo) {
+                const int nt = __builtin_ctz(todo);
+                todo &= todo - 1;
+                const uint32_t cur = Q.lab_new()[nt * 32 + n32];
+                const uint32_t prev = Q.lab()[nt * 32 + n32];
+                const bool changed = cur != prev;
+                wave_changed += __popcll(__ballot(changed) & 0xFFFFFFFFull);
+                if (changed && h == 0) Q.lab()[nt * 32 + n32] = (unsigned char)cur;
+            }
+            __builtin_amdgcn_wave_barrier();
+            if (wave_live) {
+                const int left = nrows - wave_row0;
+                full_sums<DK, NTW / 2>(Q, U.S, U.n, xw, a.ld, d, k, left < NTW * 32 ? left : NTW * 32, lane);
+            }
+        } else {
             // a dense queue of (previous, new, knob values), applied with one lane per (row, group of four
             // knobs), in batches of at most kRecCap rows
+            const int lane = opaque(lane_id), n32 = lane & 31, h = lane >> 5;
+            (void)lane;
             uint32_t todo = dirty_tiles;
             int cnt = 0;
             while (todo) {
@@ -893,7 +1060,7 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
                 const uint64_t cm = __ballot(changed) & 0xFFFFFFFFull;
                 if (cm) {
                     if (cnt + 32 > kRecCap) {
-                        apply_changes<DK>(Q, cnt, U.S, U.n, U.dirty, U.stamp, U.ojf, d, it);
+                        apply_changes<DK>(Q, cnt, U.S, U.n, U.dirty, U.ojf, d, it);
                         cnt = 0;
                     }
                     half8 bt[NS];
@@ -909,10 +1076,12 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
                         }
                     }
                     cnt += __popcll(cm);
+                    wave_changed += __popcll(cm);
                 }
             }
-            if (cnt) apply_changes<DK>(Q, cnt, U.S, U.n, U.dirty, U.stamp, U.ojf, d, it);
+            if (cnt) apply_changes<DK>(Q, cnt, U.S, U.n, U.dirty, U.ojf, d, it);
         }
+        if (wave_changed && lane_id == 0) atomicAdd(&U.stamp[2 + (it & 1)], wave_changed);
         traced_last = false;
         if (a.trace) {
             wave_loss((it & 1) * 8);
@@ -922,15 +1091,17 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
         if (a.trace && tid == 0) {
             double s = 0.0;
             for (int w = 0; w < nwaves; ++w) s = s + U.red[(it & 1) * 8 + w];
-            loss = s;
             a.trace[slot * (a.n_iter + 1) + it] = s;
         }
         // A pass that moved no row leaves every sum, hence every centroid, as it was: the labels are
-        // final.  (The flag is read between this pass's two barriers, or after its only one when the
-        // loop ends here; no wave writes it in between.)
-        const bool changed_any = __builtin_amdgcn_readfirstlane(U.stamp[0]) == it;
-        if (last_pass || !changed_any) break;
-        update_centroids<DK>(U, k, KP, d, it, false);
+        // final.  (The count is read between this pass's two barriers, or after its only one when the
+        // loop ends here; no wave adds to it in between.)
+        const int rows_changed = __builtin_amdgcn_readfirstlane(U.stamp[2 + (it & 1)]);
+        if (last_pass || rows_changed == 0) break;
+        if (tid == 0) U.stamp[2 + ((it + 1) & 1)] = 0;      // the next pass counts from zero (nobody adds before the barrier below)
+        const bool full_next = x_aligned && rows_changed > full_above;
+        update_centroids<DK>(U, k, KP, d, it, false, full_mode, full_next);
+        full_mode = full_next;
         __syncthreads();
     }
 
@@ -941,15 +1112,16 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
             if (pid < nrows) labrow[r0 + pid] = Q.lab()[e];
         }
     }
+    // the loss of the final labels: the per-wave sums of the last traced pass are still in place
+    int loss_slot = ((passes_run - 1) & 1) * 8;
     if (!traced_last) {
+        loss_slot = 0;
         wave_loss(0);
         __syncthreads();
-        if (tid == 0) {
-            double s = 0.0;
-            for (int w = 0; w < nwaves; ++w) s = s + U.red[w];
-            loss = s;
-        }
     }
+    double loss = 0.0;
+    if (tid == 0)
+        for (int w = 0; w < nwaves; ++w) loss = loss + U.red[loss_slot + w];
     if (a.trace && tid == 0) {
         // the passes that were not run would have seen the same labels and centroids
         for (int it = passes_run; it <= a.n_iter; ++it) a.trace[slot * (a.n_iter + 1) + it] = loss;
