@@ -840,7 +840,8 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
     for (int it = 0; it <= a.n_iter; ++it) {
         const bool last_pass = (it == a.n_iter);
         passes_run = it + 1;
-        uint32_t dirty_tiles = 0;        // tiles whose masks differ from the remembered ones (or that are forced)
+        uint32_t flagged_tiles = 0;      // tiles with rows that the screen could not decide
+        uint32_t changed_tiles = 0;      // tiles in which a label may differ from the current one
 
         // The tile loop, compiled once per number of live registers of the last m-tile (4, 8, 12 or 16),
         // so that the epilogue has no branches.
@@ -884,14 +885,34 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
                 return vmin(__uint_as_float(lo), __uint_as_float(hi));
             };
             // After the masks of tile nt: if any row's mask differs from the remembered one (or the tile is
-            // forced), remember the new masks and put the tile on the list of tiles to decide.
+            // forced), remember the new masks and decide the tile's rows: a row with exactly one
+            // candidate takes it, any other row is left to the exact evaluation after the tile loop
+            // (label 0xFE until then).  Tiles with such rows and tiles in which a label differs from
+            // the current one are listed.  (The matrix instructions of the next tile are under way
+            // meanwhile.)
             auto settle = [&](uint32_t far, uint32_t seen, int nt) {
                 const uint64_t diff = __ballot(far != seen);
-                uint32_t dirty32 = ((uint32_t)diff | (uint32_t)(diff >> 32)) & live_rows(nt);
-                if ((force_tiles >> nt) & 1u) dirty32 = live_rows(nt);
+                const uint32_t live32 = live_rows(nt);
+                uint32_t dirty32 = ((uint32_t)diff | (uint32_t)(diff >> 32)) & live32;
+                if ((force_tiles >> nt) & 1u) dirty32 = live32;
                 if (dirty32) {
                     Q.seen()[nt * 64 + lane] = far;
-                    dirty_tiles |= 1u << nt;
+                    const uint32_t prev = Q.lab()[nt * 32 + n32];
+                    const uint32_t cand = ~far;                          // bit 31 = position 0
+                    uint32_t cand_lo, cand_hi;
+                    both_halves(cand, cand_lo, cand_hi);
+                    const int total = __popc(cand_lo) + __popc(cand_hi);
+                    const bool live = (live32 >> n32) & 1u;
+                    const bool flagged = live && total != 1;
+                    const int hh = cand_lo ? 0 : 1;
+                    const int q = __clz((int)(cand_lo ? cand_lo : cand_hi));
+                    const uint32_t lab = (uint32_t)slot_centroid(q & 31, hh);
+                    const uint32_t now = !live ? 0xFFu : (flagged ? 0xFEu : lab);
+                    if (__ballot(flagged)) flagged_tiles |= 1u << nt;
+                    if (__ballot(now != prev)) {
+                        changed_tiles |= 1u << nt;
+                        if (lane < 32) Q.lab_new()[nt * 32 + n32] = (unsigned char)now;
+                    }
                 }
             };
 
@@ -977,12 +998,12 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
             }
         }
 
-        // ---- decide the rows of the listed tiles (this code exists once; the tile index is a run-time value)
-        uint32_t flagged_tiles = 0;
+        // ---- the undecided rows: exact evaluation, through the queue (this code exists once; the tile
+        // index is a run-time value)
         int nrec = 0;
         {
             const int lane = opaque(lane_id), n32 = lane & 31, h = lane >> 5;
-            uint32_t todo = dirty_tiles;
+            uint32_t todo = flagged_tiles;
             while (todo) {
                 const int nt = __builtin_ctz(todo);
                 todo &= todo - 1;
@@ -998,13 +1019,8 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
                 const int total = __popc(cand_lo) + __popc(cand_hi);
                 const bool live = (live32 >> n32) & 1u;
                 const bool flagged = live && total != 1;
-                const int hh = cand_lo ? 0 : 1;
-                const int q = __clz((int)(cand_lo ? cand_lo : cand_hi));
-                const int lab = slot_centroid(q & 31, hh);
-                if (h == 0) Q.lab_new()[nt * 32 + n32] = (unsigned char)(!live ? 0xFF : (flagged ? 0xFE : lab));
                 const uint64_t fm = __ballot(flagged) & 0xFFFFFFFFull;
                 if (fm) {
-                    flagged_tiles |= 1u << nt;
                     half8 bt[NS];
                     rows_of_tile(nt, bt);
                     if (flagged) {
@@ -1029,7 +1045,7 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
         if (full_mode) {
             // the new labels become the current ones; the sums are rebuilt from all of them
             const int lane = opaque(lane_id), n32 = lane & 31, h = lane >> 5;
-            uint32_t todo = dirty_tiles;
+            uint32_t todo = changed_tiles;
             while (todo) {
                 const int nt = __builtin_ctz(todo);
                 todo &= todo - 1;
@@ -1049,7 +1065,7 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
             // knobs), in batches of at most kRecCap rows
             const int lane = opaque(lane_id), n32 = lane & 31, h = lane >> 5;
             (void)lane;
-            uint32_t todo = dirty_tiles;
+            uint32_t todo = changed_tiles;
             int cnt = 0;
             while (todo) {
                 const int nt = __builtin_ctz(todo);
