@@ -183,7 +183,7 @@ SweepPath choose_path(const Plan &pl, int d, int flags)
 struct SweepWs {
     int64_t blob = 0, init_rows = 0, ndist = 0, passes = 0, counters = 0, xh = 0, labbuf = 0, total = 0;
     // streaming path
-    int64_t x2 = 0, ojf = 0, Sg = 0, ng = 0, mu = 0, afrag = 0, m2 = 0, wg_off = 0, loss = 0;
+    int64_t x2 = 0, ojf = 0, Sg = 0, ng = 0, mu = 0, afrag = 0, biasf = 0, m2 = 0, wg_off = 0, loss = 0;
     int kpm = 0, n_units = 0, total_wgs = 0;
 };
 
@@ -220,6 +220,7 @@ SweepWs sweep_ws(const Plan &pl, int64_t ld, bool own_labels, bool stream, const
         w.ng = o;      o += up(u * kpm * 4);
         w.mu = o;      o += up(u * 32 * kpm * 8);
         w.afrag = o;   o += up(u * (kpm / 32) * 4 * 64 * 16);
+        w.biasf = o;   o += up(u * kpm * 4);
         w.m2 = o;      o += up(u * 8 * 4);
         w.wg_off = o;  o += up((u + 2) * 4);
         w.loss = o;    o += up(((int64_t)w.total_wgs + 1) * 8);
@@ -426,6 +427,7 @@ static int32_t sweep_impl(const void *Xv, int xbytes, int64_t ld, int32_t d, con
             sa.ng = reinterpret_cast<int *>(ws + w.ng);
             sa.mu = reinterpret_cast<double *>(ws + w.mu);
             sa.afrag = ws + w.afrag;
+            sa.biasf = reinterpret_cast<float *>(ws + w.biasf);
             sa.m2 = reinterpret_cast<float *>(ws + w.m2);
             sa.loss_part = reinterpret_cast<double *>(ws + w.loss);
             sa.passes = a.passes;

@@ -86,13 +86,14 @@ struct StreamArgs {
     int *status;
     uint8_t *labbuf;
     double *trace;
-    uint16_t *xh;                  // [ld][16 or 32] centred f16 rows, last slot = bias constant
+    uint16_t *xh;                  // [ld][16 or 32] centred f16 rows (absent knobs zero)
     float *x2;                     // [ld] squared norm of the centred rows
     float *ojf;                    // [T][32] centring offsets
     int *Sg;                       // [n_units][kpm][32] integer sums
     int *ng;                       // [n_units][kpm] counts
     double *mu;                    // [n_units][32][kpm] exact centroids, transposed
     void *afrag;                   // [n_units][kpm/32][4][64] 16-byte A fragments
+    float *biasf;                  // [n_units][kpm] |mu'|^2 per centroid row (huge for padding rows)
     float *m2;                     // [n_units][8] bound on max |mu'|^2 per tile of 32 centroids; tile 0 negative = unit unusable
     double *loss_part;             // [total workgroups] loss partials of the last pass
     int *passes;                   // [T][n_k] labelling passes actually run (preset to n_iter + 1 by the host code)

@@ -4,12 +4,15 @@
 // stream_update_kernel over units.  Labels, integer sums and counts live in global memory and are
 // updated incrementally (a row touches the sums only when its label changes: exact, integers).
 //
-// The screen is the same f16 hi/lo matrix-core screen as in the resident kernel, for up to 256
-// centroids: centroids are taken in chunks of 64 (two 32-row m-tiles); a first sweep over the
-// chunks finds the minimum score of every row, a second one counts the scores within the error
-// bound of it.  A row with exactly one such score is decided; any other row is re-evaluated by
-// the whole wave in double against all k centroids (one centroid per lane, knobs ascending, no
-// fused multiply-add, lowest index on ties).
+// The screen is an f16 hi/lo matrix-core screen as in the resident kernel, for up to 256
+// centroids, with every knob slot of the fragments holding a knob (d <= 16 takes one 16-wide
+// step per part): |mu'|^2 enters as the initial value of the accumulator, in fp32.  Centroids
+// are taken in chunks of 64 (two 32-row m-tiles); one sweep over the chunks leaves, per chunk, the
+// minimum score of every row and the scores within the error bound of that minimum, and the chunks
+// whose minimum lies within the bound of the overall minimum contribute their marks.  A row with
+// exactly one marked score is decided; any other row is re-evaluated in double against its marked
+// centroids (one lane per (row, centroid) pair; knobs ascending, no fused multiply-add, lowest
+// index on ties), or against all k centroids when the pairs do not fit.
 #include "cham_device.h"
 #include "cham_internal.h"
 #include "mfma_common.h"
@@ -22,17 +25,7 @@ constexpr int kTiles = 4;            // 32-row tiles a wave handles per step
 constexpr int kStreamRec = 32;       // queued rows whose knob values are kept in LDS
 constexpr int kWavesPerWg = 8;
 constexpr int kPairCap = 128;        // (queued row, candidate centroid) pairs evaluated per step and wave
-
-#ifdef CHAM_KERNEL_TIMING
-// Development aid (not built into the library): per-section cycle counts summed over waves,
-// one row of 8 counters per chunk count (k <= 64, <= 128, <= 192, <= 256).
-__device__ unsigned long long g_stream_timing[4 * 8];
-#define STR_T(var) const unsigned long long var = __builtin_readcyclecounter()
-#define STR_ADD(slot, t0, t1) sacc[slot] += (t1) - (t0)
-#else
-#define STR_T(var)
-#define STR_ADD(slot, t0, t1)
-#endif
+constexpr float kPadScore = 1.0e30f; // score of a padding centroid row (real scores stay below 4 * 32 * 255^2)
 
 // Per-unit state in global memory.  KPM = kmax rounded up to 32.
 struct UnitState {
@@ -40,6 +33,7 @@ struct UnitState {
     int *n;            // [KPM]          counts
     double *mu;        // [32][KPM]      exact centroids, transposed
     half8 *afrag;      // [KPM/32][4][64] A fragments (hi steps then lo steps; NS2 <= 4)
+    float *bias;       // [KPM]          |mu'|^2 (fp32), huge for padding rows: initial accumulator values
 };
 
 __device__ __forceinline__ UnitState unit_state(const StreamArgs &a, int u)
@@ -50,6 +44,7 @@ __device__ __forceinline__ UnitState unit_state(const StreamArgs &a, int u)
     s.n = a.ng + (size_t)u * kpm;
     s.mu = a.mu + (size_t)u * 32 * kpm;
     s.afrag = reinterpret_cast<half8 *>(a.afrag) + (size_t)u * (kpm / 32) * 4 * 64;
+    s.bias = a.biasf + (size_t)u * kpm;
     return s;
 }
 
@@ -79,8 +74,8 @@ __global__ void stream_offsets_kernel(const StreamArgs a)
     a.ojf[t * 32 + j] = o;
 }
 
-// Centred f16 copy of the rows (row-major, DK halfs per row, last slot = the bias constant) and
-// the squared norm of every centred row.
+// Centred f16 copy of the rows (row-major, DK halfs per row, absent knobs zero) and the squared
+// norm of every centred row.
 template <int DK>
 __global__ void stream_pack_kernel(const StreamArgs a, int64_t n_rows)
 {
@@ -105,7 +100,6 @@ __global__ void stream_pack_kernel(const StreamArgs a, int64_t n_rows)
             x2 = __builtin_fmaf(f, f, x2);
             v[i] = (_Float16)f;
         }
-        if (g == DK / 8 - 1) v[7] = (_Float16)kBiasScale;
         *reinterpret_cast<half8 *>(dst + 8 * g) = v;
     }
     a.x2[r] = x2;
@@ -222,18 +216,8 @@ __global__ __launch_bounds__(32 * (DK / 8)) void stream_update_kernel(const Stre
     // |mu'|^2 over all knob groups of the centroid (the G lanes of a centroid are neighbours)
 #pragma unroll
     for (int off = G / 2; off >= 1; off >>= 1) b = b + __shfl_xor(b, off, 64);
-    if (g == G - 1) {
-        // bias slot: |mu'|^2 / 256 as hi + lo; padding centroid rows get a score above all others
-        if (c < k) {
-            const float bs = (float)b * (1.0f / kBiasScale);
-            const _Float16 bh = (_Float16)bs;
-            hi8[7] = bh;
-            lo8[7] = (_Float16)(bs - (float)bh);
-        } else {
-            hi8[7] = (_Float16)kPadBiasHi;
-            lo8[7] = (_Float16)0.0f;
-        }
-    }
+    // |mu'|^2 starts the accumulator; padding centroid rows get a score above all others
+    if (g == G - 1) st.bias[c] = c < k ? (float)b : kPadScore;
     const int hh = g & 1, fstep = g >> 1;
     st.afrag[(mt * 4 + fstep) * 64 + 32 * hh + m32] = hi8;
     st.afrag[(mt * 4 + NS + fstep) * 64 + 32 * hh + m32] = lo8;
@@ -256,6 +240,7 @@ struct StreamLds {
     int *S;              // [KPM][DK] changes of the sums made by this workgroup
     int *n;              // [KPM]
     float *ojf;          // [DK]
+    float *bias;         // [KPM]
     double *red;         // [8]
     unsigned char *wave_base;
     // per wave: knob values of queued rows, their row slots, resolved labels, labels of the step
@@ -266,7 +251,7 @@ struct StreamLds {
     __host__ __device__ static size_t bytes(int kpm)
     {
         size_t b = 16 * (size_t)(kpm / 32) * 4 * 64 + sizeof(int) * (size_t)kpm * DK + sizeof(int) * kpm +
-                   sizeof(float) * DK + sizeof(double) * 8;
+                   sizeof(float) * DK + sizeof(float) * kpm + sizeof(double) * 8 + 16;
         b = (b + 15) & ~(size_t)15;
         return b + ((kWaveBytes + 15) & ~(size_t)15) * kWavesPerWg;
     }
@@ -278,6 +263,8 @@ struct StreamLds {
         S = reinterpret_cast<int *>(base + o);        o += sizeof(int) * (size_t)kpm * DK;
         n = reinterpret_cast<int *>(base + o);        o += sizeof(int) * kpm;
         ojf = reinterpret_cast<float *>(base + o);    o += sizeof(float) * DK;
+        o = (o + 15) & ~(size_t)15;
+        bias = reinterpret_cast<float *>(base + o);   o += sizeof(float) * kpm;
         o = (o + 15) & ~(size_t)15;
         wave_base = base + o;
     }
@@ -334,17 +321,6 @@ __global__ __launch_bounds__(512) void stream_assign_kernel(const StreamArgs a)
     uint8_t *labrow = a.labbuf + (int64_t)ki * a.ld;
     const bool first = a.it == 0;
     const bool want_dist = a.final_pass || (a.trace != nullptr);
-
-#ifdef CHAM_KERNEL_TIMING
-    unsigned long long sacc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-#endif
-    STR_T(t_w0);
-    for (int e = tid; e < (kpu / 32) * 4 * 64; e += blockDim.x) L.afrag[e] = st.afrag[e];
-    for (int e = tid; e < k * DK; e += blockDim.x) L.S[e] = 0;
-    for (int c = tid; c < k; c += blockDim.x) L.n[c] = 0;
-    if (tid < DK) L.ojf[tid] = tid < 32 ? a.ojf[t * 32 + tid] : 0.0f;
-    __syncthreads();
-
     unsigned char *wb = L.wave_base + ((StreamLds<DK>::kWaveBytes + 15) & ~(size_t)15) * wave;
     _Float16 *rec_x = reinterpret_cast<_Float16 *>(wb);                                          // [kStreamRec][DK]
     unsigned short *rec_slot = reinterpret_cast<unsigned short *>(wb + (size_t)kStreamRec * DK * 2);   // [128]
@@ -358,7 +334,6 @@ __global__ __launch_bounds__(512) void stream_assign_kernel(const StreamArgs a)
 
     const _Float16 *xh = reinterpret_cast<const _Float16 *>(a.xh);
     const int nch = (k + 63) >> 6;
-    const float16v zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     double part = 0.0;
 
     const int64_t step_rows = (int64_t)kWavesPerWg * kTiles * 32;
@@ -390,12 +365,17 @@ __global__ __launch_bounds__(512) void stream_assign_kernel(const StreamArgs a)
     };
 
     StepRows nxt;
-    if (r0 < r1) load_step(r0 + (int64_t)wave * kTiles * 32, nxt);
-    STR_T(t_w1);
-    STR_ADD(0, t_w0, t_w1);      // set-up
+    if (r0 < r1) load_step(r0 + (int64_t)wave * kTiles * 32, nxt);    // under way during the set-up below
+
+    for (int e = tid; e < (kpu / 32) * 4 * 64; e += blockDim.x) L.afrag[e] = st.afrag[e];
+    for (int e = tid; e < kpu; e += blockDim.x) L.bias[e] = st.bias[e];
+    for (int e = tid; e < k * DK; e += blockDim.x) L.S[e] = 0;
+    for (int c = tid; c < k; c += blockDim.x) L.n[c] = 0;
+    if (tid < DK) L.ojf[tid] = tid < 32 ? a.ojf[t * 32 + tid] : 0.0f;
+    __syncthreads();
+
     for (int64_t base = r0; base < r1; base += step_rows) {
         const int64_t wrow0 = base + (int64_t)wave * kTiles * 32;      // first row of this wave's step
-        STR_T(t_s0);
         const StepRows cur = nxt;
         if (base + step_rows < r1) load_step(wrow0 + step_rows, nxt);  // next step's rows load under this step
         if (wrow0 >= r1) continue;                                      // wave-uniform
@@ -414,16 +394,25 @@ __global__ __launch_bounds__(512) void stream_assign_kernel(const StreamArgs a)
             for (int ch = 0; ch < kMaxCh; ++ch) cmask[tt][ch] = 0u;
         }
         if (lane == 0) *npairs = 0u;
-        auto load_a = [&](int ch, bool has1, half8 (&A0)[NS2], half8 (&A1)[NS2]) {
+        // fragments of the two m-tiles of chunk ch and the initial accumulator values (|mu'|^2 of the
+        // centroid rows this lane's registers belong to: rows 8 g + 4 h + (0..3) for registers 4 g + (0..3))
+        auto load_a = [&](int ch, bool has1, half8 (&A0)[NS2], half8 (&A1)[NS2], float16v &c0, float16v &c1) {
 #pragma unroll
             for (int s = 0; s < NS2; ++s) {
                 A0[s] = L.afrag[((2 * ch) * 4 + s) * 64 + lane];        // slots 0..NS-1 hi parts, NS..2NS-1 lo parts
                 A1[s] = has1 ? L.afrag[((2 * ch + 1) * 4 + s) * 64 + lane] : A0[s];
             }
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const float4 b0 = *reinterpret_cast<const float4 *>(L.bias + (2 * ch) * 32 + 8 * g + 4 * h);
+                const float4 b1 = has1 ? *reinterpret_cast<const float4 *>(L.bias + (2 * ch + 1) * 32 + 8 * g + 4 * h) : b0;
+                c0[4 * g + 0] = b0.x; c0[4 * g + 1] = b0.y; c0[4 * g + 2] = b0.z; c0[4 * g + 3] = b0.w;
+                c1[4 * g + 0] = b1.x; c1[4 * g + 1] = b1.y; c1[4 * g + 2] = b1.z; c1[4 * g + 3] = b1.w;
+            }
         };
         // one matrix instruction of the chain of a 32x32 tile
-        auto mma = [&](float16v &acc, const half8 (&Af)[NS2], const half8 (&Bt)[NS], int s) {
-            acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(Af[s], Bt[s % NS], s == 0 ? zero16 : acc, 0, 0, 0);
+        auto mma = [&](float16v &acc, const half8 (&Af)[NS2], const half8 (&Bt)[NS], const float16v &cinit, int s) {
+            acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(Af[s], Bt[s % NS], s == 0 ? cinit : acc, 0, 0, 0);
         };
         auto min16 = [&](const float16v &acc) {
             float m = min3f(acc[0], acc[1], acc[2]);
@@ -455,15 +444,16 @@ __global__ __launch_bounds__(512) void stream_assign_kernel(const StreamArgs a)
             if (ch < nch) {
                 const bool has1 = (2 * ch + 1) * 32 < kpu;
                 half8 A0[NS2], A1[NS2];
-                load_a(ch, has1, A0, A1);
+                float16v cin0, cin1;
+                load_a(ch, has1, A0, A1, cin0, cin1);
                 float16v accA, accB;
                 constexpr int kLast = kTiles - 1;
                 if (has1) {
                     // accA = centroids 0..31, accB = centroids 32..63 of the chunk
 #pragma unroll
-                    for (int s = 0; s < NS2; ++s) mma(accA, A0, cur.B[0], s);
+                    for (int s = 0; s < NS2; ++s) mma(accA, A0, cur.B[0], cin0, s);
 #pragma unroll
-                    for (int s = 0; s < NS2; ++s) mma(accB, A1, cur.B[0], s);
+                    for (int s = 0; s < NS2; ++s) mma(accB, A1, cur.B[0], cin1, s);
 #pragma unroll
                     for (int tt = 0; tt < kTiles; ++tt) {
                         const int nx = tt < kLast ? tt + 1 : tt;
@@ -476,14 +466,14 @@ __global__ __launch_bounds__(512) void stream_assign_kernel(const StreamArgs a)
 #pragma unroll
                         for (int s = 0; s < NS2; ++s) {
                             __builtin_amdgcn_sched_barrier(0);
-                            if (tt < kLast) mma(accA, A0, cur.B[nx], s);
+                            if (tt < kLast) mma(accA, A0, cur.B[nx], cin0, s);
                             __builtin_amdgcn_sched_barrier(0);
                             mark(far, accB, thr, s * CH);
                         }
                         __builtin_amdgcn_sched_barrier(0);
                         if (tt < kLast) {
 #pragma unroll
-                            for (int s = 0; s < NS2; ++s) mma(accB, A1, cur.B[nx], s);
+                            for (int s = 0; s < NS2; ++s) mma(accB, A1, cur.B[nx], cin1, s);
                         }
                         bch[tt][ch] = m;
                         cmask[tt][ch] = ~far;
@@ -492,7 +482,7 @@ __global__ __launch_bounds__(512) void stream_assign_kernel(const StreamArgs a)
                 } else {
                     // one block of 32 centroids: the accumulators alternate
 #pragma unroll
-                    for (int s = 0; s < NS2; ++s) mma(accA, A0, cur.B[0], s);
+                    for (int s = 0; s < NS2; ++s) mma(accA, A0, cur.B[0], cin0, s);
 #pragma unroll
                     for (int tt = 0; tt < kTiles; ++tt) {
                         const int nx = tt < kLast ? tt + 1 : tt;
@@ -504,7 +494,7 @@ __global__ __launch_bounds__(512) void stream_assign_kernel(const StreamArgs a)
 #pragma unroll
                         for (int s = 0; s < NS2; ++s) {
                             __builtin_amdgcn_sched_barrier(0);
-                            if (tt < kLast) mma(nxt2, A0, cur.B[nx], s);
+                            if (tt < kLast) mma(nxt2, A0, cur.B[nx], cin0, s);
                             __builtin_amdgcn_sched_barrier(0);
                             mark(far, now, thr, s * CH);
                         }
@@ -533,9 +523,6 @@ __global__ __launch_bounds__(512) void stream_assign_kernel(const StreamArgs a)
                 cmask[tt][ch] = cand;
             }
         }
-
-        STR_T(t_s1);
-        STR_ADD(1, t_s0, t_s1);      // sweep
         // decide, or queue for the exact evaluation
         int lab[kTiles];
         uint32_t flagged_mask = 0;
@@ -582,8 +569,6 @@ __global__ __launch_bounds__(512) void stream_assign_kernel(const StreamArgs a)
             }
         }
         __builtin_amdgcn_wave_barrier();
-        STR_T(t_s2);
-        STR_ADD(2, t_s1, t_s2);      // decide
         const unsigned np = nrec ? *npairs : 0u;
         const bool full_eval = nrec && (np > (unsigned)kPairCap || __ballot(no_candidate) != 0ull);
         if (nrec && !full_eval) {
@@ -681,13 +666,6 @@ __global__ __launch_bounds__(512) void stream_assign_kernel(const StreamArgs a)
             }
             __builtin_amdgcn_wave_barrier();
         }
-
-        STR_T(t_s3);
-        STR_ADD(3, t_s2, t_s3);      // exact evaluation
-#ifdef CHAM_KERNEL_TIMING
-        sacc[6] += (unsigned long long)nrec;
-        sacc[7] += 1;
-#endif
         // label changes -> sums of this workgroup (LDS), tile by tile
 #pragma unroll
         for (int tt = 0; tt < kTiles; ++tt) {
@@ -737,9 +715,6 @@ __global__ __launch_bounds__(512) void stream_assign_kernel(const StreamArgs a)
                 __builtin_amdgcn_wave_barrier();
             }
         }
-
-        STR_T(t_s4);
-        STR_ADD(4, t_s3, t_s4);      // sums
         if (want_dist) {
             // exact loss terms of the rows of this step: one row per lane, knobs ascending
             __builtin_amdgcn_wave_barrier();
@@ -763,7 +738,6 @@ __global__ __launch_bounds__(512) void stream_assign_kernel(const StreamArgs a)
         const double ws = wave_sum(part);
         if (lane == 0) L.red[wave] = ws;
     }
-    STR_T(t_w2);
     __syncthreads();
     // changes of this workgroup -> the unit's sums
     for (int e = tid; e < k * DK; e += blockDim.x) {
@@ -779,14 +753,6 @@ __global__ __launch_bounds__(512) void stream_assign_kernel(const StreamArgs a)
         for (int w = 0; w < kWavesPerWg; ++w) s = s + (w < (int)(blockDim.x >> 6) ? L.red[w] : 0.0);
         a.loss_part[blockIdx.x] = s;
     }
-#ifdef CHAM_KERNEL_TIMING
-    {
-        const unsigned long long t_w3 = __builtin_readcyclecounter();
-        sacc[5] += t_w3 - t_w2;      // barrier + flush
-        if (lane == 0)
-            for (int q = 0; q < 8; ++q) atomicAdd(&g_stream_timing[((nch - 1) & 3) * 8 + q], sacc[q]);
-    }
-#endif
 }
 
 template <int DK>
@@ -816,23 +782,14 @@ hipError_t run_stream(StreamArgs a, int64_t n_total, int total_wgs, hipStream_t 
 
 }  // namespace
 
-#ifdef CHAM_KERNEL_TIMING
-extern "C" int cham_dev_stream_timing(unsigned long long *host32, int reset)
-{
-    unsigned long long z[32] = {0};
-    if (reset) return (int)hipMemcpyToSymbol(HIP_SYMBOL(g_stream_timing), z, sizeof(z));
-    return (int)hipMemcpyFromSymbol(host32, HIP_SYMBOL(g_stream_timing), sizeof(z));
-}
-#endif
-
 int64_t stream_lds_bytes(int d, int kpm)
 {
-    return d <= 15 ? (int64_t)StreamLds<16>::bytes(kpm) : (int64_t)StreamLds<32>::bytes(kpm);
+    return d <= 16 ? (int64_t)StreamLds<16>::bytes(kpm) : (int64_t)StreamLds<32>::bytes(kpm);
 }
 
 hipError_t launch_stream_sweep(const StreamArgs &a, int64_t n_total, int total_wgs, hipStream_t s)
 {
-    if (a.d <= 15) return run_stream<16>(a, n_total, total_wgs, s);
+    if (a.d <= 16) return run_stream<16>(a, n_total, total_wgs, s);
     return run_stream<32>(a, n_total, total_wgs, s);
 }
 
