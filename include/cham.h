@@ -104,11 +104,11 @@ int64_t cham_sweep_workspace_bytes(int64_t ld, int32_t d, const int64_t *task_of
  *   inertia   [T][n_k]     double  loss: sum over rows of the squared distance to the row's
  *                                  final centroid (double terms, fixed summation tree)
  *   status    [T][n_k]     int32   0 ok; 1 = task has fewer than k distinct rows (init_mode 0):
- *                                  centroids, counts, loss and labels of that (t,k) are zero;
- *                                  2 = internal consistency check failed (a label changed in a
- *                                  pass whose centroids had not changed): results not to be used
+ *                                  centroids, counts, loss and labels of that (t,k) are zero
  *   labels    [n_k][ld]    uint8   final labels per k (optional, may be NULL)
- *   inertia_trace [T][n_k][n_iter+1] double  loss seen by every labelling pass (optional)
+ *   inertia_trace [T][n_k][n_iter+1] double  loss seen by every labelling pass (optional); a
+ *                                  kernel that stops at the fixed point (see cham_sweep_passes)
+ *                                  repeats the final loss for the passes it did not run
  * workspace: DEVICE scratch of at least cham_sweep_workspace_bytes(...) bytes, 256-byte aligned.
  */
 int32_t cham_kmeans_sweep(const uint8_t *X, int64_t ld, int32_t d,
@@ -124,7 +124,7 @@ int32_t cham_kmeans_sweep(const uint8_t *X, int64_t ld, int32_t d,
  * the choice depends only on d, the largest task, the largest k and flags (Sec. 3.3's k-means,
  * "K-means.run" of Algorithm 1, is the same computation on every path).
  *   CHAM_PATH_RESIDENT_MFMA    one workgroup per (task, k), distances on the matrix cores
- *                              (d <= 29, tasks of at most 4096 rows, k <= 64)
+ *                              (d <= 31, tasks of at most 4096 rows, k <= 64)
  *   CHAM_PATH_STREAM_MFMA      several workgroups per (task, k), one launch pair per pass (d <= 31)
  *   CHAM_PATH_RESIDENT_VECTOR  one workgroup per (task, k), vector ALU
  * cham_sweep_path_kernel gives the name of the family's dominant kernel (a static string).
@@ -236,7 +236,8 @@ int64_t cham_synth_workspace_bytes(int64_t ld, int32_t d, const int64_t *task_of
 /*
  * Sample Synthesis and dedupe (Algorithm 1, second loop; Sec. 3.3 "most frequent = mode,
  * non-invalid choice for each knob").
- *   cards [T][d] HOST uint16     cardinality of each knob (every value of X is < its card)
+ *   cards [T][d] HOST uint16     cardinality of each knob.  Precondition: every value of X is below its
+ *                                knob's cardinality; a value that is not is never counted for the mode
  *   valid [ld] DEVICE uint8      1 = valid configuration, 0 = known invalid; NULL = all valid
  *   visited DEVICE uint64        hashes (cham_hash_config) of measured configurations, sorted
  *                                ascending; membership is by hash

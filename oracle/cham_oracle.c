@@ -327,7 +327,12 @@ void orc_synthesize(const knob_t *x, int64_t n, int d, const uint16_t *cards,
         for (int64_t i = 0; i < n; ++i) {
             if (labels[i] != c || (valid && !valid[i])) continue;
             ++members;
-            for (int j = 0; j < d; ++j) hist[(size_t)j * cmax + x[(size_t)i * d + j]] += 1;
+            for (int j = 0; j < d; ++j) {
+                /* a choice index at or above the knob's cardinality (outside the design space of
+                 * Sec. 2.2; the caller's precondition) can never be the mode: it is not counted */
+                const int v = (int)x[(size_t)i * d + j];
+                if (v < (int)cards[j]) hist[(size_t)j * cmax + v] += 1;
+            }
         }
         if (members == 0) continue;                          /* stays DROPPED */
         for (int j = 0; j < d; ++j) {

@@ -39,5 +39,28 @@ def build_lib(verbose: bool = False, extra=()) -> str:
     return LIB
 
 
+def build_host_sanitized(outdir: str) -> str:
+    """A copy of the library whose host code in cham_api.hip (argument checks, planning, staging)
+    is built with AddressSanitizer and UndefinedBehaviorSanitizer; device code and the other
+    objects are the ordinary ones.  For the CPU-only driver csrc/host_check.c; never loaded by the
+    product."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    objs = []
+    for src in SOURCES:
+        obj = os.path.join(CSRC, src.replace(".hip", ".o"))
+        if src == "cham_api.hip":
+            obj = os.path.join(outdir, "cham_api_san.o")
+            san = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined",
+                   "-Xarch_host", "-fno-sanitize-recover=all", "-g"]
+            subprocess.run([hipcc, *FLAGS, *san, "-c", os.path.join(CSRC, src), "-o", obj], check=True)
+        elif not os.path.exists(obj):
+            subprocess.run([hipcc, *FLAGS, *FILE_FLAGS.get(src, []), "-c", os.path.join(CSRC, src), "-o", obj], check=True)
+        objs.append(obj)
+    lib = os.path.join(outdir, "libcham_san.so")
+    # no sanitizer runtime in the shared object: its calls resolve to the runtime of the sanitized driver
+    subprocess.run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", lib, *objs], check=True)
+    return lib
+
+
 if __name__ == "__main__":
     build_lib(verbose=True, extra=sys.argv[1:])
