@@ -256,8 +256,8 @@ def main():
         wide = dict(workload=f"{ww.name}: T={ww.T} tasks x N={ww.n_total // ww.T} rows x d={ww.d} two-byte knobs "
                              f"(cardinalities up to {int(ww.cards.max())}), k={ww.ks[0]}..{ww.ks[-1]}, "
                              f"{ww.n_iter} Lloyd steps + final pass, visited={ww.n_visited}",
-                    ms_per_step=round(w_ms, 3), evals_per_step=w_exec,
-                    evals_per_s=round(w_exec / (w_ms * 1e-3), 1),
+                    ms_per_step=round(w_ms, 3), evals_per_step=w_exec, evals_counted="executed",
+                    nominal_evals_per_step=w_nom, evals_per_s=round(w_exec / (w_ms * 1e-3), 1),
                     frac_of_fp32_vector_peak=round(w_exec * (2 * ww.d + 2) / (w_ms * 1e-3) / 1e12
                                                    / PEAK_FP32_VECTOR_TFLOPS, 4))
 

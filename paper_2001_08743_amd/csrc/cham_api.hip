@@ -346,6 +346,7 @@ static int32_t sweep_impl(const void *Xv, int xbytes, int64_t ld, int32_t d, con
     a.trace = inertia_trace;
     a.xh = reinterpret_cast<uint16_t *>(ws + w.xh);
     a.passes = reinterpret_cast<int *>(ws + w.passes);
+    a.queue_lds_off = 0;
     a.ki_begin = 0;
     a.ki_end = n_k;
     a.done = nullptr;

@@ -32,6 +32,7 @@ struct SweepArgs {
     double *trace;                 // [T][n_k][n_iter+1] or null
     uint16_t *xh;                  // [ld][16 or 32] f16 row-major copy of X (matrix-core path)
     int *passes;                   // [T][n_k] labelling passes actually run (preset to n_iter + 1 by the host code)
+    int queue_lds_off;             // vector kernel: LDS offset of the per-wave queues of moved rows, 0 = no room for them
     int *unit_counter;             // zeroed before the launch: next unit to hand out (matrix-core resident kernel)
     int ki_begin, ki_end;          // this launch runs ks[ki_begin .. ki_end) (the whole list by default)
     const int *done;               // [T] or null: tasks whose sweep has already stopped; their units are skipped (status 3)

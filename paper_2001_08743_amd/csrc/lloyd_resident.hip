@@ -92,6 +92,12 @@ __global__ __launch_bounds__(MAXNT) void resident_sweep_kernel(const SweepArgs a
     using SumT = typename std::conditional<sizeof(XT) == 1, int, long long>::type;
     constexpr double kMaxValue = sizeof(XT) == 1 ? 255.0 : 65535.0;
     extern __shared__ __align__(16) unsigned char smem[];
+    // per wave: the rows of one step that changed their label (row within the task; new | previous << 8),
+    // behind the unit's state when the LDS has room for them
+    const bool use_queue = a.queue_lds_off != 0;
+    int *q_row = reinterpret_cast<int *>(smem + a.queue_lds_off) + (threadIdx.x / kWave) * 2 * kWave;
+    int *q_lab = q_row + kWave;
+    constexpr int LPR = DP <= 8 ? 8 : (DP <= 16 ? 16 : (DP <= 32 ? 32 : 64));     // lanes per queued row
     UnitLds<DP, SumT> U(smem, a.kmax);
     const XT *X = reinterpret_cast<const XT *>(a.X);
 
@@ -167,10 +173,13 @@ __global__ __launch_bounds__(MAXNT) void resident_sweep_kernel(const SweepArgs a
     const int64_t span = r1 - g0;
     const int ntiles = (int)((span + tile_rows - 1) / tile_rows);
     double loss = 0.0;
+    int passes_run = 0;
 
     for (int it = 0; it <= a.n_iter; ++it) {
         const bool final_pass = (it == a.n_iter);
         const bool want_dist = final_pass || (a.trace != nullptr);
+        bool moved = false;              // this thread changed a label in this pass
+        ++passes_run;
         CentroidView L;
         L.mu64T = U.mu64T;
         L.wf = U.wf;
@@ -211,22 +220,58 @@ __global__ __launch_bounds__(MAXNT) void resident_sweep_kernel(const SweepArgs a
                 const bool on = (rowmask >> p) & 1u;
                 const int cur = on ? lab[p] : prev;
                 newpack |= (uint32_t)cur << (8 * p);
-                if (on && (it == 0 || cur != prev)) {
-                    changed = true;
-                    // fully unrolled: a run-time index into xf would move the rows out of registers
+                const bool ch = on && (it == 0 || cur != prev);
+                changed = changed || ch;
+                if (it == 0 || !use_queue) {
+                    // every row is new (or there is no room for the queue): each lane adds its own
+                    // row from its registers
+                    if (ch) {
+                        // fully unrolled: a run-time index into xf would move the rows out of registers
 #pragma unroll
-                    for (int j = 0; j < DP; ++j) {
-                        if (j < d) {
-                            const int xi = (int)(xf[p][j] + U.ojf[j]);
-                            lds_add(&U.S[cur * DP + j], xi);
-                            if (it > 0) lds_add(&U.S[prev * DP + j], -xi);
+                        for (int j = 0; j < DP; ++j) {
+                            if (j < d) {
+                                const int xi = (int)(xf[p][j] + U.ojf[j]);
+                                lds_add(&U.S[cur * DP + j], xi);
+                                if (it > 0) lds_add(&U.S[prev * DP + j], -xi);
+                            }
                         }
+                        atomicAdd(&U.n[cur], 1);
+                        if (it > 0) atomicSub(&U.n[prev], 1);
                     }
-                    atomicAdd(&U.n[cur], 1);
-                    if (it > 0) atomicSub(&U.n[prev], 1);
+                } else {
+                    // Later passes move few rows: they are queued (row, new and previous label) and
+                    // the wave applies the queue with one lane per (row, knob), the knob value read
+                    // again from the matrix, so that the cost follows the number of moved rows
+                    // instead of every wave walking all knobs whenever one of its lanes moved.
+                    const uint64_t cm = __ballot(ch);
+                    if (cm) {
+                        if (ch) {
+                            const int pos = __popcll(cm & ((1ull << lane) - 1ull));
+                            q_row[pos] = (int)(g + p - r0);
+                            q_lab[pos] = cur | (prev << 8);
+                        }
+                        __builtin_amdgcn_wave_barrier();
+                        const int qn = __popcll(cm);
+                        const int sub = lane / LPR, j = lane % LPR;
+                        for (int e0 = 0; e0 < qn; e0 += 64 / LPR) {
+                            const int e = e0 + sub;
+                            if (e < qn && j < d) {
+                                const int w = q_lab[e];
+                                const int xi = (int)X[(int64_t)j * a.ld + r0 + q_row[e]];
+                                lds_add(&U.S[(w & 0xFF) * DP + j], xi);
+                                lds_add(&U.S[(w >> 8) * DP + j], -xi);
+                                if (j == 0) {
+                                    atomicAdd(&U.n[w & 0xFF], 1);
+                                    atomicSub(&U.n[w >> 8], 1);
+                                }
+                            }
+                        }
+                        __builtin_amdgcn_wave_barrier();
+                    }
                 }
                 if (on && want_dist) part = part + dist[p];
             }
+            moved = moved || changed;
             if (changed) {
                 if (rowmask == (1u << R) - 1u) {
                     if (R == 4) *reinterpret_cast<uint32_t *>(labrow + g) = newpack;
@@ -244,12 +289,25 @@ __global__ __launch_bounds__(MAXNT) void resident_sweep_kernel(const SweepArgs a
             const double ws = wave_sum(part);
             if (lane == 0) U.red[wave] = ws;
         }
-        __syncthreads();
+        const bool any_moved = __syncthreads_or(moved ? 1 : 0) != 0;
         if (want_dist && tid == 0) {
             double s = 0.0;
             for (int w = 0; w < nwaves; ++w) s = s + U.red[w];
             loss = s;
             if (a.trace) a.trace[slot * (a.n_iter + 1) + it] = s;
+        }
+
+        // A pass that moved no row leaves the sums, hence the centroids, hence every later pass as
+        // they are: the remaining passes would repeat this one.  With the loss at hand (a traced
+        // run) the iteration ends here; otherwise the final pass, which computes it, runs next.
+        if (!final_pass && !any_moved) {
+            if (want_dist) {
+                if (tid == 0)
+                    for (int r = it + 1; r <= a.n_iter; ++r) a.trace[slot * (a.n_iter + 1) + r] = loss;
+                break;
+            }
+            it = a.n_iter - 1;
+            continue;
         }
 
         if (!final_pass) {
@@ -274,6 +332,7 @@ __global__ __launch_bounds__(MAXNT) void resident_sweep_kernel(const SweepArgs a
     if (tid == 0) {
         a.status[slot] = 0;
         a.inertia[slot] = loss;
+        a.passes[slot] = passes_run;
     }
 }
 
@@ -334,14 +393,21 @@ __global__ __launch_bounds__(64) void first_distinct_kernel(const SweepArgs a, i
 template <typename XT, int DP, int R, int MAXNT>
 hipError_t launch_dp(const SweepArgs &a, int nt, hipStream_t s)
 {
-    const size_t lds = resident_lds_bytes(DP, a.kmax, sizeof(XT) == 1 ? 4 : 8);
+    size_t lds = (resident_lds_bytes(DP, a.kmax, sizeof(XT) == 1 ? 4 : 8) + 15) & ~(size_t)15;
+    SweepArgs b = a;
+    if (nt > MAXNT) nt = MAXNT;
+    const size_t queue = (size_t)((nt + kWave - 1) / kWave) * 2 * kWave * sizeof(int);    // per-wave queues of moved rows
+    b.queue_lds_off = 0;
+    if (lds + queue <= 160 * 1024) {
+        b.queue_lds_off = (int)lds;
+        lds += queue;
+    }
     auto kern = resident_sweep_kernel<XT, DP, R, MAXNT>;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
-    if (nt > MAXNT) nt = MAXNT;
     const unsigned units = (unsigned)a.T * (unsigned)(a.ki_end - a.ki_begin);
-    hipLaunchKernelGGL(kern, dim3(units), dim3(nt), lds, s, a);
+    hipLaunchKernelGGL(kern, dim3(units), dim3(nt), lds, s, b);
     return hipGetLastError();
 }
 
