@@ -55,6 +55,8 @@ def main():
                     help="skip the timing of the two-byte-knob path")
     ap.add_argument("--no-large-single", dest="large_single", action="store_false",
                     help="skip the timing of the large single clustering (the streaming kernels)")
+    ap.add_argument("--sweep-flags", type=int, default=0,
+                    help="flags of cham_kmeans_sweep for the timed workload (8 = CHAM_F_NO_MFMA: the vector kernel)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run only a plain 1 GiB device copy (reference for the FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
@@ -82,7 +84,7 @@ def main():
     dw.build_visited()
 
     # all outputs and workspaces are allocated once, outside the timed region
-    first = dw.run()
+    first = dw.run(flags=args.sweep_flags)
     bufs = dict(sweep={k: first["sweep"][k] for k in ("centroids", "counts", "inertia", "status")},
                 sweep_ws=first["sweep"]["workspace"], chosen=first["chosen"],
                 snap={k: first["snap"][k] for k in ("labels_sel", "pick_row", "pick_cfg")},
@@ -97,7 +99,7 @@ def main():
         b = bufs
         if ev is not None:
             ev[0].record()
-        sw = binding.cham_kmeans_sweep(dw.X, dw.ld, dw.d, wl.task_off, wl.ks, wl.n_iter,
+        sw = binding.cham_kmeans_sweep(dw.X, dw.ld, dw.d, wl.task_off, wl.ks, wl.n_iter, flags=args.sweep_flags,
                                        out=b["sweep"], workspace=b["sweep_ws"])
         if ev is not None:
             ev[1].record()
@@ -121,7 +123,8 @@ def main():
 
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     nominal = wl.nominal_evals()
-    passes = binding.cham_sweep_passes(bufs["sweep_ws"], dw.ld, dw.d, wl.task_off, wl.ks).cpu().numpy()
+    passes = binding.cham_sweep_passes(bufs["sweep_ws"], dw.ld, dw.d, wl.task_off, wl.ks,
+                                       flags=args.sweep_flags).cpu().numpy()
     executed = executed_evals(wl, passes)
     value = executed / (ms_per_step * 1e-3)
     sweep_times = sorted(a.elapsed_time(b) for a, b in events)
@@ -130,7 +133,7 @@ def main():
     # evaluation: d multiply-adds of the expanded form plus the bias add and the compare = 2d + 2 flops.
     # The matrix-core kernels run the contraction in f16 (hi/lo split), so they are priced against the dense
     # f16 MFMA peak; the vector kernel against the fp32 vector peak.
-    path = binding.cham_sweep_path(dw.ld, dw.d, wl.task_off, wl.ks)
+    path = binding.cham_sweep_path(dw.ld, dw.d, wl.task_off, wl.ks, flags=args.sweep_flags)
     kernel = binding.cham_sweep_path_kernel(path)
     uses_mfma = path in (0, 1)
     flops_per_eval = 2 * wl.d + 2
