@@ -539,6 +539,13 @@ __device__ __forceinline__ void update_centroids(const MfmaLds<DK> &U, int k, in
         half4 hi4 = {(_Float16)0.0f, (_Float16)0.0f, (_Float16)0.0f, (_Float16)0.0f};
         half4 lo4 = hi4;
         double b = 0.0;
+        // The mean S / n with one division per item instead of one per knob: r = fl(1 / n), then
+        // q0 = fl(S r), rem = S - q0 n (exact in one fused operation), fl(q0 + rem r).  That this
+        // equals the correctly rounded quotient fl(S / n) for every count 1 <= n <= 4096 and every
+        // integer sum 0 <= S <= 255 n (the whole domain of this kernel: byte knobs, tasks of at most
+        // 4096 rows) is checked exhaustively on the CPU (quotient_check.c, run by the test suite).
+        const double dn = (double)(cnt > 0 ? cnt : 1);
+        const double rn = 1.0 / dn;
         if (act && 4 * q < d) {
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
@@ -550,7 +557,10 @@ __device__ __forceinline__ void update_centroids(const MfmaLds<DK> &U, int k, in
                         sv -= 1024 * cnt;
                         U.S[c * (DK + 1) + j] = sv;
                     }
-                    mu = (double)sv / (double)cnt;
+                    const double sd = (double)sv;
+                    const double q0 = sd * rn;
+                    const double rem = __builtin_fma(-q0, dn, sd);
+                    mu = __builtin_fma(rem, rn, q0);
                     U.mu64T[(size_t)j * KP + c] = mu;
                 }
                 const double m = j < d ? mu - (double)U.ojf[j] : 0.0;
@@ -638,6 +648,25 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
     constexpr int bstep = NS - 1, bhalf = 1, belem = 7;
     constexpr int kFullDivisor = 8;
 
+    // ---- this lane's rows as B fragments (kept in registers for every pass).  The loads are issued
+    // first (raw knob values; they are centred once the offsets are known) so that they are under way
+    // during the set-up of the unit's state.
+    const _Float16 *xh_wave = reinterpret_cast<const _Float16 *>(a.xh) + (r0 + (wave_live ? wave_row0 : 0)) * DK;
+    half8 B[NTW][NS];
+#pragma unroll
+    for (int nt = 0; nt < NTW; ++nt) {
+        const bool live = wave_live && (wave_row0 + nt * 32 + n32) < nrows;
+        const int64_t prow = live ? (int64_t)(nt * 32 + n32) : 0;         // always a row of this task
+#pragma unroll
+        for (int f = 0; f < NS; ++f) {
+            half8 v;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) v[i] = (_Float16)0.0f;
+            if (nrows > 0) v = *reinterpret_cast<const half8 *>(xh_wave + prow * DK + 16 * f + 8 * h);
+            B[nt][f] = v;
+        }
+    }
+
     // ---- set-up
     for (int e = tid; e < DK * KP; e += blockDim.x) U.mu64T[e] = 0.0;
     for (int e = tid; e < KP * (DK + 1); e += blockDim.x) U.S[e] = 0;
@@ -676,23 +705,32 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
         U.mu64T[(size_t)j * KP + c] = v;
     }
     __syncthreads();
-    if (tid < DK) {
-        float o = 0.0f;
-        if (tid < d) {
+    {
+        // centring offset of knob j: the rounded mean of the starting centroids (any integer would do:
+        // it only keeps the centred magnitudes small); eight lanes per knob
+        const int part = tid & 7;
+        for (int j = tid >> 3; j < DK; j += blockDim.x >> 3) {       // (uniform within a wave: every lane shuffles)
             double s = 0.0;
-            for (int c = 0; c < k; ++c) s += U.mu64T[(size_t)tid * KP + c];
-            double m = rint(s / (double)k);
-            m = m < 0.0 ? 0.0 : (m > 255.0 ? 255.0 : m);
-            o = (float)m;
+            if (j < d)
+                for (int c = part; c < k; c += 8) s += U.mu64T[(size_t)j * KP + c];
+            s = s + dpp_xor_f64<1>(s);
+            s = s + dpp_xor_f64<2>(s);
+            s = s + dpp_xor_f64<4>(s);
+            if (part == 0) {
+                float o = 0.0f;
+                if (j < d) {
+                    double m = rint(s / (double)k);
+                    m = m < 0.0 ? 0.0 : (m > 255.0 ? 255.0 : m);
+                    o = (float)m;
+                }
+                U.ojf[j] = o;
+            }
         }
-        U.ojf[tid] = o;
     }
     __syncthreads();
     update_centroids<DK>(U, k, KP, d, 0, true);
 
-    // ---- this lane's rows as B fragments (kept in registers for every pass)
-    const _Float16 *xh_wave = reinterpret_cast<const _Float16 *>(a.xh) + (r0 + (wave_live ? wave_row0 : 0)) * DK;
-    half8 B[NTW][NS];
+    // ---- centre the rows
     {
         float x2row[NTW];                // squared norm of this lane's row of every tile
         half8 off8[NS];
@@ -703,12 +741,9 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
 #pragma unroll
         for (int nt = 0; nt < NTW; ++nt) {
             const bool live = wave_live && (wave_row0 + nt * 32 + n32) < nrows;
-            const int64_t prow = live ? (int64_t)(nt * 32 + n32) : 0;     // always a row of this task
 #pragma unroll
             for (int f = 0; f < NS; ++f) {
-                half8 v = off8[f];
-                if (nrows > 0) v = *reinterpret_cast<const half8 *>(xh_wave + prow * DK + 16 * f + 8 * h);
-                v = v - off8[f];
+                half8 v = B[nt][f] - off8[f];
 #pragma unroll
                 for (int i = 0; i < 8; ++i)
                     if (!live || 16 * f + 8 * h + i >= d) v[i] = (_Float16)0.0f;
@@ -806,9 +841,10 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
             for (int f = 0; f < NS; ++f)
 #pragma unroll
                 for (int i = 0; i < 8; ++i) of[f][i] = U.ojf[16 * f + 8 * h + i];
+            // (unrolled over the tiles: runs once per unit, and the loads of several tiles overlap)
+#pragma unroll
             for (int nt = 0; nt < NTW; ++nt) {
-                half8 bt[NS];
-                rows_of_tile(nt, bt);
+                const half8 (&bt)[NS] = B[nt];
                 const uint32_t lab = Q.lab()[nt * 32 + n32];
                 const bool live = lab != 0xFFu;
                 const double *mc = U.mu64T + (live ? lab : 0u) + (size_t)(8 * h) * KP;
@@ -1165,12 +1201,15 @@ __global__ __launch_bounds__(512) void resident_mfma_kernel(const SweepArgs a)
     const int tid = threadIdx.x;
     const int n_units = a.T * (a.ki_end - a.ki_begin);
 
+    if (tid == 0) next_unit = atomicAdd(a.unit_counter, 1);
     for (;;) {
-        if (tid == 0) next_unit = atomicAdd(a.unit_counter, 1);
         __syncthreads();
         const int u = next_unit;
         __syncthreads();                           // everyone has read it before it is written again
         if (u >= n_units) break;
+        // the unit after this one is asked for now; the answer is needed when this one is done
+        int after = 0;
+        if (tid == 0) after = atomicAdd(a.unit_counter, 1);
         const int ki = a.ki_end - 1 - u / a.T;
         const int t = u % a.T;
         const int k = a.ks[ki];
@@ -1193,10 +1232,10 @@ __global__ __launch_bounds__(512) void resident_mfma_kernel(const SweepArgs a)
             }
             if (a.trace)
                 for (int e = tid; e <= a.n_iter; e += blockDim.x) a.trace[slot * (a.n_iter + 1) + e] = 0.0;
-            continue;
+        } else {
+            run_unit<DK, NTW>(a, smem, ki, t, k);
         }
-        run_unit<DK, NTW>(a, smem, ki, t, k);
-        __syncthreads();                           // the unit's LDS state is dead before the next unit sets its own
+        if (tid == 0) next_unit = after;            // (read by everyone after the barrier at the loop's head)
     }
 }
 
