@@ -103,6 +103,7 @@ struct MfmaLds {
     int *n;             // [KP]       cluster sizes
     int *dirty;         // [KP]       pass in which the cluster last changed
     float *ojf;         // [DK]       centring offsets
+    unsigned long long *acc64;  // [2]  sum over the task's rows of |x|^2; sum over the clusters of floor(|S|^2 / n)
     int *stamp;         // [4]        [1] float bits of the largest squared row norm, [2], [3] rows that changed in an even / odd pass
     unsigned char *wave_base;   // per-wave regions follow
     __host__ __device__ static size_t wave_bytes(int ntw)
@@ -113,7 +114,7 @@ struct MfmaLds {
     {
         size_t b = sizeof(double) * DK * KP + sizeof(double) * 16 + sizeof(float) * KP;
         b += 16 * (size_t)(KP / 32) * (2 * DK / 16) * 64;
-        b += sizeof(int) * (size_t)KP * (DK + 1) + sizeof(int) * KP * 2 + sizeof(float) * DK + 16;
+        b += sizeof(int) * (size_t)KP * (DK + 1) + sizeof(int) * KP * 2 + sizeof(float) * DK + 32;
         b = (b + 15) & ~(size_t)15;
         return b + wave_bytes(ntw) * nwaves;
     }
@@ -130,6 +131,7 @@ struct MfmaLds {
         dirty = reinterpret_cast<int *>(base + o);     o += sizeof(int) * KP;
         ojf = reinterpret_cast<float *>(base + o);     o += sizeof(float) * DK;
         stamp = reinterpret_cast<int *>(base + o);     o += 16;
+        acc64 = reinterpret_cast<unsigned long long *>(base + o);  o += 16;
         o = (o + 15) & ~(size_t)15;
         wave_base = base + o;
     }
@@ -692,6 +694,8 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
         U.stamp[1] = 0;           // float bits of the largest squared norm of a centred row
         U.stamp[2] = 0;           // rows that changed their label in an even pass
         U.stamp[3] = 0;           // ... in an odd pass
+        U.acc64[0] = 0ull;
+        U.acc64[1] = 0ull;
     }
     for (int e = tid; e < k * d; e += blockDim.x) {
         const int c = e / d, j = e % d;
@@ -729,6 +733,32 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
     }
     __syncthreads();
     update_centroids<DK>(U, k, KP, d, 0, true);
+
+    // ---- sum of |x|^2 over the task's rows, an integer (for the loss at a fixed point, see the end):
+    // per lane and tile at most 16 * 255^2 < 2^24, exact in fp32
+    {
+        unsigned q2 = 0;
+#pragma unroll
+        for (int nt = 0; nt < NTW; ++nt) {
+            const bool live = wave_live && (wave_row0 + nt * 32 + n32) < nrows;
+            float part = 0.0f;
+#pragma unroll
+            for (int f = 0; f < NS; ++f) {
+                half8 bv = B[nt][f];
+                asm volatile("" : "+v"(bv));      // (an opaque copy, as below)
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    const float v = (float)bv[i];
+                    part = __builtin_fmaf(v, v, part);
+                }
+            }
+            q2 += live ? (unsigned)part : 0u;
+        }
+        // the wave's total (at most 512 rows * 31 * 255^2 < 2^31) -> the unit's 64-bit sum
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) q2 += (unsigned)__shfl_xor((int)q2, off, 64);
+        if (lane_id == 0 && q2) atomicAdd(&U.acc64[0], (unsigned long long)q2);
+    }
 
     // ---- centre the rows
     {
@@ -799,6 +829,7 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
     const int rows_wave = __builtin_amdgcn_readfirstlane(nrows - wave_row0);   // rows from this wave's first row to the task's end
     uint32_t force_tiles = 0xFFFFFFFFu;  // tiles to decide whatever their masks say: all at first, later those with undecided rows
     int passes_run = 0;
+    bool at_fixed_point = false;         // the last pass run moved no row: every centroid is the mean of its cluster
     // A pass after one that moved many rows rebuilds the sums from the labels on the matrix cores
     // instead of applying the changes one by one; the first pass (every row is new) always does.
     const uint8_t *xw = a.X + r0 + (wave_live ? wave_row0 : 0);
@@ -1149,6 +1180,7 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
         // final.  (The count is read between this pass's two barriers, or after its only one when the
         // loop ends here; no wave adds to it in between.)
         const int rows_changed = __builtin_amdgcn_readfirstlane(U.stamp[2 + (it & 1)]);
+        at_fixed_point = rows_changed == 0;
         if (last_pass || rows_changed == 0) break;
         if (tid == 0) U.stamp[2 + ((it + 1) & 1)] = 0;      // the next pass counts from zero (nobody adds before the barrier below)
         const bool full_next = x_aligned && rows_changed > full_above;
@@ -1166,14 +1198,46 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
     }
     // the loss of the final labels: the per-wave sums of the last traced pass are still in place
     int loss_slot = ((passes_run - 1) & 1) * 8;
-    if (!traced_last) {
-        loss_slot = 0;
-        wave_loss(0);
-        __syncthreads();
-    }
     double loss = 0.0;
-    if (tid == 0)
-        for (int w = 0; w < nwaves; ++w) loss = loss + U.red[loss_slot + w];
+    if (!traced_last && at_fixed_point) {
+        // At a fixed point every non-empty centroid is the mean S / n of its cluster, so the loss is
+        // sum_rows |x|^2 - sum_c |S_c|^2 / n_c, all integers but the last division: with
+        // |S_c|^2 = q_c n_c + r_c it is the integer (sum |x|^2 - sum q_c) minus the sum of the fractions
+        // r_c / n_c, which is exact up to the rounding of those k fractions and of the final
+        // subtraction (and exactly zero when every cluster's rows coincide).  The sums left by a
+        // pass that rebuilt them on the matrix cores are still raised by 1024 n.
+        double *frac0 = WaveQueue<DK>(U.wave_base).few();     // the queues are idle: [k] doubles of the first wave's region
+        for (int c = tid; c < k; c += blockDim.x) {
+            const int nc = U.n[c];
+            double fr = 0.0;
+            if (nc > 0) {
+                unsigned long long ss = 0;
+                for (int j = 0; j < d; ++j) {
+                    const long long sv = (long long)U.S[c * (DK + 1) + j] - (full_mode ? 1024ll * nc : 0ll);
+                    ss += (unsigned long long)(sv * sv);
+                }
+                const unsigned long long qc = ss / (unsigned long long)nc;
+                const unsigned long long rc = ss - qc * (unsigned long long)nc;
+                atomicAdd(&U.acc64[1], qc);
+                fr = (double)rc / (double)nc;
+            }
+            frac0[c] = fr;
+        }
+        __syncthreads();
+        if (tid == 0) {
+            double fsum = 0.0;
+            for (int c = 0; c < k; ++c) fsum = fsum + frac0[c];
+            loss = (double)(U.acc64[0] - U.acc64[1]) - fsum;
+        }
+    } else {
+        if (!traced_last) {
+            loss_slot = 0;
+            wave_loss(0);
+            __syncthreads();
+        }
+        if (tid == 0)
+            for (int w = 0; w < nwaves; ++w) loss = loss + U.red[loss_slot + w];
+    }
     if (a.trace && tid == 0) {
         // the passes that were not run would have seen the same labels and centroids
         for (int it = passes_run; it <= a.n_iter; ++it) a.trace[slot * (a.n_iter + 1) + it] = loss;
