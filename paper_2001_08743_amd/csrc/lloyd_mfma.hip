@@ -734,81 +734,64 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
     __syncthreads();
     update_centroids<DK>(U, k, KP, d, 0, true);
 
-    // ---- sum of |x|^2 over the task's rows, an integer (for the loss at a fixed point, see the end):
-    // per lane and tile at most 16 * 255^2 < 2^24, exact in fp32
+    // ---- centre the rows; on the way, the sum of |x|^2 over the task's rows as an integer (for the loss
+    // at a fixed point, see the end) and the squared norm of every centred row (for the error bound).
+    // Squares are summed two at a time into fp32 (v_dot2): the raw values are integers below 256, so
+    // a lane's sum per tile stays below 16 * 255^2 < 2^24 and is exact.
     {
-        unsigned q2 = 0;
+        typedef _Float16 half2v __attribute__((ext_vector_type(2)));
+        typedef unsigned uint4v __attribute__((ext_vector_type(4)));
+        auto sumsq = [](const half8 &v, float acc) {
+            const uint4v w = __builtin_bit_cast(uint4v, v);
 #pragma unroll
-        for (int nt = 0; nt < NTW; ++nt) {
-            const bool live = wave_live && (wave_row0 + nt * 32 + n32) < nrows;
-            float part = 0.0f;
-#pragma unroll
-            for (int f = 0; f < NS; ++f) {
-                half8 bv = B[nt][f];
-                asm volatile("" : "+v"(bv));      // (an opaque copy, as below)
-#pragma unroll
-                for (int i = 0; i < 8; ++i) {
-                    const float v = (float)bv[i];
-                    part = __builtin_fmaf(v, v, part);
-                }
+            for (int e = 0; e < 4; ++e) {
+                const unsigned we = w[e];
+                const half2v p = __builtin_bit_cast(half2v, we);
+                acc = __builtin_amdgcn_fdot2(p, p, acc, false);
             }
-            q2 += live ? (unsigned)part : 0u;
-        }
-        // the wave's total (at most 512 rows * 31 * 255^2 < 2^31) -> the unit's 64-bit sum
-#pragma unroll
-        for (int off = 32; off >= 1; off >>= 1) q2 += (unsigned)__shfl_xor((int)q2, off, 64);
-        if (lane_id == 0 && q2) atomicAdd(&U.acc64[0], (unsigned long long)q2);
-    }
-
-    // ---- centre the rows
-    {
-        float x2row[NTW];                // squared norm of this lane's row of every tile
+            return acc;
+        };
+        float x2row[NTW];                // squared norm of this lane's centred row of every tile
         half8 off8[NS];
+        uint4v keep[NS];                 // all ones in the halves of the knobs that exist
 #pragma unroll
-        for (int f = 0; f < NS; ++f)
+        for (int f = 0; f < NS; ++f) {
 #pragma unroll
             for (int i = 0; i < 8; ++i) off8[f][i] = (_Float16)U.ojf[16 * f + 8 * h + i];
 #pragma unroll
-        for (int nt = 0; nt < NTW; ++nt) {
-            const bool live = wave_live && (wave_row0 + nt * 32 + n32) < nrows;
-#pragma unroll
-            for (int f = 0; f < NS; ++f) {
-                half8 v = B[nt][f] - off8[f];
-#pragma unroll
-                for (int i = 0; i < 8; ++i)
-                    if (!live || 16 * f + 8 * h + i >= d) v[i] = (_Float16)0.0f;
-                B[nt][f] = v;
+            for (int e = 0; e < 4; ++e) {
+                const int j = 16 * f + 8 * h + 2 * e;
+                keep[f][e] = (j < d ? 0x0000FFFFu : 0u) | (j + 1 < d ? 0xFFFF0000u : 0u);
             }
         }
+        unsigned q2 = 0;
         float xmax = 0.0f;
 #pragma unroll
         for (int nt = 0; nt < NTW; ++nt) {
-            float part = 0.0f;
+            const bool live = wave_live && (wave_row0 + nt * 32 + n32) < nrows;
+            float raw = 0.0f, part = 0.0f;
 #pragma unroll
             for (int f = 0; f < NS; ++f) {
-                // an opaque copy: otherwise the compiler keeps these conversions (128 values) alive in
-                // scratch memory through the whole iteration for the loss computation at its end
-                half8 bv = B[nt][f];
-                asm volatile("" : "+v"(bv));
+                raw = sumsq(B[nt][f], raw);
+                const half8 c8 = B[nt][f] - off8[f];
+                uint4v w = __builtin_bit_cast(uint4v, c8) & keep[f];
 #pragma unroll
-                for (int i = 0; i < 8; ++i) {
-                    const float v = (float)bv[i];
-                    part = __builtin_fmaf(v, v, part);
-                }
+                for (int e = 0; e < 4; ++e) w[e] = live ? w[e] : 0u;
+                half8 cv = __builtin_bit_cast(half8, w);
+                part = sumsq(cv, part);
+                // the bias slot: a constant for every live row (after the norm, which excludes it)
+                if (f == bstep && live && h == bhalf) cv[belem] = (_Float16)kBiasScale;
+                B[nt][f] = cv;
             }
+            q2 += live ? (unsigned)raw : 0u;
             part = part + __shfl_xor(part, 32, 64);
             x2row[nt] = part;
             xmax = __builtin_fmaxf(xmax, part);
-            // the bias slot: a constant for every live row (after the norm, which excludes it)
-            const bool live = wave_live && (wave_row0 + nt * 32 + n32) < nrows;
-            if (live && h == bhalf) {
-#pragma unroll
-                for (int f = 0; f < NS; ++f)
-#pragma unroll
-                    for (int i = 0; i < 8; ++i)
-                        if (f == bstep && i == belem) B[nt][f][i] = (_Float16)kBiasScale;
-            }
         }
+        // the wave's sum of |x|^2 (at most 512 rows * 31 * 255^2 < 2^31) -> the unit's 64-bit sum
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) q2 += (unsigned)__shfl_xor((int)q2, off, 64);
+        if (lane_id == 0 && q2) atomicAdd(&U.acc64[0], (unsigned long long)q2);
         xmax = wave_max_nonneg(xmax);
         if (lane == 0) atomicMax(&U.stamp[1], __float_as_int(xmax));     // non-negative floats order like integers
         __syncthreads();
