@@ -23,7 +23,7 @@ namespace {
 
 constexpr int kTiles = 4;            // 32-row tiles a wave handles per step
 constexpr int kStreamRec = 32;       // queued rows whose knob values are kept in LDS
-constexpr int kWavesPerWg = 8;
+constexpr int kWavesPerWg = 4;
 constexpr int kPairCap = 128;        // (queued row, candidate centroid) pairs evaluated per step and wave
 constexpr float kPadScore = 1.0e30f; // score of a padding centroid row (real scores stay below 4 * 32 * 255^2)
 
@@ -271,7 +271,7 @@ struct StreamLds {
 };
 
 template <int DK>
-__global__ __launch_bounds__(512) void stream_assign_kernel(const StreamArgs a)
+__global__ __launch_bounds__(kWavesPerWg * 64, 2) void stream_assign_kernel(const StreamArgs a)
 {
     constexpr int NS = DK / 16, NS2 = 2 * NS;
     extern __shared__ __align__(16) unsigned char smem[];
