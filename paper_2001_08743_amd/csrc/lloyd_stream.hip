@@ -367,7 +367,10 @@ __global__ __launch_bounds__(kWavesPerWg * 64, 2) void stream_assign_kernel(cons
     StepRows nxt;
     if (r0 < r1) load_step(r0 + (int64_t)wave * kTiles * 32, nxt);    // under way during the set-up below
 
-    for (int e = tid; e < (kpu / 32) * 4 * 64; e += blockDim.x) L.afrag[e] = st.afrag[e];
+    for (int e = tid; e < (kpu / 32) * NS2 * 64; e += blockDim.x) {      // the NS2 slots in use of every m-tile
+        const int src = (e / (NS2 * 64)) * 4 * 64 + e % (NS2 * 64);
+        L.afrag[src] = st.afrag[src];
+    }
     for (int e = tid; e < kpu; e += blockDim.x) L.bias[e] = st.bias[e];
     for (int e = tid; e < k * DK; e += blockDim.x) L.S[e] = 0;
     for (int c = tid; c < k; c += blockDim.x) L.n[c] = 0;

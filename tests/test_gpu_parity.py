@@ -636,3 +636,40 @@ def test_bench_prints_one_json_line_with_the_contract_fields():
     assert rf["bound"] in ("hbm", "mfma", "alu") and rf["peak"] > 0 and abs(rf["frac"] - rf["achieved"] / rf["peak"]) < 1e-3
     cb = d["cpu_baseline"]
     assert cb["kind"] == "oracle" and cb["cores"] >= 1 and cb["value"] > 0 and cb["sample"]
+
+
+# ------------------------------------------------------------------ passes really run (stop at the fixed point)
+
+@pytest.mark.parametrize("flags", [0, binding.F_NO_MFMA, binding.F_STREAMING])
+def test_passes_run_and_results_of_the_shortened_iteration(flags):
+    """The resident kernels stop at the first pass that moves no row; K-means.run of Algorithm 1 with
+    its fixed number of steps is what they report.  Checked three ways: against the oracle (which
+    runs every pass), against the count of passes the library reports (below the nominal count on
+    data that converges, never above it, 0 for a unit with too few distinct rows, nominal on the
+    streaming path), and against a second run with just as many steps as the longest unit needed."""
+    import torch
+    wl = workloads.random_task(4242, n=2500, d=11, n_blobs=5, sigma=0.6, ks=(1, 2, 5, 9, 2400), n_iter=40,
+                               n_tasks=2, card_hi=20)
+    wl.ks = [1, 2, 5, 9, 64] if flags != binding.F_STREAMING else [1, 2, 5, 9, 200]
+    dw = binding.DeviceWorkload(wl)
+    out = binding.cham_kmeans_sweep(dw.X, dw.ld, dw.d, wl.task_off, wl.ks, wl.n_iter, want_labels=True, flags=flags)
+    torch.cuda.synchronize()
+    ref = oracle.sweep(wl.rows, wl.task_off, wl.ks, wl.n_iter, want_labels=True)
+    check_sweep(wl, out, ref, dw.ld)
+    passes = binding.cham_sweep_passes(out["workspace"], dw.ld, dw.d, wl.task_off, wl.ks, flags=flags).cpu().numpy()
+    status = out["status"].cpu().numpy()
+    assert passes.shape == status.shape
+    assert (passes[status != 0] == 0).all()
+    ok = passes[status == 0]
+    assert ok.min() >= 1 and ok.max() <= wl.n_iter + 1
+    if flags == binding.F_STREAMING:
+        assert (ok == wl.n_iter + 1).all()
+    else:
+        assert ok.min() < wl.n_iter + 1                    # k = 1 settles in its second pass
+        # as many update steps as the longest unit used reproduce every output
+        n_short = int(ok.max()) - 1
+        again = binding.cham_kmeans_sweep(dw.X, dw.ld, dw.d, wl.task_off, wl.ks, n_short, want_labels=True, flags=flags)
+        torch.cuda.synchronize()
+        for key in ("status", "counts", "centroids", "labels"):
+            assert torch.equal(again[key], out[key]), key
+        np.testing.assert_allclose(again["inertia"].cpu().numpy(), out["inertia"].cpu().numpy(), rtol=1e-12, atol=0)
