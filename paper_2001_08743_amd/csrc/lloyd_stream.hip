@@ -726,10 +726,22 @@ __global__ __launch_bounds__(kWavesPerWg * 64, 2) void stream_assign_kernel(cons
                 const int64_t row = wrow0 + sl;
                 if (row < r1) {
                     const int c = lab_new[sl];
+                    // all loads of the row first (they are independent), then the sum in knob order
+                    double mu[DK];
+                    uint8_t xv[DK];
+#pragma unroll
+                    for (int j = 0; j < DK; ++j) {
+                        const int jj = j < d ? j : 0;
+                        xv[j] = a.X[(int64_t)jj * a.ld + row];
+                        mu[j] = st.mu[(size_t)jj * kpm + c];
+                    }
                     double s = 0.0;
-                    for (int j = 0; j < d; ++j) {
-                        const double tq = (double)a.X[(int64_t)j * a.ld + row] - st.mu[(size_t)j * kpm + c];
-                        s = s + tq * tq;
+#pragma unroll
+                    for (int j = 0; j < DK; ++j) {
+                        if (j < d) {
+                            const double tq = (double)xv[j] - mu[j];
+                            s = s + tq * tq;
+                        }
                     }
                     part = part + s;
                 }
