@@ -139,8 +139,9 @@ def test_hash_rows_matches_host_hash():
 
 # ------------------------------------------------------------------ full benchmark sizes
 
-def test_cfg3_full_size():
-    _full(workloads.make_config(3, 0))
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_cfg3_full_size(seed):
+    _full(workloads.make_config(3, seed))
 
 
 def test_cfg4_full_size():
