@@ -263,6 +263,14 @@ def main():
                     nominal_evals_per_step=w_nom, evals_per_s=round(w_exec / (w_ms * 1e-3), 1),
                     frac_of_fp32_vector_peak=round(w_exec * (2 * ww.d + 2) / (w_ms * 1e-3) / 1e12
                                                    / PEAK_FP32_VECTOR_TFLOPS, 4))
+        # cardinalities of at most 2048: the harness promises values below 2048 and the sweep may run on the
+        # matrix cores (the library says which kernel it is)
+        w_promise = binding.F_VALUES_BELOW_2048 if int(ww.cards.max()) <= 2048 else 0
+        w_path = binding.cham_sweep_path_u16((ww.n_total + 63) // 64 * 64, ww.d, ww.task_off, ww.ks, flags=w_promise)
+        wide["kernel"] = binding.cham_sweep_path_kernel(w_path)
+        if w_path == 0:
+            wide["frac_of_f16_mfma_peak"] = round(w_exec * (2 * ww.d + 2) / (w_ms * 1e-3) / 1e12
+                                                  / PEAK_F16_MFMA_TFLOPS, 4)
 
     # The large single clustering (1 048 576 configurations x 16 knobs, k in {16..256}, 20 Lloyd steps):
     # tasks beyond one workgroup run the streaming matrix-core kernels.

@@ -70,6 +70,11 @@ extern "C" {
 #define CHAM_F_STREAMING     2   /* force the multi-workgroup-per-task path */
 #define CHAM_F_RESIDENT      4   /* force the one-workgroup-per-(task,k) path */
 #define CHAM_F_NO_MFMA       8   /* never use the matrix-core distance path */
+#define CHAM_F_VALUES_BELOW_2048 16  /* *_u16 sweeps: the caller promises that every knob value is below 2048 (as it
+                                        is whenever every cardinality is at most 2048); tasks of at most 2048 rows
+                                        with k <= 32 (4096 rows and k <= 64 up to 31 knobs) then run on the
+                                        matrix cores.  A value of 2048 or more found on the way gives status 4
+                                        for every (task, k) and zero outputs.  Ignored by the byte entry points. */
 
 int32_t     cham_version(void);
 const char *cham_strerror(int32_t code);
@@ -105,6 +110,7 @@ int64_t cham_sweep_workspace_bytes(int64_t ld, int32_t d, const int64_t *task_of
  *                                  final centroid (double terms, fixed summation tree)
  *   status    [T][n_k]     int32   0 ok; 1 = task has fewer than k distinct rows (init_mode 0):
  *                                  centroids, counts, loss and labels of that (t,k) are zero
+ *                                  (4: see CHAM_F_VALUES_BELOW_2048)
  *   labels    [n_k][ld]    uint8   final labels per k (optional, may be NULL)
  *   inertia_trace [T][n_k][n_iter+1] double  loss seen by every labelling pass (optional); a
  *                                  kernel that stops at the fixed point (see cham_sweep_passes)
@@ -340,9 +346,16 @@ int32_t cham_hash_rows(const uint8_t *rows, int64_t n, int32_t d, const uint64_t
  *     rows are uint16; 1 <= d <= 64; knob values up to 65535.
  *   - The sweep and the snap run one workgroup per (task, k) whatever the task size (built for
  *     tasks of up to some ten thousand rows; larger ones are correct but slow).  Cluster sums
- *     are 64-bit integers.  flags: CHAM_F_FORCE_EXACT is honoured, CHAM_F_RESIDENT and
- *     CHAM_F_NO_MFMA are accepted (they name what this path does anyway), CHAM_F_STREAMING
- *     gives CHAM_E_BAD_FLAG.
+ *     are 64-bit integers.  flags: CHAM_F_FORCE_EXACT is honoured, CHAM_F_RESIDENT is accepted
+ *     (it names what these paths do anyway), CHAM_F_STREAMING gives CHAM_E_BAD_FLAG.
+ *   - Without CHAM_F_VALUES_BELOW_2048 the sweep runs on the vector ALU.  With it (values below
+ *     2048 are exact in the f16 operands of the matrix cores; Sec. 3.3's k-means is the same
+ *     computation either way, and the results are the same bit for bit) the sweep runs the
+ *     matrix-core kernel when d <= 63 and either d <= 31, tasks have at most 4096 rows and
+ *     k <= 64, or tasks have at most 2048 rows and k <= 32; otherwise, and under
+ *     CHAM_F_FORCE_EXACT or CHAM_F_NO_MFMA, the flag changes nothing.  cham_sweep_path_u16 tells
+ *     which one a call runs.  The promise is checked on the device: a value of 2048 or more
+ *     makes every (task, k) of the call report status 4 with zero outputs.
  *   - k_max * (20 * dp + 20) + 4 * dp + 192 must not exceed 160 KiB, dp = d rounded up to a
  *     multiple of 8 (k_max up to 256 for d <= 24, 247 for d <= 32, 199 for d <= 40, 166 for
  *     d <= 48, 143 for d <= 56, 125 for d <= 64); beyond that: CHAM_E_BAD_K, also from the
@@ -355,6 +368,8 @@ int32_t cham_hash_rows(const uint8_t *rows, int64_t n, int32_t d, const uint64_t
  */
 int64_t cham_sweep_workspace_bytes_u16(int64_t ld, int32_t d, const int64_t *task_off, int32_t T,
                                        const int32_t *ks, int32_t n_k, int32_t n_iter, int32_t flags);
+int32_t cham_sweep_path_u16(int64_t ld, int32_t d, const int64_t *task_off, int32_t T,
+                            const int32_t *ks, int32_t n_k, int32_t flags);
 int32_t cham_kmeans_sweep_u16(const uint16_t *X, int64_t ld, int32_t d,
                               const int64_t *task_off, int32_t T,
                               const int32_t *ks, int32_t n_k,

@@ -16,6 +16,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libcham.so")
 
 F_FORCE_EXACT, F_STREAMING, F_RESIDENT, F_NO_MFMA = 1, 2, 4, 8
+F_VALUES_BELOW_2048 = 16
 OUT_EMPTY, OUT_KEPT, OUT_SYNTH, OUT_DROPPED = 0, 1, 2, 3
 
 EXPORTS = [
@@ -26,7 +27,7 @@ EXPORTS = [
     "cham_visited_table_clear", "cham_visited_table_insert_hashes", "cham_visited_table_insert_configs",
     "cham_update_configs", "cham_sweep_path", "cham_sweep_path_kernel", "cham_sweep_passes",
     "cham_static_init", "cham_kmeans_sweep_static",
-    "cham_sweep_workspace_bytes_u16", "cham_kmeans_sweep_u16", "cham_sweep_knee_workspace_bytes_u16",
+    "cham_sweep_workspace_bytes_u16", "cham_sweep_path_u16", "cham_kmeans_sweep_u16", "cham_sweep_knee_workspace_bytes_u16",
     "cham_kmeans_sweep_knee_u16", "cham_snap_workspace_bytes_u16", "cham_snap_centroids_u16",
     "cham_synth_workspace_bytes_u16", "cham_synthesize_u16", "cham_synthesize_table_u16",
     "cham_visited_table_insert_configs_u16", "cham_hash_config_u16", "cham_hash_rows_u16",
@@ -65,6 +66,8 @@ def load() -> C.CDLL:
                                           vp, vp, vp, vp, vp, vp, vp, i64, i32, vp]
         lib.cham_sweep_path.restype = i32
         lib.cham_sweep_path.argtypes = [i64, i32, vp, i32, vp, i32, i32]
+        lib.cham_sweep_path_u16.restype = i32
+        lib.cham_sweep_path_u16.argtypes = [i64, i32, vp, i32, vp, i32, i32]
         lib.cham_sweep_path_kernel.restype = C.c_char_p
         lib.cham_sweep_path_kernel.argtypes = [i32]
         lib.cham_sweep_passes.restype = i32
@@ -270,10 +273,15 @@ def cham_kmeans_sweep(X, ld: int, d: int, task_off, ks: Sequence[int], n_iter: i
     return out
 
 
-def cham_sweep_path(ld: int, d: int, task_off, ks, flags: int = 0) -> int:
+def cham_sweep_path(ld: int, d: int, task_off, ks, flags: int = 0, _sfx: str = "") -> int:
     to, k = _host_lists(task_off, ks)
-    return _check(load().cham_sweep_path(C.c_int64(ld), C.c_int32(d), _hp(to), C.c_int32(len(to) - 1), _hp(k),
-                                         C.c_int32(len(k)), C.c_int32(flags)))
+    return _check(getattr(load(), "cham_sweep_path" + _sfx)(C.c_int64(ld), C.c_int32(d), _hp(to),
+                                                            C.c_int32(len(to) - 1), _hp(k), C.c_int32(len(k)),
+                                                            C.c_int32(flags)))
+
+
+def cham_sweep_path_u16(ld: int, d: int, task_off, ks, flags: int = 0) -> int:
+    return cham_sweep_path(ld, d, task_off, ks, flags, _sfx="_u16")
 
 
 def cham_sweep_path_kernel(path: int) -> str:
@@ -540,7 +548,9 @@ class DeviceWorkload:
         if self.visited is None:
             self.build_visited()
         b = bufs or {}
-        sw = cham_kmeans_sweep(self.X, self.ld, self.d, wl.task_off, wl.ks, wl.n_iter, flags=flags,
+        # two-byte knobs: cardinalities of at most 2048 are the caller's promise of values below 2048
+        sweep_flags = flags | (F_VALUES_BELOW_2048 if self.sfx and int(np.max(wl.cards)) <= 2048 else 0)
+        sw = cham_kmeans_sweep(self.X, self.ld, self.d, wl.task_off, wl.ks, wl.n_iter, flags=sweep_flags,
                                want_labels=want_labels, want_trace=want_trace,
                                out=b.get("sweep"), workspace=b.get("sweep_ws"), _sfx=self.sfx)
         chosen = cham_select_k(sw["inertia"], sw["status"], thr, chosen=b.get("chosen"))

@@ -166,13 +166,22 @@ int32_t check_common(const void *X, int64_t ld, int32_t d, const int64_t *task_o
 
 constexpr int kStreamRowsPerWg = 4096;      // the smallest value of stream_rows_per_wg: bounds the workgroup count
 
+constexpr int kSweepFlags = CHAM_F_FORCE_EXACT | CHAM_F_STREAMING | CHAM_F_RESIDENT | CHAM_F_NO_MFMA | CHAM_F_VALUES_BELOW_2048;
+
 // Which kernel family runs the sweep.
 enum class SweepPath { kMfmaResident, kVectorResident, kStream };
 
-SweepPath choose_path(const Plan &pl, int d, int flags)
+SweepPath choose_path(const Plan &pl, int d, int flags, int xbytes = 1)
 {
     const bool exact = (flags & CHAM_F_FORCE_EXACT) != 0;
     const bool no_mfma = (flags & CHAM_F_NO_MFMA) != 0;
+    if (xbytes == 2) {
+        // two-byte knobs: the f16 rows of the matrix-core kernel hold integers below 2048 only, which the
+        // caller has to promise (the kernel checks); there is no streaming variant for them
+        const bool promised = (flags & CHAM_F_VALUES_BELOW_2048) != 0;
+        if (promised && !exact && !no_mfma && mfma_path_fits_u16(d, pl.kmax, pl.n_max)) return SweepPath::kMfmaResident;
+        return SweepPath::kVectorResident;
+    }
     if (exact || no_mfma || d > 31) return SweepPath::kVectorResident;
     if (flags & CHAM_F_STREAMING) return SweepPath::kStream;
     if (mfma_path_fits(d, pl.kmax, pl.n_max)) return SweepPath::kMfmaResident;
@@ -187,8 +196,9 @@ struct SweepWs {
     int kpm = 0, n_units = 0, total_wgs = 0;
 };
 
+// xh_halfs: f16 values per row of the packed copy of the rows (0: the path needs none).
 SweepWs sweep_ws(const Plan &pl, int64_t ld, bool own_labels, bool stream, const int64_t *task_off,
-                 bool need_xh = true)
+                 int xh_halfs = 32)
 {
     SweepWs w;
     int64_t o = 0;
@@ -201,9 +211,9 @@ SweepWs sweep_ws(const Plan &pl, int64_t ld, bool own_labels, bool stream, const
     w.passes = o;
     o += up((int64_t)pl.T * pl.n_k * 4);
     w.counters = o;                                   // one work counter per launch of a chunked sweep
-    o += up((int64_t)pl.n_k * 4);
+    o += up(((int64_t)pl.n_k + 1) * 4);               // (+ the flag of a two-byte value too large for the f16 rows)
     w.xh = o;
-    if (need_xh) o += up(ld * 32 * 2);
+    o += up(ld * xh_halfs * 2);
     w.labbuf = o;
     if (own_labels) o += up((int64_t)pl.n_k * ld);
     if (stream) {
@@ -269,7 +279,11 @@ static int64_t sweep_ws_bytes(int xbytes, int64_t ld, int32_t d, const int64_t *
     if (no_heap) pl.blob.forbid_heap();
     const int32_t rc = check_common(nullptr, ld, d, task_off, T, ks, n_k, false, pl, xbytes);
     if (rc != CHAM_OK) return rc;
-    if (xbytes == 2) return u16_fits(pl) ? sweep_ws(pl, ld, true, false, task_off, false).total : CHAM_E_BAD_K;
+    if (xbytes == 2) {
+        if (choose_path(pl, d, flags, 2) == SweepPath::kMfmaResident)
+            return sweep_ws(pl, ld, true, false, task_off, d <= 31 ? 32 : 64).total;
+        return u16_fits(pl) ? sweep_ws(pl, ld, true, false, task_off, 0).total : CHAM_E_BAD_K;
+    }
     return sweep_ws(pl, ld, true, choose_path(pl, d, flags) == SweepPath::kStream, task_off).total;
 }
 
@@ -305,11 +319,12 @@ static int32_t sweep_impl(const void *Xv, int xbytes, int64_t ld, int32_t d, con
     if (n_iter < 0) return CHAM_E_BAD_DIM;
     if (init_mode != 0 && init_mode != 1) return CHAM_E_BAD_FLAG;
     if (init_mode == 1 && !init_centroids) return CHAM_E_NULL;
-    if (flags & ~(CHAM_F_FORCE_EXACT | CHAM_F_STREAMING | CHAM_F_RESIDENT | CHAM_F_NO_MFMA)) return CHAM_E_BAD_FLAG;
+    if (flags & ~kSweepFlags) return CHAM_E_BAD_FLAG;
     if (xbytes == 2 && (flags & CHAM_F_STREAMING)) return CHAM_E_BAD_FLAG;
-    if (xbytes == 2 && !u16_fits(pl)) return CHAM_E_BAD_K;
-    const SweepPath path = xbytes == 2 ? SweepPath::kVectorResident : choose_path(pl, d, flags);
-    const SweepWs w = sweep_ws(pl, ld, labels == nullptr, path == SweepPath::kStream, task_off, xbytes == 1);
+    const SweepPath path = choose_path(pl, d, flags, xbytes);
+    if (xbytes == 2 && path == SweepPath::kVectorResident && !u16_fits(pl)) return CHAM_E_BAD_K;
+    const int xh_halfs = xbytes == 1 ? 32 : (path == SweepPath::kMfmaResident ? (d <= 31 ? 32 : 64) : 0);
+    const SweepWs w = sweep_ws(pl, ld, labels == nullptr, path == SweepPath::kStream, task_off, xh_halfs);
     const bool chunked = chunk > 0;
     const int64_t done_bytes = chunked ? up((int64_t)T * 4) : 0;
     if (!workspace || workspace_bytes < w.total + done_bytes) return CHAM_E_WORKSPACE;
@@ -347,6 +362,7 @@ static int32_t sweep_impl(const void *Xv, int xbytes, int64_t ld, int32_t d, con
     a.xh = reinterpret_cast<uint16_t *>(ws + w.xh);
     a.passes = reinterpret_cast<int *>(ws + w.passes);
     a.queue_lds_off = 0;
+    a.too_large = (xbytes == 2 && path == SweepPath::kMfmaResident) ? reinterpret_cast<int *>(ws + w.counters) + n_k : nullptr;
     a.ki_begin = 0;
     a.ki_end = n_k;
     a.done = nullptr;
@@ -360,7 +376,7 @@ static int32_t sweep_impl(const void *Xv, int xbytes, int64_t ld, int32_t d, con
     e = launch_fill_i32(a.passes, (int64_t)T * n_k, n_iter + 1, s);
     if (e != hipSuccess) return hip_fail(e);
     // work counters of the launches (the matrix-core resident kernel hands out its units through one)
-    e = launch_fill_i32(reinterpret_cast<int *>(ws + w.counters), n_k, 0, s);
+    e = launch_fill_i32(reinterpret_cast<int *>(ws + w.counters), n_k + 1, 0, s);
     if (e != hipSuccess) return hip_fail(e);
     if (init_mode == 0) {
         e = launch_first_distinct(a, reinterpret_cast<int *>(ws + w.init_rows),
@@ -505,7 +521,7 @@ int32_t cham_kmeans_sweep_static(const uint8_t *X, int64_t ld, int32_t d, const 
     const int64_t need = sweep_ws_bytes(1, ld, d, task_off, T, ks, n_k, flags, true);
     if (need == CHAM_E_NOMEM) return CHAM_E_TOO_LARGE;      // tables beyond the part kept on the stack
     if (need < 0) return (int32_t)need;
-    if (flags & ~(CHAM_F_FORCE_EXACT | CHAM_F_STREAMING | CHAM_F_RESIDENT | CHAM_F_NO_MFMA)) return CHAM_E_BAD_FLAG;
+    if (flags & ~kSweepFlags) return CHAM_E_BAD_FLAG;
     if (need > kStaticScratchBytes) return CHAM_E_TOO_LARGE;
     void *ws = nullptr;
     int32_t rc = static_scratch_address(&ws);
@@ -526,18 +542,31 @@ int32_t cham_kmeans_sweep_u16(const uint16_t *X, int64_t ld, int32_t d, const in
                       status, labels, inertia_trace, workspace, workspace_bytes, flags, stream, 0, 0.0, nullptr);
 }
 
+static int32_t sweep_path_impl(int xbytes, int64_t ld, int32_t d, const int64_t *task_off, int32_t T,
+                              const int32_t *ks, int32_t n_k, int32_t flags)
+{
+    Plan pl;
+    const int32_t rc = check_common(nullptr, ld, d, task_off, T, ks, n_k, false, pl, xbytes);
+    if (rc != CHAM_OK) return rc;
+    if (flags & ~kSweepFlags) return CHAM_E_BAD_FLAG;
+    if (xbytes == 2 && (flags & CHAM_F_STREAMING)) return CHAM_E_BAD_FLAG;
+    switch (choose_path(pl, d, flags, xbytes)) {
+    case SweepPath::kMfmaResident: return CHAM_PATH_RESIDENT_MFMA;
+    case SweepPath::kStream: return CHAM_PATH_STREAM_MFMA;
+    default: return (xbytes == 2 && !u16_fits(pl)) ? CHAM_E_BAD_K : CHAM_PATH_RESIDENT_VECTOR;
+    }
+}
+
 int32_t cham_sweep_path(int64_t ld, int32_t d, const int64_t *task_off, int32_t T, const int32_t *ks, int32_t n_k,
                         int32_t flags)
 {
-    Plan pl;
-    const int32_t rc = check_common(nullptr, ld, d, task_off, T, ks, n_k, false, pl, 1);
-    if (rc != CHAM_OK) return rc;
-    if (flags & ~(CHAM_F_FORCE_EXACT | CHAM_F_STREAMING | CHAM_F_RESIDENT | CHAM_F_NO_MFMA)) return CHAM_E_BAD_FLAG;
-    switch (choose_path(pl, d, flags)) {
-    case SweepPath::kMfmaResident: return CHAM_PATH_RESIDENT_MFMA;
-    case SweepPath::kStream: return CHAM_PATH_STREAM_MFMA;
-    default: return CHAM_PATH_RESIDENT_VECTOR;
-    }
+    return sweep_path_impl(1, ld, d, task_off, T, ks, n_k, flags);
+}
+
+int32_t cham_sweep_path_u16(int64_t ld, int32_t d, const int64_t *task_off, int32_t T, const int32_t *ks,
+                            int32_t n_k, int32_t flags)
+{
+    return sweep_path_impl(2, ld, d, task_off, T, ks, n_k, flags);
 }
 
 const char *cham_sweep_path_kernel(int32_t path)
@@ -559,7 +588,7 @@ int32_t cham_sweep_passes(const void *workspace, int64_t workspace_bytes, int64_
     if (rc != CHAM_OK) return rc;
     if (!passes) return CHAM_E_NULL;
     // the region sits before every part of the workspace whose size depends on the path or the knob width
-    const SweepWs w = sweep_ws(pl, ld, false, false, task_off, false);
+    const SweepWs w = sweep_ws(pl, ld, false, false, task_off, 0);
     if (!workspace || workspace_bytes < w.passes + (int64_t)T * n_k * 4) return CHAM_E_WORKSPACE;
     (void)flags;
     hipError_t e = hipMemcpyAsync(passes, static_cast<const unsigned char *>(workspace) + w.passes,
@@ -707,7 +736,7 @@ static int32_t snap_impl(const void *Xv, int xbytes, int64_t ld, int32_t d, cons
     int32_t rc = check_common(X, ld, d, task_off, T, ks, n_k, true, pl, xbytes);
     if (rc != CHAM_OK) return rc;
     if (!chosen_idx || !centroids || !labels_sel || !pick_row || !pick_cfg) return CHAM_E_NULL;
-    if (flags & ~(CHAM_F_FORCE_EXACT | CHAM_F_STREAMING | CHAM_F_RESIDENT | CHAM_F_NO_MFMA)) return CHAM_E_BAD_FLAG;
+    if (flags & ~kSweepFlags) return CHAM_E_BAD_FLAG;
     if (xbytes == 2 && resident_lds_bytes(pl.DP, pl.kmax) > 160 * 1024) return CHAM_E_BAD_K;
     const bool wide = xbytes == 1 && wide_tasks(pl);
     const int64_t blob_bytes = up((int64_t)pl.blob.size() * 8);

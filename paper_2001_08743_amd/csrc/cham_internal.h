@@ -32,6 +32,7 @@ struct SweepArgs {
     double *trace;                 // [T][n_k][n_iter+1] or null
     uint16_t *xh;                  // [ld][16 or 32] f16 row-major copy of X (matrix-core path)
     int *passes;                   // [T][n_k] labelling passes actually run (preset to n_iter + 1 by the host code)
+    int *too_large;                // matrix-core kernels, two-byte knobs: set by the packing kernel when a value is 2048 or more (null: byte knobs)
     int queue_lds_off;             // vector kernel: LDS offset of the per-wave queues of moved rows, 0 = no room for them
     int *unit_counter;             // zeroed before the launch: next unit to hand out (matrix-core resident kernel)
     int ki_begin, ki_end;          // this launch runs ks[ki_begin .. ki_end) (the whole list by default)
@@ -164,6 +165,7 @@ hipError_t launch_resident_sweep(const SweepArgs &a, int nt, hipStream_t s);
 int resident_dp16(int d);      // padded knob count the two-byte kernels use for d knobs
 // Matrix-core resident kernel: usable when every task has at most 4096 rows and k <= 64.
 bool mfma_path_fits(int d, int kmax, int64_t n_max);
+bool mfma_path_fits_u16(int d, int kmax, int64_t n_max);
 hipError_t launch_mfma_sweep(const SweepArgs &a, int64_t n_max, int64_t n_total, hipStream_t s);
 int64_t stream_lds_bytes(int d, int kpm);
 hipError_t launch_stream_sweep(const StreamArgs &a, int64_t n_total, int total_wgs, hipStream_t s);

@@ -38,10 +38,11 @@ namespace cham {
 namespace {
 
 // Cross-lane exchanges done in the vector ALU (DPP), no LDS round trip.
-// xor_lanes<1|2|4>: the value held by lane ^ 1, 2 or 4.
+// xor_lanes<1|2|4|8>: the value held by lane ^ 1, 2, 4 or 8.
 template <int XOR>
 __device__ __forceinline__ int dpp_xor_i32(int v)
 {
+    if (XOR == 8) return __builtin_amdgcn_update_dpp(0, v, 0x128, 0xF, 0xF, false);     // row_ror:8 = lane ^ 8 within a row of 16
     if (XOR == 1) return __builtin_amdgcn_update_dpp(0, v, 0xB1, 0xF, 0xF, false);      // quad_perm [1,0,3,2]
     if (XOR == 2) return __builtin_amdgcn_update_dpp(0, v, 0x4E, 0xF, 0xF, false);      // quad_perm [2,3,0,1]
     // lane ^ 4 = mirror within each group of eight lanes, then reverse within each quad
@@ -339,31 +340,39 @@ template <int DK>
 __device__ __forceinline__ void resolve_queue(const WaveQueue<DK> &Q, int nrec, const double *mu64T,
                                               const float *ojf, int KP, int k, int d)
 {
-    if (nrec <= 8) {
-        resolve_few<DK>(Q, nrec, mu64T, ojf, KP, k, d);
-    } else {
-        resolve_rows<DK>(Q, nrec, mu64T, ojf, KP, k, d);
+    if constexpr (DK <= 32) {
+        if (nrec <= 8) {
+            resolve_few<DK>(Q, nrec, mu64T, ojf, KP, k, d);
+            return;
+        }
     }
+    resolve_rows<DK>(Q, nrec, mu64T, ojf, KP, k, d);
 }
 
 // Row-major f16 copy of X (one row = DK halfs, padded knobs zero): a lane fetches the eight knobs
 // of a B fragment with one 16-byte load.
-template <int DK>
-__global__ void pack_rows_kernel(const uint8_t *__restrict__ X, int64_t ld, int d, int64_t n_rows,
-                                 _Float16 *__restrict__ xh)
+// Two-byte knobs take this path only when every value is below 2048 (integers up to 2048 are
+// exact in f16): a larger value sets *too_large, which makes the sweep kernel report status 4.
+template <int DK, typename XT>
+__global__ void pack_rows_kernel(const XT *__restrict__ X, int64_t ld, int d, int64_t n_rows,
+                                 _Float16 *__restrict__ xh, int *too_large)
 {
     const int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (r >= n_rows) return;
+    unsigned top = 0;
 #pragma unroll
     for (int g = 0; g < DK / 8; ++g) {
         half8 v;
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
             const int j = 8 * g + i;
-            v[i] = j < d ? (_Float16)(float)X[(int64_t)j * ld + r] : (_Float16)0.0f;
+            const unsigned xv = j < d ? (unsigned)X[(int64_t)j * ld + r] : 0u;
+            top = xv > top ? xv : top;
+            v[i] = (_Float16)(float)xv;
         }
         *reinterpret_cast<half8 *>(xh + r * DK + 8 * g) = v;
     }
+    if (sizeof(XT) == 2 && top >= 2048u) *too_large = 1;
 }
 
 // Apply queued label changes of this wave to the integer sums and counts: 256 / DK queued rows
@@ -522,7 +531,7 @@ __device__ __forceinline__ void full_sums(const WaveQueue<DK> &Q, int *S, int *n
 // full_sums for every cluster (each still raised by 1024 n): every cluster is updated, and the sums
 // are left either corrected (the next pass applies label changes to them) or, with zero_after,
 // cleared together with the sizes (the next pass rebuilds them).
-template <int DK>
+template <int DK, bool BYTE_KNOBS = true>
 __device__ __forceinline__ void update_centroids(const MfmaLds<DK> &U, int k, int KP, int d, int stamp, bool all,
                                                  bool raw = false, bool zero_after = false)
 {
@@ -560,9 +569,13 @@ __device__ __forceinline__ void update_centroids(const MfmaLds<DK> &U, int k, in
                         U.S[c * (DK + 1) + j] = sv;
                     }
                     const double sd = (double)sv;
-                    const double q0 = sd * rn;
-                    const double rem = __builtin_fma(-q0, dn, sd);
-                    mu = __builtin_fma(rem, rn, q0);
+                    if (BYTE_KNOBS) {
+                        const double q0 = sd * rn;
+                        const double rem = __builtin_fma(-q0, dn, sd);
+                        mu = __builtin_fma(rem, rn, q0);
+                    } else {
+                        mu = sd / dn;             // (sums of two-byte knobs lie outside the checked domain)
+                    }
                     U.mu64T[(size_t)j * KP + c] = mu;
                 }
                 const double m = j < d ? mu - (double)U.ojf[j] : 0.0;
@@ -575,7 +588,8 @@ __device__ __forceinline__ void update_centroids(const MfmaLds<DK> &U, int k, in
         }
         b = b + dpp_xor_f64<1>(b);
         b = b + dpp_xor_f64<2>(b);
-        if (QN == 8) b = b + dpp_xor_f64<4>(b);
+        if (QN >= 8) b = b + dpp_xor_f64<4>(b);
+        if (QN == 16) b = b + dpp_xor_f64<8>(b);
         if (act && (4 * q < d || q == QN - 1)) {
             if (q == QN - 1) {
                 const float bs = (float)b * (1.0f / kBiasScale);
@@ -604,10 +618,14 @@ __device__ __forceinline__ void update_centroids(const MfmaLds<DK> &U, int k, in
 
 // Everything one workgroup does for its unit.  Units with more than 32 centroids use two 32-row
 // m-tiles per row tile; otherwise the two accumulators alternate between row tiles.
-template <int DK, int NTW>
+template <int DK, int NTW, typename XT>
 __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem, int ki, int t, int k)
 {
-    const bool two = k > 32;
+    constexpr bool kByteKnobs = sizeof(XT) == 1;
+    constexpr double kMaxValue = kByteKnobs ? 255.0 : 2047.0;
+    constexpr bool kAllowTwo = DK <= 32;     // 64-wide rows leave no registers for a second m-tile: k <= 32 there
+    const XT *X = reinterpret_cast<const XT *>(a.X);
+    const bool two = kAllowTwo && k > 32;
     constexpr int NS = DK / 16;          // distinct B fragments per row
     constexpr int NS2 = 2 * NS;          // chained instructions per 32x32 tile
     constexpr int CH = 16 / NS2;         // scores handled between two matrix instructions
@@ -702,7 +720,7 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
         double v;
         if (a.init_mode == 0) {
             const int row = a.init_rows[(int64_t)t * a.kmax + c];
-            v = (double)a.X[(int64_t)j * a.ld + r0 + row];
+            v = (double)X[(int64_t)j * a.ld + r0 + row];
         } else {
             v = a.init_centroids[(crow + c) * d + j];
         }
@@ -724,7 +742,7 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
                 float o = 0.0f;
                 if (j < d) {
                     double m = rint(s / (double)k);
-                    m = m < 0.0 ? 0.0 : (m > 255.0 ? 255.0 : m);
+                    m = m < 0.0 ? 0.0 : (m > kMaxValue ? kMaxValue : m);
                     o = (float)m;
                 }
                 U.ojf[j] = o;
@@ -732,7 +750,7 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
         }
     }
     __syncthreads();
-    update_centroids<DK>(U, k, KP, d, 0, true);
+    update_centroids<DK, kByteKnobs>(U, k, KP, d, 0, true);
 
     // ---- centre the rows; on the way, the sum of |x|^2 over the task's rows as an integer (for the loss
     // at a fixed point, see the end) and the squared norm of every centred row (for the error bound).
@@ -772,7 +790,7 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
             float raw = 0.0f, part = 0.0f;
 #pragma unroll
             for (int f = 0; f < NS; ++f) {
-                raw = sumsq(B[nt][f], raw);
+                if (kByteKnobs) raw = sumsq(B[nt][f], raw);
                 const half8 c8 = B[nt][f] - off8[f];
                 uint4v w = __builtin_bit_cast(uint4v, c8) & keep[f];
 #pragma unroll
@@ -783,7 +801,7 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
                 if (f == bstep && live && h == bhalf) cv[belem] = (_Float16)kBiasScale;
                 B[nt][f] = cv;
             }
-            q2 += live ? (unsigned)raw : 0u;
+            if (kByteKnobs) q2 += live ? (unsigned)raw : 0u;
             part = part + __shfl_xor(part, 32, 64);
             x2row[nt] = part;
             xmax = __builtin_fmaxf(xmax, part);
@@ -816,7 +834,8 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
     // A pass after one that moved many rows rebuilds the sums from the labels on the matrix cores
     // instead of applying the changes one by one; the first pass (every row is new) always does.
     const uint8_t *xw = a.X + r0 + (wave_live ? wave_row0 : 0);
-    const bool x_aligned = ((reinterpret_cast<uintptr_t>(a.X) | (uintptr_t)a.ld | (uintptr_t)r0) & 15) == 0 &&
+    const bool x_aligned = kByteKnobs &&                              // (the rebuild reads the byte matrix)
+                           ((reinterpret_cast<uintptr_t>(a.X) | (uintptr_t)a.ld | (uintptr_t)r0) & 15) == 0 &&
                            r0 + ((nrows + 63) & ~63) <= a.ld;       // ... and its last group of 64 rows lies inside the matrix
     bool full_mode = x_aligned;
     const int full_above = nrows / kFullDivisor;      // changed rows of a pass above which the next one rebuilds
@@ -969,7 +988,7 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
             // bound and remembered mask of the tile under way; those of the next tile are fetched a tile ahead
             float eb_cur = Q.eb()[n32];
             uint32_t seen_cur = Q.seen()[lane];
-            if (two) {
+            if (kAllowTwo && two) {
                 // accA = centroids 0..31 (all sixteen registers live), accB = centroids 32..k-1 of the current tile
 #pragma unroll
                 for (int s = 0; s < NS2; ++s) mma(accA, A0, B[0], s);
@@ -1167,7 +1186,7 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
         if (last_pass || rows_changed == 0) break;
         if (tid == 0) U.stamp[2 + ((it + 1) & 1)] = 0;      // the next pass counts from zero (nobody adds before the barrier below)
         const bool full_next = x_aligned && rows_changed > full_above;
-        update_centroids<DK>(U, k, KP, d, it, false, full_mode, full_next);
+        update_centroids<DK, kByteKnobs>(U, k, KP, d, it, false, full_mode, full_next);
         full_mode = full_next;
         __syncthreads();
     }
@@ -1182,7 +1201,7 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
     // the loss of the final labels: the per-wave sums of the last traced pass are still in place
     int loss_slot = ((passes_run - 1) & 1) * 8;
     double loss = 0.0;
-    if (!traced_last && at_fixed_point) {
+    if (kByteKnobs && !traced_last && at_fixed_point) {
         // At a fixed point every non-empty centroid is the mean S / n of its cluster, so the loss is
         // sum_rows |x|^2 - sum_c |S_c|^2 / n_c, all integers but the last division: with
         // |S_c|^2 = q_c n_c + r_c it is the integer (sum |x|^2 - sum q_c) minus the sum of the fractions
@@ -1240,7 +1259,7 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
 // Persistent workgroups (one per compute unit) take units from a counter until none is left: the
 // next unit starts as soon as the last one ends, without a new dispatch of a workgroup of this size.
 // Units are handed out in descending-k order so that the longest ones start first.
-template <int DK, int NTW>
+template <int DK, int NTW, typename XT>
 __global__ __launch_bounds__(512) void resident_mfma_kernel(const SweepArgs a)
 {
     extern __shared__ __align__(16) unsigned char smem[];
@@ -1261,9 +1280,10 @@ __global__ __launch_bounds__(512) void resident_mfma_kernel(const SweepArgs a)
         const int t = u % a.T;
         const int k = a.ks[ki];
         const bool skipped = a.done && a.done[t];     // the task's sweep stopped at a smaller k
+        const bool too_large = a.too_large && *a.too_large != 0;     // a two-byte value the f16 rows cannot hold
 
-        if (skipped || (a.init_mode == 0 && a.ndist[t] < k)) {
-            // fewer than k distinct rows, or not needed any more: all outputs zero, status says which
+        if (skipped || too_large || (a.init_mode == 0 && a.ndist[t] < k)) {
+            // fewer than k distinct rows, not needed any more, or unusable input: all outputs zero, status says which
             const int d = a.d;
             const int64_t r0 = a.task_off[t], r1 = a.task_off[t + 1];
             const int64_t slot = (int64_t)t * a.n_k + ki;
@@ -1273,25 +1293,29 @@ __global__ __launch_bounds__(512) void resident_mfma_kernel(const SweepArgs a)
             for (int c = tid; c < k; c += blockDim.x) a.counts[crow + c] = 0;
             for (int64_t r = r0 + tid; r < r1; r += blockDim.x) labrow[r] = 0;
             if (tid == 0) {
-                a.status[slot] = skipped ? 3 : 1;
+                a.status[slot] = too_large ? 4 : (skipped ? 3 : 1);
                 a.passes[slot] = 0;
                 a.inertia[slot] = 0.0;
             }
             if (a.trace)
                 for (int e = tid; e <= a.n_iter; e += blockDim.x) a.trace[slot * (a.n_iter + 1) + e] = 0.0;
         } else {
-            run_unit<DK, NTW>(a, smem, ki, t, k);
+            run_unit<DK, NTW, XT>(a, smem, ki, t, k);
         }
         if (tid == 0) next_unit = after;            // (read by everyone after the barrier at the loop's head)
     }
 }
 
-template <int DK, int NTW>
-hipError_t launch_mfma_t(const SweepArgs &a, int nwaves, hipStream_t s)
+template <int DK, int NTW, typename XT>
+hipError_t launch_mfma_t(const SweepArgs &a, int nwaves, int64_t n_total, hipStream_t s)
 {
+    const unsigned pb = (unsigned)((n_total + 255) / 256);
+    if (pb && a.ki_begin == 0)
+        hipLaunchKernelGGL((pack_rows_kernel<DK, XT>), dim3(pb), dim3(256), 0, s, reinterpret_cast<const XT *>(a.X), a.ld, a.d,
+                           n_total, reinterpret_cast<_Float16 *>(a.xh), a.too_large);
     const int KP = a.kmax > 32 ? 64 : 32;
     const size_t lds = MfmaLds<DK>::bytes(KP, nwaves, NTW);
-    auto kern = resident_mfma_kernel<DK, NTW>;
+    auto kern = resident_mfma_kernel<DK, NTW, XT>;
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return e;
@@ -1314,28 +1338,38 @@ hipError_t launch_mfma_t(const SweepArgs &a, int nwaves, hipStream_t s)
 
 }  // namespace
 
-// One knob slot stays free for the bias, so d <= 31.
+// One knob slot stays free for the bias.  Byte knobs: d <= 31, k <= 64, tasks of at most 4096 rows.
 bool mfma_path_fits(int d, int kmax, int64_t n_max)
 {
     return d >= 1 && d <= 31 && kmax <= 64 && n_max <= 4096;
 }
 
-// The packed row copy is made by the launch that starts at the first k (chunked sweeps reuse it).
-hipError_t launch_mfma_sweep(const SweepArgs &a, int64_t n_max, int64_t n_total, hipStream_t s)
+// Two-byte knobs whose values the caller promises to be below 2048: the same limits up to 31 knobs;
+// up to 63 knobs in 64-wide rows, which leave registers for 2048 rows and one tile of 32 centroids.
+bool mfma_path_fits_u16(int d, int kmax, int64_t n_max)
 {
-    const int ntw = n_max <= 1024 ? 4 : 16;
+    if (mfma_path_fits(d, kmax, n_max)) return true;
+    return d >= 1 && d <= 63 && kmax <= 32 && n_max <= 2048;
+}
+
+template <typename XT>
+static hipError_t launch_mfma_sweep_t(const SweepArgs &a, int64_t n_max, int64_t n_total, hipStream_t s)
+{
+    const int DK = a.d <= 15 ? 16 : (a.d <= 31 ? 32 : 64);
+    const int ntw = n_max <= 1024 ? 4 : (DK == 64 ? 8 : 16);
     int nwaves = (int)((n_max + 32 * ntw - 1) / (32 * ntw));
     if (nwaves < 1) nwaves = 1;
     if (nwaves > 8) nwaves = 8;
-    const unsigned pb = (unsigned)((n_total + 255) / 256);
-    if (a.d <= 15) {
-        if (pb && a.ki_begin == 0) hipLaunchKernelGGL(pack_rows_kernel<16>, dim3(pb), dim3(256), 0, s, a.X, a.ld, a.d, n_total,
-                                   reinterpret_cast<_Float16 *>(a.xh));
-        return ntw == 4 ? launch_mfma_t<16, 4>(a, nwaves, s) : launch_mfma_t<16, 16>(a, nwaves, s);
-    }
-    if (pb && a.ki_begin == 0) hipLaunchKernelGGL(pack_rows_kernel<32>, dim3(pb), dim3(256), 0, s, a.X, a.ld, a.d, n_total,
-                               reinterpret_cast<_Float16 *>(a.xh));
-    return ntw == 4 ? launch_mfma_t<32, 4>(a, nwaves, s) : launch_mfma_t<32, 16>(a, nwaves, s);
+    if (DK == 16) return ntw == 4 ? launch_mfma_t<16, 4, XT>(a, nwaves, n_total, s) : launch_mfma_t<16, 16, XT>(a, nwaves, n_total, s);
+    if (DK == 32) return ntw == 4 ? launch_mfma_t<32, 4, XT>(a, nwaves, n_total, s) : launch_mfma_t<32, 16, XT>(a, nwaves, n_total, s);
+    if (sizeof(XT) == 1) return hipErrorInvalidValue;        // (byte knobs never come with more than 32 knobs)
+    return ntw == 4 ? launch_mfma_t<64, 4, uint16_t>(a, nwaves, n_total, s) : launch_mfma_t<64, 8, uint16_t>(a, nwaves, n_total, s);
+}
+
+hipError_t launch_mfma_sweep(const SweepArgs &a, int64_t n_max, int64_t n_total, hipStream_t s)
+{
+    if (a.xbytes == 2) return launch_mfma_sweep_t<uint16_t>(a, n_max, n_total, s);
+    return launch_mfma_sweep_t<uint8_t>(a, n_max, n_total, s);
 }
 
 }  // namespace cham

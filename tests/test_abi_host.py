@@ -189,6 +189,38 @@ def test_sweep_path_query(lib):
         binding.cham_sweep_path(4096, 24, [0, 4096], [3, 2])
 
 
+def test_sweep_path_query_for_two_byte_knobs(lib):
+    """Sweeps over two-byte knobs run on the vector ALU unless the caller promises values below 2048 and the
+    matrix-core kernel's limits hold: d <= 63, and (d <= 31, 4096 rows, k <= 64) or (2048 rows, k <= 32)."""
+    P = binding.F_VALUES_BELOW_2048
+    ks64, ks32 = list(range(1, 65)), list(range(1, 33))
+    path = binding.cham_sweep_path_u16
+    assert path(2048, 40, [0, 2048], ks32) == 2                                # no promise
+    assert path(2048, 40, [0, 2048], ks32, flags=P) == 0
+    assert path(2048, 63, [0, 2048], ks32, flags=P) == 0
+    assert path(2048, 64, [0, 2048], ks32, flags=P) == 2                       # no room for the spare slot
+    assert path(2048, 40, [0, 2048], ks32 + [33], flags=P) == 2                # k above 32 with more than 31 knobs
+    assert path(2112, 40, [0, 2049], ks32, flags=P) == 2                       # task above 2048 rows
+    assert path(4096, 31, [0, 4096], ks64, flags=P) == 0
+    assert path(4096, 32, [0, 4096], ks64, flags=P) == 2
+    assert path(4160, 31, [0, 4097], ks64, flags=P) == 2
+    assert path(4096, 16, [0, 4096], [16, 128], flags=P) == 2
+    assert path(2048, 40, [0, 2048], ks32, flags=P | binding.F_NO_MFMA) == 2
+    assert path(2048, 40, [0, 2048], ks32, flags=P | binding.F_FORCE_EXACT) == 2
+    with pytest.raises(binding.ChamError):
+        path(2048, 40, [0, 2048], ks32, flags=binding.F_STREAMING)
+    with pytest.raises(binding.ChamError):
+        path(2048, 64, [0, 2048], [126], flags=P)                               # beyond the vector kernel's LDS
+    # the workspace of the promised path holds the f16 copy of the rows: 64 halves a row above 31 knobs, 32 below
+    w0 = binding.cham_sweep_workspace_bytes_u16(2048, 40, [0, 2048], ks32, 10)
+    w1 = binding.cham_sweep_workspace_bytes_u16(2048, 40, [0, 2048], ks32, 10, flags=P)
+    w2 = binding.cham_sweep_workspace_bytes_u16(2048, 24, [0, 2048], ks32, 10, flags=P)
+    w3 = binding.cham_sweep_workspace_bytes_u16(2048, 24, [0, 2048], ks32, 10)
+    assert w1 - w0 == 2048 * 64 * 2 and w2 - w3 == 2048 * 32 * 2
+    # the byte entry points accept and ignore the promise
+    assert binding.cham_sweep_path(4096, 24, [0, 4096], ks64, flags=P) == 0
+
+
 def test_static_sweep_rejects_bad_arguments_and_sizes_before_any_device_work(lib):
     vp = C.c_void_p
 

@@ -189,3 +189,67 @@ def test_limits_are_reported():
     wl.ks = [125]
     out = binding.cham_kmeans_sweep_u16(dw.X, dw.ld, dw.d, wl.task_off, wl.ks, wl.n_iter, want_labels=True)
     check_sweep(wl, out, oracle.sweep(wl.rows, wl.task_off, wl.ks, wl.n_iter, want_labels=True), dw.ld)
+
+
+# ------------------------------------------------------------------ two-byte knobs on the matrix cores
+
+def _to_device(rows):
+    import torch
+    n, d = rows.shape
+    ld = (n + 63) // 64 * 64
+    X = torch.zeros((d, ld), dtype=torch.int16, device="cuda")
+    X[:, :n] = torch.from_numpy(np.ascontiguousarray(rows.T).view(np.int16)).cuda()
+    return X, ld
+
+
+@pytest.mark.parametrize("d,n,ks", [(1, 700, (1, 2, 5)), (15, 1500, (3, 33, 64)), (16, 4096, (2, 64)), (31, 3000, (7, 40)),
+                                     (32, 2048, (1, 9, 32)), (40, 2048, (2, 17, 32)), (63, 1100, (5, 31)),
+                                     (47, 1024, (4, 32)), (33, 130, (3, 6))])
+def test_small_valued_two_byte_knobs_on_the_matrix_cores(d, n, ks):
+    """Cardinalities of at most 2048: the whole path with the caller's promise (the harness gives it from
+    the cardinalities) against the oracle, and the sweep bit for bit against the vector kernel."""
+    import torch
+    wl = workloads.wide_space(300 + d, n_tasks=3, n=n, d=d, ks=ks, n_iter=9, ragged=True, n_visited=256,
+                              card_wide=(64, 2048), wide_frac=0.5)
+    assert wl.cards.max() <= 2048 and (d < 15 or wl.rows.max() > 255)
+    dw, g, c = _full(wl, threshold=1.2)
+    v = binding.cham_kmeans_sweep(dw.X, dw.ld, dw.d, wl.task_off, wl.ks, wl.n_iter, want_labels=True,
+                                  flags=binding.F_NO_MFMA, _sfx="_u16")
+    m = binding.cham_kmeans_sweep(dw.X, dw.ld, dw.d, wl.task_off, wl.ks, wl.n_iter, want_labels=True,
+                                  flags=binding.F_VALUES_BELOW_2048, _sfx="_u16")
+    torch.cuda.synchronize()
+    for key in ("status", "counts", "centroids", "labels"):
+        assert torch.equal(v[key], m[key]), key
+    np.testing.assert_allclose(m["inertia"].cpu().numpy(), v["inertia"].cpu().numpy(), rtol=1e-12, atol=0)
+    passes = binding.cham_sweep_passes(m["workspace"], dw.ld, dw.d, wl.task_off, wl.ks).cpu().numpy()
+    assert passes.min() >= 1 and passes.max() <= wl.n_iter + 1
+    on_matrix_cores = binding.cham_sweep_path_u16(dw.ld, dw.d, wl.task_off, wl.ks, flags=binding.F_VALUES_BELOW_2048) == 0
+    assert on_matrix_cores == (d <= 63 and ((d <= 31 and max(ks) <= 64 and n <= 4096) or (max(ks) <= 32 and n <= 2048)))
+
+
+@pytest.mark.parametrize("flags", [binding.F_NO_MFMA, binding.F_FORCE_EXACT])
+def test_small_valued_two_byte_knobs_on_the_vector_kernel(flags):
+    wl = workloads.wide_space(77, n_tasks=4, n=1500, d=40, ks=range(2, 20), n_iter=8, ragged=True, n_visited=512)
+    assert wl.cards.max() <= 2048
+    _full(wl, threshold=1.2, flags=flags)
+
+
+def test_a_value_above_the_promised_range_is_reported():
+    """CHAM_F_VALUES_BELOW_2048 with a value of 2048 in the rows: every (task, k) reports status 4 and zero
+    outputs; without the promise the same rows run on the vector kernel as usual."""
+    import torch
+    rng = np.random.default_rng(9)
+    rows = rng.integers(0, 300, size=(900, 12)).astype(np.uint16)
+    rows[517, 3] = 2048
+    X, ld = _to_device(rows)
+    off = np.array([0, 400, 900], dtype=np.int64)
+    ks = [2, 5, 9]
+    bad = binding.cham_kmeans_sweep(X, ld, 12, off, ks, 6, want_labels=True, flags=binding.F_VALUES_BELOW_2048,
+                                    _sfx="_u16")
+    good = binding.cham_kmeans_sweep(X, ld, 12, off, ks, 6, want_labels=True, _sfx="_u16")
+    torch.cuda.synchronize()
+    assert (bad["status"].cpu().numpy() == 4).all()
+    assert float(bad["centroids"].abs().sum().item()) == 0.0 and int(bad["counts"].abs().sum().item()) == 0
+    assert (good["status"].cpu().numpy() == 0).all()
+    ref = oracle.sweep(rows, off, ks, 6, want_labels=True)
+    np.testing.assert_array_equal(good["counts"].cpu().numpy(), ref["counts"])
