@@ -57,6 +57,8 @@ def main():
                     help="skip the timing of the large single clustering (the streaming kernels)")
     ap.add_argument("--sweep-flags", type=int, default=0,
                     help="flags of cham_kmeans_sweep for the timed workload (8 = CHAM_F_NO_MFMA: the vector kernel)")
+    ap.add_argument("--wide-flags", type=int, default=0,
+                    help="flags of the sweep over the two-byte workload (8 = CHAM_F_NO_MFMA: the vector kernel)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run only a plain 1 GiB device copy (reference for the FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
@@ -226,11 +228,11 @@ def main():
     updater = dict(episodes=B_u, steps=S_u, d=wl.d, ms=round(best_u, 4), distinct=int(n_u.item()),
                    config_steps_per_s=round(B_u * S_u / (best_u * 1e-3), 1))
 
-    def side_workload(ww, reps=5):
+    def side_workload(ww, reps=5, flags=0):
         """Whole path on another workload: median step time and evaluation rates."""
         dww = binding.DeviceWorkload(ww, "cuda:0")
         dww.build_visited()
-        wfirst = dww.run()
+        wfirst = dww.run(flags=flags)
         wbufs = dict(sweep={k: wfirst["sweep"][k] for k in ("centroids", "counts", "inertia", "status")},
                      sweep_ws=wfirst["sweep"]["workspace"], chosen=wfirst["chosen"],
                      snap={k: wfirst["snap"][k] for k in ("labels_sel", "pick_row", "pick_cfg")},
@@ -243,7 +245,7 @@ def main():
         wev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
         for e0, e1 in wev:
             e0.record()
-            dww.run(bufs=wbufs)
+            dww.run(bufs=wbufs, flags=flags)
             e1.record()
         torch.cuda.synchronize()
         w_ms = float(np.median([a.elapsed_time(b) for a, b in wev]))
@@ -255,7 +257,7 @@ def main():
     wide = None
     if args.wide_knobs:
         ww = workloads.wide_space(0)
-        w_ms, w_exec, w_nom = side_workload(ww)
+        w_ms, w_exec, w_nom = side_workload(ww, flags=args.wide_flags)
         wide = dict(workload=f"{ww.name}: T={ww.T} tasks x N={ww.n_total // ww.T} rows x d={ww.d} two-byte knobs "
                              f"(cardinalities up to {int(ww.cards.max())}), k={ww.ks[0]}..{ww.ks[-1]}, "
                              f"{ww.n_iter} Lloyd steps + final pass, visited={ww.n_visited}",
@@ -265,7 +267,7 @@ def main():
                                                    / PEAK_FP32_VECTOR_TFLOPS, 4))
         # cardinalities of at most 2048: the harness promises values below 2048 and the sweep may run on the
         # matrix cores (the library says which kernel it is)
-        w_promise = binding.F_VALUES_BELOW_2048 if int(ww.cards.max()) <= 2048 else 0
+        w_promise = args.wide_flags | (binding.F_VALUES_BELOW_2048 if int(ww.cards.max()) <= 2048 else 0)
         w_path = binding.cham_sweep_path_u16((ww.n_total + 63) // 64 * 64, ww.d, ww.task_off, ww.ks, flags=w_promise)
         wide["kernel"] = binding.cham_sweep_path_kernel(w_path)
         if w_path == 0:
