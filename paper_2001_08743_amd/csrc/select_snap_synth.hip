@@ -258,50 +258,83 @@ __device__ __forceinline__ bool table_insert(uint64_t *v, uint64_t mask, uint64_
 }
 
 // Configuration updater of the exploration step (Sec. 3.2: the agent emits increment / decrement /
-// stay per knob and the updater applies it): one thread carries one configuration through n_steps
-// steps, theta <- clip(theta + a, 0, card - 1) per knob.  Every configuration reached is entered
-// into the table of configurations seen; the first thread to enter one also appends it to the list
-// of distinct configurations (the set S_Theta that the sampling step receives; order unspecified).
-__global__ void update_configs_kernel(uint8_t *theta, const int8_t *actions, int64_t B, int d, int n_steps,
-                                      const uint16_t *cards, uint64_t salt, uint64_t *seen, int64_t slots,
-                                      uint8_t *unique_rows, int64_t cap, int *n_unique, int *overflow)
+// stay per knob and the updater applies it): theta <- clip(theta + a, 0, card - 1) per knob, n_steps
+// times.  One workgroup carries one configuration, a chunk of steps at a time, in three phases: all
+// threads stage the chunk's actions in LDS; one lane per knob walks the chunk (the knobs of a
+// configuration move independently of each other, the steps of a knob do not) and leaves every
+// configuration reached in LDS; then one thread per step hashes its configuration and enters it
+// into the table of configurations seen, all steps of the chunk at once, so the latency of the
+// table's compare-and-swap is paid once per chunk instead of once per step.  The thread that
+// enters a configuration first also appends it to the list of distinct configurations (the set
+// S_Theta that the sampling step receives; order unspecified); a wave reserves its list slots with
+// one atomic add.
+constexpr int kUpdChunk = 512;
+constexpr int kUpdThreads = 256;
+
+__global__ void __launch_bounds__(kUpdThreads)
+update_configs_kernel(uint8_t *theta, const int8_t *actions, int64_t B, int d, int n_steps,
+                      const uint16_t *cards, uint64_t salt, uint64_t *seen, int64_t slots,
+                      uint8_t *unique_rows, int64_t cap, int *n_unique, int *overflow)
 {
-    const int64_t b = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (b >= B) return;
-    int cur[32];
-#pragma unroll
-    for (int j = 0; j < 32; ++j) cur[j] = j < d ? theta[b * d + j] : 0;
-    for (int s = 0; s < n_steps; ++s) {
-        const int8_t *a = actions + ((int64_t)s * B + b) * d;
-        uint64_t h = fnv_begin(salt);
-#pragma unroll
-        for (int j = 0; j < 32; ++j) {
-            if (j < d) {
-                int v = cur[j] + (int)a[j];
-                const int hi = (int)cards[j] - 1;
-                v = v < 0 ? 0 : (v > hi ? hi : v);
-                cur[j] = v;
-                h = fnv_step(h, (uint8_t)v);
-            }
+    __shared__ int8_t act[kUpdChunk * 32];
+    __shared__ uint8_t cfg[kUpdChunk * 32];
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    for (int64_t b = blockIdx.x; b < B; b += gridDim.x) {
+        int cur = 0, hi = 0;
+        if (tid < d) {
+            cur = theta[b * d + tid];
+            hi = (int)cards[tid] - 1;
         }
-        if (seen) {
-            const int r = table_insert_new(seen, (uint64_t)slots - 1, h);
-            if (r == 0 && overflow) *overflow = 1;
-            if (r == 1) {
-                const int idx = atomicAdd(n_unique, 1);
-                if (idx < cap) {
-#pragma unroll
-                    for (int j = 0; j < 32; ++j)
-                        if (j < d) unique_rows[(int64_t)idx * d + j] = (uint8_t)cur[j];
-                } else if (overflow) {
-                    *overflow = 1;
+        for (int t0 = 0; t0 < n_steps; t0 += kUpdChunk) {
+            const int nt = min(kUpdChunk, n_steps - t0);
+            for (int e = tid; e < nt * d; e += kUpdThreads) {
+                const int t = e / d;
+                act[e] = actions[((int64_t)(t0 + t) * B + b) * d + (e - t * d)];
+            }
+            __syncthreads();
+            if (tid < d) {
+#pragma unroll 8
+                for (int t = 0; t < nt; ++t) {
+                    int v = cur + (int)act[t * d + tid];
+                    v = v < 0 ? 0 : (v > hi ? hi : v);
+                    cur = v;
+                    cfg[t * d + tid] = (uint8_t)v;
                 }
             }
+            __syncthreads();
+            if (seen) {
+                for (int base = 0; base < nt; base += kUpdThreads) {
+                    const int t = base + tid;
+                    bool is_new = false;
+                    if (t < nt) {
+                        uint64_t h = fnv_begin(salt);
+                        for (int j = 0; j < d; ++j) h = fnv_step(h, cfg[t * d + j]);
+                        const int r = table_insert_new(seen, (uint64_t)slots - 1, h);
+                        if (r == 0 && overflow) *overflow = 1;
+                        is_new = r == 1;
+                    }
+                    const uint64_t m = __ballot(is_new);
+                    if (m != 0) {                                  // wave-uniform
+                        const int leader = __ffsll((unsigned long long)m) - 1;
+                        int first = 0;
+                        if (lane == leader) first = atomicAdd(n_unique, __popcll(m));
+                        first = __shfl(first, leader);
+                        if (is_new) {
+                            const int64_t idx = (int64_t)first + __popcll(m & ((1ull << lane) - 1ull));
+                            if (idx < cap) {
+                                for (int j = 0; j < d; ++j) unique_rows[idx * d + j] = cfg[t * d + j];
+                            } else if (overflow) {
+                                *overflow = 1;
+                            }
+                        }
+                    }
+                }
+            }
+            __syncthreads();                                       // the next chunk overwrites act and cfg
         }
+        if (tid < d) theta[b * d + tid] = (uint8_t)cur;
     }
-#pragma unroll
-    for (int j = 0; j < 32; ++j)
-        if (j < d) theta[b * d + j] = (uint8_t)cur[j];
 }
 
 __global__ void table_clear_kernel(uint64_t *v, int64_t slots)
@@ -999,8 +1032,8 @@ hipError_t launch_update_configs(uint8_t *theta, const int8_t *actions, int64_t 
                                  uint8_t *unique_rows, int64_t cap, int *n_unique, int *overflow, hipStream_t s)
 {
     if (B > 0)
-        hipLaunchKernelGGL(update_configs_kernel, dim3((unsigned)((B + 63) / 64)), dim3(64), 0, s, theta, actions, B, d,
-                           n_steps, cards, salt, seen, slots, unique_rows, cap, n_unique, overflow);
+        hipLaunchKernelGGL(update_configs_kernel, dim3((unsigned)(B < (1 << 20) ? B : (1 << 20))), dim3(kUpdThreads), 0, s,
+                           theta, actions, B, d, n_steps, cards, salt, seen, slots, unique_rows, cap, n_unique, overflow);
     return hipGetLastError();
 }
 

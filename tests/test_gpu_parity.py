@@ -579,8 +579,11 @@ def test_visited_table_overflow_is_reported_and_lookups_end():
 
 # ------------------------------------------------------------------ configuration updater
 
-@pytest.mark.parametrize("B,d,steps,card_hi", [(128, 8, 60, 6), (37, 24, 25, 32), (1, 1, 10, 2), (300, 32, 12, 256)])
+@pytest.mark.parametrize("B,d,steps,card_hi", [(128, 8, 60, 6), (37, 24, 25, 32), (1, 1, 10, 2), (300, 32, 12, 256),
+                                               (5, 24, 1300, 16), (3, 31, 1025, 4), (128, 24, 500, 32)])
 def test_configuration_updater_matches_the_oracle(B, d, steps, card_hi):
+    """Final configurations and the set of distinct configurations reached, against the oracle's walk; the
+    step counts span less than one, exactly two and several of the kernel's chunks of steps."""
     import torch
     rng = np.random.default_rng(1000 + B + d)
     cards = rng.integers(1 if d == 1 else 2, card_hi + 1, size=d).astype(np.uint16)
@@ -589,7 +592,7 @@ def test_configuration_updater_matches_the_oracle(B, d, steps, card_hi):
     final, order = oracle.update_configs(theta, actions, cards)
     dev = "cuda:0"
     th = torch.from_numpy(theta.copy()).to(dev)
-    table = torch.empty(1 << 16, dtype=torch.int64, device=dev)
+    table = torch.empty(max(1 << 16, 1 << int(np.ceil(np.log2(4 * B * steps)))), dtype=torch.int64, device=dev)
     binding.cham_visited_table_clear(table)
     uniq = torch.zeros((B * steps, d), dtype=torch.uint8, device=dev)
     n_unique = torch.zeros(1, dtype=torch.int32, device=dev)
@@ -612,6 +615,35 @@ def test_configuration_updater_matches_the_oracle(B, d, steps, card_hi):
     binding.cham_update_configs(th2, torch.from_numpy(actions).to(dev), cards_dev)
     torch.cuda.synchronize()
     np.testing.assert_array_equal(th2.cpu().numpy(), final)
+
+
+def test_configuration_updater_reports_a_full_list():
+    """A list of distinct configurations shorter than their number: the counter still counts all of them, the
+    list holds distinct configurations that were reached, and the overflow word is set."""
+    import torch
+    rng = np.random.default_rng(5)
+    B, d, steps, cap = 16, 12, 700, 100
+    cards = rng.integers(8, 33, size=d).astype(np.uint16)
+    theta = (rng.random((B, d)) * cards).astype(np.uint8)
+    actions = rng.integers(-1, 2, size=(steps, B, d)).astype(np.int8)
+    final, order = oracle.update_configs(theta, actions, cards)
+    assert len(order) > cap
+    dev = "cuda:0"
+    th = torch.from_numpy(theta.copy()).to(dev)
+    table = torch.empty(1 << 16, dtype=torch.int64, device=dev)
+    binding.cham_visited_table_clear(table)
+    uniq = torch.full((cap + 8, d), 255, dtype=torch.uint8, device=dev)
+    n_unique = torch.zeros(1, dtype=torch.int32, device=dev)
+    ovf = torch.zeros(1, dtype=torch.int32, device=dev)
+    binding.cham_update_configs(th, torch.from_numpy(actions).to(dev), torch.from_numpy(cards.astype(np.int16)).to(dev),
+                                salt=3, seen_table=table, unique_rows=uniq[:cap], n_unique=n_unique, overflow=ovf)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(th.cpu().numpy(), final)
+    assert int(n_unique.item()) == len(order) and int(ovf.item()) == 1
+    rows = uniq.cpu().numpy()
+    assert (rows[cap:] == 255).all()                                # nothing written past the capacity
+    got = list(map(tuple, rows[:cap].tolist()))
+    assert len(set(got)) == cap and set(got) <= set(order)
 
 
 def test_bench_prints_one_json_line_with_the_contract_fields():
