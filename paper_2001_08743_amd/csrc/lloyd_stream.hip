@@ -21,7 +21,8 @@ namespace cham {
 
 namespace {
 
-constexpr int kTiles = 4;            // 32-row tiles a wave handles per step
+constexpr int kMaxTiles = 8;         // 32-row tiles a wave handles per step, at most
+constexpr int kStepRows = kMaxTiles * 32;
 constexpr int kStreamRec = 32;       // queued rows whose knob values are kept in LDS
 constexpr int kWavesPerWg = 4;
 constexpr int kPairCap = 128;        // (queued row, candidate centroid) pairs evaluated per step and wave
@@ -246,8 +247,8 @@ struct StreamLds {
     // per wave: knob values of queued rows, their row slots, resolved labels, labels of the step
     // ... and for the exact evaluation of queued rows: (record, centroid) pairs, per record the
     // smallest distance (bits) and the lowest centroid attaining it, the pair counter
-    static constexpr size_t kWaveBytes = (size_t)kStreamRec * DK * 2 + 128 * 2 + 128 + 128 + 128 * 4 +
-                                         kPairCap * 2 + 128 * 8 + 128 * 4 + 16;
+    static constexpr size_t kWaveBytes = (size_t)kStreamRec * DK * 2 + kStepRows * 2 + kStepRows + kStepRows +
+                                         kStreamRec * 4 + kPairCap * 2 + kStepRows * 8 + kStepRows * 4 + 16;
     __host__ __device__ static size_t bytes(int kpm)
     {
         size_t b = 16 * (size_t)(kpm / 32) * 4 * 64 + sizeof(int) * (size_t)kpm * DK + sizeof(int) * kpm +
@@ -270,38 +271,22 @@ struct StreamLds {
     }
 };
 
-template <int DK>
-__global__ __launch_bounds__(kWavesPerWg * 64, 2) void stream_assign_kernel(const StreamArgs a)
+// One (unit, row chunk) workgroup of the assignment.  NCH = chunks of 64 centroids of the unit
+// (compiled for 1, 2 or 4), TILES = 32-row tiles a wave handles per step: the more rows a step
+// holds, the fewer chains of dependent short phases (decision, exact evaluation, label changes) a
+// workgroup goes through, within what the registers hold beside the per-chunk marks.
+template <int DK, int NCH, int TILES>
+__device__ __forceinline__ void assign_unit(const StreamArgs &a, int unit_idx)
 {
     constexpr int NS = DK / 16, NS2 = 2 * NS;
     extern __shared__ __align__(16) unsigned char smem[];
-    __shared__ int unit_sh;
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = tid >> 6;
     const int n32 = lane & 31;
     const int h = lane >> 5;
-
-    if (tid < 64) {
-        // last unit with wg_off[unit] <= blockIdx.x: a 64-way search by the first wave (one or two
-        // rounds of independent loads instead of a chain of dependent ones)
-        int lo = 0, hi = a.n_units;
-        while (hi - lo > 1) {
-            const int span = hi - lo;
-            const int stride = (span + 63) / 64;
-            const int probe = lo + tid * stride;
-            const bool le = probe < hi && a.wg_off[probe] <= (int)blockIdx.x;     // true for a prefix of the lanes
-            const int cntle = __popcll(__ballot(le));                              // >= 1: wg_off[lo] <= blockIdx.x
-            const int nlo = lo + (cntle - 1) * stride;
-            const int nhi = nlo + stride < hi ? nlo + stride : hi;
-            lo = nlo;
-            hi = nhi;
-        }
-        if (tid == 0) unit_sh = lo;
-    }
-    __syncthreads();
-    const int wgi = blockIdx.x - a.wg_off[unit_sh];
-    const int u = a.u_begin + unit_sh;
+    const int wgi = blockIdx.x - a.wg_off[unit_idx];
+    const int u = a.u_begin + unit_idx;
     const int ki = a.n_k - 1 - u / a.T;
     const int t = u % a.T;
     const int k = a.ks[ki];
@@ -323,30 +308,30 @@ __global__ __launch_bounds__(kWavesPerWg * 64, 2) void stream_assign_kernel(cons
     const bool want_dist = a.final_pass || (a.trace != nullptr);
     unsigned char *wb = L.wave_base + ((StreamLds<DK>::kWaveBytes + 15) & ~(size_t)15) * wave;
     _Float16 *rec_x = reinterpret_cast<_Float16 *>(wb);                                          // [kStreamRec][DK]
-    unsigned short *rec_slot = reinterpret_cast<unsigned short *>(wb + (size_t)kStreamRec * DK * 2);   // [128]
-    unsigned char *lab_res = wb + (size_t)kStreamRec * DK * 2 + 256;                              // [128]
-    unsigned char *lab_new = lab_res + 128;                                                        // [128]
-    unsigned *chg = reinterpret_cast<unsigned *>(lab_new + 128);                                   // [128] cur | prev << 8 | first << 16
-    unsigned short *pairs = reinterpret_cast<unsigned short *>(chg + 128);                         // [kPairCap] record << 8 | centroid
-    unsigned long long *best_bits = reinterpret_cast<unsigned long long *>(pairs + kPairCap);      // [128]
-    int *best_c = reinterpret_cast<int *>(best_bits + 128);                                        // [128]
-    unsigned *npairs = reinterpret_cast<unsigned *>(best_c + 128);
+    unsigned short *rec_slot = reinterpret_cast<unsigned short *>(wb + (size_t)kStreamRec * DK * 2);   // [kStepRows]
+    unsigned char *lab_res = wb + (size_t)kStreamRec * DK * 2 + kStepRows * 2;                    // [kStepRows]
+    unsigned char *lab_new = lab_res + kStepRows;                                                  // [kStepRows]
+    unsigned *chg = reinterpret_cast<unsigned *>(lab_new + kStepRows);                             // [kStreamRec] cur | prev << 8 | first << 16
+    unsigned short *pairs = reinterpret_cast<unsigned short *>(chg + kStreamRec);                  // [kPairCap] record << 8 | centroid
+    unsigned long long *best_bits = reinterpret_cast<unsigned long long *>(pairs + kPairCap);      // [kStepRows]
+    int *best_c = reinterpret_cast<int *>(best_bits + kStepRows);                                  // [kStepRows]
+    unsigned *npairs = reinterpret_cast<unsigned *>(best_c + kStepRows);
 
     const _Float16 *xh = reinterpret_cast<const _Float16 *>(a.xh);
     const int nch = (k + 63) >> 6;
     double part = 0.0;
 
-    const int64_t step_rows = (int64_t)kWavesPerWg * kTiles * 32;
+    const int64_t step_rows = (int64_t)kWavesPerWg * TILES * 32;
 
     // rows of one step of this wave: B fragments, squared norms, previous labels
     struct StepRows {
-        half8 B[kTiles][NS];
-        float x2[kTiles];
-        int prev[kTiles];
+        half8 B[TILES][NS];
+        float x2[TILES];
+        int prev[TILES];
     };
     auto load_step = [&](int64_t wrow0, StepRows &R) {
 #pragma unroll
-        for (int tt = 0; tt < kTiles; ++tt) {
+        for (int tt = 0; tt < TILES; ++tt) {
             const int64_t row = wrow0 + tt * 32 + n32;
             const bool lv = row < r1;
             const int64_t rr = lv ? row : (wrow0 < r1 ? wrow0 : r0);     // a valid row either way
@@ -365,7 +350,7 @@ __global__ __launch_bounds__(kWavesPerWg * 64, 2) void stream_assign_kernel(cons
     };
 
     StepRows nxt;
-    if (r0 < r1) load_step(r0 + (int64_t)wave * kTiles * 32, nxt);    // under way during the set-up below
+    if (r0 < r1) load_step(r0 + (int64_t)wave * TILES * 32, nxt);    // under way during the set-up below
 
     for (int e = tid; e < (kpu / 32) * NS2 * 64; e += blockDim.x) {      // the NS2 slots in use of every m-tile
         const int src = (e / (NS2 * 64)) * 4 * 64 + e % (NS2 * 64);
@@ -378,19 +363,19 @@ __global__ __launch_bounds__(kWavesPerWg * 64, 2) void stream_assign_kernel(cons
     __syncthreads();
 
     for (int64_t base = r0; base < r1; base += step_rows) {
-        const int64_t wrow0 = base + (int64_t)wave * kTiles * 32;      // first row of this wave's step
+        const int64_t wrow0 = base + (int64_t)wave * TILES * 32;      // first row of this wave's step
         const StepRows cur = nxt;
         if (base + step_rows < r1) load_step(wrow0 + step_rows, nxt);  // next step's rows load under this step
         if (wrow0 >= r1) continue;                                      // wave-uniform
-        bool live[kTiles];
+        bool live[TILES];
 #pragma unroll
-        for (int tt = 0; tt < kTiles; ++tt) live[tt] = (wrow0 + tt * 32 + n32) < r1;
+        for (int tt = 0; tt < TILES; ++tt) live[tt] = (wrow0 + tt * 32 + n32) < r1;
 
-        constexpr int kMaxCh = 4;                    // chunks of 64 centroids, k <= 256
-        int cnt[kTiles], candq[kTiles];
-        uint32_t cmask[kTiles][kMaxCh];             // candidate centroids of this lane half, per chunk
+        constexpr int kMaxCh = NCH;                  // chunks of 64 centroids
+        int cnt[TILES], candq[TILES];
+        uint32_t cmask[TILES][kMaxCh];             // candidate centroids of this lane half, per chunk
 #pragma unroll
-        for (int tt = 0; tt < kTiles; ++tt) {
+        for (int tt = 0; tt < TILES; ++tt) {
             cnt[tt] = 0;
             candq[tt] = 0;
 #pragma unroll
@@ -438,10 +423,10 @@ __global__ __launch_bounds__(kWavesPerWg * 64, 2) void stream_assign_kernel(cons
         // no larger than their score), at worst joined by some up to two bounds away, which
         // only sends a few more rows to the exact evaluation.  Within a chunk the tiles are
         // pipelined: the chain of the next tile is issued under the marking of the current one.
-        float bch[kTiles][kMaxCh];
-        float bnd[kTiles];
+        float bch[TILES][kMaxCh];
+        float bnd[TILES];
 #pragma unroll
-        for (int tt = 0; tt < kTiles; ++tt) bnd[tt] = mfma_bound<NS2>(cur.x2[tt], m2);
+        for (int tt = 0; tt < TILES; ++tt) bnd[tt] = mfma_bound<NS2>(cur.x2[tt], m2);
 #pragma unroll
         for (int ch = 0; ch < kMaxCh; ++ch) {
             if (ch < nch) {
@@ -450,7 +435,7 @@ __global__ __launch_bounds__(kWavesPerWg * 64, 2) void stream_assign_kernel(cons
                 float16v cin0, cin1;
                 load_a(ch, has1, A0, A1, cin0, cin1);
                 float16v accA, accB;
-                constexpr int kLast = kTiles - 1;
+                constexpr int kLast = TILES - 1;
                 if (has1) {
                     // accA = centroids 0..31, accB = centroids 32..63 of the chunk
 #pragma unroll
@@ -458,7 +443,7 @@ __global__ __launch_bounds__(kWavesPerWg * 64, 2) void stream_assign_kernel(cons
 #pragma unroll
                     for (int s = 0; s < NS2; ++s) mma(accB, A1, cur.B[0], cin1, s);
 #pragma unroll
-                    for (int tt = 0; tt < kTiles; ++tt) {
+                    for (int tt = 0; tt < TILES; ++tt) {
                         const int nx = tt < kLast ? tt + 1 : tt;
                         const float m = min_halves(__builtin_fminf(min16(accA), min16(accB)));
                         const float thr = m + bnd[tt];
@@ -487,7 +472,7 @@ __global__ __launch_bounds__(kWavesPerWg * 64, 2) void stream_assign_kernel(cons
 #pragma unroll
                     for (int s = 0; s < NS2; ++s) mma(accA, A0, cur.B[0], cin0, s);
 #pragma unroll
-                    for (int tt = 0; tt < kTiles; ++tt) {
+                    for (int tt = 0; tt < TILES; ++tt) {
                         const int nx = tt < kLast ? tt + 1 : tt;
                         float16v &now = (tt & 1) ? accB : accA;
                         float16v &nxt2 = (tt & 1) ? accA : accB;
@@ -509,11 +494,11 @@ __global__ __launch_bounds__(kWavesPerWg * 64, 2) void stream_assign_kernel(cons
                 }
             } else {
 #pragma unroll
-                for (int tt = 0; tt < kTiles; ++tt) bch[tt][ch] = __builtin_inff();
+                for (int tt = 0; tt < TILES; ++tt) bch[tt][ch] = __builtin_inff();
             }
         }
 #pragma unroll
-        for (int tt = 0; tt < kTiles; ++tt) {
+        for (int tt = 0; tt < TILES; ++tt) {
             float best = bch[tt][0];
 #pragma unroll
             for (int ch = 1; ch < kMaxCh; ++ch) best = __builtin_fminf(best, bch[tt][ch]);
@@ -527,13 +512,13 @@ __global__ __launch_bounds__(kWavesPerWg * 64, 2) void stream_assign_kernel(cons
             }
         }
         // decide, or queue for the exact evaluation
-        int lab[kTiles];
+        int lab[TILES];
         uint32_t flagged_mask = 0;
         int nrec = 0;
         bool no_candidate = false;          // a queued row without any candidate (cannot happen with a valid bound)
         __builtin_amdgcn_wave_barrier();    // the pair counter is zero
 #pragma unroll
-        for (int tt = 0; tt < kTiles; ++tt) {
+        for (int tt = 0; tt < TILES; ++tt) {
             unsigned c_lo, c_hi, q_lo, q_hi;
             both_halves((unsigned)cnt[tt], c_lo, c_hi);
             both_halves((unsigned)candq[tt], q_lo, q_hi);
@@ -669,9 +654,39 @@ __global__ __launch_bounds__(kWavesPerWg * 64, 2) void stream_assign_kernel(cons
             }
             __builtin_amdgcn_wave_barrier();
         }
-        // label changes -> sums of this workgroup (LDS), tile by tile
+        // Label changes -> sums of this workgroup (LDS).  The rows of the step whose label changed
+        // are listed with their knob values (kStreamRec of them at most, then the list is applied
+        // and starts again) and applied together, one lane per (row, group of 4 knobs): one chain
+        // of dependent LDS accesses per step when few rows move, however many tiles hold one.
+        auto apply_changes = [&](int count) {
+            __builtin_amdgcn_wave_barrier();
+            constexpr int LPR = DK / 4, EPI = 64 / LPR;
+            const int j0 = 4 * (lane % LPR);
+            for (int e0 = 0; e0 < count; e0 += EPI) {
+                const int e = e0 + lane / LPR;
+                if (e < count && j0 < d) {
+                    const unsigned w = chg[e];
+                    const int cc = w & 0xFF, pp = (w >> 8) & 0xFF;
+                    const bool had = ((w >> 16) & 1u) == 0u;     // the row had a label before
 #pragma unroll
-        for (int tt = 0; tt < kTiles; ++tt) {
+                    for (int i = 0; i < 4; ++i) {
+                        if (j0 + i < d) {
+                            const int xi = (int)((float)rec_x[(size_t)e * DK + j0 + i] + L.ojf[j0 + i]);
+                            atomicAdd(&L.S[cc * DK + j0 + i], xi);
+                            if (had) atomicSub(&L.S[pp * DK + j0 + i], xi);
+                        }
+                    }
+                    if (j0 == 0) {
+                        atomicAdd(&L.n[cc], 1);
+                        if (had) atomicSub(&L.n[pp], 1);
+                    }
+                }
+            }
+            __builtin_amdgcn_wave_barrier();
+        };
+        int nchg = 0;
+#pragma unroll
+        for (int tt = 0; tt < TILES; ++tt) {
             const int64_t row = wrow0 + tt * 32 + n32;
             int cl = lab[tt];
             if ((flagged_mask >> tt) & 1u) cl = lab_res[tt * 32 + n32];
@@ -680,8 +695,13 @@ __global__ __launch_bounds__(kWavesPerWg * 64, 2) void stream_assign_kernel(cons
             if (want_dist && h == 0) lab_new[tt * 32 + n32] = (unsigned char)(live[tt] ? cl : 0);
             const uint64_t cm = __ballot(changed) & 0xFFFFFFFFull;
             if (cm) {
+                const int c = __popcll(cm);
+                if (nchg + c > kStreamRec) {                       // wave-uniform
+                    apply_changes(nchg);
+                    nchg = 0;
+                }
                 if (changed) {
-                    const int rs = __popcll(cm & ((1ull << n32) - 1ull));
+                    const int rs = nchg + __popcll(cm & ((1ull << n32) - 1ull));
 #pragma unroll
                     for (int f = 0; f < NS; ++f)
                         *reinterpret_cast<half8 *>(rec_x + (size_t)rs * DK + 16 * f + 8 * h) = cur.B[tt][f];
@@ -690,38 +710,14 @@ __global__ __launch_bounds__(kWavesPerWg * 64, 2) void stream_assign_kernel(cons
                         labrow[row] = (uint8_t)cl;
                     }
                 }
-                const int ccount = __popcll(cm);
-                __builtin_amdgcn_wave_barrier();
-                // one lane per (row, group of 4 knobs)
-                constexpr int LPR = DK / 4, EPI = 64 / LPR;
-                const int j0 = 4 * (lane % LPR);
-                for (int e0 = 0; e0 < ccount; e0 += EPI) {
-                    const int e = e0 + lane / LPR;
-                    if (e < ccount && j0 < d) {
-                        const unsigned w = chg[e];
-                        const int cc = w & 0xFF, pp = (w >> 8) & 0xFF;
-                        const bool had = ((w >> 16) & 1u) == 0u;     // the row had a label before
-#pragma unroll
-                        for (int i = 0; i < 4; ++i) {
-                            if (j0 + i < d) {
-                                const int xi = (int)((float)rec_x[(size_t)e * DK + j0 + i] + L.ojf[j0 + i]);
-                                atomicAdd(&L.S[cc * DK + j0 + i], xi);
-                                if (had) atomicSub(&L.S[pp * DK + j0 + i], xi);
-                            }
-                        }
-                        if (j0 == 0) {
-                            atomicAdd(&L.n[cc], 1);
-                            if (had) atomicSub(&L.n[pp], 1);
-                        }
-                    }
-                }
-                __builtin_amdgcn_wave_barrier();
+                nchg += c;
             }
         }
+        if (nchg) apply_changes(nchg);
         if (want_dist) {
             // exact loss terms of the rows of this step: one row per lane, knobs ascending
             __builtin_amdgcn_wave_barrier();
-            for (int s0 = 0; s0 < kTiles * 32; s0 += 64) {
+            for (int s0 = 0; s0 < TILES * 32; s0 += 64) {
                 const int sl = s0 + lane;
                 const int64_t row = wrow0 + sl;
                 if (row < r1) {
@@ -767,6 +763,47 @@ __global__ __launch_bounds__(kWavesPerWg * 64, 2) void stream_assign_kernel(cons
         double s = 0.0;
         for (int w = 0; w < kWavesPerWg; ++w) s = s + (w < (int)(blockDim.x >> 6) ? L.red[w] : 0.0);
         a.loss_part[blockIdx.x] = s;
+    }
+}
+
+template <int DK>
+__global__ __launch_bounds__(kWavesPerWg * 64, 2) void stream_assign_kernel(const StreamArgs a)
+{
+    __shared__ int unit_sh;
+    const int tid = threadIdx.x;
+    if (tid < 64) {
+        // last unit with wg_off[unit] <= blockIdx.x: a 64-way search by the first wave (one or two
+        // rounds of independent loads instead of a chain of dependent ones)
+        int lo = 0, hi = a.n_units;
+        while (hi - lo > 1) {
+            const int span = hi - lo;
+            const int stride = (span + 63) / 64;
+            const int probe = lo + tid * stride;
+            const bool le = probe < hi && a.wg_off[probe] <= (int)blockIdx.x;     // true for a prefix of the lanes
+            const int cntle = __popcll(__ballot(le));                              // >= 1: wg_off[lo] <= blockIdx.x
+            const int nlo = lo + (cntle - 1) * stride;
+            const int nhi = nlo + stride < hi ? nlo + stride : hi;
+            lo = nlo;
+            hi = nhi;
+        }
+        if (tid == 0) unit_sh = lo;
+    }
+    __syncthreads();
+    const int unit_idx = __builtin_amdgcn_readfirstlane(unit_sh);
+    const int u = a.u_begin + unit_idx;
+    const int k = a.ks[a.n_k - 1 - u / a.T];
+    // the unit index goes through an opaque copy per variant: what a variant derives from it stays inside
+    // its branch instead of being computed for all three ahead of the branch (scalar registers)
+    int ui = unit_idx;
+    if (k <= 64) {
+        asm volatile("" : "+s"(ui));
+        assign_unit<DK, 1, (DK == 16 ? 8 : 4)>(a, ui);
+    } else if (k <= 128) {
+        asm volatile("" : "+s"(ui));
+        assign_unit<DK, 2, 4>(a, ui);
+    } else {
+        asm volatile("" : "+s"(ui));
+        assign_unit<DK, 4, 4>(a, ui);
     }
 }
 
