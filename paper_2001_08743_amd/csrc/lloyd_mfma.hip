@@ -1270,7 +1270,7 @@ __global__ __launch_bounds__(512) void resident_mfma_kernel(const SweepArgs a)
     if (tid == 0) next_unit = atomicAdd(a.unit_counter, 1);
     for (;;) {
         __syncthreads();
-        const int u = next_unit;
+        const int u = __builtin_amdgcn_readfirstlane(next_unit);     // uniform: what derives from it lives in scalar registers
         __syncthreads();                           // everyone has read it before it is written again
         if (u >= n_units) break;
         // the unit after this one is asked for now; the answer is needed when this one is done
