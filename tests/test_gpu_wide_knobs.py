@@ -253,3 +253,29 @@ def test_a_value_above_the_promised_range_is_reported():
     assert (good["status"].cpu().numpy() == 0).all()
     ref = oracle.sweep(rows, off, ks, 6, want_labels=True)
     np.testing.assert_array_equal(good["counts"].cpu().numpy(), ref["counts"])
+
+
+@pytest.mark.parametrize("d,chunk", [(36, 3), (20, 5)])
+def test_knee_sweep_of_small_valued_two_byte_knobs_on_the_matrix_cores(d, chunk):
+    """The chunked sweep with the caller's promise: several launches of the matrix-core kernel share one
+    packed copy of the rows and one check of the promise."""
+    wl = workloads.wide_space(16 + d, n_tasks=4, n=1000, d=d, ks=range(1, 21), n_iter=6, n_visited=300, ragged=True)
+    assert wl.cards.max() <= 2048
+    ld = (wl.n_total + 63) // 64 * 64
+    assert binding.cham_sweep_path_u16(ld, d, wl.task_off, wl.ks, flags=binding.F_VALUES_BELOW_2048) == 0
+    _check_knee_sweep(wl, 2.0, chunk, flags=binding.F_VALUES_BELOW_2048)
+    _check_knee_sweep(wl, 1.05, chunk, flags=binding.F_VALUES_BELOW_2048)
+
+
+def test_a_value_above_the_promised_range_is_reported_by_the_knee_sweep():
+    import torch
+    rng = np.random.default_rng(10)
+    rows = rng.integers(0, 500, size=(640, 9)).astype(np.uint16)
+    rows[3, 8] = 40000
+    X, ld = _to_device(rows)
+    off = np.array([0, 640], dtype=np.int64)
+    out = binding.cham_kmeans_sweep_knee(X, ld, 9, off, [2, 3, 4, 5], 4, threshold=2.5, chunk=2,
+                                         flags=binding.F_VALUES_BELOW_2048, _sfx="_u16")
+    torch.cuda.synchronize()
+    assert (out["status"].cpu().numpy() == 4).all()
+    assert int(out["chosen"].cpu().numpy()[0]) == -1
