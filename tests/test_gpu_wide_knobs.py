@@ -209,7 +209,7 @@ def test_small_valued_two_byte_knobs_on_the_matrix_cores(d, n, ks):
     """Cardinalities of at most 2048: the whole path with the caller's promise (the harness gives it from
     the cardinalities) against the oracle, and the sweep bit for bit against the vector kernel."""
     import torch
-    wl = workloads.wide_space(300 + d, n_tasks=3, n=n, d=d, ks=ks, n_iter=9, ragged=True, n_visited=256,
+    wl = workloads.wide_space(300 + d, n_tasks=3, n=n, d=d, ks=ks, n_iter={47: 0, 31: 1}.get(d, 9), ragged=True, n_visited=256,
                               card_wide=(64, 2048), wide_frac=0.5)
     assert wl.cards.max() <= 2048 and (d < 15 or wl.rows.max() > 255)
     dw, g, c = _full(wl, threshold=1.2)
