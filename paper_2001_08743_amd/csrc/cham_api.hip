@@ -72,12 +72,14 @@ private:
 
 // Small host arrays travel to the device inside kernel arguments (copied at launch time), so
 // no host buffer has to outlive the call and no device memory is allocated.
-constexpr int kPokeWords = 120;
+constexpr int kPokeWords = 496;           // with the two fields below just under the 4 KiB of kernel arguments
+constexpr int kPokeThreads = 512;
 struct PokeArgs {
     uint64_t v[kPokeWords];
     uint64_t *dst;
     int n;
 };
+static_assert(sizeof(PokeArgs) <= 4096 && kPokeWords <= kPokeThreads, "one thread per word, arguments within 4 KiB");
 __global__ void poke_kernel(const PokeArgs p)
 {
     const int i = threadIdx.x;
@@ -91,7 +93,7 @@ hipError_t stage_words(const Words &blob, uint64_t *dst, hipStream_t s)
         p.n = (int)((blob.size() - o) < (size_t)kPokeWords ? (blob.size() - o) : (size_t)kPokeWords);
         for (int i = 0; i < p.n; ++i) p.v[i] = blob[o + i];
         p.dst = dst + o;
-        hipLaunchKernelGGL(poke_kernel, dim3(1), dim3(128), 0, s, p);
+        hipLaunchKernelGGL(poke_kernel, dim3(1), dim3(kPokeThreads), 0, s, p);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
