@@ -881,6 +881,12 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
                 const uint32_t lab = Q.lab()[nt * 32 + n32];
                 const bool live = lab != 0xFFu;
                 const double *mc = U.mu64T + (live ? lab : 0u) + (size_t)(8 * h) * KP;
+                // the centroid's knobs first, all loads under way together, then the sum in knob order
+                double mu[NS][8];
+#pragma unroll
+                for (int f = 0; f < NS; ++f)
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) mu[f][i] = mc[(size_t)(16 * f + i) * KP];
                 double s = 0.0;
 #pragma unroll
                 for (int f = 0; f < NS; ++f)
@@ -888,7 +894,7 @@ __device__ __forceinline__ void run_unit(const SweepArgs &a, unsigned char *smem
                     for (int i = 0; i < 8; ++i) {
                         float xf = (float)bt[f][i] + of[f][i];
                         if (f == bstep && i == belem) xf = h == bhalf ? 0.0f : xf;     // the bias slot is no knob
-                        const double tq = (double)xf - mc[(size_t)(16 * f + i) * KP];
+                        const double tq = (double)xf - mu[f][i];
                         s = s + tq * tq;
                     }
                 part = part + (live ? s : 0.0);
