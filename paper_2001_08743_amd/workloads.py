@@ -282,3 +282,34 @@ def wide_space(seed: int, n_tasks: int = 64, n: int = 2048, d: int = 40, ks=rang
     blobs = rng.integers(8, 25, size=n_tasks)
     return _assemble(f"wide-{seed}", rng, sizes, card_list, blobs, 1.5, 0.05, ks, n_iter, n_visited,
                      dtype=np.uint16, sigma_rel=0.02)
+
+
+def random_workload(seed: int) -> Workload:
+    """A small workload of random shape for randomised parity tests: 1..5 ragged tasks (a quarter of
+    the draws with tasks of up to 9000 rows, else up to 2500), byte knobs (d = 1..31, cardinalities up
+    to 4 / 16 / 64 / 256) or, for a third of the draws, two-byte knobs (d = 1..64, two fifths of
+    the knobs with cardinalities up to 300 / 2048 / 5000), 1..6 values of k up to 3..256, 0..14 Lloyd
+    steps, 1..19 blobs per task of spread 0.5 / 1.5 / 3, 5 % invalid rows."""
+    rng = np.random.default_rng(BASE_SEED * 11 + seed)
+    wide = rng.random() < 0.35
+    d = int(rng.integers(1, 65 if wide else 32))
+    T = int(rng.integers(1, 6))
+    big = rng.random() < 0.25
+    sizes = [int(rng.integers(1, 9000 if big else 2500)) for _ in range(T)]
+    kmax = int(rng.choice([3, 8, 16, 31, 32, 33, 64, 100, 256]))
+    if wide:
+        kmax = min(kmax, 100 if d <= 48 else 64)
+    ks = sorted(set(int(x) for x in rng.integers(1, kmax + 1, size=int(rng.integers(1, 6)))) | {kmax})
+    n_iter = int(rng.choice([0, 1, 2, 5, 9, 14]))
+    if wide:
+        hi = int(rng.choice([300, 2048, 5000]))
+        card_list = [np.where(rng.random(d) < 0.4, rng.integers(2, hi + 1, size=d),
+                              rng.integers(2, 33, size=d)).astype(np.uint16) for _ in range(T)]
+    else:
+        hi = int(rng.choice([4, 16, 64, 256]))
+        card_list = [rng.integers(1 if d == 1 else 2, hi + 1, size=d).astype(np.uint16) for _ in range(T)]
+    blobs = rng.integers(1, 20, size=T)
+    sigma = float(rng.choice([0.5, 1.5, 3.0]))
+    return _assemble(f"random-{seed}", rng, sizes, card_list, blobs, sigma, 0.05, ks, n_iter,
+                     int(rng.integers(1, 400)), threshold=float(rng.choice([1.05, 1.3, 2.5])),
+                     dtype=np.uint16 if wide else np.uint8, sigma_rel=0.02 if wide else 0.0)
